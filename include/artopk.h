@@ -1,0 +1,178 @@
+/*
+ * artopk.h -- C ABI of the MI355X (gfx950) AR-Topk gradient compressor.
+ *
+ * One call of artopk_step() performs, for W data-parallel workers whose
+ * gradients all live on one GPU, the loop body of Alg. 1 of "Flexible
+ * Communication for Optimal Distributed Learning over Unpredictable Networks"
+ * (AR-Topk compression, Sec. III-A/III-B) together with the error feedback of
+ * Sec. II-C:
+ *
+ *     acc_w   = g_w + residual_w                       (EF equations, Alg. 1)
+ *     leader  = step mod W            (STAR-Topk)   or
+ *               first argmax_w var(acc_w)  (VAR-Topk)  (Sec. III-B)
+ *     idx     = the k positions of largest |acc_leader| (Sec. III-A, Topk)
+ *     vals_w  = acc_w[idx]                             (Alg. 1, gather)
+ *     sum     = ((vals_0 + vals_1) + ...) + vals_{W-1}  (stand-in for AllReduce)
+ *     update  = zeros(N); update[idx] = sum            (input of the SGD update)
+ *     residual_w = acc_w with the idx positions set to +0.0
+ *
+ * Conventions
+ *   - W is the paper's cluster size N, N here is the number of gradient
+ *     elements (the paper's G), k = ceil(c * N) is computed by the caller.
+ *   - All data buffers are caller-owned DEVICE memory, float32 / int32 /
+ *     float64 as typed, 16-byte aligned, non-overlapping.  Arrays of pointers
+ *     (g, residual, acc, x) and the segment tables are HOST memory and are
+ *     read before the call returns.
+ *   - Work is enqueued on the stream given to artopk_create(); calls return
+ *     without synchronising.  Outputs are valid once that stream has been
+ *     synchronised by the caller.  Calls on one context must not overlap.
+ *   - The library allocates device memory only inside artopk_create().
+ *   - Return value: ARTOPK_OK or a negative error code; on ARTOPK_EINVAL
+ *     nothing has been enqueued.  No exception or abort crosses this boundary.
+ *   - Magnitudes are ordered by the raw 31 magnitude bits of the float32, so
+ *     +x and -x tie, denormals keep their order, Inf > finite, NaN > Inf.
+ *     Among equal magnitudes the lowest index wins.  idx is ascending.
+ *   - N < 2^31, 1 <= k <= N, 1 <= W <= ARTOPK_MAX_WORKERS.
+ */
+#ifndef ARTOPK_H
+#define ARTOPK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct artopk_ctx artopk_ctx;
+
+enum {
+  ARTOPK_OK = 0,
+  ARTOPK_EINVAL = -1, /* bad argument; nothing enqueued                        */
+  ARTOPK_ENOMEM = -2, /* device allocation failed in artopk_create             */
+  ARTOPK_EHIP = -3,   /* a HIP runtime call failed; see artopk_last_error      */
+  ARTOPK_ESTATE = -4  /* a kernel reported an internal inconsistency           */
+};
+
+/* Leader rule (Sec. III-B).  FIXED takes the leader from the caller. */
+enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2 };
+
+#define ARTOPK_MAX_WORKERS 64
+
+/* Stages whose duration artopk_get_profile() reports (milliseconds). */
+enum {
+  ARTOPK_PROF_PASS_A = 0, /* fused EF add + variance partials + histogram      */
+  ARTOPK_PROF_SELECT = 1, /* everything between pass A and the final idx       */
+  ARTOPK_PROF_GATHER = 2, /* gather + ordered sum + residual zeroing           */
+  ARTOPK_PROF_UPDATE = 3, /* dense update fill                                 */
+  ARTOPK_PROF_TOTAL = 4,  /* whole call                                        */
+  ARTOPK_PROF_COUNT = 5
+};
+
+/*
+ * Create a context bound to `hip_stream` (a hipStream_t; NULL = the default
+ * stream) on the current device and allocate its scratch for problems up to
+ * max_w workers, max_n elements, max_k kept entries and max_segments segments.
+ * *out is set only on success.
+ */
+int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
+                  int32_t max_segments, void* hip_stream);
+
+/* Free the scratch.  The caller must have synchronised the stream. */
+int artopk_destroy(artopk_ctx* ctx);
+
+/* Text of the last error on this context (never NULL). */
+const char* artopk_last_error(const artopk_ctx* ctx);
+
+/*
+ * Synchronise the context's stream and report whether any kernel since the
+ * last call flagged an internal error (ARTOPK_ESTATE) -- e.g. a bounded wait
+ * that expired.  Returns ARTOPK_OK otherwise.
+ */
+int artopk_status(artopk_ctx* ctx);
+
+/*
+ * Per-worker variance used by the VAR-Topk leader rule (Sec. III-B; Alg. 1,
+ * worker-selection branch): population variance (divide by N) of each of the W
+ * vectors, accumulated in float64.
+ *   x          host array of W device pointers, each N float32 (read only)
+ *   var_out    device, W float64
+ *   argmax_out device int32, lowest w attaining the maximum; may be NULL
+ */
+int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n,
+                    double* var_out, int32_t* argmax_out);
+
+/*
+ * Exact Top-k by magnitude (Sec. II-C "largest k%", Sec. III-A, Alg. 1 Topk).
+ *   acc      device, N float32 (read only)
+ *   nseg     number of segments; 1 with seg_off = seg_k = NULL selects k
+ *            entries of the whole vector
+ *   seg_off  host, nseg+1 int64, ascending, seg_off[0] = 0, seg_off[nseg] = N
+ *   seg_k    host, nseg int64, 1 <= seg_k[s] <= size of segment s; their sum
+ *            must equal k
+ *   idx_out  device, k int32: global indices, ascending
+ */
+int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nseg,
+                       const int64_t* seg_off, const int64_t* seg_k, int64_t k,
+                       int32_t* idx_out);
+
+/*
+ * Gather every worker's values at the shared indices and add them in worker
+ * order 0..W-1 in float32 (Alg. 1: G[ix] on every worker, then AllReduce).
+ *   acc      host array of W device pointers, each N float32 (read only)
+ *   idx      device, k int32, ascending, each in [0, N)
+ *   vals_out device, W*k float32 row-major [w][m]; may be NULL
+ *   sum_out  device, k float32
+ */
+int artopk_gather_sum(artopk_ctx* ctx, const float* const* acc, int32_t w, int64_t n,
+                      const int32_t* idx, int64_t k, float* vals_out, float* sum_out);
+
+/*
+ * Residual rewrite and dense update (Alg. 1: residual = G - g~, and the update
+ * that consumes the reduced values; second EF equation of Sec. II-C).
+ *   residual host array of W device pointers; each holds acc_w on entry and on
+ *            exit differs only at the idx positions, which become +0.0
+ *   sum      device, k float32
+ *   update   device, N float32, fully overwritten: zeros, and sum[m] at idx[m]
+ */
+int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, int64_t n,
+                            const int32_t* idx, int64_t k, const float* sum, float* update);
+
+/*
+ * One whole step (Alg. 1 loop body for all W workers).
+ *   g            host array of W device pointers, N float32 each, read only
+ *   residual     host array of W device pointers, N float32 each, updated in
+ *                place (holds residual_{i-1} on entry, residual_i on exit)
+ *   nseg/seg_off/seg_k/k  as in artopk_select_topk (one leader per step even
+ *                when the selection is per segment)
+ *   mode         ARTOPK_STAR (leader = step mod W), ARTOPK_VAR, ARTOPK_FIXED
+ *   step         the paper's iteration counter i
+ *   fixed_leader used by ARTOPK_FIXED only
+ *   leader_out   device int32 (may be NULL)
+ *   var_out      device W float64, written in VAR mode only (may be NULL)
+ *   idx_out      device k int32
+ *   vals_out     device W*k float32 (may be NULL)
+ *   sum_out      device k float32
+ *   update_out   device N float32
+ */
+int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w,
+                int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k,
+                int64_t k, int32_t mode, uint64_t step, int32_t fixed_leader,
+                int32_t* leader_out, double* var_out, int32_t* idx_out, float* vals_out,
+                float* sum_out, float* update_out);
+
+/*
+ * Stage timing.  With profiling enabled every call records HIP events on the
+ * context's stream around its stages; artopk_get_profile synchronises on the
+ * last call's events and writes up to `count` stage durations in milliseconds
+ * (order: the ARTOPK_PROF_* enum; stages that did not run report 0).
+ */
+int artopk_set_profile(artopk_ctx* ctx, int32_t enable);
+int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t artopk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARTOPK_H */

@@ -1,0 +1,10 @@
+"""MI355X-native AR-Topk gradient compressor (one GPU, W simulated workers).
+
+The compute lives in libartopk.so (hand-written HIP for gfx950) behind the C
+ABI of include/artopk.h; this package only marshals arguments.  There is no CPU
+fallback: using the library without the built extension raises.
+"""
+
+from .binding import (  # noqa: F401
+    ARTOPK_FIXED, ARTOPK_STAR, ARTOPK_VAR, ArTopkError, Context, exported_symbols, lib_path, load_library,
+)

@@ -1,0 +1,163 @@
+"""ctypes binding of libartopk.so.  Same names as the C ABI; marshalling only.
+
+PyTorch is used for device memory (tensor.data_ptr()) and for the stream handle;
+no step of the compressor runs in PyTorch.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED = 0, 1, 2
+PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
+
+_SYMBOLS = (
+    "artopk_create", "artopk_destroy", "artopk_last_error", "artopk_status", "artopk_variance",
+    "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
+    "artopk_set_profile", "artopk_get_profile", "artopk_version",
+)
+
+
+class ArTopkError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"artopk error {code}: {text}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libartopk.so")
+
+
+def exported_symbols():
+    return _SYMBOLS
+
+
+_lib = None
+
+
+def load_library():
+    """Load libartopk.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2312_02493_amd.build`")
+    lib = C.CDLL(path)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+    lib.artopk_create.argtypes = [C.POINTER(vp), i32, i64, i64, i32, vp]
+    lib.artopk_destroy.argtypes = [vp]
+    lib.artopk_last_error.argtypes = [vp]
+    lib.artopk_last_error.restype = C.c_char_p
+    lib.artopk_status.argtypes = [vp]
+    lib.artopk_variance.argtypes = [vp, vp, i32, i64, vp, vp]
+    lib.artopk_select_topk.argtypes = [vp, vp, i64, i32, vp, vp, i64, vp]
+    lib.artopk_gather_sum.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
+    lib.artopk_scatter_residual.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
+    lib.artopk_step.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, i64, i32, u64, i32, vp, vp, vp, vp, vp, vp]
+    lib.artopk_set_profile.argtypes = [vp, i32]
+    lib.artopk_get_profile.argtypes = [vp, C.POINTER(C.c_float), i32]
+    lib.artopk_version.restype = i32
+    for name in _SYMBOLS:
+        if name not in ("artopk_last_error", "artopk_version"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _ptr_table(tensors: Sequence):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = int(t.data_ptr())
+    return arr
+
+
+def _i64_array(values):
+    if values is None:
+        return None
+    arr = (C.c_int64 * len(values))()
+    for i, v in enumerate(values):
+        arr[i] = int(v)
+    return arr
+
+
+class Context:
+    """Owns one artopk_ctx bound to the current torch stream of the current device."""
+
+    def __init__(self, max_w: int, max_n: int, max_k: int, max_segments: int = 1, stream: Optional[int] = None):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("the AR-Topk library needs a GPU; there is no CPU path")
+        self._lib = load_library()
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        self._h = C.c_void_p()
+        rc = self._lib.artopk_create(C.byref(self._h), max_w, max_n, max_k, max_segments, C.c_void_p(stream))
+        if rc != 0:
+            raise ArTopkError(rc, "artopk_create failed")
+
+    # -- plumbing ------------------------------------------------------------
+    def _check(self, rc: int):
+        if rc != 0:
+            raise ArTopkError(rc, self._lib.artopk_last_error(self._h).decode())
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.artopk_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def status(self):
+        self._check(self._lib.artopk_status(self._h))
+
+    def set_profile(self, enable: bool):
+        self._check(self._lib.artopk_set_profile(self._h, 1 if enable else 0))
+
+    def get_profile(self) -> dict:
+        buf = (C.c_float * len(PROF_NAMES))()
+        self._check(self._lib.artopk_get_profile(self._h, buf, len(PROF_NAMES)))
+        return {name: float(buf[i]) for i, name in enumerate(PROF_NAMES)}
+
+    # -- the five entry points ---------------------------------------------
+    def artopk_variance(self, x: Sequence, var_out, argmax_out=None):
+        n = x[0].numel()
+        self._check(self._lib.artopk_variance(self._h, _ptr_table(x), len(x), n, _ptr(var_out), _ptr(argmax_out)))
+
+    def artopk_select_topk(self, acc, k: int, idx_out, seg_off=None, seg_k=None):
+        nseg = 1 if seg_off is None else len(seg_k)
+        self._check(self._lib.artopk_select_topk(self._h, _ptr(acc), acc.numel(), nseg, _i64_array(seg_off),
+                                                 _i64_array(seg_k), k, _ptr(idx_out)))
+
+    def artopk_gather_sum(self, acc: Sequence, idx, k: int, vals_out, sum_out):
+        n = acc[0].numel()
+        self._check(self._lib.artopk_gather_sum(self._h, _ptr_table(acc), len(acc), n, _ptr(idx), k,
+                                                _ptr(vals_out), _ptr(sum_out)))
+
+    def artopk_scatter_residual(self, residual: Sequence, idx, k: int, summed, update):
+        n = residual[0].numel()
+        self._check(self._lib.artopk_scatter_residual(self._h, _ptr_table(residual), len(residual), n, _ptr(idx), k,
+                                                      _ptr(summed), _ptr(update)))
+
+    def artopk_step(self, g: Sequence, residual: Sequence, k: int, mode: int, step: int, idx_out, sum_out,
+                    update_out, vals_out=None, leader_out=None, var_out=None, fixed_leader: int = 0,
+                    seg_off=None, seg_k=None):
+        n = g[0].numel()
+        nseg = 1 if seg_off is None else len(seg_k)
+        self._check(self._lib.artopk_step(self._h, _ptr_table(g), _ptr_table(residual), len(g), n, nseg,
+                                          _i64_array(seg_off), _i64_array(seg_k), k, mode, step, fixed_leader,
+                                          _ptr(leader_out), _ptr(var_out), _ptr(idx_out), _ptr(vals_out),
+                                          _ptr(sum_out), _ptr(update_out)))

@@ -1,0 +1,550 @@
+// Host side of the AR-Topk compressor library: argument checks, scratch
+// management and kernel sequencing behind the C ABI declared in artopk.h.
+// No call synchronises the stream except artopk_status / artopk_get_profile /
+// artopk_destroy; all decisions that depend on the data (leader, thresholds,
+// tie quotas, list sizes) stay in device memory.
+
+#include "artopk.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "artopk_kernels.h"
+
+using namespace artopk;
+
+namespace {
+
+constexpr int kNumCompactLaunches = 4;  // array level 1, 2, 3 and the list pass
+
+struct Scratch {
+  // zeroed before every select
+  uint32_t* zero_base = nullptr;  // start of the zeroed head
+  size_t head_words = 0;          // state + counters + hist1 + hist2 + hist0[0]
+  size_t hist0_all_words = 0;     // hist0[0..max_w) (the first 4096 are part of the head)
+  SelState* state = nullptr;
+  uint32_t* counters = nullptr;   // kNumCompactLaunches tile counters
+  uint32_t* hist1 = nullptr;
+  uint32_t* hist2 = nullptr;
+  uint32_t* hist0 = nullptr;      // [max_w][4096]
+  uint64_t* flags = nullptr;      // [max_tiles][kNumCompactLaunches]
+  int64_t max_tiles = 0;
+  // not zeroed
+  double* partials = nullptr;     // [max_w][max_nblk][2]
+  double* var_scratch = nullptr;  // [max_w]
+  int32_t* leader_dev = nullptr;
+  uint32_t* err_dev = nullptr;
+  int32_t* list_idx = nullptr;
+  uint32_t* list_key = nullptr;
+  uint32_t cap = 0;               // usable list entries
+};
+
+}  // namespace
+
+struct artopk_ctx {
+  int device = 0;
+  int num_cu = 256;
+  hipStream_t stream = nullptr;
+  int32_t max_w = 0;
+  int64_t max_n = 0, max_k = 0;
+  int32_t max_seg = 0;
+  int max_nblk = 0;
+  void* slab = nullptr;
+  Scratch s;
+  bool profile = false;
+  hipEvent_t ev[ARTOPK_PROF_COUNT + 1] = {};
+  bool ev_valid[ARTOPK_PROF_COUNT + 1] = {};
+  char err[512] = {0};
+};
+
+namespace {
+
+char g_noctx_err[] = "";
+
+int fail(artopk_ctx* c, int code, const char* fmt, ...) {
+  if (c) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                   \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail((ctx), ARTOPK_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                  __FILE__, __LINE__);                                                       \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_ptr_table(artopk_ctx* c, const float* const* tab, int32_t w, const char* name) {
+  if (!tab) return fail(c, ARTOPK_EINVAL, "%s is NULL", name);
+  for (int i = 0; i < w; ++i) {
+    if (!tab[i]) return fail(c, ARTOPK_EINVAL, "%s[%d] is NULL", name, i);
+    if (!aligned16(tab[i])) return fail(c, ARTOPK_EINVAL, "%s[%d] is not 16-byte aligned", name, i);
+  }
+  return ARTOPK_OK;
+}
+
+int check_common(artopk_ctx* c, int32_t w, int64_t n, int64_t k) {
+  if (!c) return ARTOPK_EINVAL;
+  if (w < 1 || w > c->max_w) return fail(c, ARTOPK_EINVAL, "W=%d outside [1, %d]", w, c->max_w);
+  if (n < 1 || n > c->max_n) return fail(c, ARTOPK_EINVAL, "N=%lld outside [1, %lld]", (long long)n, (long long)c->max_n);
+  if (n >= (1ll << 31)) return fail(c, ARTOPK_EINVAL, "N must be below 2^31");
+  if (k < 1 || k > n) return fail(c, ARTOPK_EINVAL, "k=%lld outside [1, N]", (long long)k);
+  if (k > c->max_k) return fail(c, ARTOPK_EINVAL, "k=%lld above max_k=%lld", (long long)k, (long long)c->max_k);
+  return ARTOPK_OK;
+}
+
+int check_segments(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k,
+                   int64_t k) {
+  if (nseg < 1) return fail(c, ARTOPK_EINVAL, "nseg must be >= 1");
+  if (nseg > c->max_seg) return fail(c, ARTOPK_EINVAL, "nseg=%d above max_segments=%d", nseg, c->max_seg);
+  if ((seg_off == nullptr) != (seg_k == nullptr))
+    return fail(c, ARTOPK_EINVAL, "seg_off and seg_k must both be given or both be NULL");
+  if (!seg_off) {
+    if (nseg != 1) return fail(c, ARTOPK_EINVAL, "nseg > 1 needs seg_off and seg_k");
+    return ARTOPK_OK;
+  }
+  if (seg_off[0] != 0 || seg_off[nseg] != n) return fail(c, ARTOPK_EINVAL, "segments must cover [0, N)");
+  int64_t ksum = 0;
+  for (int s = 0; s < nseg; ++s) {
+    const int64_t sz = seg_off[s + 1] - seg_off[s];
+    if (sz < 1) return fail(c, ARTOPK_EINVAL, "segment %d is empty or descending", s);
+    if (seg_k[s] < 1 || seg_k[s] > sz) return fail(c, ARTOPK_EINVAL, "seg_k[%d] outside [1, size]", s);
+    ksum += seg_k[s];
+  }
+  if (ksum != k) return fail(c, ARTOPK_EINVAL, "sum of seg_k (%lld) differs from k (%lld)", (long long)ksum, (long long)k);
+  return ARTOPK_OK;
+}
+
+PtrTable make_table(const float* const* tab, int32_t w) {
+  PtrTable t;
+  for (int i = 0; i < kMaxW; ++i) t.p[i] = (i < w) ? const_cast<float*>(tab[i]) : nullptr;
+  return t;
+}
+
+int pass_a_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
+  const int64_t n4 = n >> 2;
+  const int64_t tile = 256 * kPassAUnroll;
+  int64_t ntile = (n4 + tile - 1) / tile;
+  if (ntile < 1) ntile = 1;
+  int64_t want = ((int64_t)c->num_cu * 8 + w - 1) / w;
+  if (want < 1) want = 1;
+  int64_t nblk = ntile < want ? ntile : want;
+  if (nblk > c->max_nblk) nblk = c->max_nblk;
+  return (int)nblk;
+}
+
+void prof_mark(artopk_ctx* c, int slot) {
+  if (!c->profile) return;
+  if (hipEventRecord(c->ev[slot], c->stream) == hipSuccess) c->ev_valid[slot] = true;
+}
+
+void prof_reset(artopk_ctx* c) {
+  for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i) c->ev_valid[i] = false;
+}
+
+// Clears the select scratch for a range that spans `ntiles` compaction tiles.
+// With all_hist0 the per-worker top-digit histograms are cleared as well.
+int enqueue_clear(artopk_ctx* c, int64_t ntiles, bool all_hist0) {
+  Scratch& s = c->s;
+  size_t words1 = all_hist0 ? (s.head_words - kHistBins + s.hist0_all_words) : s.head_words;
+  size_t words2 = (size_t)ntiles * kNumCompactLaunches * 2;
+  size_t total = words1 + words2;
+  int blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
+  if (blocks < 1) blocks = 1;
+  if (blocks > c->num_cu * 4) blocks = c->num_cu * 4;
+  hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, c->stream, s.zero_base, words1,
+                     reinterpret_cast<uint32_t*>(s.flags), words2);
+  HIP_TRY(c, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+int64_t tiles_of_range(int64_t e_lo, int64_t e_hi) {
+  return (e_hi + kCompactTile - 1) / kCompactTile - e_lo / kCompactTile;
+}
+
+// Selection of the k largest magnitudes of x[e_lo, e_hi) of the vector
+// tab.p[*leader_dev]; the scratch must have been cleared.  If hist_ready the
+// top-digit histogram is already in hist0 (+ leader * hist_stride).
+int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, int64_t e_hi, int64_t k,
+                   int32_t* idx_out, bool hist_ready, int hist_stride) {
+  Scratch& s = c->s;
+  hipStream_t st = c->stream;
+  const int64_t nrange = e_hi - e_lo;
+  const int64_t ntiles = tiles_of_range(e_lo, e_hi);
+  if (ntiles > s.max_tiles) return fail(c, ARTOPK_EINVAL, "range needs more scan tiles than the context holds");
+
+  if (!hist_ready) {
+    int64_t groups = ((e_hi + 3) >> 2) - (e_lo >> 2);
+    int blocks = (int)((groups + 256 * 8 - 1) / (256 * 8));
+    if (blocks < 1) blocks = 1;
+    if (blocks > c->num_cu * 8) blocks = c->num_cu * 8;
+    hipLaunchKernelGGL(k_hist0, dim3(blocks), dim3(256), 0, st, tab, s.leader_dev, n, e_lo, e_hi, s.hist0);
+    hist_stride = 0;
+  }
+  const uint32_t cap = s.cap;
+  int cblocks = (int)(ntiles < (int64_t)c->num_cu * 4 ? ntiles : (int64_t)c->num_cu * 4);
+  if (cblocks < 1) cblocks = 1;
+
+  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist0, s.leader_dev, hist_stride, 0,
+                     (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
+  for (int level = 1; level <= 3; ++level) {
+    uint32_t* hist_next = level == 1 ? s.hist1 : s.hist2;
+    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev,
+                       s.state, level, n, e_lo, e_hi, cap, hist_next, s.flags + (level - 1),
+                       kNumCompactLaunches, s.counters + (level - 1), s.list_idx, s.list_key,
+                       (int32_t*)nullptr, 0u, s.err_dev);
+    hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, hist_next, s.leader_dev, 0, level,
+                       (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
+  }
+  // the list cannot hold more than n_gt + cand <= cap entries; k + typical candidates in practice
+  int64_t list_bound = (int64_t)cap < nrange ? (int64_t)cap : nrange;
+  int lblocks = (int)((list_bound + 256 * 16 - 1) / (256 * 16));
+  if (lblocks < 1) lblocks = 1;
+  if (lblocks > c->num_cu * 4) lblocks = c->num_cu * 4;
+  hipLaunchKernelGGL(k_list_hist, dim3(lblocks), dim3(256), 0, st, s.state, s.list_key, s.hist2, s.err_dev);
+  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, s.leader_dev, 0, 4,
+                     (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
+  int64_t ltiles = (list_bound + kCompactTile - 1) / kCompactTile;
+  int fblocks = (int)(ltiles < (int64_t)c->num_cu * 4 ? ltiles : (int64_t)c->num_cu * 4);
+  if (fblocks < 1) fblocks = 1;
+  hipLaunchKernelGGL(k_compact<true>, dim3(fblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev, s.state,
+                     3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 3,
+                     kNumCompactLaunches, s.counters + 3, s.list_idx, s.list_key, idx_out, (uint32_t)k,
+                     s.err_dev);
+  HIP_TRY(c, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+// Select over all segments of the leader's vector (host loop over segments).
+int enqueue_select_segments(artopk_ctx* c, const PtrTable& tab, int64_t n, int32_t nseg,
+                            const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t* idx_out,
+                            bool flat_hist_ready, int hist_stride) {
+  if (!seg_off) {
+    return enqueue_select(c, tab, n, 0, n, k, idx_out, flat_hist_ready, hist_stride);
+  }
+  int64_t koff = 0;
+  for (int sgi = 0; sgi < nseg; ++sgi) {
+    const int64_t lo = seg_off[sgi], hi = seg_off[sgi + 1];
+    if (sgi > 0 || !flat_hist_ready) {
+      int rc = enqueue_clear(c, tiles_of_range(lo, hi), false);
+      if (rc) return rc;
+    }
+    int rc = enqueue_select(c, tab, n, lo, hi, seg_k[sgi], idx_out + koff, nseg == 1 && flat_hist_ready,
+                            hist_stride);
+    if (rc) return rc;
+    koff += seg_k[sgi];
+  }
+  return ARTOPK_OK;
+}
+
+int enqueue_gather(artopk_ctx* c, const PtrTable& tab, int32_t w, const int32_t* idx, int64_t k, float* vals,
+                   float* sum, bool zero) {
+  const int blocks = (int)((k + 255) / 256);
+  if (zero)
+    hipLaunchKernelGGL(k_gather<true>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, idx, k, vals, sum);
+  else
+    hipLaunchKernelGGL(k_gather<false>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, idx, k, vals, sum);
+  HIP_TRY(c, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* idx, const float* sum,
+                        int64_t k) {
+  const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
+  int blocks = (int)(nchunk < (int64_t)c->num_cu * 4 ? nchunk : (int64_t)c->num_cu * 4);
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_update_fill, dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
+  HIP_TRY(c, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t artopk_version(void) { return 100; }
+
+const char* artopk_last_error(const artopk_ctx* ctx) { return ctx ? ctx->err : g_noctx_err; }
+
+int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments,
+                  void* hip_stream) {
+  if (!out) return ARTOPK_EINVAL;
+  if (max_w < 1 || max_w > ARTOPK_MAX_WORKERS || max_n < 1 || max_n >= (1ll << 31) || max_k < 1 ||
+      max_k > max_n || max_segments < 1)
+    return ARTOPK_EINVAL;
+  artopk_ctx* c = new (std::nothrow) artopk_ctx();
+  if (!c) return ARTOPK_ENOMEM;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->max_w = max_w;
+  c->max_n = max_n;
+  c->max_k = max_k;
+  c->max_seg = max_segments;
+  hipError_t e = hipGetDevice(&c->device);
+  int cus = 0;
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device);
+  if (e != hipSuccess) {
+    delete c;
+    return ARTOPK_EHIP;
+  }
+  c->num_cu = cus > 0 ? cus : 256;
+  c->max_nblk = c->num_cu * 8;
+
+  Scratch& s = c->s;
+  // list capacity: every key above the range (< k of them) plus a generous share of candidates
+  int64_t cand_share = max_n / 8;
+  if (cand_share < 65536) cand_share = 65536;
+  int64_t cap = max_k + cand_share;
+  if (cap > max_n) cap = max_n;
+  s.cap = (uint32_t)cap;
+  const size_t cap_pad = align_up((size_t)cap, kCompactTile) + kCompactTile;
+  // a range [lo, hi) touches at most ceil(len / tile) + 1 tiles
+  s.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 1;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  // zeroed head: state | counters | hist1 | hist2 | hist0[0..max_w)
+  const size_t o_state = take(sizeof(SelState));
+  const size_t o_cnt = take(16 * sizeof(uint32_t));
+  const size_t o_h1 = take(kHistBins * sizeof(uint32_t));
+  const size_t o_h2 = take(kHistBins * sizeof(uint32_t));
+  const size_t o_h0 = take((size_t)max_w * kHistBins * sizeof(uint32_t));
+  const size_t o_head_end = off;
+  const size_t o_flags = take((size_t)s.max_tiles * kNumCompactLaunches * sizeof(uint64_t));
+  const size_t o_part = take((size_t)max_w * c->max_nblk * 2 * sizeof(double));
+  const size_t o_var = take((size_t)max_w * sizeof(double));
+  const size_t o_leader = take(sizeof(int32_t));
+  const size_t o_err = take(sizeof(uint32_t));
+  const size_t o_lidx = take(cap_pad * sizeof(int32_t));
+  const size_t o_lkey = take(cap_pad * sizeof(uint32_t));
+  const size_t total = off;
+
+  e = hipMalloc(&c->slab, total);
+  if (e != hipSuccess) {
+    delete c;
+    return ARTOPK_ENOMEM;
+  }
+  char* base = static_cast<char*>(c->slab);
+  s.zero_base = reinterpret_cast<uint32_t*>(base + o_state);
+  s.state = reinterpret_cast<SelState*>(base + o_state);
+  s.counters = reinterpret_cast<uint32_t*>(base + o_cnt);
+  s.hist1 = reinterpret_cast<uint32_t*>(base + o_h1);
+  s.hist2 = reinterpret_cast<uint32_t*>(base + o_h2);
+  s.hist0 = reinterpret_cast<uint32_t*>(base + o_h0);
+  s.head_words = (o_h0 - o_state) / sizeof(uint32_t) + kHistBins;
+  s.hist0_all_words = (o_head_end - o_h0) / sizeof(uint32_t);
+  s.flags = reinterpret_cast<uint64_t*>(base + o_flags);
+  s.partials = reinterpret_cast<double*>(base + o_part);
+  s.var_scratch = reinterpret_cast<double*>(base + o_var);
+  s.leader_dev = reinterpret_cast<int32_t*>(base + o_leader);
+  s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
+  s.list_idx = reinterpret_cast<int32_t*>(base + o_lidx);
+  s.list_key = reinterpret_cast<uint32_t*>(base + o_lkey);
+
+  // leader and error words start at zero (stream-ordered before any later call)
+  hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
+                     reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1);
+  if (hipGetLastError() != hipSuccess) {
+    (void)hipFree(c->slab);
+    delete c;
+    return ARTOPK_EHIP;
+  }
+  *out = c;
+  return ARTOPK_OK;
+}
+
+int artopk_destroy(artopk_ctx* ctx) {
+  if (!ctx) return ARTOPK_EINVAL;
+  for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i)
+    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  if (ctx->slab) (void)hipFree(ctx->slab);
+  delete ctx;
+  return ARTOPK_OK;
+}
+
+int artopk_status(artopk_ctx* ctx) {
+  if (!ctx) return ARTOPK_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  uint32_t err = 0;
+  HIP_TRY(ctx, hipMemcpy(&err, ctx->s.err_dev, sizeof(err), hipMemcpyDeviceToHost));
+  if (err) {
+    uint32_t zero = 0;
+    HIP_TRY(ctx, hipMemcpy(ctx->s.err_dev, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    return fail(ctx, ARTOPK_ESTATE, "device error word 0x%x (1 = histogram/count mismatch, 2 = scan wait expired, 4 = kernel sequence)", err);
+  }
+  return ARTOPK_OK;
+}
+
+int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
+  if (!ctx) return ARTOPK_EINVAL;
+  if (enable) {
+    for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i)
+      if (!ctx->ev[i]) HIP_TRY(ctx, hipEventCreate(&ctx->ev[i]));
+  }
+  ctx->profile = enable != 0;
+  prof_reset(ctx);
+  return ARTOPK_OK;
+}
+
+// Event slots: 0 start, 1 after pass A, 2 after select, 3 after gather, 4 after update.
+int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count) {
+  if (!ctx || !ms_out || count < 0) return ARTOPK_EINVAL;
+  if (!ctx->profile) return fail(ctx, ARTOPK_EINVAL, "profiling is not enabled");
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  float ms[ARTOPK_PROF_COUNT] = {0, 0, 0, 0, 0};
+  for (int i = 0; i < 4; ++i)
+    if (ctx->ev_valid[i] && ctx->ev_valid[i + 1]) HIP_TRY(ctx, hipEventElapsedTime(&ms[i], ctx->ev[i], ctx->ev[i + 1]));
+  int last = -1;
+  for (int i = 4; i >= 1; --i)
+    if (ctx->ev_valid[i]) {
+      last = i;
+      break;
+    }
+  if (ctx->ev_valid[0] && last > 0) HIP_TRY(ctx, hipEventElapsedTime(&ms[ARTOPK_PROF_TOTAL], ctx->ev[0], ctx->ev[last]));
+  for (int i = 0; i < count && i < ARTOPK_PROF_COUNT; ++i) ms_out[i] = ms[i];
+  return ARTOPK_OK;
+}
+
+int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n, double* var_out,
+                    int32_t* argmax_out) {
+  int rc = check_common(ctx, w, n, 1);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, x, w, "x"))) return rc;
+  if (!var_out) return fail(ctx, ARTOPK_EINVAL, "var_out is NULL");
+  const PtrTable tab = make_table(x, w);
+  const int nblk = pass_a_blocks(ctx, w, n);
+  Scratch& s = ctx->s;
+  hipLaunchKernelGGL(k_stats, dim3(nblk, w), dim3(256), 0, ctx->stream, tab, n, s.partials);
+  hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, ctx->stream, s.partials, (int)w, nblk, n, s.var_scratch,
+                     var_out, s.leader_dev, argmax_out);
+  HIP_TRY(ctx, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nseg, const int64_t* seg_off,
+                       const int64_t* seg_k, int64_t k, int32_t* idx_out) {
+  int rc = check_common(ctx, 1, n, k);
+  if (rc) return rc;
+  if (!acc || !aligned16(acc)) return fail(ctx, ARTOPK_EINVAL, "acc is NULL or not 16-byte aligned");
+  if (!idx_out) return fail(ctx, ARTOPK_EINVAL, "idx_out is NULL");
+  if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
+  const float* one[1] = {acc};
+  const PtrTable tab = make_table(one, 1);
+  prof_reset(ctx);
+  prof_mark(ctx, 1);
+  hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, ctx->stream, 0, ctx->s.leader_dev, (int32_t*)nullptr);
+  if (!seg_off) {
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), false))) return rc;
+  }
+  rc = enqueue_select_segments(ctx, tab, n, nseg, seg_off, seg_k, k, idx_out, false, 0);
+  prof_mark(ctx, 2);
+  return rc;
+}
+
+int artopk_gather_sum(artopk_ctx* ctx, const float* const* acc, int32_t w, int64_t n, const int32_t* idx,
+                      int64_t k, float* vals_out, float* sum_out) {
+  int rc = check_common(ctx, w, n, k);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, acc, w, "acc"))) return rc;
+  if (!idx || !sum_out) return fail(ctx, ARTOPK_EINVAL, "idx or sum_out is NULL");
+  const PtrTable tab = make_table(acc, w);
+  return enqueue_gather(ctx, tab, w, idx, k, vals_out, sum_out, false);
+}
+
+int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, int64_t n, const int32_t* idx,
+                            int64_t k, const float* sum, float* update) {
+  int rc = check_common(ctx, w, n, k);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
+  if (!idx || !sum || !update) return fail(ctx, ARTOPK_EINVAL, "idx, sum or update is NULL");
+  if (!aligned16(update)) return fail(ctx, ARTOPK_EINVAL, "update is not 16-byte aligned");
+  const PtrTable tab = make_table(residual, w);
+  const int blocks = (int)((k + 255) / 256);
+  hipLaunchKernelGGL(k_zero_at, dim3(blocks), dim3(256), 0, ctx->stream, tab, (int)w, idx, k);
+  return enqueue_update_fill(ctx, update, n, idx, sum, k);
+}
+
+int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w, int64_t n,
+                int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t mode,
+                uint64_t step, int32_t fixed_leader, int32_t* leader_out, double* var_out, int32_t* idx_out,
+                float* vals_out, float* sum_out, float* update_out) {
+  int rc = check_common(ctx, w, n, k);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, g, w, "g"))) return rc;
+  if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
+  if (!idx_out || !sum_out || !update_out) return fail(ctx, ARTOPK_EINVAL, "idx_out, sum_out or update_out is NULL");
+  if (!aligned16(update_out)) return fail(ctx, ARTOPK_EINVAL, "update_out is not 16-byte aligned");
+  if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
+  int leader_host = -1;
+  if (mode == ARTOPK_STAR) {
+    leader_host = (int)(step % (uint64_t)w);
+  } else if (mode == ARTOPK_FIXED) {
+    if (fixed_leader < 0 || fixed_leader >= w) return fail(ctx, ARTOPK_EINVAL, "fixed_leader outside [0, W)");
+    leader_host = fixed_leader;
+  } else if (mode != ARTOPK_VAR) {
+    return fail(ctx, ARTOPK_EINVAL, "unknown mode %d", mode);
+  }
+
+  Scratch& s = ctx->s;
+  hipStream_t st = ctx->stream;
+  const PtrTable gt = make_table(g, w);
+  const PtrTable rt = make_table(residual, w);
+  const bool segmented = seg_off != nullptr && nseg > 1;
+  const int nblk = pass_a_blocks(ctx, w, n);
+  const dim3 grid(nblk, w), block(256);
+
+  prof_reset(ctx);
+  prof_mark(ctx, 0);
+  // the flat select reuses the histogram pass A builds; segments build their own
+  if (!segmented) {
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), mode == ARTOPK_VAR))) return rc;
+  }
+  int hist_stride = 0;
+  if (mode == ARTOPK_VAR) {
+    if (segmented) {
+      hipLaunchKernelGGL((k_pass_a<true, 0>), grid, block, 0, st, gt, rt, n, -1, s.hist0, s.partials);
+    } else {
+      hipLaunchKernelGGL((k_pass_a<true, 2>), grid, block, 0, st, gt, rt, n, -1, s.hist0, s.partials);
+      hist_stride = kHistBins;
+    }
+    prof_mark(ctx, 1);
+    hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, nblk, n, s.var_scratch, var_out,
+                       s.leader_dev, leader_out);
+  } else {
+    if (segmented)
+      hipLaunchKernelGGL((k_pass_a<false, 0>), grid, block, 0, st, gt, rt, n, leader_host, s.hist0, s.partials);
+    else
+      hipLaunchKernelGGL((k_pass_a<false, 1>), grid, block, 0, st, gt, rt, n, leader_host, s.hist0, s.partials);
+    prof_mark(ctx, 1);
+    hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
+  }
+  HIP_TRY(ctx, hipGetLastError());
+
+  rc = enqueue_select_segments(ctx, rt, n, segmented ? nseg : 1, segmented ? seg_off : nullptr,
+                               segmented ? seg_k : nullptr, k, idx_out, !segmented, hist_stride);
+  if (rc) return rc;
+  prof_mark(ctx, 2);
+  if ((rc = enqueue_gather(ctx, rt, w, idx_out, k, vals_out, sum_out, true))) return rc;
+  prof_mark(ctx, 3);
+  if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+  prof_mark(ctx, 4);
+  return ARTOPK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,878 @@
+// Device code of the AR-Topk compressor for gfx950 (wave64).
+//
+// Kernels (in the order one step runs them):
+//   k_fill_zero      clears the per-call scratch (histograms, scan flags, ...)
+//   k_pass_a         acc = g + residual in place, per-worker variance
+//                    partials, 12-bit top-digit histogram of |acc|
+//   k_hist0          the same histogram alone (stand-alone select, segments)
+//   k_stats          variance partials alone (stand-alone variance)
+//   k_leader         finishes the variances and takes the first argmax
+//   k_pick           narrows the candidate key range by one radix digit
+//   k_compact        ordered stream compaction of "keys above the range" and
+//                    "keys inside the range" with a decoupled look-back scan;
+//                    source is either the leader's vector or the survivor list
+//   k_list_hist      last-digit histogram over the survivor list
+//   k_gather         vals / ordered sum / residual zeroing at the k indices
+//   k_zero_at        residual zeroing alone
+//   k_update_fill    dense update = zeros + k scattered sums, written once
+//
+// Keys are the 31 magnitude bits of the float32 (sign cleared), so integer
+// order on keys is the order of |x|.  The radix digits are 12 + 12 + 7 bits.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace artopk {
+
+constexpr int kMaxW = 64;
+constexpr int kHistBins = 4096;          // 12-bit digits (the last digit uses 128 of them)
+constexpr uint32_t kKeyMask = 0x7fffffffu;
+constexpr uint32_t kQuotaInf = 0x7fffffffu;
+
+// digit l (0,1,2) of a key: shift and mask
+__host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 19 : (level == 1 ? 7 : 0); }
+__host__ __device__ constexpr uint32_t digit_mask(int level) { return level == 2 ? 0x7fu : 0xfffu; }
+
+struct PtrTable {
+  float* p[kMaxW];
+};
+
+// Device-resident selection state; one per select in flight.
+struct SelState {
+  uint32_t lo, hi;         // candidate keys: lo <= key <= hi
+  uint32_t n_gt;           // keys > hi inside the element range
+  uint32_t need;           // entries still to be taken from the candidates (>= 1)
+  uint32_t cand;           // number of candidate keys
+  uint32_t level;          // radix digits resolved so far (0..3)
+  uint32_t compact_level;  // level at which the survivor list was written (0 = not yet)
+  uint32_t list_count;     // entries in the survivor list
+  uint32_t pad[8];
+};
+
+// Bits of the sticky device-side error word.
+constexpr uint32_t kErrPick = 1u;      // a histogram did not cover the wanted count
+constexpr uint32_t kErrWait = 2u;      // a bounded look-back wait expired
+constexpr uint32_t kErrSequence = 4u;  // a kernel found the state it needs missing
+
+// ---------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t popc_lt(uint64_t mask) {
+  // number of set bits of `mask` in lanes below the calling lane
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;  // valid in lane 0
+}
+
+__device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    uint32_t lo = __shfl_xor((uint32_t)v, off, 64);
+    uint32_t hi = __shfl_xor((uint32_t)(v >> 32), off, 64);
+    v += ((uint64_t)hi << 32) | lo;
+  }
+  return v;  // the total, in every lane
+}
+
+// ---------------------------------------------------------------------------
+// k_fill_zero : clears two word ranges (either may be empty)
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2, size_t words2) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words1; i += stride) p1[i] = 0u;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words2; i += stride) p2[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// k_pass_a : acc = g + residual (in place over residual), variance partials,
+//            top-digit histogram.
+//   grid = (nblk, W), block = 256.
+//   HIST: 0 none, 1 only worker `hist_worker` (into hist0[0]), 2 every worker
+//         (into hist0[w]).
+//   Variance partials use the shift c_w = g_w[0]: per block the sums of
+//   (acc - c_w) and (acc - c_w)^2 in float64, written to partials[w][bx][0..1].
+// ---------------------------------------------------------------------------
+constexpr int kPassAUnroll = 4;
+
+template <bool STATS, int HIST>
+__global__ void __launch_bounds__(256)
+k_pass_a(PtrTable g, PtrTable res, int64_t n, int hist_worker, uint32_t* __restrict__ hist0,
+         double* __restrict__ partials) {
+  __shared__ uint32_t lh[HIST ? kHistBins : 1];
+  __shared__ double red[2][4];
+
+  const int w = blockIdx.y;
+  const int bx = blockIdx.x;
+  const int nblk = gridDim.x;
+  const int tid = threadIdx.x;
+  const float* __restrict__ gp = g.p[w];
+  float* __restrict__ rp = res.p[w];
+  const bool do_hist = (HIST == 2) || (HIST == 1 && w == hist_worker);
+
+  if (HIST) {
+    if (do_hist)
+      for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+    __syncthreads();
+  }
+
+  double c = 0.0, s = 0.0, ss = 0.0;
+  if (STATS) c = (double)gp[0];  // g is never written, so every block sees the same shift
+
+  const int64_t n4 = n >> 2;
+  const float4* __restrict__ g4 = reinterpret_cast<const float4*>(gp);
+  float4* __restrict__ r4 = reinterpret_cast<float4*>(rp);
+  const int64_t tile = 256 * kPassAUnroll;
+  const int64_t ntile = (n4 + tile - 1) / tile;
+
+  for (int64_t t = bx; t < ntile; t += nblk) {
+    const int64_t q0 = t * tile + tid;
+    float4 a[kPassAUnroll], b[kPassAUnroll];
+#pragma unroll
+    for (int u = 0; u < kPassAUnroll; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < n4) {
+        a[u] = g4[q];
+        b[u] = r4[q];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kPassAUnroll; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < n4) {
+        float4 v;
+        v.x = a[u].x + b[u].x;
+        v.y = a[u].y + b[u].y;
+        v.z = a[u].z + b[u].z;
+        v.w = a[u].w + b[u].w;
+        r4[q] = v;
+        if (STATS) {
+          double d0 = (double)v.x - c, d1 = (double)v.y - c, d2 = (double)v.z - c, d3 = (double)v.w - c;
+          s += (d0 + d1) + (d2 + d3);
+          ss = fma(d0, d0, ss);
+          ss = fma(d1, d1, ss);
+          ss = fma(d2, d2, ss);
+          ss = fma(d3, d3, ss);
+        }
+        if (HIST) {
+          if (do_hist) {
+            atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
+            atomicAdd(&lh[(__float_as_uint(v.y) & kKeyMask) >> 19], 1u);
+            atomicAdd(&lh[(__float_as_uint(v.z) & kKeyMask) >> 19], 1u);
+            atomicAdd(&lh[(__float_as_uint(v.w) & kKeyMask) >> 19], 1u);
+          }
+        }
+      }
+    }
+  }
+  // scalar tail (n not a multiple of 4): block 0, first threads
+  if (bx == 0) {
+    const int64_t j = n4 * 4 + tid;
+    if (j < n) {
+      const float v = gp[j] + rp[j];
+      rp[j] = v;
+      if (STATS) {
+        const double d = (double)v - c;
+        s += d;
+        ss = fma(d, d, ss);
+      }
+      if (HIST) {
+        if (do_hist) atomicAdd(&lh[(__float_as_uint(v) & kKeyMask) >> 19], 1u);
+      }
+    }
+  }
+
+  if (STATS) {
+    s = wave_sum(s);
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) {
+      red[0][tid >> 6] = s;
+      red[1][tid >> 6] = ss;
+    }
+  }
+  __syncthreads();
+  if (STATS && tid == 0) {
+    const double S = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    const double SS = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    partials[((size_t)w * nblk + bx) * 2 + 0] = S;
+    partials[((size_t)w * nblk + bx) * 2 + 1] = SS;
+  }
+  if (HIST) {
+    if (do_hist) {
+      uint32_t* __restrict__ hg = hist0 + (HIST == 2 ? (size_t)w * kHistBins : 0);
+      for (int b = tid; b < kHistBins; b += 256) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&hg[b], v);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_stats : variance partials of read-only vectors.  grid = (nblk, W).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
+  __shared__ double red[2][4];
+  const int w = blockIdx.y, bx = blockIdx.x, nblk = gridDim.x, tid = threadIdx.x;
+  const float* __restrict__ xp = x.p[w];
+  const double c = (double)xp[0];
+  double s = 0.0, ss = 0.0;
+  const int64_t n4 = n >> 2;
+  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
+  const int64_t tile = 256 * kPassAUnroll;
+  const int64_t ntile = (n4 + tile - 1) / tile;
+  for (int64_t t = bx; t < ntile; t += nblk) {
+    const int64_t q0 = t * tile + tid;
+    float4 a[kPassAUnroll];
+#pragma unroll
+    for (int u = 0; u < kPassAUnroll; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < n4) a[u] = x4[q];
+    }
+#pragma unroll
+    for (int u = 0; u < kPassAUnroll; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < n4) {
+        double d0 = (double)a[u].x - c, d1 = (double)a[u].y - c, d2 = (double)a[u].z - c, d3 = (double)a[u].w - c;
+        s += (d0 + d1) + (d2 + d3);
+        ss = fma(d0, d0, ss);
+        ss = fma(d1, d1, ss);
+        ss = fma(d2, d2, ss);
+        ss = fma(d3, d3, ss);
+      }
+    }
+  }
+  if (bx == 0) {
+    const int64_t j = n4 * 4 + tid;
+    if (j < n) {
+      const double d = (double)xp[j] - c;
+      s += d;
+      ss = fma(d, d, ss);
+    }
+  }
+  s = wave_sum(s);
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) {
+    red[0][tid >> 6] = s;
+    red[1][tid >> 6] = ss;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    partials[((size_t)w * nblk + bx) * 2 + 0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    partials[((size_t)w * nblk + bx) * 2 + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_leader : one block of 1024 threads.  Sums the per-block partials of every
+// worker in a fixed order, var_w = (SS - S*S/n)/n, leader = first argmax.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_leader(const double* __restrict__ partials, int w_count, int nblk, int64_t n,
+         double* __restrict__ var_scratch, double* __restrict__ var_out,
+         int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int w = wave; w < w_count; w += 16) {
+    double s = 0.0, ss = 0.0;
+    for (int b = lane; b < nblk; b += 64) {
+      s += partials[((size_t)w * nblk + b) * 2 + 0];
+      ss += partials[((size_t)w * nblk + b) * 2 + 1];
+    }
+    s = wave_sum(s);
+    ss = wave_sum(ss);
+    if (lane == 0) {
+      const double dn = (double)n;
+      double v = (ss - s * s / dn) / dn;
+      if (!(v > 0.0)) v = (v != v) ? v : 0.0;
+      var_scratch[w] = v;
+      if (var_out) var_out[w] = v;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int best = 0;
+    for (int w = 1; w < w_count; ++w)
+      if (var_scratch[w] > var_scratch[best]) best = w;
+    *leader_dev = best;
+    if (leader_out) *leader_out = best;
+  }
+}
+
+__global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    *leader_dev = leader;
+    if (leader_out) *leader_out = leader;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_hist0 : top-digit histogram of |x[e_lo .. e_hi)| for the leader's vector.
+// Reads whole aligned float4 groups where they lie inside both the range and
+// the array, single elements at the edges.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_hist0(PtrTable tab, const int32_t* __restrict__ leader_dev, int64_t n, int64_t e_lo, int64_t e_hi,
+        uint32_t* __restrict__ hist0) {
+  __shared__ uint32_t lh[kHistBins];
+  const int tid = threadIdx.x;
+  const float* __restrict__ xp = tab.p[*leader_dev];
+  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  __syncthreads();
+  const int64_t q_lo = e_lo >> 2;
+  const int64_t q_hi = (e_hi + 3) >> 2;  // exclusive
+  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
+  for (int64_t q = q_lo + (int64_t)blockIdx.x * 256 + tid; q < q_hi; q += (int64_t)gridDim.x * 256) {
+    const int64_t j = q << 2;
+    if (j >= e_lo && j + 4 <= e_hi) {
+      const float4 v = x4[q];
+      atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(v.y) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(v.z) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(v.w) & kKeyMask) >> 19], 1u);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int64_t je = j + e;
+        if (je >= e_lo && je < e_hi) atomicAdd(&lh[(__float_as_uint(xp[je]) & kKeyMask) >> 19], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  for (int b = tid; b < kHistBins; b += 256) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&hist0[b], v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_pick : one block of 1024 threads narrows the candidate range by one digit.
+//
+//   stage 0 : initialise the state for a range of `n_range` elements with `k`
+//             wanted, then resolve digit 0 from hist (level 0 -> 1).
+//   stage 1,2 (after the array compaction launched at that level): if the list
+//             has not been written yet and state.level == stage, record whether
+//             that compaction wrote the list, then resolve digit `stage`.
+//   stage 3 : after the level-3 array compaction: record the list.
+//   stage 4 : after the list histogram: resolve digit 2 if the list was written
+//             at level 1.
+// The decision "did the compaction at this level write the list" is the same
+// expression the compaction kernel evaluates: n_gt + cand <= cap.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bool fits_list(const SelState& st, uint32_t cap) {
+  return (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
+}
+
+__global__ void __launch_bounds__(1024)
+k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, const int32_t* __restrict__ leader_dev,
+       int hist_stride, int stage, uint32_t n_range, uint32_t k, uint32_t cap, uint32_t* __restrict__ err) {
+  if (hist_stride) hist += (size_t)(*leader_dev) * (size_t)hist_stride;
+  __shared__ uint32_t part[1024];
+  __shared__ SelState st;
+  __shared__ int run_pick;
+  __shared__ uint32_t found;
+  const int t = threadIdx.x;
+  if (t == 0) {
+    st = *stp;
+    found = 0u;
+    int digit = -1;
+    if (stage == 0) {
+      st.lo = 0u;
+      st.hi = kKeyMask;
+      st.n_gt = 0u;
+      st.need = k;
+      st.cand = n_range;
+      st.level = 0u;
+      st.compact_level = 0u;
+      st.list_count = 0u;
+      digit = 0;
+    } else if (stage == 1 || stage == 2) {
+      if (st.compact_level == 0u && st.level == (uint32_t)stage) {
+        if (fits_list(st, cap)) {
+          st.compact_level = (uint32_t)stage;
+          st.list_count = st.n_gt + st.cand;
+        }
+        digit = stage;
+      }
+    } else if (stage == 3) {
+      if (st.compact_level == 0u && st.level == 3u) {
+        st.compact_level = 3u;
+        st.list_count = st.n_gt + (st.cand < st.need ? st.cand : st.need);
+      }
+    } else {  // stage 4
+      if (st.compact_level == 1u && st.level == 2u) digit = 2;
+    }
+    run_pick = digit;
+  }
+  __syncthreads();
+  const int digit = run_pick;
+  if (digit >= 0) {
+    const int nbins = (int)digit_mask(digit) + 1;
+    uint32_t h[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int b = 4 * t + j;
+      h[j] = (b < nbins) ? hist[b] : 0u;
+    }
+    part[t] = h[0] + h[1] + h[2] + h[3];
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // inclusive suffix sums
+      const uint32_t v = (t + off < 1024) ? part[t + off] : 0u;
+      __syncthreads();
+      part[t] += v;
+      __syncthreads();
+    }
+    uint32_t above = (t + 1 < 1024) ? part[t + 1] : 0u;
+    const uint32_t need = st.need;
+    int hit = -1;
+    uint32_t hit_above = 0u, hit_cnt = 0u;
+#pragma unroll
+    for (int j = 3; j >= 0; --j) {
+      if (hit < 0 && above < need && need <= above + h[j]) {
+        hit = 4 * t + j;
+        hit_above = above;
+        hit_cnt = h[j];
+      }
+      above += h[j];
+    }
+    __syncthreads();
+    if (hit >= 0) {  // exactly one thread when the histogram holds >= need keys
+      const int sh = digit_shift(digit);
+      st.lo = st.lo | ((uint32_t)hit << sh);
+      st.hi = st.lo | ((1u << sh) - 1u);
+      st.n_gt += hit_above;
+      st.need -= hit_above;
+      st.cand = hit_cnt;
+      st.level = (uint32_t)digit + 1u;
+      found = 1u;
+    }
+    __syncthreads();
+    if (t == 0 && !found) atomicOr(err, kErrPick);  // histogram does not cover `need`
+  }
+  __syncthreads();
+  if (t == 0) *stp = st;
+}
+
+// ---------------------------------------------------------------------------
+// Decoupled look-back over tiles.  Each tile publishes a 64-bit word
+//   [63:62] status (0 none, 1 tile aggregate, 2 inclusive prefix)
+//   [61:31] count A (keys above the range)      [30:0] count B (keys inside)
+// Counts never exceed 2^31-1 in total, so packed words add field-wise.
+// Called by the 64 lanes of one wave; returns the exclusive prefix of `tile`.
+// The wait on a predecessor is bounded; expiry sets *err and returns what was
+// gathered so far (every wave still leaves the kernel).
+// ---------------------------------------------------------------------------
+constexpr uint64_t kFlagAgg = 1ull << 62;
+constexpr uint64_t kFlagIncl = 2ull << 62;
+constexpr uint64_t kFlagValMask = (1ull << 62) - 1ull;
+constexpr int kSpinLimit = 1 << 22;
+
+__device__ __forceinline__ uint64_t flag_load(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void flag_store(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ uint64_t lookback_exclusive(uint64_t* __restrict__ flags, int flag_stride, int64_t tile,
+                                       uint64_t agg, uint32_t* __restrict__ err) {
+  const uint32_t lane = lane_id();
+  if (tile == 0) {
+    if (lane == 0) flag_store(&flags[0], kFlagIncl | agg);
+    return 0ull;
+  }
+  if (lane == 0) flag_store(&flags[tile * flag_stride], kFlagAgg | agg);
+  uint64_t excl = 0ull;     // wave-uniform running total
+  int64_t base = tile - 1;  // lane L inspects tile base - L
+  while (true) {
+    const int64_t my = base - (int64_t)lane;
+    uint64_t word = kFlagIncl;  // tiles before the first act as an inclusive prefix of zero
+    if (my >= 0) {
+      int spins = 0;
+      word = flag_load(&flags[my * flag_stride]);
+      while ((word >> 62) == 0ull) {
+        if (++spins > kSpinLimit) {
+          atomicOr(err, kErrWait);
+          word = kFlagIncl;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+        word = flag_load(&flags[my * flag_stride]);
+      }
+    }
+    const uint64_t incl_mask = __ballot((word >> 62) == 2ull);
+    uint64_t contrib = word & kFlagValMask;
+    if (incl_mask != 0ull) {
+      const int first = __ffsll((long long)incl_mask) - 1;  // nearest tile holding an inclusive prefix
+      if ((int)lane > first) contrib = 0ull;
+      excl += wave_allsum_u64(contrib);
+      break;
+    }
+    excl += wave_allsum_u64(contrib);
+    base -= 64;
+  }
+  if (lane == 0) flag_store(&flags[tile * flag_stride], kFlagIncl | ((excl + agg) & kFlagValMask));
+  return excl;
+}
+
+// ---------------------------------------------------------------------------
+// k_compact : ordered compaction with two classes.
+//   class A: key > st.hi           class B: st.lo <= key <= st.hi
+//   An element is kept if it is in A, or in B with fewer than `quota` B
+//   elements before it; its output position is
+//        (#A before it) + min(#B before it, quota)
+//   which is ascending in element order.  quota = infinity below level 3.
+//
+//   SRC_ARRAY (LIST = false): elements are x[e_lo .. e_hi) of the leader's
+//     vector, kept entries go to the survivor list as (index, key).  Runs only
+//     if the list has not been written and st.level == level; writes the list
+//     only if it fits (otherwise the pass only feeds the next digit histogram).
+//   SRC_LIST (LIST = true): elements are the survivor list, kept entries'
+//     indices go to idx_out[0 .. k).  Requires level 3.
+//
+//   block = 512 threads = 8 waves; a tile is 8 waves x 8 rows x 64 lanes x 4
+//   consecutive elements, each wave owning a contiguous 2048-element piece.
+// ---------------------------------------------------------------------------
+constexpr int kCompactThreads = 512;
+constexpr int kCompactRows = 8;
+constexpr int kCompactTile = kCompactThreads * 4 * kCompactRows;  // 16384 elements
+constexpr int kWaveSpan = 64 * 4 * kCompactRows;                  // 2048 elements
+
+template <bool LIST>
+__global__ void __launch_bounds__(kCompactThreads)
+k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __restrict__ stp, int level,
+          int64_t n, int64_t e_lo, int64_t e_hi, uint32_t cap, uint32_t* __restrict__ hist_next,
+          uint64_t* __restrict__ flags, int flag_stride, uint32_t* __restrict__ tile_counter,
+          int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
+          int32_t* __restrict__ idx_out, uint32_t k_out, uint32_t* __restrict__ err) {
+  __shared__ uint32_t lh[kHistBins];
+  __shared__ uint64_t wave_tot[8];
+  __shared__ uint64_t tile_excl;
+  __shared__ int64_t tile_sh;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const uint32_t lane = lane_id();
+
+  const SelState st = *stp;
+  bool write_out;
+  bool do_hist;
+  uint32_t quota;
+  int64_t first_tile, ntiles;
+  if (!LIST) {
+    if (st.compact_level != 0u || st.level != (uint32_t)level || *err) return;
+    quota = (level == 3) ? st.need : kQuotaInf;
+    const uint32_t takeB = st.cand < quota ? st.cand : quota;
+    write_out = (uint64_t)st.n_gt + takeB <= (uint64_t)cap;
+    do_hist = level < 3;
+    first_tile = e_lo / kCompactTile;
+    ntiles = (e_hi + kCompactTile - 1) / kCompactTile - first_tile;
+  } else {
+    if (st.compact_level == 0u || st.level != 3u || *err) {
+      if (tid == 0 && blockIdx.x == 0) atomicOr(err, kErrSequence);
+      return;
+    }
+    quota = st.need;
+    write_out = true;
+    do_hist = false;
+    e_lo = 0;
+    e_hi = (int64_t)st.list_count;
+    n = (int64_t)cap;  // list arrays are allocated with cap rounded up to a whole tile
+    first_tile = 0;
+    ntiles = (e_hi + kCompactTile - 1) / kCompactTile;
+  }
+  const uint32_t klo = st.lo, khi = st.hi;
+  const int dshift = digit_shift(level < 3 ? level : 2);
+  const uint32_t dmask = digit_mask(level < 3 ? level : 2);
+
+  const float* __restrict__ xp = LIST ? nullptr : tab.p[*leader_dev];
+
+  if (do_hist) {
+    for (int b = tid; b < kHistBins; b += kCompactThreads) lh[b] = 0u;
+  }
+  __syncthreads();
+
+  while (true) {
+    if (tid == 0) tile_sh = (int64_t)atomicAdd(tile_counter, 1u);
+    __syncthreads();
+    const int64_t trel = tile_sh;
+    if (trel >= ntiles) break;
+    const int64_t tbase = (first_tile + trel) * kCompactTile + (int64_t)wave * kWaveSpan;
+
+    // ---- load keys (and list payloads) --------------------------------
+    uint32_t key[kCompactRows][4];
+    int32_t pay[LIST ? kCompactRows : 1][4];
+    uint32_t valid = 0u;  // bit (r*4+e)
+    const bool full = (tbase >= e_lo) && (tbase + kWaveSpan <= e_hi) && (tbase + kWaveSpan <= (n & ~(int64_t)3));
+    if (full) {
+#pragma unroll
+      for (int r = 0; r < kCompactRows; ++r) {
+        const int64_t j = tbase + (int64_t)r * 256 + (int64_t)lane * 4;
+        uint4 v;
+        if (!LIST) {
+          v = *reinterpret_cast<const uint4*>(xp + j);
+        } else {
+          v = *reinterpret_cast<const uint4*>(list_key + j);
+          const int4 pv = *reinterpret_cast<const int4*>(list_idx + j);
+          pay[LIST ? r : 0][0] = pv.x;
+          pay[LIST ? r : 0][1] = pv.y;
+          pay[LIST ? r : 0][2] = pv.z;
+          pay[LIST ? r : 0][3] = pv.w;
+        }
+        key[r][0] = v.x & kKeyMask;
+        key[r][1] = v.y & kKeyMask;
+        key[r][2] = v.z & kKeyMask;
+        key[r][3] = v.w & kKeyMask;
+      }
+      valid = 0xffffffffu;
+    } else {
+#pragma unroll
+      for (int r = 0; r < kCompactRows; ++r) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t j = tbase + (int64_t)r * 256 + (int64_t)lane * 4 + e;
+          key[r][e] = 0u;
+          if (LIST) pay[LIST ? r : 0][e] = 0;
+          if (j >= e_lo && j < e_hi) {
+            valid |= 1u << (r * 4 + e);
+            if (!LIST) {
+              key[r][e] = __float_as_uint(xp[j]) & kKeyMask;
+            } else {
+              key[r][e] = list_key[j] & kKeyMask;
+              pay[LIST ? r : 0][e] = list_idx[j];
+            }
+          }
+        }
+      }
+    }
+
+    // ---- classify, count, feed the next-digit histogram ----------------
+    uint32_t isA = 0u, isB = 0u;
+    uint32_t cntA = 0u, cntB = 0u;  // wave totals (uniform)
+#pragma unroll
+    for (int r = 0; r < kCompactRows; ++r) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool ok = (valid >> (r * 4 + e)) & 1u;
+        const bool a = ok && key[r][e] > khi;
+        const bool b = ok && key[r][e] >= klo && key[r][e] <= khi;
+        if (a) isA |= 1u << (r * 4 + e);
+        if (b) isB |= 1u << (r * 4 + e);
+        cntA += (uint32_t)__popcll(__ballot(a));
+        cntB += (uint32_t)__popcll(__ballot(b));
+        if (do_hist && b) atomicAdd(&lh[(key[r][e] >> dshift) & dmask], 1u);
+      }
+    }
+
+    if (write_out) {
+      if (lane == 0) wave_tot[wave] = ((uint64_t)cntA << 31) | (uint64_t)cntB;
+      __syncthreads();
+      if (wave == 0) {
+        uint64_t agg = 0ull;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) agg += wave_tot[i];
+        const uint64_t ex = lookback_exclusive(flags, flag_stride, trel, agg, err);
+        if (lane == 0) tile_excl = ex;
+      }
+      __syncthreads();
+      uint64_t mine = tile_excl;
+      for (int i = 0; i < wave; ++i) mine += wave_tot[i];
+      uint32_t runA = (uint32_t)(mine >> 31);
+      uint32_t runB = (uint32_t)(mine & 0x7fffffffu);
+
+      if ((cntA | cntB) != 0u) {
+#pragma unroll
+        for (int r = 0; r < kCompactRows; ++r) {
+          uint64_t bA[4], bB[4];
+          uint32_t rowA = 0u, rowB = 0u, ltA = 0u, ltB = 0u;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            bA[e] = __ballot((isA >> (r * 4 + e)) & 1u);
+            bB[e] = __ballot((isB >> (r * 4 + e)) & 1u);
+            rowA += (uint32_t)__popcll(bA[e]);
+            rowB += (uint32_t)__popcll(bB[e]);
+          }
+          if ((rowA | rowB) != 0u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              ltA += popc_lt(bA[e]);
+              ltB += popc_lt(bB[e]);
+            }
+            uint32_t befA = runA + ltA, befB = runB + ltB;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const bool a = (isA >> (r * 4 + e)) & 1u;
+              const bool b = (isB >> (r * 4 + e)) & 1u;
+              if (a || (b && befB < quota)) {
+                const uint32_t pos = befA + (befB < quota ? befB : quota);
+                const int64_t j = tbase + (int64_t)r * 256 + (int64_t)lane * 4 + e;
+                if (!LIST) {
+                  if (pos < cap) {
+                    list_idx[pos] = (int32_t)j;
+                    list_key[pos] = key[r][e];
+                  }
+                } else {
+                  if (pos < k_out) idx_out[pos] = pay[LIST ? r : 0][e];
+                }
+              }
+              befA += a ? 1u : 0u;
+              befB += b ? 1u : 0u;
+            }
+          }
+          runA += rowA;
+          runB += rowB;
+        }
+      }
+    }
+    __syncthreads();  // tile_sh / wave_tot / tile_excl reused by the next tile
+  }
+
+  if (do_hist) {
+    __syncthreads();
+    for (int b = tid; b < kHistBins; b += kCompactThreads) {
+      const uint32_t v = lh[b];
+      if (v) atomicAdd(&hist_next[b], v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_list_hist : histogram of the last digit (7 bits) over the candidates in the
+// survivor list; runs only when the list was written at level 1.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_key,
+            uint32_t* __restrict__ hist2, const uint32_t* __restrict__ err) {
+  __shared__ uint32_t lh[128];
+  const SelState st = *stp;
+  if (st.compact_level != 1u || st.level != 2u || *err) return;
+  const int tid = threadIdx.x;
+  if (tid < 128) lh[tid] = 0u;
+  __syncthreads();
+  const uint32_t cnt = st.list_count;
+  for (uint32_t p = blockIdx.x * 256u + tid; p < cnt; p += gridDim.x * 256u) {
+    const uint32_t key = list_key[p];
+    if (key >= st.lo && key <= st.hi) atomicAdd(&lh[key & 0x7fu], 1u);
+  }
+  __syncthreads();
+  if (tid < 128) {
+    const uint32_t v = lh[tid];
+    if (v) atomicAdd(&hist2[tid], v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_gather : one thread per kept index m.  vals[w][m] = x_w[idx[m]], sum[m] is
+// the float32 sum over w = 0, 1, ..., W-1 in that order; with ZERO the
+// position is then overwritten by +0.0 in every worker.
+// ---------------------------------------------------------------------------
+template <bool ZERO>
+__global__ void __launch_bounds__(256)
+k_gather(PtrTable tab, int w_count, const int32_t* __restrict__ idx, int64_t k,
+         float* __restrict__ vals, float* __restrict__ sum) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= k) return;
+  const int64_t i = (int64_t)idx[m];
+  float s = 0.0f;
+  for (int w = 0; w < w_count; ++w) {
+    float* __restrict__ xp = tab.p[w];
+    const float v = xp[i];
+    if (vals) vals[(size_t)w * (size_t)k + (size_t)m] = v;
+    s = (w == 0) ? v : (s + v);
+    if (ZERO) xp[i] = 0.0f;
+  }
+  sum[m] = s;
+}
+
+__global__ void __launch_bounds__(256)
+k_zero_at(PtrTable tab, int w_count, const int32_t* __restrict__ idx, int64_t k) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= k) return;
+  const int64_t i = (int64_t)idx[m];
+  for (int w = 0; w < w_count; ++w) tab.p[w][i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// k_update_fill : update = zeros(N) with update[idx[m]] = sum[m], every output
+// element written exactly once.  Block b owns a contiguous run of 8192-element
+// chunks; it locates its first index with a 256-way search, then per chunk
+// builds the chunk in LDS and streams it out.
+// ---------------------------------------------------------------------------
+constexpr int kFillChunk = 8192;
+
+__global__ void __launch_bounds__(256)
+k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
+              const float* __restrict__ sum, int64_t k) {
+  __shared__ float buf[kFillChunk];
+  __shared__ int64_t s_lo, s_hi;
+  const int tid = threadIdx.x;
+  const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
+  const int64_t c_begin = nchunk * (int64_t)blockIdx.x / (int64_t)gridDim.x;
+  const int64_t c_end = nchunk * ((int64_t)blockIdx.x + 1) / (int64_t)gridDim.x;
+  if (c_begin >= c_end) return;
+
+  // m = number of indices below the first element of this block's run
+  const int64_t target = c_begin * kFillChunk;
+  if (tid == 0) {
+    s_lo = 0;
+    s_hi = k;
+  }
+  __syncthreads();
+  while (true) {
+    const int64_t lo = s_lo, hi = s_hi;  // answer lies in [lo, hi]
+    const int64_t span = hi - lo;
+    if (span <= 0) break;
+    const int64_t stepw = (span + 255) / 256;
+    const int64_t p = lo + (int64_t)tid * stepw;  // probe positions lo, lo+stepw, ...
+    const bool below = (p < hi) && ((int64_t)idx[p] < target);
+    const int cnt = __syncthreads_count(below);
+    // probes 0..cnt-1 are below the target: the answer is in (lo+(cnt-1)*stepw, lo+cnt*stepw]
+    if (tid == 0) {
+      if (cnt == 0) {
+        s_hi = lo;
+      } else {
+        const int64_t nlo = lo + (int64_t)(cnt - 1) * stepw + 1;
+        int64_t nhi = lo + (int64_t)cnt * stepw;
+        if (nhi > hi) nhi = hi;
+        s_lo = nlo;
+        s_hi = nhi;
+      }
+    }
+    __syncthreads();
+  }
+  int64_t m = s_lo;
+
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    const int64_t lo = c * kFillChunk;
+    const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
+    float4* b4 = reinterpret_cast<float4*>(buf);
+    for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    while (true) {
+      const int64_t p = m + tid;
+      int64_t i = hi;
+      if (p < k) i = (int64_t)idx[p];
+      const bool in = i < hi;
+      if (in) buf[i - lo] = sum[p];
+      const int cnt = __syncthreads_count(in);
+      m += cnt;
+      if (cnt < 256) break;
+    }
+    // (the count barrier above also orders the LDS writes before the reads)
+    const int64_t len = hi - lo;
+    float* __restrict__ up = update + lo;
+    const int64_t len4 = len >> 2;
+    for (int64_t i = tid; i < len4; i += 256) reinterpret_cast<float4*>(up)[i] = b4[i];
+    for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];
+    __syncthreads();
+  }
+}
+
+}  // namespace artopk
