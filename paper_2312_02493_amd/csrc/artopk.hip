@@ -250,13 +250,15 @@ int enqueue_select_segments(artopk_ctx* c, const PtrTable& tab, int64_t n, int32
   return ARTOPK_OK;
 }
 
-int enqueue_gather(artopk_ctx* c, const PtrTable& tab, int32_t w, const int32_t* idx, int64_t k, float* vals,
-                   float* sum, bool zero) {
+int enqueue_gather(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t n, const int32_t* idx, int64_t k,
+                   float* vals, float* sum, bool zero) {
   const int blocks = (int)((k + 255) / 256);
   if (zero)
-    hipLaunchKernelGGL(k_gather<true>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, idx, k, vals, sum);
+    hipLaunchKernelGGL(k_gather<true>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, n, idx, k, vals, sum,
+                       c->s.err_dev);
   else
-    hipLaunchKernelGGL(k_gather<false>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, idx, k, vals, sum);
+    hipLaunchKernelGGL(k_gather<false>, dim3(blocks), dim3(256), 0, c->stream, tab, (int)w, n, idx, k, vals, sum,
+                       c->s.err_dev);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
 }
@@ -386,7 +388,7 @@ int artopk_status(artopk_ctx* ctx) {
   if (err) {
     uint32_t zero = 0;
     HIP_TRY(ctx, hipMemcpy(ctx->s.err_dev, &zero, sizeof(zero), hipMemcpyHostToDevice));
-    return fail(ctx, ARTOPK_ESTATE, "device error word 0x%x (1 = histogram/count mismatch, 2 = scan wait expired, 4 = kernel sequence)", err);
+    return fail(ctx, ARTOPK_ESTATE, "device error word 0x%x (1 = histogram/count mismatch, 2 = scan wait expired, 4 = kernel sequence, 8 = index out of range)", err);
   }
   return ARTOPK_OK;
 }
@@ -464,7 +466,7 @@ int artopk_gather_sum(artopk_ctx* ctx, const float* const* acc, int32_t w, int64
   if ((rc = check_ptr_table(ctx, acc, w, "acc"))) return rc;
   if (!idx || !sum_out) return fail(ctx, ARTOPK_EINVAL, "idx or sum_out is NULL");
   const PtrTable tab = make_table(acc, w);
-  return enqueue_gather(ctx, tab, w, idx, k, vals_out, sum_out, false);
+  return enqueue_gather(ctx, tab, w, n, idx, k, vals_out, sum_out, false);
 }
 
 int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, int64_t n, const int32_t* idx,
@@ -476,7 +478,7 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
   if (!aligned16(update)) return fail(ctx, ARTOPK_EINVAL, "update is not 16-byte aligned");
   const PtrTable tab = make_table(residual, w);
   const int blocks = (int)((k + 255) / 256);
-  hipLaunchKernelGGL(k_zero_at, dim3(blocks), dim3(256), 0, ctx->stream, tab, (int)w, idx, k);
+  hipLaunchKernelGGL(k_zero_at, dim3(blocks), dim3(256), 0, ctx->stream, tab, (int)w, n, idx, k, ctx->s.err_dev);
   return enqueue_update_fill(ctx, update, n, idx, sum, k);
 }
 
@@ -540,7 +542,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
                                segmented ? seg_k : nullptr, k, idx_out, !segmented, hist_stride);
   if (rc) return rc;
   prof_mark(ctx, 2);
-  if ((rc = enqueue_gather(ctx, rt, w, idx_out, k, vals_out, sum_out, true))) return rc;
+  if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;
   prof_mark(ctx, 3);
   if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
   prof_mark(ctx, 4);

@@ -54,6 +54,7 @@ struct SelState {
 constexpr uint32_t kErrPick = 1u;      // a histogram did not cover the wanted count
 constexpr uint32_t kErrWait = 2u;      // a bounded look-back wait expired
 constexpr uint32_t kErrSequence = 4u;  // a kernel found the state it needs missing
+constexpr uint32_t kErrIndex = 8u;     // an index outside [0, N) reached gather / scatter
 
 // ---------------------------------------------------------------------------
 // small helpers
@@ -472,7 +473,7 @@ k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, const int3
 constexpr uint64_t kFlagAgg = 1ull << 62;
 constexpr uint64_t kFlagIncl = 2ull << 62;
 constexpr uint64_t kFlagValMask = (1ull << 62) - 1ull;
-constexpr int kSpinLimit = 1 << 22;
+constexpr int kSpinLimit = 1 << 20;
 
 __device__ __forceinline__ uint64_t flag_load(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -775,11 +776,15 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
 // ---------------------------------------------------------------------------
 template <bool ZERO>
 __global__ void __launch_bounds__(256)
-k_gather(PtrTable tab, int w_count, const int32_t* __restrict__ idx, int64_t k,
-         float* __restrict__ vals, float* __restrict__ sum) {
+k_gather(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx, int64_t k,
+         float* __restrict__ vals, float* __restrict__ sum, uint32_t* __restrict__ err) {
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= k) return;
   const int64_t i = (int64_t)idx[m];
+  if (i < 0 || i >= n) {  // never touch memory through an index outside the vector
+    atomicOr(err, kErrIndex);
+    return;
+  }
   float s = 0.0f;
   for (int w = 0; w < w_count; ++w) {
     float* __restrict__ xp = tab.p[w];
@@ -792,10 +797,15 @@ k_gather(PtrTable tab, int w_count, const int32_t* __restrict__ idx, int64_t k,
 }
 
 __global__ void __launch_bounds__(256)
-k_zero_at(PtrTable tab, int w_count, const int32_t* __restrict__ idx, int64_t k) {
+k_zero_at(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx, int64_t k,
+          uint32_t* __restrict__ err) {
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (m >= k) return;
   const int64_t i = (int64_t)idx[m];
+  if (i < 0 || i >= n) {
+    atomicOr(err, kErrIndex);
+    return;
+  }
   for (int w = 0; w < w_count; ++w) tab.p[w][i] = 0.0f;
 }
 
@@ -860,7 +870,7 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
       int64_t i = hi;
       if (p < k) i = (int64_t)idx[p];
       const bool in = i < hi;
-      if (in) buf[i - lo] = sum[p];
+      if (in && i >= lo) buf[i - lo] = sum[p];  // i >= lo always holds for ascending idx
       const int cnt = __syncthreads_count(in);
       m += cnt;
       if (cnt < 256) break;
