@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the AR-Topk compressor step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c4|c2|c1|c3] [--rho R]
+
+A "step" is one artopk_step() call: EF add + leader choice + exact Top-k on the
+leader + gather + ordered sum + residual rewrite + dense update, for all W
+simulated workers, with every input already resident in HBM.  Prints ONE JSON
+line.  `value` is W*N / t_step in G elements/s.  `roofline` describes the
+dominant kernel (the fused EF-add / variance / histogram pass, 12*W*N
+algorithmic bytes per launch), timed with HIP events on the library's stream.
+`cpu_baseline` is the NumPy oracle timed on a bounded sample of the same
+workload on the host (single thread).
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per pass-A launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(w, n, k, with_vals):
+    """Bytes one step must move (fp32, 4-byte granularity for the k-sized terms)."""
+    pass_a = 12 * w * n                 # read g, read residual, write acc
+    select = 4 * n                      # one re-read of the leader after the threshold digit is known
+    update = 4 * n                      # dense update written once
+    ksized = k * (8 * w + (4 * w if with_vals else 0) + 20)
+    return pass_a, pass_a + select + update + ksized
+
+
+def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
+    wl = inp.workload(cfg)
+    k = wl.k(rho)
+    seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
+    seg_k = None if wl.seg_off is None else [int(v) for v in wl.seg_k(rho)]
+    dev = torch.device("cuda:0")
+    mode = pkg.ARTOPK_STAR if wl.mode == inp.MODE_STAR else pkg.ARTOPK_VAR
+    log(f"[bench] workload {wl.name}: N={wl.n} W={wl.w} rho={rho} k={k} mode={'STAR' if mode == 0 else 'VAR'}")
+
+    t0 = time.perf_counter()
+    g, res = [], []
+    import numpy as np
+    host = np.empty(wl.n, dtype=np.float32)
+    for r in range(wl.w):
+        wl.gen_into(host, 1, r, threads=args.gen_threads)
+        g.append(torch.from_numpy(host).to(dev))
+        res.append(torch.zeros(wl.n, dtype=torch.float32, device=dev))
+        log(f"[bench]   worker {r} generated and uploaded ({time.perf_counter() - t0:.1f} s)")
+    del host
+    ctx = pkg.Context(wl.w, wl.n, k, 1 if seg_k is None else len(seg_k))
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    summed = torch.empty(k, dtype=torch.float32, device=dev)
+    update = torch.empty(wl.n, dtype=torch.float32, device=dev)
+    leader = torch.zeros(1, dtype=torch.int32, device=dev)
+    var = torch.zeros(wl.w, dtype=torch.float64, device=dev)
+
+    def one(step_no):
+        ctx.artopk_step(g, res, k, mode, step_no, idx, summed, update, leader_out=leader, var_out=var,
+                        seg_off=seg_off, seg_k=seg_k)
+
+    step_no = 1
+    for _ in range(warmup):
+        one(step_no)
+        step_no += 1
+    torch.cuda.synchronize()
+    ctx.status()
+
+    # timed region: K steps, pass A bracketed by HIP events on the library's stream
+    ctx.set_profile(True)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(steps):
+        one(step_no)
+        step_no += 1
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+    pr = ctx.get_profile()              # stage events averaged over the timed steps
+    pass_a_ms = [pr["pass_a"]]
+    stage_ms = [pr]
+    ctx.set_profile(False)
+    ctx.status()
+    ms_per_step = 1e3 * t_total / steps
+    pa = sum(pass_a_ms) / len(pass_a_ms)
+    b_pass_a, b_step = algorithmic_bytes(wl.w, wl.n, k, False)
+    out = {
+        "wl": wl, "k": k, "rho": rho, "ms_per_step": ms_per_step,
+        "gelem_per_s": wl.w * wl.n / (ms_per_step * 1e-3) / 1e9,
+        "pass_a_ms": pa, "pass_a_gbps": b_pass_a / (pa * 1e-3) / 1e9,
+        "step_alg_gbps": b_step / (ms_per_step * 1e-3) / 1e9,
+        "stages": {name: sum(s[name] for s in stage_ms) / len(stage_ms) for name in stage_ms[0]},
+        "b_pass_a": b_pass_a, "b_step": b_step, "leader": int(leader.item()),
+    }
+    log(f"[bench]   {ms_per_step:.3f} ms/step, {out['gelem_per_s']:.1f} G elem/s, pass A {pa:.3f} ms = "
+        f"{out['pass_a_gbps']:.0f} GB/s, whole step {out['step_alg_gbps']:.0f} GB/s algorithmic; stages {out['stages']}")
+    del g, res, update, ctx
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(cfg, rho, inp, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the workload (one thread)."""
+    import numpy as np
+    from oracle import artopk_oracle as orc
+
+    full = inp.workload(cfg)
+    n = min(full.n, 1 << 22)
+    wl = inp.workload(cfg, n=n)
+    k = wl.k(rho)
+    seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
+    seg_k = None if wl.seg_off is None else [int(v) for v in wl.seg_k(rho)]
+    mode = orc.MODE_STAR if wl.mode == inp.MODE_STAR else orc.MODE_VAR
+    res = [np.zeros(n, np.float32) for _ in range(wl.w)]
+    steps, spent = 0, 0.0
+    while spent < budget_s and steps < 8:
+        g = [wl.gen(steps + 1, r) for r in range(wl.w)]
+        t0 = time.perf_counter()
+        out = orc.step(g, res, k, mode, step_no=steps + 1, seg_off=seg_off, seg_k=seg_k)
+        spent += time.perf_counter() - t0
+        res = out.residual
+        steps += 1
+    return {
+        "value": wl.w * n * steps / spent / 1e9, "unit": "G elements/s", "cores": 1, "kind": "oracle",
+        "sample": f"{steps} steps of workload {wl.name} shrunk to N={n} (W={wl.w}, rho={rho}), "
+                  f"{spent:.1f} s of single-thread NumPy",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--rho", type=float, default=None)
+    ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also-c4", action="store_true", help="append the 138M workload's numbers under 'other'")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import artopk_inputs as inp
+    import paper_2312_02493_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
+        sys.exit(2)
+    pkg.load_library()
+
+    cfg = int(args.workload[1])
+    wl0 = inp.workload(cfg)
+    rho = args.rho if args.rho is not None else {1: 0.01, 2: 0.01, 3: 0.01, 4: 0.01, 5: 0.001}[cfg]
+    r = run_workload(args, cfg, rho, args.steps, args.warmup, torch, pkg, inp)
+
+    other = {}
+    if args.also_c4 and cfg != 4:
+        for rh in (0.1, 0.01, 0.001):
+            o = run_workload(args, 4, rh, args.steps, args.warmup, torch, pkg, inp)
+            other[f"c4_rho{rh}"] = {"ms_per_step": round(o["ms_per_step"], 4),
+                                    "G_elements_per_s": round(o["gelem_per_s"], 2),
+                                    "step_alg_GBps": round(o["step_alg_gbps"], 1),
+                                    "pass_a_GBps": round(o["pass_a_gbps"], 1)}
+
+    base = None if args.no_cpu_baseline else cpu_baseline(cfg, rho, inp)
+
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, rho))
+    line = {
+        "metric": "compressed gradient elements/s per AR-Topk step (1 GPU)",
+        "value": round(r["gelem_per_s"], 3),
+        "unit": "G elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(r["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic (seeded recipe of the workload; step-1 gradients reused every step, residual carried)",
+        "config": {"workload": wl0.name, "N": wl0.n, "W": wl0.w, "rho": rho, "k": r["k"],
+                   "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR"},
+        "roofline": {"bound": "hbm", "kernel": "k_pass_a", "achieved": round(r["pass_a_gbps"], 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r["pass_a_gbps"] / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": r["b_pass_a"],
+                     "avg_launch_ms": round(r["pass_a_ms"], 4)},
+        "step_algorithmic": {"bytes": r["b_step"], "GBps": round(r["step_alg_gbps"], 1),
+                             "frac_of_hbm_peak": round(r["step_alg_gbps"] / HBM_PEAK_GBPS, 4),
+                             "stage_ms": {k_: round(v, 4) for k_, v in r["stages"].items()}},
+        "cpu_baseline": base,
+    }
+    if other:
+        line["other"] = other
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

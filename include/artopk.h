@@ -162,9 +162,10 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
 
 /*
  * Stage timing.  With profiling enabled every call records HIP events on the
- * context's stream around its stages; artopk_get_profile synchronises on the
- * last call's events and writes up to `count` stage durations in milliseconds
- * (order: the ARTOPK_PROF_* enum; stages that did not run report 0).
+ * context's stream around its stages.  artopk_get_profile synchronises the
+ * stream and writes up to `count` stage durations in milliseconds (order: the
+ * ARTOPK_PROF_* enum; stages that did not run report 0), each averaged over
+ * the calls made since profiling was enabled (at most the 64 most recent).
  */
 int artopk_set_profile(artopk_ctx* ctx, int32_t enable);
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count);

@@ -10,6 +10,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -19,22 +20,23 @@ using namespace artopk;
 
 namespace {
 
-constexpr int kNumCompactLaunches = 4;  // array level 1, 2, 3 and the list pass
+constexpr int kNumCompactLaunches = 4;  // look-back passes: array level 2, 3 and the list pass (+1 spare)
 
 struct Scratch {
   // zeroed before every select
   uint32_t* zero_base = nullptr;  // start of the zeroed head
-  size_t head_words = 0;          // state + counters + hist1 + hist2 + hist0[0]
-  size_t hist0_all_words = 0;     // hist0[0..max_w) (the first 4096 are part of the head)
+  size_t head_words = 0;          // state + counters + hist1 + hist2 + Ssum
   SelState* state = nullptr;
   uint32_t* counters = nullptr;   // kNumCompactLaunches tile counters
   uint32_t* hist1 = nullptr;
   uint32_t* hist2 = nullptr;
-  uint32_t* hist0 = nullptr;      // [max_w][4096]
+  uint32_t* ssum = nullptr;       // [4096] suffix sums of the leader's top-digit histogram
   uint64_t* flags = nullptr;      // [max_tiles][kNumCompactLaunches]
   int64_t max_tiles = 0;
   // not zeroed
-  double* partials = nullptr;     // [max_w][max_nblk][2]
+  uint32_t* S = nullptr;          // [slots][kMaxChunks][4096] per-chunk suffix histograms
+  uint32_t* chunk_off = nullptr;  // [kMaxChunks]
+  double* partials = nullptr;     // [max_w][kMaxChunks][2]
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
   uint32_t* err_dev = nullptr;
@@ -52,12 +54,19 @@ struct artopk_ctx {
   int32_t max_w = 0;
   int64_t max_n = 0, max_k = 0;
   int32_t max_seg = 0;
-  int max_nblk = 0;
+  bool pass_a_nt = true;  // non-temporal g loads / acc stores in pass A
   void* slab = nullptr;
   Scratch s;
+  // stage events: a ring of the most recent calls, 5 marks per call
+  // (0 start, 1 after pass A, 2 after select, 3 after gather, 4 after update)
   bool profile = false;
-  hipEvent_t ev[ARTOPK_PROF_COUNT + 1] = {};
-  bool ev_valid[ARTOPK_PROF_COUNT + 1] = {};
+  static constexpr int kRing = 64;
+  static constexpr int kMarks = 5;
+  hipEvent_t ev[kRing][kMarks] = {};
+  bool ev_valid[kRing][kMarks] = {};
+  bool ev_created = false;
+  long prof_calls = 0;  // calls recorded since profiling was switched on
+  int cur = 0;          // ring slot of the call being recorded
   char err[512] = {0};
 };
 
@@ -134,7 +143,23 @@ PtrTable make_table(const float* const* tab, int32_t w) {
   return t;
 }
 
-int pass_a_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
+// Chunk layout of the element range [e_lo, e_hi): at most kMaxChunks chunks of
+// whole tiles, chunk 0 starting at the tile boundary at or below e_lo.
+ChunkGeom make_geom(int64_t e_lo, int64_t e_hi) {
+  ChunkGeom g;
+  g.chunk0 = e_lo / kTile * kTile;
+  const int64_t span = e_hi - g.chunk0;
+  int64_t ce = (span + kMaxChunks - 1) / kMaxChunks;
+  ce = (ce + kTile - 1) / kTile * kTile;
+  if (ce < kTile) ce = kTile;
+  g.chunk_elems = ce;
+  g.nchunks = (int32_t)((span + ce - 1) / ce);
+  if (g.nchunks < 1) g.nchunks = 1;
+  return g;
+}
+
+// Blocks per worker of the stand-alone variance kernel.
+int stats_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
   const int64_t n4 = n >> 2;
   const int64_t tile = 256 * kPassAUnroll;
   int64_t ntile = (n4 + tile - 1) / tile;
@@ -142,26 +167,29 @@ int pass_a_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
   int64_t want = ((int64_t)c->num_cu * 8 + w - 1) / w;
   if (want < 1) want = 1;
   int64_t nblk = ntile < want ? ntile : want;
-  if (nblk > c->max_nblk) nblk = c->max_nblk;
+  if (nblk > kMaxChunks) nblk = kMaxChunks;
   return (int)nblk;
 }
 
-void prof_mark(artopk_ctx* c, int slot) {
+void prof_mark(artopk_ctx* c, int mark) {
   if (!c->profile) return;
-  if (hipEventRecord(c->ev[slot], c->stream) == hipSuccess) c->ev_valid[slot] = true;
+  if (hipEventRecord(c->ev[c->cur][mark], c->stream) == hipSuccess) c->ev_valid[c->cur][mark] = true;
 }
 
-void prof_reset(artopk_ctx* c) {
-  for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i) c->ev_valid[i] = false;
+// Starts the record of a new call in the next ring slot.
+void prof_begin(artopk_ctx* c) {
+  if (!c->profile) return;
+  c->cur = (int)(c->prof_calls % artopk_ctx::kRing);
+  c->prof_calls++;
+  for (int i = 0; i < artopk_ctx::kMarks; ++i) c->ev_valid[c->cur][i] = false;
 }
 
-// Clears the select scratch for a range that spans `ntiles` compaction tiles.
-// With all_hist0 the per-worker top-digit histograms are cleared as well.
-int enqueue_clear(artopk_ctx* c, int64_t ntiles, bool all_hist0) {
+// Clears the select scratch for a range that spans `ntiles` look-back tiles.
+int enqueue_clear(artopk_ctx* c, int64_t ntiles) {
   Scratch& s = c->s;
-  size_t words1 = all_hist0 ? (s.head_words - kHistBins + s.hist0_all_words) : s.head_words;
-  size_t words2 = (size_t)ntiles * kNumCompactLaunches * 2;
-  size_t total = words1 + words2;
+  const size_t words1 = s.head_words;
+  const size_t words2 = (size_t)ntiles * kNumCompactLaunches * 2;
+  const size_t total = words1 + words2;
   int blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
   if (blocks < 1) blocks = 1;
   if (blocks > c->num_cu * 4) blocks = c->num_cu * 4;
@@ -177,52 +205,54 @@ int64_t tiles_of_range(int64_t e_lo, int64_t e_hi) {
 
 // Selection of the k largest magnitudes of x[e_lo, e_hi) of the vector
 // tab.p[*leader_dev]; the scratch must have been cleared.  If hist_ready the
-// top-digit histogram is already in hist0 (+ leader * hist_stride).
+// per-chunk suffix histograms of the range (layout make_geom(e_lo, e_hi)) are
+// already in S, in slot *leader_dev if slot_by_leader, else in slot 0.
 int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, int64_t e_hi, int64_t k,
-                   int32_t* idx_out, bool hist_ready, int hist_stride) {
+                   int32_t* idx_out, bool hist_ready, int slot_by_leader) {
   Scratch& s = c->s;
   hipStream_t st = c->stream;
   const int64_t nrange = e_hi - e_lo;
   const int64_t ntiles = tiles_of_range(e_lo, e_hi);
   if (ntiles > s.max_tiles) return fail(c, ARTOPK_EINVAL, "range needs more scan tiles than the context holds");
+  const ChunkGeom geom = make_geom(e_lo, e_hi);
+  const uint32_t cap = s.cap;
 
   if (!hist_ready) {
-    int64_t groups = ((e_hi + 3) >> 2) - (e_lo >> 2);
-    int blocks = (int)((groups + 256 * 8 - 1) / (256 * 8));
-    if (blocks < 1) blocks = 1;
-    if (blocks > c->num_cu * 8) blocks = c->num_cu * 8;
-    hipLaunchKernelGGL(k_hist0, dim3(blocks), dim3(256), 0, st, tab, s.leader_dev, n, e_lo, e_hi, s.hist0);
-    hist_stride = 0;
+    hipLaunchKernelGGL(k_hist0, dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, n, e_lo, e_hi, geom, s.S);
+    slot_by_leader = 0;
   }
-  const uint32_t cap = s.cap;
-  int cblocks = (int)(ntiles < (int64_t)c->num_cu * 4 ? ntiles : (int64_t)c->num_cu * 4);
-  if (cblocks < 1) cblocks = 1;
+  int ysplit = geom.nchunks / 32;
+  if (ysplit < 1) ysplit = 1;
+  hipLaunchKernelGGL(k_reduce_hist, dim3(kHistBins / 256, ysplit), dim3(256), 0, st, s.S, s.leader_dev,
+                     slot_by_leader, (int)geom.nchunks, s.ssum);
+  hipLaunchKernelGGL(k_pick0, dim3(1), dim3(1024), 0, st, s.state, s.ssum, s.S, s.leader_dev, slot_by_leader,
+                     (int)geom.nchunks, (uint32_t)nrange, (uint32_t)k, s.chunk_off, s.err_dev);
+  hipLaunchKernelGGL(k_compact1, dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, s.state, n, e_lo, e_hi,
+                     geom, s.chunk_off, cap, s.hist1, s.list_idx, s.list_key, s.err_dev);
+  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist1, 1, cap, s.err_dev);
 
-  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist0, s.leader_dev, hist_stride, 0,
-                     (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
-  for (int level = 1; level <= 3; ++level) {
-    uint32_t* hist_next = level == 1 ? s.hist1 : s.hist2;
+  // deeper array passes: they run only when the level-1 survivors did not fit the list
+  int cblocks = (int)(ntiles < (int64_t)c->num_cu * 2 ? ntiles : (int64_t)c->num_cu * 2);
+  if (cblocks < 1) cblocks = 1;
+  for (int level = 2; level <= 3; ++level) {
     hipLaunchKernelGGL(k_compact<false>, dim3(cblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev,
-                       s.state, level, n, e_lo, e_hi, cap, hist_next, s.flags + (level - 1),
-                       kNumCompactLaunches, s.counters + (level - 1), s.list_idx, s.list_key,
-                       (int32_t*)nullptr, 0u, s.err_dev);
-    hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, hist_next, s.leader_dev, 0, level,
-                       (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
+                       s.state, level, n, e_lo, e_hi, cap, s.hist2, s.flags + (level - 2), kNumCompactLaunches,
+                       s.counters + (level - 2), s.list_idx, s.list_key, (int32_t*)nullptr, 0u, s.err_dev);
+    hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, level, cap, s.err_dev);
   }
-  // the list cannot hold more than n_gt + cand <= cap entries; k + typical candidates in practice
+  // the list holds n_gt + cand <= cap entries
   int64_t list_bound = (int64_t)cap < nrange ? (int64_t)cap : nrange;
   int lblocks = (int)((list_bound + 256 * 16 - 1) / (256 * 16));
   if (lblocks < 1) lblocks = 1;
   if (lblocks > c->num_cu * 4) lblocks = c->num_cu * 4;
   hipLaunchKernelGGL(k_list_hist, dim3(lblocks), dim3(256), 0, st, s.state, s.list_key, s.hist2, s.err_dev);
-  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, s.leader_dev, 0, 4,
-                     (uint32_t)nrange, (uint32_t)k, cap, s.err_dev);
+  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, 4, cap, s.err_dev);
   int64_t ltiles = (list_bound + kCompactTile - 1) / kCompactTile;
-  int fblocks = (int)(ltiles < (int64_t)c->num_cu * 4 ? ltiles : (int64_t)c->num_cu * 4);
+  int fblocks = (int)(ltiles < (int64_t)c->num_cu * 2 ? ltiles : (int64_t)c->num_cu * 2);
   if (fblocks < 1) fblocks = 1;
   hipLaunchKernelGGL(k_compact<true>, dim3(fblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev, s.state,
-                     3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 3,
-                     kNumCompactLaunches, s.counters + 3, s.list_idx, s.list_key, idx_out, (uint32_t)k,
+                     3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 2,
+                     kNumCompactLaunches, s.counters + 2, s.list_idx, s.list_key, idx_out, (uint32_t)k,
                      s.err_dev);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
@@ -231,19 +261,18 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
 // Select over all segments of the leader's vector (host loop over segments).
 int enqueue_select_segments(artopk_ctx* c, const PtrTable& tab, int64_t n, int32_t nseg,
                             const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t* idx_out,
-                            bool flat_hist_ready, int hist_stride) {
+                            bool flat_hist_ready, int slot_by_leader) {
   if (!seg_off) {
-    return enqueue_select(c, tab, n, 0, n, k, idx_out, flat_hist_ready, hist_stride);
+    return enqueue_select(c, tab, n, 0, n, k, idx_out, flat_hist_ready, slot_by_leader);
   }
   int64_t koff = 0;
   for (int sgi = 0; sgi < nseg; ++sgi) {
     const int64_t lo = seg_off[sgi], hi = seg_off[sgi + 1];
-    if (sgi > 0 || !flat_hist_ready) {
-      int rc = enqueue_clear(c, tiles_of_range(lo, hi), false);
+    {
+      int rc = enqueue_clear(c, tiles_of_range(lo, hi));
       if (rc) return rc;
     }
-    int rc = enqueue_select(c, tab, n, lo, hi, seg_k[sgi], idx_out + koff, nseg == 1 && flat_hist_ready,
-                            hist_stride);
+    int rc = enqueue_select(c, tab, n, lo, hi, seg_k[sgi], idx_out + koff, false, 0);
     if (rc) return rc;
     koff += seg_k[sgi];
   }
@@ -302,7 +331,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return ARTOPK_EHIP;
   }
   c->num_cu = cus > 0 ? cus : 256;
-  c->max_nblk = c->num_cu * 8;
+  if (const char* e_nt = getenv("ARTOPK_PASS_A_NT")) c->pass_a_nt = atoi(e_nt) != 0;
 
   Scratch& s = c->s;
   // list capacity: every key above the range (< k of them) plus a generous share of candidates
@@ -312,7 +341,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   if (cap > max_n) cap = max_n;
   s.cap = (uint32_t)cap;
   const size_t cap_pad = align_up((size_t)cap, kCompactTile) + kCompactTile;
-  // a range [lo, hi) touches at most ceil(len / tile) + 1 tiles
+  // a range [lo, hi) touches at most ceil(len / tile) + 1 look-back tiles
   s.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 1;
 
   size_t off = 0;
@@ -321,15 +350,17 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     off = align_up(off + bytes, 256);
     return o;
   };
-  // zeroed head: state | counters | hist1 | hist2 | hist0[0..max_w)
+  // zeroed head: state | counters | hist1 | hist2 | ssum
   const size_t o_state = take(sizeof(SelState));
   const size_t o_cnt = take(16 * sizeof(uint32_t));
   const size_t o_h1 = take(kHistBins * sizeof(uint32_t));
   const size_t o_h2 = take(kHistBins * sizeof(uint32_t));
-  const size_t o_h0 = take((size_t)max_w * kHistBins * sizeof(uint32_t));
+  const size_t o_ssum = take(kHistBins * sizeof(uint32_t));
   const size_t o_head_end = off;
   const size_t o_flags = take((size_t)s.max_tiles * kNumCompactLaunches * sizeof(uint64_t));
-  const size_t o_part = take((size_t)max_w * c->max_nblk * 2 * sizeof(double));
+  const size_t o_S = take((size_t)max_w * kMaxChunks * kHistBins * sizeof(uint32_t));
+  const size_t o_coff = take(kMaxChunks * sizeof(uint32_t));
+  const size_t o_part = take((size_t)max_w * kMaxChunks * 2 * sizeof(double));
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
@@ -348,10 +379,11 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.counters = reinterpret_cast<uint32_t*>(base + o_cnt);
   s.hist1 = reinterpret_cast<uint32_t*>(base + o_h1);
   s.hist2 = reinterpret_cast<uint32_t*>(base + o_h2);
-  s.hist0 = reinterpret_cast<uint32_t*>(base + o_h0);
-  s.head_words = (o_h0 - o_state) / sizeof(uint32_t) + kHistBins;
-  s.hist0_all_words = (o_head_end - o_h0) / sizeof(uint32_t);
+  s.ssum = reinterpret_cast<uint32_t*>(base + o_ssum);
+  s.head_words = (o_head_end - o_state) / sizeof(uint32_t);
   s.flags = reinterpret_cast<uint64_t*>(base + o_flags);
+  s.S = reinterpret_cast<uint32_t*>(base + o_S);
+  s.chunk_off = reinterpret_cast<uint32_t*>(base + o_coff);
   s.partials = reinterpret_cast<double*>(base + o_part);
   s.var_scratch = reinterpret_cast<double*>(base + o_var);
   s.leader_dev = reinterpret_cast<int32_t*>(base + o_leader);
@@ -373,8 +405,10 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
 
 int artopk_destroy(artopk_ctx* ctx) {
   if (!ctx) return ARTOPK_EINVAL;
-  for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i)
-    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  if (ctx->ev_created)
+    for (int r = 0; r < artopk_ctx::kRing; ++r)
+      for (int i = 0; i < artopk_ctx::kMarks; ++i)
+        if (ctx->ev[r][i]) (void)hipEventDestroy(ctx->ev[r][i]);
   if (ctx->slab) (void)hipFree(ctx->slab);
   delete ctx;
   return ARTOPK_OK;
@@ -395,31 +429,50 @@ int artopk_status(artopk_ctx* ctx) {
 
 int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
   if (!ctx) return ARTOPK_EINVAL;
-  if (enable) {
-    for (int i = 0; i <= ARTOPK_PROF_COUNT; ++i)
-      if (!ctx->ev[i]) HIP_TRY(ctx, hipEventCreate(&ctx->ev[i]));
+  if (enable && !ctx->ev_created) {
+    for (int r = 0; r < artopk_ctx::kRing; ++r)
+      for (int i = 0; i < artopk_ctx::kMarks; ++i) HIP_TRY(ctx, hipEventCreate(&ctx->ev[r][i]));
+    ctx->ev_created = true;
   }
   ctx->profile = enable != 0;
-  prof_reset(ctx);
+  ctx->prof_calls = 0;
+  for (int r = 0; r < artopk_ctx::kRing; ++r)
+    for (int i = 0; i < artopk_ctx::kMarks; ++i) ctx->ev_valid[r][i] = false;
   return ARTOPK_OK;
 }
 
-// Event slots: 0 start, 1 after pass A, 2 after select, 3 after gather, 4 after update.
+// Averages every stage over the calls recorded since profiling was enabled
+// (at most the kRing most recent ones).
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count) {
   if (!ctx || !ms_out || count < 0) return ARTOPK_EINVAL;
-  if (!ctx->profile) return fail(ctx, ARTOPK_EINVAL, "profiling is not enabled");
+  if (!ctx->ev_created) return fail(ctx, ARTOPK_EINVAL, "profiling was never enabled");
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-  float ms[ARTOPK_PROF_COUNT] = {0, 0, 0, 0, 0};
-  for (int i = 0; i < 4; ++i)
-    if (ctx->ev_valid[i] && ctx->ev_valid[i + 1]) HIP_TRY(ctx, hipEventElapsedTime(&ms[i], ctx->ev[i], ctx->ev[i + 1]));
-  int last = -1;
-  for (int i = 4; i >= 1; --i)
-    if (ctx->ev_valid[i]) {
-      last = i;
-      break;
+  double acc[ARTOPK_PROF_COUNT] = {0, 0, 0, 0, 0};
+  int cnt[ARTOPK_PROF_COUNT] = {0, 0, 0, 0, 0};
+  for (int r = 0; r < artopk_ctx::kRing; ++r) {
+    const bool* v = ctx->ev_valid[r];
+    for (int i = 0; i < 4; ++i) {
+      if (v[i] && v[i + 1]) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[r][i], ctx->ev[r][i + 1]));
+        acc[i] += ms;
+        cnt[i]++;
+      }
     }
-  if (ctx->ev_valid[0] && last > 0) HIP_TRY(ctx, hipEventElapsedTime(&ms[ARTOPK_PROF_TOTAL], ctx->ev[0], ctx->ev[last]));
-  for (int i = 0; i < count && i < ARTOPK_PROF_COUNT; ++i) ms_out[i] = ms[i];
+    int last = -1;
+    for (int i = 4; i >= 1; --i)
+      if (v[i]) {
+        last = i;
+        break;
+      }
+    if (v[0] && last > 0) {
+      float ms = 0.f;
+      HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->ev[r][0], ctx->ev[r][last]));
+      acc[ARTOPK_PROF_TOTAL] += ms;
+      cnt[ARTOPK_PROF_TOTAL]++;
+    }
+  }
+  for (int i = 0; i < count && i < ARTOPK_PROF_COUNT; ++i) ms_out[i] = cnt[i] ? (float)(acc[i] / cnt[i]) : 0.f;
   return ARTOPK_OK;
 }
 
@@ -430,7 +483,7 @@ int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n
   if ((rc = check_ptr_table(ctx, x, w, "x"))) return rc;
   if (!var_out) return fail(ctx, ARTOPK_EINVAL, "var_out is NULL");
   const PtrTable tab = make_table(x, w);
-  const int nblk = pass_a_blocks(ctx, w, n);
+  const int nblk = stats_blocks(ctx, w, n);
   Scratch& s = ctx->s;
   hipLaunchKernelGGL(k_stats, dim3(nblk, w), dim3(256), 0, ctx->stream, tab, n, s.partials);
   hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, ctx->stream, s.partials, (int)w, nblk, n, s.var_scratch,
@@ -448,11 +501,11 @@ int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nse
   if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
   const float* one[1] = {acc};
   const PtrTable tab = make_table(one, 1);
-  prof_reset(ctx);
+  prof_begin(ctx);
   prof_mark(ctx, 1);
   hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, ctx->stream, 0, ctx->s.leader_dev, (int32_t*)nullptr);
   if (!seg_off) {
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), false))) return rc;
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
   }
   rc = enqueue_select_segments(ctx, tab, n, nseg, seg_off, seg_k, k, idx_out, false, 0);
   prof_mark(ctx, 2);
@@ -508,38 +561,49 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   const PtrTable gt = make_table(g, w);
   const PtrTable rt = make_table(residual, w);
   const bool segmented = seg_off != nullptr && nseg > 1;
-  const int nblk = pass_a_blocks(ctx, w, n);
-  const dim3 grid(nblk, w), block(256);
+  const ChunkGeom geom = make_geom(0, n);
+  const dim3 grid(geom.nchunks, w), block(256);
+  const bool nt = ctx->pass_a_nt;
 
-  prof_reset(ctx);
+  prof_begin(ctx);
   prof_mark(ctx, 0);
-  // the flat select reuses the histogram pass A builds; segments build their own
+  // the flat select reuses the histograms pass A builds; segments build their own
   if (!segmented) {
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), mode == ARTOPK_VAR))) return rc;
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
   }
-  int hist_stride = 0;
+  int slot_by_leader = 0;
+#define LAUNCH_PASS_A(STATS, HIST, LEADER)                                                                  \
+  do {                                                                                                      \
+    if (nt)                                                                                                 \
+      hipLaunchKernelGGL((k_pass_a<STATS, HIST, true>), grid, block, 0, st, gt, rt, n, geom, LEADER, s.S,   \
+                         s.partials);                                                                       \
+    else                                                                                                    \
+      hipLaunchKernelGGL((k_pass_a<STATS, HIST, false>), grid, block, 0, st, gt, rt, n, geom, LEADER, s.S,  \
+                         s.partials);                                                                       \
+  } while (0)
   if (mode == ARTOPK_VAR) {
     if (segmented) {
-      hipLaunchKernelGGL((k_pass_a<true, 0>), grid, block, 0, st, gt, rt, n, -1, s.hist0, s.partials);
+      LAUNCH_PASS_A(true, 0, -1);
     } else {
-      hipLaunchKernelGGL((k_pass_a<true, 2>), grid, block, 0, st, gt, rt, n, -1, s.hist0, s.partials);
-      hist_stride = kHistBins;
+      LAUNCH_PASS_A(true, 2, -1);
+      slot_by_leader = 1;
     }
     prof_mark(ctx, 1);
-    hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, nblk, n, s.var_scratch, var_out,
-                       s.leader_dev, leader_out);
+    hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, (int)geom.nchunks, n,
+                       s.var_scratch, var_out, s.leader_dev, leader_out);
   } else {
     if (segmented)
-      hipLaunchKernelGGL((k_pass_a<false, 0>), grid, block, 0, st, gt, rt, n, leader_host, s.hist0, s.partials);
+      LAUNCH_PASS_A(false, 0, leader_host);
     else
-      hipLaunchKernelGGL((k_pass_a<false, 1>), grid, block, 0, st, gt, rt, n, leader_host, s.hist0, s.partials);
+      LAUNCH_PASS_A(false, 1, leader_host);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
   }
+#undef LAUNCH_PASS_A
   HIP_TRY(ctx, hipGetLastError());
 
   rc = enqueue_select_segments(ctx, rt, n, segmented ? nseg : 1, segmented ? seg_off : nullptr,
-                               segmented ? seg_k : nullptr, k, idx_out, !segmented, hist_stride);
+                               segmented ? seg_k : nullptr, k, idx_out, !segmented, slot_by_leader);
   if (rc) return rc;
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;

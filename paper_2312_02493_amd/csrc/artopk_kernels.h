@@ -3,14 +3,18 @@
 // Kernels (in the order one step runs them):
 //   k_fill_zero      clears the per-call scratch (histograms, scan flags, ...)
 //   k_pass_a         acc = g + residual in place, per-worker variance
-//                    partials, 12-bit top-digit histogram of |acc|
-//   k_hist0          the same histogram alone (stand-alone select, segments)
+//                    partials, per-chunk 12-bit top-digit histograms of |acc|
+//   k_hist0          the same histograms alone (stand-alone select, segments)
 //   k_stats          variance partials alone (stand-alone variance)
 //   k_leader         finishes the variances and takes the first argmax
-//   k_pick           narrows the candidate key range by one radix digit
-//   k_compact        ordered stream compaction of "keys above the range" and
-//                    "keys inside the range" with a decoupled look-back scan;
-//                    source is either the leader's vector or the survivor list
+//   k_reduce_hist    adds the leader's per-chunk histograms
+//   k_pick0          finds the threshold digit and every chunk's list offset
+//   k_compact1       ordered compaction of the leader's survivors, one block
+//                    per chunk, no inter-block dependency
+//   k_pick           narrows the candidate key range by one more radix digit
+//   k_compact        ordered compaction with a decoupled look-back scan: the
+//                    rarely needed deeper array passes and the final pass over
+//                    the survivor list
 //   k_list_hist      last-digit histogram over the survivor list
 //   k_gather         vals / ordered sum / residual zeroing at the k indices
 //   k_zero_at        residual zeroing alone
@@ -18,6 +22,14 @@
 //
 // Keys are the 31 magnitude bits of the float32 (sign cleared), so integer
 // order on keys is the order of |x|.  The radix digits are 12 + 12 + 7 bits.
+//
+// Chunks.  A vector range is cut into at most kMaxChunks contiguous chunks, each
+// a whole number of 4096-element tiles.  The histogram pass stores, per chunk,
+// the SUFFIX sums of its top-digit histogram: S[c][b] = number of keys of chunk
+// c whose top digit is >= b.  Once the threshold digit b0 is known, S[c][b0] is
+// exactly the number of survivors chunk c will emit, so an exclusive scan over
+// the chunks gives every chunk its place in the survivor list and the big
+// compaction pass needs no communication between blocks.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -82,6 +94,66 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
   return v;  // the total, in every lane
 }
 
+constexpr int kTile = 4096;       // elements per tile: 256 threads x 4 float4
+constexpr int kMaxChunks = 1024;  // chunks per vector range
+
+struct ChunkGeom {
+  int64_t chunk0;       // first element of chunk 0 (a multiple of kTile, <= range start)
+  int64_t chunk_elems;  // elements per chunk (a multiple of kTile)
+  int32_t nchunks;
+};
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ v4f load4(const float* p) {
+  return NT ? __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p)) : *reinterpret_cast<const v4f*>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void store4(float* p, v4f v) {
+  if (NT)
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+  else
+    *reinterpret_cast<v4f*>(p) = v;
+}
+
+// Turns the 4096-bin LDS histogram `lh` of a 256-thread block into suffix sums
+// and writes them to dst[0..4096).  `red` is 256 words of LDS.  All threads of
+// the block must call it after their last histogram update.
+__device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, uint32_t* __restrict__ dst) {
+  const int t = threadIdx.x;
+  __syncthreads();
+  uint32_t v[16];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint4 q = reinterpret_cast<const uint4*>(lh)[4 * t + j];
+    v[4 * j + 0] = q.x;
+    v[4 * j + 1] = q.y;
+    v[4 * j + 2] = q.z;
+    v[4 * j + 3] = q.w;
+  }
+#pragma unroll
+  for (int j = 14; j >= 0; --j) v[j] += v[j + 1];
+  red[t] = v[0];
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    const uint32_t x = (t + off < 256) ? red[t + off] : 0u;
+    __syncthreads();
+    red[t] += x;
+    __syncthreads();
+  }
+  const uint32_t carry = (t + 1 < 256) ? red[t + 1] : 0u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint4 q;
+    q.x = v[4 * j + 0] + carry;
+    q.y = v[4 * j + 1] + carry;
+    q.z = v[4 * j + 2] + carry;
+    q.w = v[4 * j + 3] + carry;
+    reinterpret_cast<uint4*>(dst)[4 * t + j] = q;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // k_fill_zero : clears two word ranges (either may be empty)
 // ---------------------------------------------------------------------------
@@ -94,24 +166,26 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 
 // ---------------------------------------------------------------------------
 // k_pass_a : acc = g + residual (in place over residual), variance partials,
-//            top-digit histogram.
-//   grid = (nblk, W), block = 256.
-//   HIST: 0 none, 1 only worker `hist_worker` (into hist0[0]), 2 every worker
-//         (into hist0[w]).
+//            per-chunk top-digit suffix histograms.
+//   grid = (nchunks, W), block = 256; block (c, w) owns chunk c of worker w.
+//   HIST: 0 none, 1 only worker `hist_worker` (into S[0][c]), 2 every worker
+//         (into S[w][c]).
 //   Variance partials use the shift c_w = g_w[0]: per block the sums of
-//   (acc - c_w) and (acc - c_w)^2 in float64, written to partials[w][bx][0..1].
+//   (acc - c_w) and (acc - c_w)^2 in float64, written to partials[w][c][0..1].
+//   NT: non-temporal loads of g and stores of acc.
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST>
+template <bool STATS, int HIST, bool NT>
 __global__ void __launch_bounds__(256)
-k_pass_a(PtrTable g, PtrTable res, int64_t n, int hist_worker, uint32_t* __restrict__ hist0,
+k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
          double* __restrict__ partials) {
-  __shared__ uint32_t lh[HIST ? kHistBins : 1];
+  __shared__ __attribute__((aligned(16))) uint32_t lh[HIST ? kHistBins : 4];
+  __shared__ uint32_t red_u[HIST ? 256 : 1];
   __shared__ double red[2][4];
 
   const int w = blockIdx.y;
-  const int bx = blockIdx.x;
+  const int c = blockIdx.x;
   const int nblk = gridDim.x;
   const int tid = threadIdx.x;
   const float* __restrict__ gp = g.p[w];
@@ -124,38 +198,37 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, int hist_worker, uint32_t* __restr
     __syncthreads();
   }
 
-  double c = 0.0, s = 0.0, ss = 0.0;
-  if (STATS) c = (double)gp[0];  // g is never written, so every block sees the same shift
+  double cshift = 0.0, s = 0.0, ss = 0.0;
+  if (STATS) cshift = (double)gp[0];  // g is never written, so every block sees the same shift
 
-  const int64_t n4 = n >> 2;
-  const float4* __restrict__ g4 = reinterpret_cast<const float4*>(gp);
-  float4* __restrict__ r4 = reinterpret_cast<float4*>(rp);
-  const int64_t tile = 256 * kPassAUnroll;
-  const int64_t ntile = (n4 + tile - 1) / tile;
+  const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
+  int64_t c_hi = c_lo + geom.chunk_elems;
+  if (c_hi > n) c_hi = n;
+  const int64_t q_hi = c_hi >> 2;  // whole float4 groups of this chunk
 
-  for (int64_t t = bx; t < ntile; t += nblk) {
-    const int64_t q0 = t * tile + tid;
-    float4 a[kPassAUnroll], b[kPassAUnroll];
+  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += 256 * kPassAUnroll) {
+    v4f a[kPassAUnroll], b[kPassAUnroll];
 #pragma unroll
     for (int u = 0; u < kPassAUnroll; ++u) {
       const int64_t q = q0 + u * 256;
-      if (q < n4) {
-        a[u] = g4[q];
-        b[u] = r4[q];
+      if (q < q_hi) {
+        a[u] = load4<NT>(gp + 4 * q);
+        b[u] = load4<false>(rp + 4 * q);
       }
     }
 #pragma unroll
     for (int u = 0; u < kPassAUnroll; ++u) {
       const int64_t q = q0 + u * 256;
-      if (q < n4) {
-        float4 v;
+      if (q < q_hi) {
+        v4f v;
         v.x = a[u].x + b[u].x;
         v.y = a[u].y + b[u].y;
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
-        r4[q] = v;
+        store4<NT>(rp + 4 * q, v);
         if (STATS) {
-          double d0 = (double)v.x - c, d1 = (double)v.y - c, d2 = (double)v.z - c, d3 = (double)v.w - c;
+          double d0 = (double)v.x - cshift, d1 = (double)v.y - cshift, d2 = (double)v.z - cshift,
+                 d3 = (double)v.w - cshift;
           s += (d0 + d1) + (d2 + d3);
           ss = fma(d0, d0, ss);
           ss = fma(d1, d1, ss);
@@ -173,14 +246,14 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, int hist_worker, uint32_t* __restr
       }
     }
   }
-  // scalar tail (n not a multiple of 4): block 0, first threads
-  if (bx == 0) {
-    const int64_t j = n4 * 4 + tid;
+  // scalar tail (n not a multiple of 4): the block that owns the last chunk
+  if (c_hi == n) {
+    const int64_t j = (n >> 2) * 4 + tid;
     if (j < n) {
       const float v = gp[j] + rp[j];
       rp[j] = v;
       if (STATS) {
-        const double d = (double)v - c;
+        const double d = (double)v - cshift;
         s += d;
         ss = fma(d, d, ss);
       }
@@ -200,18 +273,15 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, int hist_worker, uint32_t* __restr
   }
   __syncthreads();
   if (STATS && tid == 0) {
-    const double S = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-    const double SS = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
-    partials[((size_t)w * nblk + bx) * 2 + 0] = S;
-    partials[((size_t)w * nblk + bx) * 2 + 1] = SS;
+    const double S1 = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    const double S2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    partials[((size_t)w * nblk + c) * 2 + 0] = S1;
+    partials[((size_t)w * nblk + c) * 2 + 1] = S2;
   }
   if (HIST) {
     if (do_hist) {
-      uint32_t* __restrict__ hg = hist0 + (HIST == 2 ? (size_t)w * kHistBins : 0);
-      for (int b = tid; b < kHistBins; b += 256) {
-        const uint32_t v = lh[b];
-        if (v) atomicAdd(&hg[b], v);
-      }
+      const size_t slot = (HIST == 2) ? (size_t)w : 0;
+      flush_suffix_hist(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins);
     }
   }
 }
@@ -315,52 +385,296 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
 }
 
 // ---------------------------------------------------------------------------
-// k_hist0 : top-digit histogram of |x[e_lo .. e_hi)| for the leader's vector.
-// Reads whole aligned float4 groups where they lie inside both the range and
-// the array, single elements at the edges.
+// k_hist0 : per-chunk top-digit suffix histograms of |x[e_lo .. e_hi)| for the
+// leader's vector.  grid = nchunks, block = 256.  Whole aligned float4 groups
+// are read where they lie inside the chunk and the array, single elements at
+// the ragged ends of the range.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_hist0(PtrTable tab, const int32_t* __restrict__ leader_dev, int64_t n, int64_t e_lo, int64_t e_hi,
-        uint32_t* __restrict__ hist0) {
-  __shared__ uint32_t lh[kHistBins];
+        ChunkGeom geom, uint32_t* __restrict__ S) {
+  __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
+  __shared__ uint32_t red_u[256];
   const int tid = threadIdx.x;
+  const int c = blockIdx.x;
   const float* __restrict__ xp = tab.p[*leader_dev];
   for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
   __syncthreads();
-  const int64_t q_lo = e_lo >> 2;
-  const int64_t q_hi = (e_hi + 3) >> 2;  // exclusive
-  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
-  for (int64_t q = q_lo + (int64_t)blockIdx.x * 256 + tid; q < q_hi; q += (int64_t)gridDim.x * 256) {
+  int64_t cs = geom.chunk0 + (int64_t)c * geom.chunk_elems;
+  int64_t ce = cs + geom.chunk_elems;
+  if (cs < e_lo) cs = e_lo;
+  if (ce > e_hi) ce = e_hi;
+  const int64_t q_lo = cs >> 2;
+  const int64_t q_hi = (ce + 3) >> 2;  // exclusive
+  for (int64_t q = q_lo + tid; q < q_hi; q += 256) {
     const int64_t j = q << 2;
-    if (j >= e_lo && j + 4 <= e_hi) {
-      const float4 v = x4[q];
-      atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(v.y) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(v.z) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(v.w) & kKeyMask) >> 19], 1u);
+    if (j >= cs && j + 4 <= ce) {
+      const uint4 v = *reinterpret_cast<const uint4*>(xp + j);
+      atomicAdd(&lh[(v.x & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(v.y & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(v.z & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(v.w & kKeyMask) >> 19], 1u);
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int64_t je = j + e;
-        if (je >= e_lo && je < e_hi) atomicAdd(&lh[(__float_as_uint(xp[je]) & kKeyMask) >> 19], 1u);
+        if (je >= cs && je < ce) atomicAdd(&lh[(__float_as_uint(xp[je]) & kKeyMask) >> 19], 1u);
       }
     }
   }
+  flush_suffix_hist(lh, red_u, S + (size_t)c * kHistBins);
+}
+
+// ---------------------------------------------------------------------------
+// k_reduce_hist : Ssum[b] += sum over chunks of S[slot][c][b] for the leader's
+// slot.  grid = (16, ysplit), block = 256; Ssum must be zero on entry.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_reduce_hist(const uint32_t* __restrict__ S, const int32_t* __restrict__ leader_dev, int slot_by_leader,
+              int nchunks, uint32_t* __restrict__ Ssum) {
+  const size_t slot = slot_by_leader ? (size_t)(*leader_dev) : 0;
+  const uint32_t* __restrict__ base = S + slot * kMaxChunks * kHistBins;
+  const int bin = blockIdx.x * 256 + threadIdx.x;
+  const int per = (nchunks + gridDim.y - 1) / gridDim.y;
+  const int c0 = blockIdx.y * per;
+  int c1 = c0 + per;
+  if (c1 > nchunks) c1 = nchunks;
+  uint32_t acc = 0u;
+#pragma unroll 8
+  for (int c = c0; c < c1; ++c) acc += base[(size_t)c * kHistBins + bin];
+  if (acc) atomicAdd(&Ssum[bin], acc);
+}
+
+// ---------------------------------------------------------------------------
+// k_pick0 : one block of 1024 threads.  Initialises the selection state for a
+// range of n_range elements with k wanted, finds the threshold top digit b0 =
+// the largest b with Ssum[b] >= k, and gives every chunk the offset of its
+// survivors (keys with top digit >= b0) in the survivor list.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uint32_t* __restrict__ S,
+        const int32_t* __restrict__ leader_dev, int slot_by_leader, int nchunks, uint32_t n_range, uint32_t k,
+        uint32_t* __restrict__ chunk_off, uint32_t* __restrict__ err) {
+  __shared__ uint32_t part[1024];
+  __shared__ int b0_sh;
+  const int t = threadIdx.x;
+  if (t == 0) b0_sh = -1;
+  __syncthreads();
+  uint32_t sv[5];
+#pragma unroll
+  for (int j = 0; j < 5; ++j) {
+    const int b = 4 * t + j;
+    sv[j] = (b < kHistBins) ? Ssum[b] : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (sv[j] >= k && sv[j + 1] < k) b0_sh = 4 * t + j;  // Ssum is non-increasing: one hit
+  }
+  __syncthreads();
+  const int b0 = b0_sh;
+  if (b0 < 0) {
+    if (t == 0) atomicOr(err, kErrPick);
+    return;
+  }
+  if (t == 0) {
+    SelState st;
+    const uint32_t above = (b0 + 1 < kHistBins) ? Ssum[b0 + 1] : 0u;
+    st.lo = (uint32_t)b0 << 19;
+    st.hi = st.lo | 0x7ffffu;
+    st.n_gt = above;
+    st.need = k - above;
+    st.cand = Ssum[b0] - above;
+    st.level = 1u;
+    st.compact_level = 0u;
+    st.list_count = 0u;
+    for (int i = 0; i < 8; ++i) st.pad[i] = 0u;
+    st.pad[0] = n_range;
+    *stp = st;
+  }
+  // exclusive scan of the per-chunk survivor counts
+  const size_t slot = slot_by_leader ? (size_t)(*leader_dev) : 0;
+  const uint32_t mine = (t < nchunks) ? S[(slot * kMaxChunks + (size_t)t) * kHistBins + b0] : 0u;
+  part[t] = mine;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {  // inclusive prefix sums
+    const uint32_t v = (t >= off) ? part[t - off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  if (t < nchunks) chunk_off[t] = part[t] - mine;
+}
+
+// ---------------------------------------------------------------------------
+// k_compact1 : level-1 compaction of the leader's range, one block per chunk.
+// Survivors (key >= st.lo, i.e. top digit >= b0) are written to the survivor
+// list in ascending element order at chunk_off[c] + rank inside the chunk;
+// candidates (top digit == b0) also feed the next-digit histogram hist1.
+// If the list cannot hold n_gt + cand entries nothing is written and only the
+// histogram is built.  block = 256 threads = 4 waves; a tile is 4 waves x 4
+// rows x 64 lanes x 4 consecutive elements, each wave owning 1024 consecutive
+// elements; the next tile is loaded while the current one is processed.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState* __restrict__ stp, int64_t n,
+           int64_t e_lo, int64_t e_hi, ChunkGeom geom, const uint32_t* __restrict__ chunk_off, uint32_t cap,
+           uint32_t* __restrict__ hist1, int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
+           const uint32_t* __restrict__ err) {
+  __shared__ uint32_t lh[kHistBins];
+  __shared__ uint32_t wtot[2][4];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const uint32_t lane = lane_id();
+  const int c = blockIdx.x;
+
+  const SelState st = *stp;
+  if (st.level != 1u || st.compact_level != 0u || *err) return;
+  const bool write_out = (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
+  const uint32_t klo = st.lo, khi = st.hi;
+  const float* __restrict__ xp = tab.p[*leader_dev];
+
+  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  __syncthreads();
+
+  int64_t cs = geom.chunk0 + (int64_t)c * geom.chunk_elems;
+  int64_t ce = cs + geom.chunk_elems;
+  if (ce > e_hi) ce = e_hi;
+  const int64_t t_begin = cs / kTile;                 // cs is a tile boundary
+  const int64_t t_end = (ce + kTile - 1) / kTile;     // exclusive
+  if (cs < e_lo) cs = e_lo;
+  const int64_t n_vec = n & ~(int64_t)3;
+
+  // loads the 16 keys of this lane for tile t; returns the validity mask
+  auto load_tile = [&](int64_t t, uint32_t (&key)[4][4]) -> uint32_t {
+    const int64_t wb = t * kTile + (int64_t)wave * 1024;
+    uint32_t valid = 0u;
+    if (wb >= cs && wb + 1024 <= ce && wb + 1024 <= n_vec) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xp + wb + r * 256 + lane * 4);
+        key[r][0] = v.x & kKeyMask;
+        key[r][1] = v.y & kKeyMask;
+        key[r][2] = v.z & kKeyMask;
+        key[r][3] = v.w & kKeyMask;
+      }
+      valid = 0xffffu;
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t j = wb + r * 256 + lane * 4 + e;
+          key[r][e] = 0u;
+          if (j >= cs && j < ce) {
+            valid |= 1u << (r * 4 + e);
+            key[r][e] = __float_as_uint(xp[j]) & kKeyMask;
+          }
+        }
+      }
+    }
+    return valid;
+  };
+
+  uint32_t run = write_out ? chunk_off[c] : 0u;  // survivors of this chunk written so far (+ chunk offset)
+  int buf = 0;
+
+  auto process = [&](int64_t t, const uint32_t (&key)[4][4], uint32_t valid) {
+    const int64_t wb = t * kTile + (int64_t)wave * 1024;
+    uint32_t smask = 0u;  // survivors among this lane's 16 elements
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool ok = (valid >> (r * 4 + e)) & 1u;
+        const uint32_t kk = key[r][e];
+        if (ok && kk >= klo) {
+          smask |= 1u << (r * 4 + e);
+          if (kk <= khi) atomicAdd(&lh[(kk >> 7) & 0xfffu], 1u);
+        }
+      }
+    }
+    if (!write_out) return;
+    // wave total
+    uint32_t cnt = 0u;
+    uint64_t rowany[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      rowany[r] = __ballot(((smask >> (r * 4)) & 0xfu) != 0u);
+    }
+    uint32_t rowcnt[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      rowcnt[r] = 0u;
+      if (rowany[r] != 0ull) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rowcnt[r] += (uint32_t)__popcll(__ballot((smask >> (r * 4 + e)) & 1u));
+      }
+      cnt += rowcnt[r];
+    }
+    if (lane == 0) wtot[buf][wave] = cnt;
+    __syncthreads();
+    uint32_t base = run;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t wt = wtot[buf][i];
+      if (i < wave) base += wt;
+      run += wt;
+    }
+    buf ^= 1;
+    if (cnt != 0u) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (rowcnt[r] != 0u) {
+          uint32_t lt = 0u;
+          uint32_t own = (smask >> (r * 4)) & 0xfu;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) lt += popc_lt(__ballot((own >> e) & 1u));
+          uint32_t pos = base + lt;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if ((own >> e) & 1u) {
+              if (pos < cap) {
+                list_idx[pos] = (int32_t)(wb + r * 256 + lane * 4 + e);
+                list_key[pos] = key[r][e];
+              }
+              ++pos;
+            }
+          }
+          base += rowcnt[r];
+        }
+      }
+    }
+  };
+
+  uint32_t k0[4][4], k1[4][4];
+  uint32_t v0 = 0u, v1 = 0u;
+  if (t_begin < t_end) v0 = load_tile(t_begin, k0);
+  for (int64_t t = t_begin; t < t_end; t += 2) {
+    const bool has1 = t + 1 < t_end;
+    if (has1) v1 = load_tile(t + 1, k1);
+    process(t, k0, v0);
+    if (has1) {
+      if (t + 2 < t_end) v0 = load_tile(t + 2, k0);
+      process(t + 1, k1, v1);
+    }
+  }
+
   __syncthreads();
   for (int b = tid; b < kHistBins; b += 256) {
     const uint32_t v = lh[b];
-    if (v) atomicAdd(&hist0[b], v);
+    if (v) atomicAdd(&hist1[b], v);
   }
 }
 
 // ---------------------------------------------------------------------------
 // k_pick : one block of 1024 threads narrows the candidate range by one digit.
 //
-//   stage 0 : initialise the state for a range of `n_range` elements with `k`
-//             wanted, then resolve digit 0 from hist (level 0 -> 1).
-//   stage 1,2 (after the array compaction launched at that level): if the list
-//             has not been written yet and state.level == stage, record whether
-//             that compaction wrote the list, then resolve digit `stage`.
+//   stage 1 (after k_compact1): record whether that pass wrote the list, then
+//             resolve digit 1 from hist1.
+//   stage 2 (after the level-2 array compaction): if the list has not been
+//             written and state.level == 2, record whether that pass wrote it,
+//             then resolve digit 2.
 //   stage 3 : after the level-3 array compaction: record the list.
 //   stage 4 : after the list histogram: resolve digit 2 if the list was written
 //             at level 1.
@@ -372,9 +686,8 @@ __device__ __forceinline__ bool fits_list(const SelState& st, uint32_t cap) {
 }
 
 __global__ void __launch_bounds__(1024)
-k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, const int32_t* __restrict__ leader_dev,
-       int hist_stride, int stage, uint32_t n_range, uint32_t k, uint32_t cap, uint32_t* __restrict__ err) {
-  if (hist_stride) hist += (size_t)(*leader_dev) * (size_t)hist_stride;
+k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, int stage, uint32_t cap,
+       uint32_t* __restrict__ err) {
   __shared__ uint32_t part[1024];
   __shared__ SelState st;
   __shared__ int run_pick;
@@ -384,17 +697,7 @@ k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, const int3
     st = *stp;
     found = 0u;
     int digit = -1;
-    if (stage == 0) {
-      st.lo = 0u;
-      st.hi = kKeyMask;
-      st.n_gt = 0u;
-      st.need = k;
-      st.cand = n_range;
-      st.level = 0u;
-      st.compact_level = 0u;
-      st.list_count = 0u;
-      digit = 0;
-    } else if (stage == 1 || stage == 2) {
+    if (stage == 1 || stage == 2) {
       if (st.compact_level == 0u && st.level == (uint32_t)stage) {
         if (fits_list(st, cap)) {
           st.compact_level = (uint32_t)stage;
