@@ -58,12 +58,18 @@ enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2 };
 
 #define ARTOPK_MAX_WORKERS 64
 
-/* Stages whose duration artopk_get_profile() reports (milliseconds). */
+/* Stages whose duration artopk_get_profile() reports (milliseconds).  With the
+ * leader known up front (STAR / FIXED, unsegmented) the step runs the leader's
+ * pass and the selection first and then ONE fused pass over the other W-1
+ * workers; that pass is reported as ARTOPK_PROF_GATHER. */
 enum {
-  ARTOPK_PROF_PASS_A = 0, /* fused EF add + variance partials + histogram      */
+  ARTOPK_PROF_PASS_A = 0, /* fused EF add + variance partials + histograms
+                             (VAR: all workers; leader known: the leader only)  */
   ARTOPK_PROF_SELECT = 1, /* everything between pass A and the final idx       */
-  ARTOPK_PROF_GATHER = 2, /* gather + ordered sum + residual zeroing           */
-  ARTOPK_PROF_UPDATE = 3, /* dense update fill                                 */
+  ARTOPK_PROF_GATHER = 2, /* VAR: gather + ordered sum + residual zeroing;
+                             leader known: fused EF add + gather + zeroing of
+                             the W-1 other workers                              */
+  ARTOPK_PROF_UPDATE = 3, /* (leader zeroing, ordered sum,) dense update fill  */
   ARTOPK_PROF_TOTAL = 4,  /* whole call                                        */
   ARTOPK_PROF_COUNT = 5
 };
@@ -161,8 +167,10 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
                 float* sum_out, float* update_out);
 
 /*
- * Stage timing.  With profiling enabled every call records HIP events on the
- * context's stream around its stages.  artopk_get_profile synchronises the
+ * Stage timing.  enable = 1 brackets only the dominant kernel of every
+ * artopk_step (PASS_A, or GATHER when the leader is known up front) with two
+ * HIP events on the context's stream; enable = 2 records
+ * an event at every stage boundary; 0 switches it off.  artopk_get_profile synchronises the
  * stream and writes up to `count` stage durations in milliseconds (order: the
  * ARTOPK_PROF_* enum; stages that did not run report 0), each averaged over
  * the calls made since profiling was enabled (at most the 64 most recent).

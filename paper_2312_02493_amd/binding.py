@@ -124,8 +124,9 @@ class Context:
     def status(self):
         self._check(self._lib.artopk_status(self._h))
 
-    def set_profile(self, enable: bool):
-        self._check(self._lib.artopk_set_profile(self._h, 1 if enable else 0))
+    def set_profile(self, level: int):
+        """0 off, 1 events around pass A only, 2 events at every stage boundary."""
+        self._check(self._lib.artopk_set_profile(self._h, int(level)))
 
     def get_profile(self) -> dict:
         buf = (C.c_float * len(PROF_NAMES))()

@@ -42,6 +42,7 @@ struct Scratch {
   uint32_t* err_dev = nullptr;
   int32_t* list_idx = nullptr;
   uint32_t* list_key = nullptr;
+  float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
   uint32_t cap = 0;               // usable list entries
 };
 
@@ -54,12 +55,15 @@ struct artopk_ctx {
   int32_t max_w = 0;
   int64_t max_n = 0, max_k = 0;
   int32_t max_seg = 0;
-  bool pass_a_nt = true;  // non-temporal g loads / acc stores in pass A
+  bool pass_a_nt = true;   // non-temporal g loads / acc stores in pass A
+  bool leader_first = true;  // STAR / FIXED: leader pass + select first, then one fused pass over the rest
   void* slab = nullptr;
   Scratch s;
   // stage events: a ring of the most recent calls, 5 marks per call
   // (0 start, 1 after pass A, 2 after select, 3 after gather, 4 after update)
   bool profile = false;
+  int profile_level = 0;
+  int lvl1_a = 0, lvl1_b = 1;  // the two marks level 1 records (they bracket the dominant kernel)
   static constexpr int kRing = 64;
   static constexpr int kMarks = 5;
   hipEvent_t ev[kRing][kMarks] = {};
@@ -173,6 +177,7 @@ int stats_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
 
 void prof_mark(artopk_ctx* c, int mark) {
   if (!c->profile) return;
+  if (c->profile_level < 2 && !(mark == c->lvl1_a || mark == c->lvl1_b)) return;  // level 1: dominant kernel only
   if (hipEventRecord(c->ev[c->cur][mark], c->stream) == hipSuccess) c->ev_valid[c->cur][mark] = true;
 }
 
@@ -208,7 +213,7 @@ int64_t tiles_of_range(int64_t e_lo, int64_t e_hi) {
 // per-chunk suffix histograms of the range (layout make_geom(e_lo, e_hi)) are
 // already in S, in slot *leader_dev if slot_by_leader, else in slot 0.
 int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, int64_t e_hi, int64_t k,
-                   int32_t* idx_out, bool hist_ready, int slot_by_leader) {
+                   int32_t* idx_out, bool hist_ready, int slot_by_leader, float* vals_row = nullptr) {
   Scratch& s = c->s;
   hipStream_t st = c->stream;
   const int64_t nrange = e_hi - e_lo;
@@ -227,7 +232,7 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
                      slot_by_leader, (int)geom.nchunks, s.ssum);
   hipLaunchKernelGGL(k_pick0, dim3(1), dim3(1024), 0, st, s.state, s.ssum, s.S, s.leader_dev, slot_by_leader,
                      (int)geom.nchunks, (uint32_t)nrange, (uint32_t)k, s.chunk_off, s.err_dev);
-  hipLaunchKernelGGL(k_compact1, dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, s.state, n, e_lo, e_hi,
+  hipLaunchKernelGGL(k_compact1, dim3(geom.nchunks), dim3(kC1Threads), 0, st, tab, s.leader_dev, s.state, n, e_lo, e_hi,
                      geom, s.chunk_off, cap, s.hist1, s.list_idx, s.list_key, s.err_dev);
   hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist1, 1, cap, s.err_dev);
 
@@ -237,7 +242,8 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
   for (int level = 2; level <= 3; ++level) {
     hipLaunchKernelGGL(k_compact<false>, dim3(cblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev,
                        s.state, level, n, e_lo, e_hi, cap, s.hist2, s.flags + (level - 2), kNumCompactLaunches,
-                       s.counters + (level - 2), s.list_idx, s.list_key, (int32_t*)nullptr, 0u, s.err_dev);
+                       s.counters + (level - 2), s.list_idx, s.list_key, (int32_t*)nullptr, (float*)nullptr, 0u,
+                       s.err_dev);
     hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, level, cap, s.err_dev);
   }
   // the list holds n_gt + cand <= cap entries
@@ -252,7 +258,7 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
   if (fblocks < 1) fblocks = 1;
   hipLaunchKernelGGL(k_compact<true>, dim3(fblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev, s.state,
                      3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 2,
-                     kNumCompactLaunches, s.counters + 2, s.list_idx, s.list_key, idx_out, (uint32_t)k,
+                     kNumCompactLaunches, s.counters + 2, s.list_idx, s.list_key, idx_out, vals_row, (uint32_t)k,
                      s.err_dev);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
@@ -332,6 +338,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   }
   c->num_cu = cus > 0 ? cus : 256;
   if (const char* e_nt = getenv("ARTOPK_PASS_A_NT")) c->pass_a_nt = atoi(e_nt) != 0;
+  if (const char* e_lf = getenv("ARTOPK_LEADER_FIRST")) c->leader_first = atoi(e_lf) != 0;
 
   Scratch& s = c->s;
   // list capacity: every key above the range (< k of them) plus a generous share of candidates
@@ -366,6 +373,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_err = take(sizeof(uint32_t));
   const size_t o_lidx = take(cap_pad * sizeof(int32_t));
   const size_t o_lkey = take(cap_pad * sizeof(uint32_t));
+  const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
   const size_t total = off;
 
   e = hipMalloc(&c->slab, total);
@@ -390,6 +398,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
   s.list_idx = reinterpret_cast<int32_t*>(base + o_lidx);
   s.list_key = reinterpret_cast<uint32_t*>(base + o_lkey);
+  s.vals = reinterpret_cast<float*>(base + o_vals);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
@@ -435,6 +444,7 @@ int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
     ctx->ev_created = true;
   }
   ctx->profile = enable != 0;
+  ctx->profile_level = enable;
   ctx->prof_calls = 0;
   for (int r = 0; r < artopk_ctx::kRing; ++r)
     for (int i = 0; i < artopk_ctx::kMarks; ++i) ctx->ev_valid[r][i] = false;
@@ -565,6 +575,49 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   const dim3 grid(geom.nchunks, w), block(256);
   const bool nt = ctx->pass_a_nt;
 
+  if (mode != ARTOPK_VAR && !segmented && ctx->leader_first) {
+    // The leader is known up front: run its pass and the selection first, then
+    // stream over the other workers once, gathering and zeroing on the way.
+    const int L = leader_host;
+    ctx->lvl1_a = 2;
+    ctx->lvl1_b = 3;
+    float* vals = vals_out ? vals_out : s.vals;
+    const float* g1[1] = {g[L]};
+    const float* r1[1] = {residual[L]};
+    const PtrTable g1t = make_table(g1, 1), r1t = make_table(r1, 1);
+    prof_begin(ctx);
+    prof_mark(ctx, 0);
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
+    if (nt)
+      hipLaunchKernelGGL((k_pass_a<false, 1, true>), dim3(geom.nchunks, 1), block, 0, st, g1t, r1t, n, geom, 0, s.S,
+                         s.partials);
+    else
+      hipLaunchKernelGGL((k_pass_a<false, 1, false>), dim3(geom.nchunks, 1), block, 0, st, g1t, r1t, n, geom, 0, s.S,
+                         s.partials);
+    hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)L, s.leader_dev, leader_out);
+    prof_mark(ctx, 1);
+    if ((rc = enqueue_select(ctx, rt, n, 0, n, k, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
+    prof_mark(ctx, 2);
+    if (w > 1) {
+      if (nt)
+        hipLaunchKernelGGL((k_pass_rest<true>), dim3(geom.nchunks, w - 1), block, 0, st, gt, rt, (int)w, L, n, geom,
+                           idx_out, k, vals);
+      else
+        hipLaunchKernelGGL((k_pass_rest<false>), dim3(geom.nchunks, w - 1), block, 0, st, gt, rt, (int)w, L, n, geom,
+                           idx_out, k, vals);
+    }
+    prof_mark(ctx, 3);
+    const int kblocks = (int)((k + 255) / 256);
+    hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
+    hipLaunchKernelGGL(k_sum_rows, dim3(kblocks), dim3(256), 0, st, vals, (int)w, k, sum_out);
+    HIP_TRY(ctx, hipGetLastError());
+    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+    prof_mark(ctx, 4);
+    return ARTOPK_OK;
+  }
+
+  ctx->lvl1_a = 0;
+  ctx->lvl1_b = 1;
   prof_begin(ctx);
   prof_mark(ctx, 0);
   // the flat select reuses the histograms pass A builds; segments build their own

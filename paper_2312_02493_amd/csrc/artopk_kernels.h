@@ -16,6 +16,9 @@
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
 //   k_list_hist      last-digit histogram over the survivor list
+//   k_pass_rest      (leader known up front) EF add + gather + residual zeroing
+//                    of all other workers in one streaming pass
+//   k_sum_rows       ordered sum over the workers' gathered rows
 //   k_gather         vals / ordered sum / residual zeroing at the k indices
 //   k_zero_at        residual zeroing alone
 //   k_update_fill    dense update = zeros + k scattered sums, written once
@@ -94,7 +97,7 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
   return v;  // the total, in every lane
 }
 
-constexpr int kTile = 4096;       // elements per tile: 256 threads x 4 float4
+constexpr int kTile = 8192;       // chunk granularity = compaction tile (two pass-A tiles)
 constexpr int kMaxChunks = 1024;  // chunks per vector range
 
 struct ChunkGeom {
@@ -184,7 +187,8 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   __shared__ uint32_t red_u[HIST ? 256 : 1];
   __shared__ double red[2][4];
 
-  const int w = blockIdx.y;
+  // with a known leader its blocks (the only ones that build histograms) are dispatched first
+  const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
   const int c = blockIdx.x;
   const int nblk = gridDim.x;
   const int tid = threadIdx.x;
@@ -511,17 +515,21 @@ k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uin
 // list in ascending element order at chunk_off[c] + rank inside the chunk;
 // candidates (top digit == b0) also feed the next-digit histogram hist1.
 // If the list cannot hold n_gt + cand entries nothing is written and only the
-// histogram is built.  block = 256 threads = 4 waves; a tile is 4 waves x 4
+// histogram is built.  block = 512 threads = 8 waves; a tile is 8 waves x 4
 // rows x 64 lanes x 4 consecutive elements, each wave owning 1024 consecutive
 // elements; the next tile is loaded while the current one is processed.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+constexpr int kC1Waves = 8;
+constexpr int kC1Threads = 64 * kC1Waves;
+static_assert(kTile == 1024 * kC1Waves, "each wave owns 1024 consecutive elements of a tile");
+
+__global__ void __launch_bounds__(kC1Threads)
 k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState* __restrict__ stp, int64_t n,
            int64_t e_lo, int64_t e_hi, ChunkGeom geom, const uint32_t* __restrict__ chunk_off, uint32_t cap,
            uint32_t* __restrict__ hist1, int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
            const uint32_t* __restrict__ err) {
   __shared__ uint32_t lh[kHistBins];
-  __shared__ uint32_t wtot[2][4];
+  __shared__ uint32_t wtot[2][kC1Waves];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -534,134 +542,111 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
   const uint32_t klo = st.lo, khi = st.hi;
   const float* __restrict__ xp = tab.p[*leader_dev];
 
-  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  for (int b = tid; b < kHistBins; b += kC1Threads) lh[b] = 0u;
   __syncthreads();
 
-  int64_t cs = geom.chunk0 + (int64_t)c * geom.chunk_elems;
-  int64_t ce = cs + geom.chunk_elems;
-  if (ce > e_hi) ce = e_hi;
-  const int64_t t_begin = cs / kTile;                 // cs is a tile boundary
-  const int64_t t_end = (ce + kTile - 1) / kTile;     // exclusive
-  if (cs < e_lo) cs = e_lo;
+  const int64_t c_begin = geom.chunk0 + (int64_t)c * geom.chunk_elems;  // a tile boundary
+  const int64_t c_end = c_begin + geom.chunk_elems;
+  const int64_t cs = c_begin > e_lo ? c_begin : e_lo;  // elements of the range owned by this chunk
+  const int64_t ce = c_end < e_hi ? c_end : e_hi;
   const int64_t n_vec = n & ~(int64_t)3;
+  // every group of four this block touches is a whole, in-range, in-bounds group
+  const bool clean = (c_begin >= e_lo) && (c_end <= e_hi) && (c_end <= n_vec);
+  const int64_t t_begin = c_begin / kTile;
+  const int64_t t_end = (ce + kTile - 1) / kTile;  // exclusive; <= t_begin when the chunk is empty
+  const int64_t lane_off = (int64_t)wave * 1024 + (int64_t)lane * 4;
 
-  // loads the 16 keys of this lane for tile t; returns the validity mask
-  auto load_tile = [&](int64_t t, uint32_t (&key)[4][4]) -> uint32_t {
-    const int64_t wb = t * kTile + (int64_t)wave * 1024;
-    uint32_t valid = 0u;
-    if (wb >= cs && wb + 1024 <= ce && wb + 1024 <= n_vec) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint4 v = *reinterpret_cast<const uint4*>(xp + wb + r * 256 + lane * 4);
-        key[r][0] = v.x & kKeyMask;
-        key[r][1] = v.y & kKeyMask;
-        key[r][2] = v.z & kKeyMask;
-        key[r][3] = v.w & kKeyMask;
-      }
-      valid = 0xffffu;
-    } else {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int64_t j = wb + r * 256 + lane * 4 + e;
-          key[r][e] = 0u;
-          if (j >= cs && j < ce) {
-            valid |= 1u << (r * 4 + e);
-            key[r][e] = __float_as_uint(xp[j]) & kKeyMask;
-          }
-        }
-      }
-    }
-    return valid;
-  };
-
-  uint32_t run = write_out ? chunk_off[c] : 0u;  // survivors of this chunk written so far (+ chunk offset)
-  int buf = 0;
-
-  auto process = [&](int64_t t, const uint32_t (&key)[4][4], uint32_t valid) {
-    const int64_t wb = t * kTile + (int64_t)wave * 1024;
-    uint32_t smask = 0u;  // survivors among this lane's 16 elements
+  // raw bits of this lane's 4 x 4 elements of tile t (bits outside the array read as 0)
+  auto load_tile = [&](int64_t t, uint4 (&v)[4]) {
+    const int64_t j0 = t * kTile + lane_off;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
+      const int64_t j = j0 + r * 256;
+      if (clean || j + 4 <= n_vec) {
+        v[r] = *reinterpret_cast<const uint4*>(xp + j);
+      } else {
+        v[r].x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
+        v[r].y = (j + 1 < n) ? __float_as_uint(xp[j + 1]) : 0u;
+        v[r].z = (j + 2 < n) ? __float_as_uint(xp[j + 2]) : 0u;
+        v[r].w = (j + 3 < n) ? __float_as_uint(xp[j + 3]) : 0u;
+      }
+    }
+  };
+
+  uint32_t run = write_out ? chunk_off[c] : 0u;  // list position of the next survivor of this chunk
+  int buf = 0;
+  uint4 cur[4], nxt[4];
+  if (t_begin < t_end) load_tile(t_begin, cur);
+
+  for (int64_t t = t_begin; t < t_end; ++t) {
+    if (t + 1 < t_end) load_tile(t + 1, nxt);
+
+    const int64_t j0 = t * kTile + lane_off;
+    // one lane mask per element slot: which lanes hold a survivor there
+    uint64_t bm[16];
+    uint32_t cnt = 0u;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t kk[4] = {cur[r].x & kKeyMask, cur[r].y & kKeyMask, cur[r].z & kKeyMask, cur[r].w & kKeyMask};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const bool ok = (valid >> (r * 4 + e)) & 1u;
-        const uint32_t kk = key[r][e];
-        if (ok && kk >= klo) {
-          smask |= 1u << (r * 4 + e);
-          if (kk <= khi) atomicAdd(&lh[(kk >> 7) & 0xfffu], 1u);
+        bool ok = kk[e] >= klo;
+        if (!clean) {
+          const int64_t j = j0 + r * 256 + e;
+          ok = ok && j >= cs && j < ce;
+        }
+        const uint64_t m = __ballot(ok);
+        bm[r * 4 + e] = m;
+        if (m != 0ull) {
+          cnt += (uint32_t)__popcll(m);
+          if (ok && kk[e] <= khi) atomicAdd(&lh[(kk[e] >> 7) & 0xfffu], 1u);
         }
       }
     }
-    if (!write_out) return;
-    // wave total
-    uint32_t cnt = 0u;
-    uint64_t rowany[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      rowany[r] = __ballot(((smask >> (r * 4)) & 0xfu) != 0u);
-    }
-    uint32_t rowcnt[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      rowcnt[r] = 0u;
-      if (rowany[r] != 0ull) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) rowcnt[r] += (uint32_t)__popcll(__ballot((smask >> (r * 4 + e)) & 1u));
-      }
-      cnt += rowcnt[r];
-    }
-    if (lane == 0) wtot[buf][wave] = cnt;
-    __syncthreads();
-    uint32_t base = run;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t wt = wtot[buf][i];
-      if (i < wave) base += wt;
-      run += wt;
-    }
-    buf ^= 1;
-    if (cnt != 0u) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (rowcnt[r] != 0u) {
-          uint32_t lt = 0u;
-          uint32_t own = (smask >> (r * 4)) & 0xfu;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) lt += popc_lt(__ballot((own >> e) & 1u));
-          uint32_t pos = base + lt;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if ((own >> e) & 1u) {
-              if (pos < cap) {
-                list_idx[pos] = (int32_t)(wb + r * 256 + lane * 4 + e);
-                list_key[pos] = key[r][e];
-              }
-              ++pos;
-            }
-          }
-          base += rowcnt[r];
-        }
-      }
-    }
-  };
 
-  uint32_t k0[4][4], k1[4][4];
-  uint32_t v0 = 0u, v1 = 0u;
-  if (t_begin < t_end) v0 = load_tile(t_begin, k0);
-  for (int64_t t = t_begin; t < t_end; t += 2) {
-    const bool has1 = t + 1 < t_end;
-    if (has1) v1 = load_tile(t + 1, k1);
-    process(t, k0, v0);
-    if (has1) {
-      if (t + 2 < t_end) v0 = load_tile(t + 2, k0);
-      process(t + 1, k1, v1);
+    if (write_out) {
+      if (lane == 0) wtot[buf][wave] = cnt;
+      __syncthreads();
+      uint32_t base = run;
+#pragma unroll
+      for (int i = 0; i < kC1Waves; ++i) {
+        const uint32_t wt = wtot[buf][i];
+        if (i < wave) base += wt;
+        run += wt;
+      }
+      buf ^= 1;
+      if (cnt != 0u) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint64_t rowm = bm[r * 4] | bm[r * 4 + 1] | bm[r * 4 + 2] | bm[r * 4 + 3];
+          if (rowm != 0ull) {
+            // survivors of lower lanes in this row come first, then this lane's own in slot order
+            uint32_t pos = base;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pos += popc_lt(bm[r * 4 + e]);
+            const uint32_t kk[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if ((bm[r * 4 + e] >> lane) & 1ull) {
+                if (pos < cap) {
+                  list_idx[pos] = (int32_t)(j0 + r * 256 + e);
+                  list_key[pos] = kk[e];  // raw bits: the sign travels with the survivor
+                }
+                ++pos;
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) base += (uint32_t)__popcll(bm[r * 4 + e]);
+          }
+        }
+      }
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) cur[r] = nxt[r];
   }
 
   __syncthreads();
-  for (int b = tid; b < kHistBins; b += 256) {
+  for (int b = tid; b < kHistBins; b += kC1Threads) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&hist1[b], v);
   }
@@ -839,7 +824,9 @@ __device__ uint64_t lookback_exclusive(uint64_t* __restrict__ flags, int flag_st
 //     if the list has not been written and st.level == level; writes the list
 //     only if it fits (otherwise the pass only feeds the next digit histogram).
 //   SRC_LIST (LIST = true): elements are the survivor list, kept entries'
-//     indices go to idx_out[0 .. k).  Requires level 3.
+//     indices go to idx_out[0 .. k) and, if vals_row is given, their values
+//     (the list carries the raw float bits) to vals_row[0 .. k).  Requires
+//     level 3.
 //
 //   block = 512 threads = 8 waves; a tile is 8 waves x 8 rows x 64 lanes x 4
 //   consecutive elements, each wave owning a contiguous 2048-element piece.
@@ -855,7 +842,8 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
           int64_t n, int64_t e_lo, int64_t e_hi, uint32_t cap, uint32_t* __restrict__ hist_next,
           uint64_t* __restrict__ flags, int flag_stride, uint32_t* __restrict__ tile_counter,
           int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
-          int32_t* __restrict__ idx_out, uint32_t k_out, uint32_t* __restrict__ err) {
+          int32_t* __restrict__ idx_out, float* __restrict__ vals_row, uint32_t k_out,
+          uint32_t* __restrict__ err) {
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint64_t wave_tot[8];
   __shared__ uint64_t tile_excl;
@@ -930,10 +918,10 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
           pay[LIST ? r : 0][2] = pv.z;
           pay[LIST ? r : 0][3] = pv.w;
         }
-        key[r][0] = v.x & kKeyMask;
-        key[r][1] = v.y & kKeyMask;
-        key[r][2] = v.z & kKeyMask;
-        key[r][3] = v.w & kKeyMask;
+        key[r][0] = v.x;  // raw bits; comparisons mask the sign off
+        key[r][1] = v.y;
+        key[r][2] = v.z;
+        key[r][3] = v.w;
       }
       valid = 0xffffffffu;
     } else {
@@ -947,9 +935,9 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
           if (j >= e_lo && j < e_hi) {
             valid |= 1u << (r * 4 + e);
             if (!LIST) {
-              key[r][e] = __float_as_uint(xp[j]) & kKeyMask;
+              key[r][e] = __float_as_uint(xp[j]);
             } else {
-              key[r][e] = list_key[j] & kKeyMask;
+              key[r][e] = list_key[j];
               pay[LIST ? r : 0][e] = list_idx[j];
             }
           }
@@ -965,13 +953,14 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const bool ok = (valid >> (r * 4 + e)) & 1u;
-        const bool a = ok && key[r][e] > khi;
-        const bool b = ok && key[r][e] >= klo && key[r][e] <= khi;
+        const uint32_t mk = key[r][e] & kKeyMask;
+        const bool a = ok && mk > khi;
+        const bool b = ok && mk >= klo && mk <= khi;
         if (a) isA |= 1u << (r * 4 + e);
         if (b) isB |= 1u << (r * 4 + e);
         cntA += (uint32_t)__popcll(__ballot(a));
         cntB += (uint32_t)__popcll(__ballot(b));
-        if (do_hist && b) atomicAdd(&lh[(key[r][e] >> dshift) & dmask], 1u);
+        if (do_hist && b) atomicAdd(&lh[(mk >> dshift) & dmask], 1u);
       }
     }
 
@@ -1023,7 +1012,10 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
                     list_key[pos] = key[r][e];
                   }
                 } else {
-                  if (pos < k_out) idx_out[pos] = pay[LIST ? r : 0][e];
+                  if (pos < k_out) {
+                    idx_out[pos] = pay[LIST ? r : 0][e];
+                    if (vals_row) vals_row[pos] = __uint_as_float(key[r][e]);
+                  }
                 }
               }
               befA += a ? 1u : 0u;
@@ -1062,7 +1054,7 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
   __syncthreads();
   const uint32_t cnt = st.list_count;
   for (uint32_t p = blockIdx.x * 256u + tid; p < cnt; p += gridDim.x * 256u) {
-    const uint32_t key = list_key[p];
+    const uint32_t key = list_key[p] & kKeyMask;
     if (key >= st.lo && key <= st.hi) atomicAdd(&lh[key & 0x7fu], 1u);
   }
   __syncthreads();
@@ -1070,6 +1062,142 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
     const uint32_t v = lh[tid];
     if (v) atomicAdd(&hist2[tid], v);
   }
+}
+
+// ---------------------------------------------------------------------------
+// k_pass_rest : for every worker except the leader, in one streaming pass:
+//   acc = g + residual; at the kept indices vals[w][m] = acc and the residual
+//   becomes +0.0, elsewhere the residual becomes acc.
+// Used when the leader is known before the step starts (its own pass and the
+// selection have already run, so idx is final).  grid = (nchunks, W-1), block =
+// 256; block (c, y) owns chunk c of worker (leader + 1 + y) mod W.  The block
+// finds its first index with a 256-way search; per 4096-element tile it marks
+// the kept positions in an LDS slot table (slot = m or -1) while the tile's
+// loads are in flight.
+// ---------------------------------------------------------------------------
+template <bool NT>
+__global__ void __launch_bounds__(256)
+k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkGeom geom,
+            const int32_t* __restrict__ idx, int64_t k, float* __restrict__ vals) {
+  __shared__ __attribute__((aligned(16))) int32_t slot[4096];
+  __shared__ int64_t s_lo, s_hi;
+  const int tid = threadIdx.x;
+  const int c = blockIdx.x;
+  const int w = (int)(((unsigned)leader + 1u + blockIdx.y) % (unsigned)w_count);
+  const float* __restrict__ gp = g.p[w];
+  float* __restrict__ rp = res.p[w];
+  float* __restrict__ vrow = vals + (size_t)w * (size_t)k;
+
+  const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
+  int64_t c_hi = c_lo + geom.chunk_elems;
+  if (c_hi > n) c_hi = n;
+  if (c_lo >= c_hi) return;
+
+  // m = number of indices below c_lo
+  if (tid == 0) {
+    s_lo = 0;
+    s_hi = k;
+  }
+  __syncthreads();
+  while (true) {
+    const int64_t lo = s_lo, hi = s_hi;
+    const int64_t span = hi - lo;
+    if (span <= 0) break;
+    const int64_t stepw = (span + 255) / 256;
+    const int64_t p = lo + (int64_t)tid * stepw;
+    const bool below = (p < hi) && ((int64_t)idx[p] < c_lo);
+    const int cnt = __syncthreads_count(below);
+    if (tid == 0) {
+      if (cnt == 0) {
+        s_hi = lo;
+      } else {
+        const int64_t nlo = lo + (int64_t)(cnt - 1) * stepw + 1;
+        int64_t nhi = lo + (int64_t)cnt * stepw;
+        if (nhi > hi) nhi = hi;
+        s_lo = nlo;
+        s_hi = nhi;
+      }
+    }
+    __syncthreads();
+  }
+  int64_t m = s_lo;
+
+  const int64_t q_end = c_hi >> 2;  // whole float4 groups end here
+  for (int64_t lo = c_lo; lo < c_hi; lo += 4096) {
+    const int64_t hi = (lo + 4096 < c_hi) ? lo + 4096 : c_hi;
+    const int64_t q0 = (lo >> 2) + tid;
+    v4f a[4], b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < q_end) {
+        a[u] = load4<NT>(gp + 4 * q);
+        b[u] = load4<false>(rp + 4 * q);
+      }
+    }
+    int4* s4 = reinterpret_cast<int4*>(slot);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s4[tid + u * 256] = make_int4(-1, -1, -1, -1);
+    __syncthreads();
+    while (true) {
+      const int64_t p = m + tid;
+      int64_t i = hi;
+      if (p < k) i = (int64_t)idx[p];
+      const bool in = i < hi;
+      if (in && i >= lo) slot[i - lo] = (int32_t)p;
+      const int cnt = __syncthreads_count(in);
+      m += cnt;
+      if (cnt < 256) break;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t q = q0 + u * 256;
+      if (q < q_end) {
+        const int4 sl = s4[tid + u * 256];
+        v4f v;
+        v.x = a[u].x + b[u].x;
+        v.y = a[u].y + b[u].y;
+        v.z = a[u].z + b[u].z;
+        v.w = a[u].w + b[u].w;
+        if (sl.x >= 0) { vrow[sl.x] = v.x; v.x = 0.0f; }
+        if (sl.y >= 0) { vrow[sl.y] = v.y; v.y = 0.0f; }
+        if (sl.z >= 0) { vrow[sl.z] = v.z; v.z = 0.0f; }
+        if (sl.w >= 0) { vrow[sl.w] = v.w; v.w = 0.0f; }
+        store4<NT>(rp + 4 * q, v);
+      }
+    }
+    __syncthreads();  // the slot table is rebuilt for the next tile
+  }
+  // scalar tail of the vector (n not a multiple of 4): the block that owns the last chunk
+  if (c_hi == n) {
+    const int64_t j = (n >> 2) * 4 + tid;
+    if (j < n) {
+      float v = gp[j] + rp[j];
+      int64_t lo = 0, hi = k;  // binary search for j among the indices
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)idx[mid] < j) lo = mid + 1; else hi = mid;
+      }
+      if (lo < k && (int64_t)idx[lo] == j) {
+        vrow[lo] = v;
+        v = 0.0f;
+      }
+      rp[j] = v;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_sum_rows : sum[m] = ((vals[0][m] + vals[1][m]) + ...) + vals[W-1][m], float32,
+// in that order.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_sum_rows(const float* __restrict__ vals, int w_count, int64_t k, float* __restrict__ sum) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= k) return;
+  float s = vals[m];
+  for (int w = 1; w < w_count; ++w) s = s + vals[(size_t)w * (size_t)k + (size_t)m];
+  sum[m] = s;
 }
 
 // ---------------------------------------------------------------------------
@@ -1089,12 +1217,19 @@ k_gather(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx, 
     return;
   }
   float s = 0.0f;
-  for (int w = 0; w < w_count; ++w) {
-    float* __restrict__ xp = tab.p[w];
-    const float v = xp[i];
-    if (vals) vals[(size_t)w * (size_t)k + (size_t)m] = v;
-    s = (w == 0) ? v : (s + v);
-    if (ZERO) xp[i] = 0.0f;
+  for (int w0 = 0; w0 < w_count; w0 += 8) {  // eight independent loads in flight, then the ordered adds
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (w0 + j < w_count) v[j] = tab.p[w0 + j][i];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (w0 + j < w_count) {
+        if (vals) vals[(size_t)(w0 + j) * (size_t)k + (size_t)m] = v[j];
+        s = (w0 + j == 0) ? v[j] : (s + v[j]);
+        if (ZERO) tab.p[w0 + j][i] = 0.0f;
+      }
+    }
   }
   sum[m] = s;
 }
