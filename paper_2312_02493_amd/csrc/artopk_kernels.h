@@ -120,40 +120,43 @@ __device__ __forceinline__ void store4(float* p, v4f v) {
     *reinterpret_cast<v4f*>(p) = v;
 }
 
-// Turns the 4096-bin LDS histogram `lh` of a 256-thread block into suffix sums
-// and writes them to dst[0..4096).  `red` is 256 words of LDS.  All threads of
+// Turns the 4096-bin LDS histogram `lh` of a T-thread block into suffix sums
+// and writes them to dst[0..4096).  `red` is T words of LDS.  All threads of
 // the block must call it after their last histogram update.
+template <int T>
 __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, uint32_t* __restrict__ dst) {
+  constexpr int BPT = kHistBins / T;  // consecutive bins per thread (a multiple of 4)
+  static_assert(BPT >= 4 && BPT % 4 == 0, "block size must divide 1024");
   const int t = threadIdx.x;
   __syncthreads();
-  uint32_t v[16];
+  uint32_t v[BPT];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint4 q = reinterpret_cast<const uint4*>(lh)[4 * t + j];
+  for (int j = 0; j < BPT / 4; ++j) {
+    const uint4 q = reinterpret_cast<const uint4*>(lh)[(BPT / 4) * t + j];
     v[4 * j + 0] = q.x;
     v[4 * j + 1] = q.y;
     v[4 * j + 2] = q.z;
     v[4 * j + 3] = q.w;
   }
 #pragma unroll
-  for (int j = 14; j >= 0; --j) v[j] += v[j + 1];
+  for (int j = BPT - 2; j >= 0; --j) v[j] += v[j + 1];
   red[t] = v[0];
   __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
-    const uint32_t x = (t + off < 256) ? red[t + off] : 0u;
+  for (int off = 1; off < T; off <<= 1) {
+    const uint32_t x = (t + off < T) ? red[t + off] : 0u;
     __syncthreads();
     red[t] += x;
     __syncthreads();
   }
-  const uint32_t carry = (t + 1 < 256) ? red[t + 1] : 0u;
+  const uint32_t carry = (t + 1 < T) ? red[t + 1] : 0u;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < BPT / 4; ++j) {
     uint4 q;
     q.x = v[4 * j + 0] + carry;
     q.y = v[4 * j + 1] + carry;
     q.z = v[4 * j + 2] + carry;
     q.w = v[4 * j + 3] + carry;
-    reinterpret_cast<uint4*>(dst)[4 * t + j] = q;
+    reinterpret_cast<uint4*>(dst)[(BPT / 4) * t + j] = q;
   }
 }
 
@@ -179,13 +182,13 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST, bool NT>
-__global__ void __launch_bounds__(256)
+template <bool STATS, int HIST, bool NT, int T>
+__global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
          double* __restrict__ partials) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[HIST ? kHistBins : 4];
-  __shared__ uint32_t red_u[HIST ? 256 : 1];
-  __shared__ double red[2][4];
+  __shared__ uint32_t red_u[HIST ? T : 1];
+  __shared__ double red[2][T / 64];
 
   // with a known leader its blocks (the only ones that build histograms) are dispatched first
   const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
@@ -198,7 +201,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 
   if (HIST) {
     if (do_hist)
-      for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+      for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
     __syncthreads();
   }
 
@@ -210,19 +213,19 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (c_hi > n) c_hi = n;
   const int64_t q_hi = c_hi >> 2;  // whole float4 groups of this chunk
 
-  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += 256 * kPassAUnroll) {
+  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += T * kPassAUnroll) {
     v4f a[kPassAUnroll], b[kPassAUnroll];
 #pragma unroll
     for (int u = 0; u < kPassAUnroll; ++u) {
-      const int64_t q = q0 + u * 256;
+      const int64_t q = q0 + u * T;
       if (q < q_hi) {
         a[u] = load4<NT>(gp + 4 * q);
-        b[u] = load4<false>(rp + 4 * q);
+        b[u] = load4<NT>(rp + 4 * q);
       }
     }
 #pragma unroll
     for (int u = 0; u < kPassAUnroll; ++u) {
-      const int64_t q = q0 + u * 256;
+      const int64_t q = q0 + u * T;
       if (q < q_hi) {
         v4f v;
         v.x = a[u].x + b[u].x;
@@ -277,15 +280,19 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   }
   __syncthreads();
   if (STATS && tid == 0) {
-    const double S1 = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-    const double S2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    double S1 = 0.0, S2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < T / 64; ++i) {
+      S1 += red[0][i];
+      S2 += red[1][i];
+    }
     partials[((size_t)w * nblk + c) * 2 + 0] = S1;
     partials[((size_t)w * nblk + c) * 2 + 1] = S2;
   }
   if (HIST) {
     if (do_hist) {
       const size_t slot = (HIST == 2) ? (size_t)w : 0;
-      flush_suffix_hist(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins);
+      flush_suffix_hist<T>(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins);
     }
   }
 }
@@ -426,7 +433,7 @@ k_hist0(PtrTable tab, const int32_t* __restrict__ leader_dev, int64_t n, int64_t
       }
     }
   }
-  flush_suffix_hist(lh, red_u, S + (size_t)c * kHistBins);
+  flush_suffix_hist<256>(lh, red_u, S + (size_t)c * kHistBins);
 }
 
 // ---------------------------------------------------------------------------
@@ -1070,16 +1077,17 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
 //   becomes +0.0, elsewhere the residual becomes acc.
 // Used when the leader is known before the step starts (its own pass and the
 // selection have already run, so idx is final).  grid = (nchunks, W-1), block =
-// 256; block (c, y) owns chunk c of worker (leader + 1 + y) mod W.  The block
-// finds its first index with a 256-way search; per 4096-element tile it marks
-// the kept positions in an LDS slot table (slot = m or -1) while the tile's
-// loads are in flight.
+// T; block (c, y) owns chunk c of worker (leader + 1 + y) mod W.  The block
+// finds its first index with a T-way search; per tile of 16 T elements it marks
+// the kept positions in an LDS slot table while the tile's loads are in flight.
 // ---------------------------------------------------------------------------
-template <bool NT>
-__global__ void __launch_bounds__(256)
+template <bool NT, int T>
+__global__ void __launch_bounds__(T, 8)
 k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkGeom geom,
             const int32_t* __restrict__ idx, int64_t k, float* __restrict__ vals) {
-  __shared__ __attribute__((aligned(16))) int32_t slot[4096];
+  constexpr int TILE = T * 16;  // elements per tile: T threads x 4 float4
+  static_assert(TILE <= 32768, "slot entries are 16-bit offsets from the tile's first index");
+  __shared__ __attribute__((aligned(16))) int16_t slot[TILE];
   __shared__ int64_t s_lo, s_hi;
   const int tid = threadIdx.x;
   const int c = blockIdx.x;
@@ -1093,7 +1101,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
   if (c_hi > n) c_hi = n;
   if (c_lo >= c_hi) return;
 
-  // m = number of indices below c_lo
+  // m = number of indices below c_lo (T-way search)
   if (tid == 0) {
     s_lo = 0;
     s_hi = k;
@@ -1103,7 +1111,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
     const int64_t lo = s_lo, hi = s_hi;
     const int64_t span = hi - lo;
     if (span <= 0) break;
-    const int64_t stepw = (span + 255) / 256;
+    const int64_t stepw = (span + T - 1) / T;
     const int64_t p = lo + (int64_t)tid * stepw;
     const bool below = (p < hi) && ((int64_t)idx[p] < c_lo);
     const int cnt = __syncthreads_count(below);
@@ -1123,46 +1131,52 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
   int64_t m = s_lo;
 
   const int64_t q_end = c_hi >> 2;  // whole float4 groups end here
-  for (int64_t lo = c_lo; lo < c_hi; lo += 4096) {
-    const int64_t hi = (lo + 4096 < c_hi) ? lo + 4096 : c_hi;
+  for (int64_t lo = c_lo; lo < c_hi; lo += TILE) {
+    const int64_t hi = (lo + TILE < c_hi) ? lo + TILE : c_hi;
     const int64_t q0 = (lo >> 2) + tid;
     v4f a[4], b[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t q = q0 + u * 256;
+      const int64_t q = q0 + u * T;
       if (q < q_end) {
         a[u] = load4<NT>(gp + 4 * q);
-        b[u] = load4<false>(rp + 4 * q);
+        b[u] = load4<NT>(rp + 4 * q);
       }
     }
-    int4* s4 = reinterpret_cast<int4*>(slot);
+    // slot[j] = (position in idx) - m_base for a kept element j of this tile, else -1
+    const int64_t m_base = m;
+    uint2* s2 = reinterpret_cast<uint2*>(slot);  // four 16-bit slots
 #pragma unroll
-    for (int u = 0; u < 4; ++u) s4[tid + u * 256] = make_int4(-1, -1, -1, -1);
+    for (int u = 0; u < 4; ++u) s2[tid + u * T] = make_uint2(0xffffffffu, 0xffffffffu);
     __syncthreads();
     while (true) {
       const int64_t p = m + tid;
       int64_t i = hi;
       if (p < k) i = (int64_t)idx[p];
       const bool in = i < hi;
-      if (in && i >= lo) slot[i - lo] = (int32_t)p;
+      if (in && i >= lo) slot[i - lo] = (int16_t)(p - m_base);
       const int cnt = __syncthreads_count(in);
       m += cnt;
-      if (cnt < 256) break;
+      if (cnt < T) break;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t q = q0 + u * 256;
+      const int64_t q = q0 + u * T;
       if (q < q_end) {
-        const int4 sl = s4[tid + u * 256];
+        const uint2 sl = s2[tid + u * T];
         v4f v;
         v.x = a[u].x + b[u].x;
         v.y = a[u].y + b[u].y;
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
-        if (sl.x >= 0) { vrow[sl.x] = v.x; v.x = 0.0f; }
-        if (sl.y >= 0) { vrow[sl.y] = v.y; v.y = 0.0f; }
-        if (sl.z >= 0) { vrow[sl.z] = v.z; v.z = 0.0f; }
-        if (sl.w >= 0) { vrow[sl.w] = v.w; v.w = 0.0f; }
+        if ((sl.x & sl.y) != 0xffffffffu) {  // some element of this group is kept
+          const int s0 = (int16_t)(sl.x & 0xffffu), s1 = (int16_t)(sl.x >> 16);
+          const int s2v = (int16_t)(sl.y & 0xffffu), s3 = (int16_t)(sl.y >> 16);
+          if (s0 >= 0) { vrow[m_base + s0] = v.x; v.x = 0.0f; }
+          if (s1 >= 0) { vrow[m_base + s1] = v.y; v.y = 0.0f; }
+          if (s2v >= 0) { vrow[m_base + s2v] = v.z; v.z = 0.0f; }
+          if (s3 >= 0) { vrow[m_base + s3] = v.w; v.w = 0.0f; }
+        }
         store4<NT>(rp + 4 * q, v);
       }
     }
