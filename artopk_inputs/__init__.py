@@ -15,6 +15,11 @@ workers, r = 254 the stream that lays out segments).  Chunks are independent,
 so any sub-range can be produced, on any number of threads, with identical
 bits.  Steps are counted from 1 as in Alg. 1 of the paper.
 
+Workloads 3 and 5 draw every worker from the same distribution; to keep the
+VAR-Topk leader well defined their worker r is scaled by (1 + 0.01 r) and
+(1 + 0.004 r) respectively, so the per-worker variances differ by far more than
+the sampling noise of the variance estimate (about 5e-4 and 5e-5 relative).
+
 The five workloads stand in for the real gradients of the models the paper
 trains and for its 1e8 / 1e9 element tensors: same element counts, fp32,
 bell-shaped / heavy-tailed value distributions concentrated in a few binades,
@@ -87,12 +92,12 @@ class Workload:
             x = 0.01 * zs + (0.01 * s_w) * zw
         elif self.cfg == 3:
             lap = _rng(cfg, step, worker, c).laplace(0.0, 1.0, m)
-            x = lap * self._elem_scale(lo, lo + m)
+            x = lap * ((1.0 + 0.01 * worker) * self._elem_scale(lo, lo + m))
         elif self.cfg == 4:
             x = 1e-3 * _rng(cfg, step, worker, c).standard_t(3.0, m)
         elif self.cfg == 5:
             r = _rng(cfg, step, worker, c)
-            x = 1e-3 * r.standard_normal(m)
+            x = (1e-3 * (1.0 + 0.004 * worker)) * r.standard_normal(m)
             u = r.random(m)
             q = np.rint(x * 1024.0) / 1024.0
             x = np.where(u < 0.1, q, x)

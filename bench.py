@@ -25,9 +25,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per pass-A launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel, measured with two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 1 GiB
+# device copy (profiles/step_<workload>_rho<rho>.md); None where it was not measured.
+MEASURED_TRAFFIC_BYTES = {
+    ("c5", 0.001): 96132.4e6,   # k_pass_a, all 8 workers: 64.0 GB fetched + 32.1 GB written
+    ("c4", 0.01): 5206.8e6,     # k_pass_rest, 3 workers: 3.37 GB fetched + 1.84 GB written
+}
 
 
 def log(*a):
@@ -159,6 +163,9 @@ def main():
     ap.add_argument("--gen-threads", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also-c4", action="store_true", help="append the 138M workload's numbers under 'other'")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy five times (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
@@ -173,6 +180,15 @@ def main():
         print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
         sys.exit(2)
     pkg.load_library()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
 
     cfg = int(args.workload[1])
     wl0 = inp.workload(cfg)
