@@ -131,7 +131,7 @@ def cpu_baseline(cfg, rho, inp, budget_s=20.0):
     from oracle import artopk_oracle as orc
 
     full = inp.workload(cfg)
-    n = min(full.n, 1 << 22)
+    n = min(full.n, 1 << 24)
     wl = inp.workload(cfg, n=n)
     k = wl.k(rho)
     seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
@@ -139,7 +139,7 @@ def cpu_baseline(cfg, rho, inp, budget_s=20.0):
     mode = orc.MODE_STAR if wl.mode == inp.MODE_STAR else orc.MODE_VAR
     res = [np.zeros(n, np.float32) for _ in range(wl.w)]
     steps, spent = 0, 0.0
-    while spent < budget_s and steps < 8:
+    while spent < budget_s and steps < 4:
         g = [wl.gen(steps + 1, r) for r in range(wl.w)]
         t0 = time.perf_counter()
         out = orc.step(g, res, k, mode, step_no=steps + 1, seg_off=seg_off, seg_k=seg_k)
