@@ -20,8 +20,8 @@ using namespace artopk;
 
 namespace {
 
-constexpr int kPassAThreads = 1024;
-constexpr int kPassRestThreads = 1024;
+constexpr int kPassAThreads = 1024, kPassAU = 8;        // 128 KiB of each array per block iteration
+constexpr int kPassRestThreads = 1024, kPassRestU = 8;
 constexpr int kNumCompactLaunches = 4;  // look-back passes: array level 2, 3 and the list pass (+1 spare)
 
 struct Scratch {
@@ -591,10 +591,10 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
     if (nt)
-      hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
+      hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
     else
-      hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
+      hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)L, s.leader_dev, leader_out);
     prof_mark(ctx, 1);
@@ -602,10 +602,10 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_mark(ctx, 2);
     if (w > 1) {
       if (nt)
-        hipLaunchKernelGGL((k_pass_rest<true, kPassRestThreads>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
+        hipLaunchKernelGGL((k_pass_rest<true, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
                            0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
       else
-        hipLaunchKernelGGL((k_pass_rest<false, kPassRestThreads>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
+        hipLaunchKernelGGL((k_pass_rest<false, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
                            0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
     }
     prof_mark(ctx, 3);
@@ -630,10 +630,10 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
 #define LAUNCH_PASS_A(STATS, HIST, LEADER)                                                                 \
   do {                                                                                                     \
     if (nt)                                                                                                \
-      hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, kPassAThreads>), grid, dim3(kPassAThreads), 0, st,   \
+      hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,   \
                          gt, rt, n, geom, LEADER, s.S, s.partials);                                        \
     else                                                                                                   \
-      hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, kPassAThreads>), grid, dim3(kPassAThreads), 0, st,  \
+      hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,  \
                          gt, rt, n, geom, LEADER, s.S, s.partials);                                        \
   } while (0)
   if (mode == ARTOPK_VAR) {

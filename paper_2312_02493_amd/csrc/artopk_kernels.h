@@ -182,7 +182,7 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST, bool NT, int T>
+template <bool STATS, int HIST, bool NT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
          double* __restrict__ partials) {
@@ -213,10 +213,10 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (c_hi > n) c_hi = n;
   const int64_t q_hi = c_hi >> 2;  // whole float4 groups of this chunk
 
-  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += T * kPassAUnroll) {
-    v4f a[kPassAUnroll], b[kPassAUnroll];
+  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += T * U) {
+    v4f a[U], b[U];
 #pragma unroll
-    for (int u = 0; u < kPassAUnroll; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
       if (q < q_hi) {
         a[u] = load4<NT>(gp + 4 * q);
@@ -224,7 +224,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       }
     }
 #pragma unroll
-    for (int u = 0; u < kPassAUnroll; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
       if (q < q_hi) {
         v4f v;
@@ -1081,11 +1081,11 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
 // finds its first index with a T-way search; per tile of 16 T elements it marks
 // the kept positions in an LDS slot table while the tile's loads are in flight.
 // ---------------------------------------------------------------------------
-template <bool NT, int T>
-__global__ void __launch_bounds__(T, 8)
+template <bool NT, int T, int U>
+__global__ void __launch_bounds__(T)
 k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkGeom geom,
             const int32_t* __restrict__ idx, int64_t k, float* __restrict__ vals) {
-  constexpr int TILE = T * 16;  // elements per tile: T threads x 4 float4
+  constexpr int TILE = T * 4 * U;  // elements per tile: T threads x U float4
   static_assert(TILE <= 32768, "slot entries are 16-bit offsets from the tile's first index");
   __shared__ __attribute__((aligned(16))) int16_t slot[TILE];
   __shared__ int64_t s_lo, s_hi;
@@ -1134,9 +1134,9 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
   for (int64_t lo = c_lo; lo < c_hi; lo += TILE) {
     const int64_t hi = (lo + TILE < c_hi) ? lo + TILE : c_hi;
     const int64_t q0 = (lo >> 2) + tid;
-    v4f a[4], b[4];
+    v4f a[U], b[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
       if (q < q_end) {
         a[u] = load4<NT>(gp + 4 * q);
@@ -1147,7 +1147,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
     const int64_t m_base = m;
     uint2* s2 = reinterpret_cast<uint2*>(slot);  // four 16-bit slots
 #pragma unroll
-    for (int u = 0; u < 4; ++u) s2[tid + u * T] = make_uint2(0xffffffffu, 0xffffffffu);
+    for (int u = 0; u < U; ++u) s2[tid + u * T] = make_uint2(0xffffffffu, 0xffffffffu);
     __syncthreads();
     while (true) {
       const int64_t p = m + tid;
@@ -1160,7 +1160,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
       if (cnt < T) break;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
       if (q < q_end) {
         const uint2 sl = s2[tid + u * T];
