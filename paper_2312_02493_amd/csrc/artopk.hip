@@ -42,8 +42,7 @@ struct Scratch {
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
   uint32_t* err_dev = nullptr;
-  int32_t* list_idx = nullptr;
-  uint32_t* list_key = nullptr;
+  uint2* list = nullptr;          // survivor list: (index, raw float bits)
   float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
   uint32_t cap = 0;               // usable list entries
 };
@@ -192,7 +191,8 @@ void prof_begin(artopk_ctx* c) {
 }
 
 // Clears the select scratch for a range that spans `ntiles` look-back tiles.
-int enqueue_clear(artopk_ctx* c, int64_t ntiles) {
+// leader >= 0 also records a host-known leader (and copies it to leader_out).
+int enqueue_clear(artopk_ctx* c, int64_t ntiles, int32_t leader = -1, int32_t* leader_out = nullptr) {
   Scratch& s = c->s;
   const size_t words1 = s.head_words;
   const size_t words2 = (size_t)ntiles * kNumCompactLaunches * 2;
@@ -201,7 +201,8 @@ int enqueue_clear(artopk_ctx* c, int64_t ntiles) {
   if (blocks < 1) blocks = 1;
   if (blocks > c->num_cu * 4) blocks = c->num_cu * 4;
   hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, c->stream, s.zero_base, words1,
-                     reinterpret_cast<uint32_t*>(s.flags), words2);
+                     reinterpret_cast<uint32_t*>(s.flags), words2, leader, leader >= 0 ? s.leader_dev : nullptr,
+                     leader_out);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
 }
@@ -234,8 +235,9 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
                      slot_by_leader, (int)geom.nchunks, s.ssum);
   hipLaunchKernelGGL(k_pick0, dim3(1), dim3(1024), 0, st, s.state, s.ssum, s.S, s.leader_dev, slot_by_leader,
                      (int)geom.nchunks, (uint32_t)nrange, (uint32_t)k, s.chunk_off, s.err_dev);
-  hipLaunchKernelGGL(k_compact1, dim3(geom.nchunks), dim3(kC1Threads), 0, st, tab, s.leader_dev, s.state, n, e_lo, e_hi,
-                     geom, s.chunk_off, cap, s.hist1, s.list_idx, s.list_key, s.err_dev);
+  // 4 waves x 4 rows with prefetch measured best at both 138 M and 1 G elements
+  hipLaunchKernelGGL((k_compact1<4, 4, true>), dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, s.state, n,
+                     e_lo, e_hi, geom, s.chunk_off, cap, s.hist1, s.list, s.err_dev);
   hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist1, 1, cap, s.err_dev);
 
   // deeper array passes: they run only when the level-1 survivors did not fit the list
@@ -244,23 +246,23 @@ int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, 
   for (int level = 2; level <= 3; ++level) {
     hipLaunchKernelGGL(k_compact<false>, dim3(cblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev,
                        s.state, level, n, e_lo, e_hi, cap, s.hist2, s.flags + (level - 2), kNumCompactLaunches,
-                       s.counters + (level - 2), s.list_idx, s.list_key, (int32_t*)nullptr, (float*)nullptr, 0u,
+                       s.counters + (level - 2), s.list, (int32_t*)nullptr, (float*)nullptr, 0u,
                        s.err_dev);
-    hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, level, cap, s.err_dev);
+    if (level == 2) hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, level, cap, s.err_dev);
   }
   // the list holds n_gt + cand <= cap entries
   int64_t list_bound = (int64_t)cap < nrange ? (int64_t)cap : nrange;
   int lblocks = (int)((list_bound + 256 * 16 - 1) / (256 * 16));
   if (lblocks < 1) lblocks = 1;
   if (lblocks > c->num_cu * 4) lblocks = c->num_cu * 4;
-  hipLaunchKernelGGL(k_list_hist, dim3(lblocks), dim3(256), 0, st, s.state, s.list_key, s.hist2, s.err_dev);
+  hipLaunchKernelGGL(k_list_hist, dim3(lblocks), dim3(256), 0, st, s.state, s.list, s.hist2, s.err_dev);
   hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, 4, cap, s.err_dev);
   int64_t ltiles = (list_bound + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < (int64_t)c->num_cu * 2 ? ltiles : (int64_t)c->num_cu * 2);
   if (fblocks < 1) fblocks = 1;
   hipLaunchKernelGGL(k_compact<true>, dim3(fblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev, s.state,
                      3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 2,
-                     kNumCompactLaunches, s.counters + 2, s.list_idx, s.list_key, idx_out, vals_row, (uint32_t)k,
+                     kNumCompactLaunches, s.counters + 2, s.list, idx_out, vals_row, (uint32_t)k,
                      s.err_dev);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
@@ -373,8 +375,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
-  const size_t o_lidx = take(cap_pad * sizeof(int32_t));
-  const size_t o_lkey = take(cap_pad * sizeof(uint32_t));
+  const size_t o_list = take(cap_pad * sizeof(uint2));
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
   const size_t total = off;
 
@@ -398,13 +399,13 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.var_scratch = reinterpret_cast<double*>(base + o_var);
   s.leader_dev = reinterpret_cast<int32_t*>(base + o_leader);
   s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
-  s.list_idx = reinterpret_cast<int32_t*>(base + o_lidx);
-  s.list_key = reinterpret_cast<uint32_t*>(base + o_lkey);
+  s.list = reinterpret_cast<uint2*>(base + o_list);
   s.vals = reinterpret_cast<float*>(base + o_vals);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
-                     reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1);
+                     reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1, 0,
+                     (int32_t*)nullptr, (int32_t*)nullptr);
   if (hipGetLastError() != hipSuccess) {
     (void)hipFree(c->slab);
     delete c;
@@ -589,14 +590,13 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     const PtrTable g1t = make_table(g1, 1), r1t = make_table(r1, 1);
     prof_begin(ctx);
     prof_mark(ctx, 0);
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
+    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), L, leader_out))) return rc;
     if (nt)
       hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
     else
       hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
-    hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)L, s.leader_dev, leader_out);
     prof_mark(ctx, 1);
     if ((rc = enqueue_select(ctx, rt, n, 0, n, k, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
     prof_mark(ctx, 2);
@@ -611,7 +611,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_mark(ctx, 3);
     const int kblocks = (int)((k + 255) / 256);
     hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
-    hipLaunchKernelGGL(k_sum_rows, dim3(kblocks), dim3(256), 0, st, vals, (int)w, k, sum_out);
+    hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
     if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
     prof_mark(ctx, 4);

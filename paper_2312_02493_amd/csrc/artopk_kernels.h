@@ -161,10 +161,16 @@ __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, u
 }
 
 // ---------------------------------------------------------------------------
-// k_fill_zero : clears two word ranges (either may be empty)
+// k_fill_zero : clears two word ranges (either may be empty); if leader_dev is
+// given it also records a leader that the host already knows.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2, size_t words2) {
+k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2, size_t words2,
+            int32_t leader, int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
+  if (leader_dev != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    *leader_dev = leader;
+    if (leader_out) *leader_out = leader;
+  }
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words1; i += stride) p1[i] = 0u;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words2; i += stride) p2[i] = 0u;
@@ -522,21 +528,20 @@ k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uin
 // list in ascending element order at chunk_off[c] + rank inside the chunk;
 // candidates (top digit == b0) also feed the next-digit histogram hist1.
 // If the list cannot hold n_gt + cand entries nothing is written and only the
-// histogram is built.  block = 512 threads = 8 waves; a tile is 8 waves x 4
-// rows x 64 lanes x 4 consecutive elements, each wave owning 1024 consecutive
-// elements; the next tile is loaded while the current one is processed.
+// histogram is built.  block = WAVES waves; a tile is WAVES x R rows x 64 lanes
+// x 4 consecutive elements, each wave owning R*256 consecutive elements; with
+// PF the next tile is loaded while the current one is processed.
 // ---------------------------------------------------------------------------
-constexpr int kC1Waves = 8;
-constexpr int kC1Threads = 64 * kC1Waves;
-static_assert(kTile == 1024 * kC1Waves, "each wave owns 1024 consecutive elements of a tile");
-
-__global__ void __launch_bounds__(kC1Threads)
+template <int WAVES, int R, bool PF>
+__global__ void __launch_bounds__(64 * WAVES)
 k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState* __restrict__ stp, int64_t n,
            int64_t e_lo, int64_t e_hi, ChunkGeom geom, const uint32_t* __restrict__ chunk_off, uint32_t cap,
-           uint32_t* __restrict__ hist1, int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
-           const uint32_t* __restrict__ err) {
+           uint32_t* __restrict__ hist1, uint2* __restrict__ list, const uint32_t* __restrict__ err) {
+  constexpr int T = 64 * WAVES;
+  constexpr int WSPAN = R * 256;       // consecutive elements one wave owns in a tile
+  constexpr int TILE = WAVES * WSPAN;  // elements per block iteration
   __shared__ uint32_t lh[kHistBins];
-  __shared__ uint32_t wtot[2][kC1Waves];
+  __shared__ uint32_t wtot[2][WAVES];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -549,27 +554,24 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
   const uint32_t klo = st.lo, khi = st.hi;
   const float* __restrict__ xp = tab.p[*leader_dev];
 
-  for (int b = tid; b < kHistBins; b += kC1Threads) lh[b] = 0u;
+  for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
   __syncthreads();
 
-  const int64_t c_begin = geom.chunk0 + (int64_t)c * geom.chunk_elems;  // a tile boundary
+  const int64_t c_begin = geom.chunk0 + (int64_t)c * geom.chunk_elems;  // a multiple of kTile
   const int64_t c_end = c_begin + geom.chunk_elems;
   const int64_t cs = c_begin > e_lo ? c_begin : e_lo;  // elements of the range owned by this chunk
   const int64_t ce = c_end < e_hi ? c_end : e_hi;
   const int64_t n_vec = n & ~(int64_t)3;
-  // every group of four this block touches is a whole, in-range, in-bounds group
-  const bool clean = (c_begin >= e_lo) && (c_end <= e_hi) && (c_end <= n_vec);
-  const int64_t t_begin = c_begin / kTile;
-  const int64_t t_end = (ce + kTile - 1) / kTile;  // exclusive; <= t_begin when the chunk is empty
-  const int64_t lane_off = (int64_t)wave * 1024 + (int64_t)lane * 4;
+  const int64_t lane_off = (int64_t)wave * WSPAN + (int64_t)lane * 4;
 
-  // raw bits of this lane's 4 x 4 elements of tile t (bits outside the array read as 0)
-  auto load_tile = [&](int64_t t, uint4 (&v)[4]) {
-    const int64_t j0 = t * kTile + lane_off;
+  // raw bits of this lane's R x 4 elements of the tile starting at element tb
+  // (groups that are not wholly inside the array are read element by element, absent ones as 0)
+  auto load_tile = [&](int64_t tb, uint4 (&v)[R]) {
+    const int64_t j0 = tb + lane_off;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < R; ++r) {
       const int64_t j = j0 + r * 256;
-      if (clean || j + 4 <= n_vec) {
+      if (j + 4 <= n_vec) {
         v[r] = *reinterpret_cast<const uint4*>(xp + j);
       } else {
         v[r].x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
@@ -582,18 +584,23 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
 
   uint32_t run = write_out ? chunk_off[c] : 0u;  // list position of the next survivor of this chunk
   int buf = 0;
-  uint4 cur[4], nxt[4];
-  if (t_begin < t_end) load_tile(t_begin, cur);
+  uint4 cur[R], nxt[R];
+  if (PF && c_begin < ce) load_tile(c_begin, cur);
 
-  for (int64_t t = t_begin; t < t_end; ++t) {
-    if (t + 1 < t_end) load_tile(t + 1, nxt);
+  for (int64_t tb = c_begin; tb < ce; tb += TILE) {
+    if constexpr (PF) {
+      if (tb + TILE < ce) load_tile(tb + TILE, nxt);
+    } else {
+      load_tile(tb, cur);
+    }
+    const int64_t j0 = tb + lane_off;
+    // every element of this tile belongs to the chunk and the range?
+    const bool clean = (tb >= cs) && (tb + TILE <= ce);
 
-    const int64_t j0 = t * kTile + lane_off;
-    // one lane mask per element slot: which lanes hold a survivor there
-    uint64_t bm[16];
+    // ---- count survivors (key >= klo); candidates (key <= khi) feed the next-digit histogram
     uint32_t cnt = 0u;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < R; ++r) {
       const uint32_t kk[4] = {cur[r].x & kKeyMask, cur[r].y & kKeyMask, cur[r].z & kKeyMask, cur[r].w & kKeyMask};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -603,7 +610,6 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
           ok = ok && j >= cs && j < ce;
         }
         const uint64_t m = __ballot(ok);
-        bm[r * 4 + e] = m;
         if (m != 0ull) {
           cnt += (uint32_t)__popcll(m);
           if (ok && kk[e] <= khi) atomicAdd(&lh[(kk[e] >> 7) & 0xfffu], 1u);
@@ -616,44 +622,52 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
       __syncthreads();
       uint32_t base = run;
 #pragma unroll
-      for (int i = 0; i < kC1Waves; ++i) {
+      for (int i = 0; i < WAVES; ++i) {
         const uint32_t wt = wtot[buf][i];
         if (i < wave) base += wt;
         run += wt;
       }
       buf ^= 1;
       if (cnt != 0u) {
+        // ---- emit: survivors of lower lanes of a row come first, then this lane's own in slot order
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint64_t rowm = bm[r * 4] | bm[r * 4 + 1] | bm[r * 4 + 2] | bm[r * 4 + 3];
-          if (rowm != 0ull) {
-            // survivors of lower lanes in this row come first, then this lane's own in slot order
-            uint32_t pos = base;
+        for (int r = 0; r < R; ++r) {
+          const uint32_t raw[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
+          uint64_t bm[4];
+          bool mine[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) pos += popc_lt(bm[r * 4 + e]);
-            const uint32_t kk[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
+          for (int e = 0; e < 4; ++e) {
+            bool ok = (raw[e] & kKeyMask) >= klo;
+            if (!clean) {
+              const int64_t j = j0 + r * 256 + e;
+              ok = ok && j >= cs && j < ce;
+            }
+            mine[e] = ok;
+            bm[e] = __ballot(ok);
+          }
+          if ((bm[0] | bm[1] | bm[2] | bm[3]) != 0ull) {
+            uint32_t pos = base + popc_lt(bm[0]) + popc_lt(bm[1]) + popc_lt(bm[2]) + popc_lt(bm[3]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              if ((bm[r * 4 + e] >> lane) & 1ull) {
-                if (pos < cap) {
-                  list_idx[pos] = (int32_t)(j0 + r * 256 + e);
-                  list_key[pos] = kk[e];  // raw bits: the sign travels with the survivor
-                }
+              if (mine[e]) {
+                // (index, raw bits): the sign travels with the survivor
+                if (pos < cap) list[pos] = make_uint2((uint32_t)(j0 + r * 256 + e), raw[e]);
                 ++pos;
               }
             }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) base += (uint32_t)__popcll(bm[r * 4 + e]);
+            base += (uint32_t)(__popcll(bm[0]) + __popcll(bm[1]) + __popcll(bm[2]) + __popcll(bm[3]));
           }
         }
       }
     }
+    if constexpr (PF) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) cur[r] = nxt[r];
+      for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+    }
   }
 
   __syncthreads();
-  for (int b = tid; b < kHistBins; b += kC1Threads) {
+  for (int b = tid; b < kHistBins; b += T) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&hist1[b], v);
   }
@@ -667,9 +681,9 @@ k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState*
 //   stage 2 (after the level-2 array compaction): if the list has not been
 //             written and state.level == 2, record whether that pass wrote it,
 //             then resolve digit 2.
-//   stage 3 : after the level-3 array compaction: record the list.
-//   stage 4 : after the list histogram: resolve digit 2 if the list was written
-//             at level 1.
+//   stage 4 (after the level-3 array compaction and the list histogram): record
+//             the list if the level-3 pass wrote it; resolve digit 2 if the
+//             list was written at level 1.
 // The decision "did the compaction at this level write the list" is the same
 // expression the compaction kernel evaluates: n_gt + cand <= cap.
 // ---------------------------------------------------------------------------
@@ -697,13 +711,13 @@ k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, int stage,
         }
         digit = stage;
       }
-    } else if (stage == 3) {
-      if (st.compact_level == 0u && st.level == 3u) {
+    } else {  // stage 4
+      if (st.compact_level == 0u && st.level == 3u) {  // the level-3 array pass wrote the list
         st.compact_level = 3u;
         st.list_count = st.n_gt + (st.cand < st.need ? st.cand : st.need);
+      } else if (st.compact_level == 1u && st.level == 2u) {
+        digit = 2;
       }
-    } else {  // stage 4
-      if (st.compact_level == 1u && st.level == 2u) digit = 2;
     }
     run_pick = digit;
   }
@@ -848,8 +862,7 @@ __global__ void __launch_bounds__(kCompactThreads)
 k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __restrict__ stp, int level,
           int64_t n, int64_t e_lo, int64_t e_hi, uint32_t cap, uint32_t* __restrict__ hist_next,
           uint64_t* __restrict__ flags, int flag_stride, uint32_t* __restrict__ tile_counter,
-          int32_t* __restrict__ list_idx, uint32_t* __restrict__ list_key,
-          int32_t* __restrict__ idx_out, float* __restrict__ vals_row, uint32_t k_out,
+          uint2* __restrict__ list, int32_t* __restrict__ idx_out, float* __restrict__ vals_row, uint32_t k_out,
           uint32_t* __restrict__ err) {
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint64_t wave_tot[8];
@@ -918,12 +931,13 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
         if (!LIST) {
           v = *reinterpret_cast<const uint4*>(xp + j);
         } else {
-          v = *reinterpret_cast<const uint4*>(list_key + j);
-          const int4 pv = *reinterpret_cast<const int4*>(list_idx + j);
-          pay[LIST ? r : 0][0] = pv.x;
-          pay[LIST ? r : 0][1] = pv.y;
-          pay[LIST ? r : 0][2] = pv.z;
-          pay[LIST ? r : 0][3] = pv.w;
+          const uint4 e01 = reinterpret_cast<const uint4*>(list + j)[0];  // (idx, bits) x 2
+          const uint4 e23 = reinterpret_cast<const uint4*>(list + j)[1];
+          v = make_uint4(e01.y, e01.w, e23.y, e23.w);
+          pay[LIST ? r : 0][0] = (int32_t)e01.x;
+          pay[LIST ? r : 0][1] = (int32_t)e01.z;
+          pay[LIST ? r : 0][2] = (int32_t)e23.x;
+          pay[LIST ? r : 0][3] = (int32_t)e23.z;
         }
         key[r][0] = v.x;  // raw bits; comparisons mask the sign off
         key[r][1] = v.y;
@@ -944,8 +958,9 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
             if (!LIST) {
               key[r][e] = __float_as_uint(xp[j]);
             } else {
-              key[r][e] = list_key[j];
-              pay[LIST ? r : 0][e] = list_idx[j];
+              const uint2 ent = list[j];
+              key[r][e] = ent.y;
+              pay[LIST ? r : 0][e] = (int32_t)ent.x;
             }
           }
         }
@@ -1014,10 +1029,7 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
                 const uint32_t pos = befA + (befB < quota ? befB : quota);
                 const int64_t j = tbase + (int64_t)r * 256 + (int64_t)lane * 4 + e;
                 if (!LIST) {
-                  if (pos < cap) {
-                    list_idx[pos] = (int32_t)j;
-                    list_key[pos] = key[r][e];
-                  }
+                  if (pos < cap) list[pos] = make_uint2((uint32_t)j, key[r][e]);
                 } else {
                   if (pos < k_out) {
                     idx_out[pos] = pay[LIST ? r : 0][e];
@@ -1051,7 +1063,7 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
 // survivor list; runs only when the list was written at level 1.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_key,
+k_list_hist(const SelState* __restrict__ stp, const uint2* __restrict__ list,
             uint32_t* __restrict__ hist2, const uint32_t* __restrict__ err) {
   __shared__ uint32_t lh[128];
   const SelState st = *stp;
@@ -1061,7 +1073,7 @@ k_list_hist(const SelState* __restrict__ stp, const uint32_t* __restrict__ list_
   __syncthreads();
   const uint32_t cnt = st.list_count;
   for (uint32_t p = blockIdx.x * 256u + tid; p < cnt; p += gridDim.x * 256u) {
-    const uint32_t key = list_key[p] & kKeyMask;
+    const uint32_t key = list[p].y & kKeyMask;
     if (key >= st.lo && key <= st.hi) atomicAdd(&lh[key & 0x7fu], 1u);
   }
   __syncthreads();
@@ -1207,11 +1219,19 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_sum_rows(const float* __restrict__ vals, int w_count, int64_t k, float* __restrict__ sum) {
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (m >= k) return;
-  float s = vals[m];
-  for (int w = 1; w < w_count; ++w) s = s + vals[(size_t)w * (size_t)k + (size_t)m];
-  sum[m] = s;
+  const int64_t m0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (m0 >= k) return;
+  if (m0 + 4 <= k && (k & 3) == 0) {  // rows stay 16-byte aligned when k is a multiple of 4
+    v4f s = *reinterpret_cast<const v4f*>(vals + m0);
+    for (int w = 1; w < w_count; ++w) s = s + *reinterpret_cast<const v4f*>(vals + (size_t)w * (size_t)k + m0);
+    *reinterpret_cast<v4f*>(sum + m0) = s;
+  } else {
+    for (int64_t m = m0; m < m0 + 4 && m < k; ++m) {
+      float s = vals[m];
+      for (int w = 1; w < w_count; ++w) s = s + vals[(size_t)w * (size_t)k + (size_t)m];
+      sum[m] = s;
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
