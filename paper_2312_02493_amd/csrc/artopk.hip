@@ -13,6 +13,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "artopk_kernels.h"
 
@@ -22,29 +23,36 @@ namespace {
 
 constexpr int kPassAThreads = 1024, kPassAU = 8;        // 128 KiB of each array per block iteration
 constexpr int kPassRestThreads = 1024, kPassRestU = 8;
-constexpr int kNumCompactLaunches = 4;  // look-back passes: array level 2, 3 and the list pass (+1 spare)
 
 struct Scratch {
-  // zeroed before every select
-  uint32_t* zero_base = nullptr;  // start of the zeroed head
-  size_t head_words = 0;          // state + counters + hist1 + hist2 + Ssum
-  SelState* state = nullptr;
-  uint32_t* counters = nullptr;   // kNumCompactLaunches tile counters
-  uint32_t* hist1 = nullptr;
-  uint32_t* hist2 = nullptr;
-  uint32_t* ssum = nullptr;       // [4096] suffix sums of the leader's top-digit histogram
-  uint64_t* flags = nullptr;      // [max_tiles][kNumCompactLaunches]
+  // zeroed before every select: one kSegWords block per segment, then the look-back flags
+  uint32_t* zero_base = nullptr;  // [max_seg][kSegWords]
+  uint64_t* flags = nullptr;      // [max_tiles][kNumLookback], directly behind the blocks
   int64_t max_tiles = 0;
   // not zeroed
-  uint32_t* S = nullptr;          // [slots][kMaxChunks][4096] per-chunk suffix histograms
-  uint32_t* chunk_off = nullptr;  // [kMaxChunks]
+  uint32_t* S = nullptr;          // [max_w * kMaxChunks + max_seg][4096] per-chunk suffix histograms
+  uint32_t* chunk_off = nullptr;  // [kMaxChunks + max_seg]
   double* partials = nullptr;     // [max_w][kMaxChunks][2]
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
   uint32_t* err_dev = nullptr;
-  uint2* list = nullptr;          // survivor list: (index, raw float bits)
+  uint2* list = nullptr;          // survivor lists: (index, raw float bits)
+  int64_t list_entries = 0;       // allocated entries
   float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
-  uint32_t cap = 0;               // usable list entries
+  SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
+  uint32_t cap = 0;               // list capacity of a flat (one-segment) select
+};
+
+// A selection problem laid out for the kernels: one descriptor per segment and
+// the launch bounds derived from them.
+struct Plan {
+  int32_t nseg = 1;
+  std::vector<SegDesc> desc;
+  bool use_table = false;   // descriptors live in the device table (nseg > 1)
+  int32_t max_chunks = 1;   // largest chunk count of a segment
+  int64_t max_tiles = 1;    // largest look-back tile count of a segment
+  int64_t total_tiles = 1;
+  int64_t max_cap = 1;      // largest list capacity of a segment
 };
 
 }  // namespace
@@ -60,6 +68,10 @@ struct artopk_ctx {
   bool leader_first = true;  // STAR / FIXED: leader pass + select first, then one fused pass over the rest
   void* slab = nullptr;
   Scratch s;
+  // descriptors of the last segmented layout uploaded to table_dev
+  std::vector<int64_t> cached_off, cached_k;
+  int64_t cached_n = -1;
+  Plan cached_plan;
   // stage events: a ring of the most recent calls, 5 marks per call
   // (0 start, 1 after pass A, 2 after select, 3 after gather, 4 after update)
   bool profile = false;
@@ -148,13 +160,13 @@ PtrTable make_table(const float* const* tab, int32_t w) {
   return t;
 }
 
-// Chunk layout of the element range [e_lo, e_hi): at most kMaxChunks chunks of
+// Chunk layout of the element range [e_lo, e_hi): at most max_chunks chunks of
 // whole tiles, chunk 0 starting at the tile boundary at or below e_lo.
-ChunkGeom make_geom(int64_t e_lo, int64_t e_hi) {
+ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks) {
   ChunkGeom g;
   g.chunk0 = e_lo / kTile * kTile;
   const int64_t span = e_hi - g.chunk0;
-  int64_t ce = (span + kMaxChunks - 1) / kMaxChunks;
+  int64_t ce = (span + max_chunks - 1) / max_chunks;
   ce = (ce + kTile - 1) / kTile * kTile;
   if (ce < kTile) ce = kTile;
   g.chunk_elems = ce;
@@ -190,12 +202,122 @@ void prof_begin(artopk_ctx* c) {
   for (int i = 0; i < artopk_ctx::kMarks; ++i) c->ev_valid[c->cur][i] = false;
 }
 
-// Clears the select scratch for a range that spans `ntiles` look-back tiles.
+int64_t tiles_of_range(int64_t e_lo, int64_t e_hi) {
+  return (e_hi + kCompactTile - 1) / kCompactTile - e_lo / kCompactTile;
+}
+
+int64_t seg_list_cap(int64_t n_s, int64_t k_s) {
+  int64_t share = n_s / 8;
+  if (share < 4096) share = 4096;
+  int64_t cap = k_s + share;
+  return cap < n_s ? cap : n_s;
+}
+
+// One segment covering the whole vector.
+Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k) {
+  Plan pl;
+  pl.nseg = 1;
+  SegDesc d{};
+  d.e_lo = 0;
+  d.e_hi = n;
+  d.geom = make_geom(0, n);
+  d.koff = 0;
+  d.list_base = 0;
+  d.flag_base = 0;
+  d.chunk_begin = 0;
+  d.k = (uint32_t)k;
+  d.cap = c->s.cap < (uint64_t)n ? c->s.cap : (uint32_t)n;
+  pl.desc.push_back(d);
+  pl.max_chunks = d.geom.nchunks;
+  pl.max_tiles = pl.total_tiles = tiles_of_range(0, n);
+  pl.max_cap = d.cap;
+  return pl;
+}
+
+// Descriptors for nseg > 1 segments; uploads them to the device table unless the
+// same layout is already there.  Copies from pageable memory, so the host
+// buffer may be reused as soon as the call returns.
+int segmented_plan(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k,
+                   const Plan** out) {
+  const bool same = c->cached_n == n && (int32_t)c->cached_k.size() == nseg &&
+                    memcmp(c->cached_off.data(), seg_off, sizeof(int64_t) * (nseg + 1)) == 0 &&
+                    memcmp(c->cached_k.data(), seg_k, sizeof(int64_t) * nseg) == 0;
+  if (!same) {
+    Plan pl;
+    pl.nseg = nseg;
+    pl.use_table = true;
+    pl.max_chunks = 1;
+    pl.max_tiles = 1;
+    pl.total_tiles = 0;
+    pl.max_cap = 1;
+    int64_t koff = 0, list_base = 0, flag_base = 0;
+    int32_t chunk_begin = 0;
+    for (int sgi = 0; sgi < nseg; ++sgi) {
+      SegDesc d{};
+      d.e_lo = seg_off[sgi];
+      d.e_hi = seg_off[sgi + 1];
+      const int64_t ns = d.e_hi - d.e_lo;
+      int64_t mc = (int64_t)((double)kMaxChunks * (double)ns / (double)n);
+      if (mc < 1) mc = 1;
+      d.geom = make_geom(d.e_lo, d.e_hi, mc);
+      d.koff = koff;
+      d.list_base = list_base;
+      d.flag_base = flag_base;
+      d.chunk_begin = chunk_begin;
+      d.k = (uint32_t)seg_k[sgi];
+      d.cap = (uint32_t)seg_list_cap(ns, seg_k[sgi]);
+      koff += seg_k[sgi];
+      list_base += ((int64_t)d.cap + 3) / 4 * 4;
+      const int64_t tiles = tiles_of_range(d.e_lo, d.e_hi);
+      flag_base += tiles;
+      chunk_begin += d.geom.nchunks;
+      if (d.geom.nchunks > pl.max_chunks) pl.max_chunks = d.geom.nchunks;
+      if (tiles > pl.max_tiles) pl.max_tiles = tiles;
+      if ((int64_t)d.cap > pl.max_cap) pl.max_cap = d.cap;
+      pl.desc.push_back(d);
+    }
+    pl.total_tiles = flag_base;
+    if (list_base > c->s.list_entries || flag_base > c->s.max_tiles || chunk_begin > kMaxChunks + c->max_seg)
+      return fail(c, ARTOPK_EINVAL, "segment layout exceeds the scratch sized at artopk_create");
+    HIP_TRY(c, hipMemcpyAsync(c->s.table_dev, pl.desc.data(), sizeof(SegDesc) * nseg, hipMemcpyHostToDevice,
+                              c->stream));
+    c->cached_plan = pl;
+    c->cached_n = n;
+    c->cached_off.assign(seg_off, seg_off + nseg + 1);
+    c->cached_k.assign(seg_k, seg_k + nseg);
+  }
+  *out = &c->cached_plan;
+  return ARTOPK_OK;
+}
+
+SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
+                      float* vals_row, int slot_by_leader) {
+  const Scratch& s = c->s;
+  SelParams p;
+  p.tab = tab;
+  p.leader_dev = s.leader_dev;
+  p.n = n;
+  p.zero_base = s.zero_base;
+  p.flags = s.flags;
+  p.S = s.S;
+  p.chunk_off = s.chunk_off;
+  p.list = s.list;
+  p.idx_out = idx_out;
+  p.vals_row = vals_row;
+  p.err = s.err_dev;
+  p.table = pl.use_table ? s.table_dev : nullptr;
+  p.slot_by_leader = slot_by_leader;
+  p.pad = 0;
+  p.one = pl.desc[0];
+  return p;
+}
+
+// Clears the per-segment scratch blocks and the look-back flags of a plan.
 // leader >= 0 also records a host-known leader (and copies it to leader_out).
-int enqueue_clear(artopk_ctx* c, int64_t ntiles, int32_t leader = -1, int32_t* leader_out = nullptr) {
+int enqueue_clear(artopk_ctx* c, const Plan& pl, int32_t leader = -1, int32_t* leader_out = nullptr) {
   Scratch& s = c->s;
-  const size_t words1 = s.head_words;
-  const size_t words2 = (size_t)ntiles * kNumCompactLaunches * 2;
+  const size_t words1 = (size_t)pl.nseg * kSegWords;
+  const size_t words2 = (size_t)pl.total_tiles * kNumLookback * 2;
   const size_t total = words1 + words2;
   int blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
   if (blocks < 1) blocks = 1;
@@ -207,85 +329,43 @@ int enqueue_clear(artopk_ctx* c, int64_t ntiles, int32_t leader = -1, int32_t* l
   return ARTOPK_OK;
 }
 
-int64_t tiles_of_range(int64_t e_lo, int64_t e_hi) {
-  return (e_hi + kCompactTile - 1) / kCompactTile - e_lo / kCompactTile;
-}
-
-// Selection of the k largest magnitudes of x[e_lo, e_hi) of the vector
-// tab.p[*leader_dev]; the scratch must have been cleared.  If hist_ready the
-// per-chunk suffix histograms of the range (layout make_geom(e_lo, e_hi)) are
-// already in S, in slot *leader_dev if slot_by_leader, else in slot 0.
-int enqueue_select(artopk_ctx* c, const PtrTable& tab, int64_t n, int64_t e_lo, int64_t e_hi, int64_t k,
-                   int32_t* idx_out, bool hist_ready, int slot_by_leader, float* vals_row = nullptr) {
-  Scratch& s = c->s;
+// Top-k of every segment of the plan on the vector tab.p[*leader_dev]; the
+// scratch must have been cleared.  If hist_ready the per-chunk suffix
+// histograms are already in S (flat plans only: pass A built them, in slot
+// *leader_dev if slot_by_leader, else in slot 0).  vals_row, if given, receives
+// the leader's values at the selected indices.
+int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
+                   bool hist_ready, int slot_by_leader, float* vals_row = nullptr) {
   hipStream_t st = c->stream;
-  const int64_t nrange = e_hi - e_lo;
-  const int64_t ntiles = tiles_of_range(e_lo, e_hi);
-  if (ntiles > s.max_tiles) return fail(c, ARTOPK_EINVAL, "range needs more scan tiles than the context holds");
-  const ChunkGeom geom = make_geom(e_lo, e_hi);
-  const uint32_t cap = s.cap;
+  const unsigned nseg = (unsigned)pl.nseg;
+  const SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0);
 
-  if (!hist_ready) {
-    hipLaunchKernelGGL(k_hist0, dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, n, e_lo, e_hi, geom, s.S);
-    slot_by_leader = 0;
-  }
-  int ysplit = geom.nchunks / 32;
+  if (!hist_ready) hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+  int ysplit = pl.max_chunks / 32;
   if (ysplit < 1) ysplit = 1;
-  hipLaunchKernelGGL(k_reduce_hist, dim3(kHistBins / 256, ysplit), dim3(256), 0, st, s.S, s.leader_dev,
-                     slot_by_leader, (int)geom.nchunks, s.ssum);
-  hipLaunchKernelGGL(k_pick0, dim3(1), dim3(1024), 0, st, s.state, s.ssum, s.S, s.leader_dev, slot_by_leader,
-                     (int)geom.nchunks, (uint32_t)nrange, (uint32_t)k, s.chunk_off, s.err_dev);
+  hipLaunchKernelGGL(k_reduce_hist, dim3(kHistBins / 256, ysplit, nseg), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p);
   // 4 waves x 4 rows with prefetch measured best at both 138 M and 1 G elements
-  hipLaunchKernelGGL((k_compact1<4, 4, true>), dim3(geom.nchunks), dim3(256), 0, st, tab, s.leader_dev, s.state, n,
-                     e_lo, e_hi, geom, s.chunk_off, cap, s.hist1, s.list, s.err_dev);
-  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist1, 1, cap, s.err_dev);
+  hipLaunchKernelGGL((k_compact1<4, 4, true>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 1);
 
-  // deeper array passes: they run only when the level-1 survivors did not fit the list
-  int cblocks = (int)(ntiles < (int64_t)c->num_cu * 2 ? ntiles : (int64_t)c->num_cu * 2);
+  // deeper array passes: they run only for segments whose level-1 survivors did not fit the list
+  int cblocks = (int)(pl.max_tiles < (int64_t)c->num_cu * 2 ? pl.max_tiles : (int64_t)c->num_cu * 2);
   if (cblocks < 1) cblocks = 1;
-  for (int level = 2; level <= 3; ++level) {
-    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev,
-                       s.state, level, n, e_lo, e_hi, cap, s.hist2, s.flags + (level - 2), kNumCompactLaunches,
-                       s.counters + (level - 2), s.list, (int32_t*)nullptr, (float*)nullptr, 0u,
-                       s.err_dev);
-    if (level == 2) hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, level, cap, s.err_dev);
-  }
-  // the list holds n_gt + cand <= cap entries
-  int64_t list_bound = (int64_t)cap < nrange ? (int64_t)cap : nrange;
-  int lblocks = (int)((list_bound + 256 * 16 - 1) / (256 * 16));
+  hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
+  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 2);
+  hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 1);
+
+  int lblocks = (int)((pl.max_cap + 256 * 16 - 1) / (256 * 16));
   if (lblocks < 1) lblocks = 1;
   if (lblocks > c->num_cu * 4) lblocks = c->num_cu * 4;
-  hipLaunchKernelGGL(k_list_hist, dim3(lblocks), dim3(256), 0, st, s.state, s.list, s.hist2, s.err_dev);
-  hipLaunchKernelGGL(k_pick, dim3(1), dim3(1024), 0, st, s.state, s.hist2, 4, cap, s.err_dev);
-  int64_t ltiles = (list_bound + kCompactTile - 1) / kCompactTile;
+  hipLaunchKernelGGL(k_list_hist, dim3(lblocks, nseg), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 4);
+  int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < (int64_t)c->num_cu * 2 ? ltiles : (int64_t)c->num_cu * 2);
   if (fblocks < 1) fblocks = 1;
-  hipLaunchKernelGGL(k_compact<true>, dim3(fblocks), dim3(kCompactThreads), 0, st, tab, s.leader_dev, s.state,
-                     3, (int64_t)cap, (int64_t)0, (int64_t)0, cap, (uint32_t*)nullptr, s.flags + 2,
-                     kNumCompactLaunches, s.counters + 2, s.list, idx_out, vals_row, (uint32_t)k,
-                     s.err_dev);
+  hipLaunchKernelGGL(k_compact<true>, dim3(fblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 2);
   HIP_TRY(c, hipGetLastError());
-  return ARTOPK_OK;
-}
-
-// Select over all segments of the leader's vector (host loop over segments).
-int enqueue_select_segments(artopk_ctx* c, const PtrTable& tab, int64_t n, int32_t nseg,
-                            const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t* idx_out,
-                            bool flat_hist_ready, int slot_by_leader) {
-  if (!seg_off) {
-    return enqueue_select(c, tab, n, 0, n, k, idx_out, flat_hist_ready, slot_by_leader);
-  }
-  int64_t koff = 0;
-  for (int sgi = 0; sgi < nseg; ++sgi) {
-    const int64_t lo = seg_off[sgi], hi = seg_off[sgi + 1];
-    {
-      int rc = enqueue_clear(c, tiles_of_range(lo, hi));
-      if (rc) return rc;
-    }
-    int rc = enqueue_select(c, tab, n, lo, hi, seg_k[sgi], idx_out + koff, false, 0);
-    if (rc) return rc;
-    koff += seg_k[sgi];
-  }
   return ARTOPK_OK;
 }
 
@@ -324,7 +404,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
                   void* hip_stream) {
   if (!out) return ARTOPK_EINVAL;
   if (max_w < 1 || max_w > ARTOPK_MAX_WORKERS || max_n < 1 || max_n >= (1ll << 31) || max_k < 1 ||
-      max_k > max_n || max_segments < 1)
+      max_k > max_n || max_segments < 1 || max_segments > 65535)
     return ARTOPK_EINVAL;
   artopk_ctx* c = new (std::nothrow) artopk_ctx();
   if (!c) return ARTOPK_ENOMEM;
@@ -351,9 +431,10 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   int64_t cap = max_k + cand_share;
   if (cap > max_n) cap = max_n;
   s.cap = (uint32_t)cap;
-  const size_t cap_pad = align_up((size_t)cap, kCompactTile) + kCompactTile;
+  // segmented layouts add per-segment rounding: n_s/8 may be raised to 4096 and bases are aligned
+  s.list_entries = (int64_t)align_up((size_t)cap + (size_t)max_segments * 4100, kCompactTile) + kCompactTile;
   // a range [lo, hi) touches at most ceil(len / tile) + 1 look-back tiles
-  s.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 1;
+  s.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 2 * (int64_t)max_segments + 1;
 
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -361,22 +442,18 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     off = align_up(off + bytes, 256);
     return o;
   };
-  // zeroed head: state | counters | hist1 | hist2 | ssum
-  const size_t o_state = take(sizeof(SelState));
-  const size_t o_cnt = take(16 * sizeof(uint32_t));
-  const size_t o_h1 = take(kHistBins * sizeof(uint32_t));
-  const size_t o_h2 = take(kHistBins * sizeof(uint32_t));
-  const size_t o_ssum = take(kHistBins * sizeof(uint32_t));
-  const size_t o_head_end = off;
-  const size_t o_flags = take((size_t)s.max_tiles * kNumCompactLaunches * sizeof(uint64_t));
-  const size_t o_S = take((size_t)max_w * kMaxChunks * kHistBins * sizeof(uint32_t));
-  const size_t o_coff = take(kMaxChunks * sizeof(uint32_t));
+  // zeroed region: one block per segment, then the look-back flags
+  const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
+                             (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
+  const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
+  const size_t o_coff = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
   const size_t o_part = take((size_t)max_w * kMaxChunks * 2 * sizeof(double));
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
-  const size_t o_list = take(cap_pad * sizeof(uint2));
+  const size_t o_list = take((size_t)s.list_entries * sizeof(uint2));
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
+  const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
   const size_t total = off;
 
   e = hipMalloc(&c->slab, total);
@@ -385,14 +462,9 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return ARTOPK_ENOMEM;
   }
   char* base = static_cast<char*>(c->slab);
-  s.zero_base = reinterpret_cast<uint32_t*>(base + o_state);
-  s.state = reinterpret_cast<SelState*>(base + o_state);
-  s.counters = reinterpret_cast<uint32_t*>(base + o_cnt);
-  s.hist1 = reinterpret_cast<uint32_t*>(base + o_h1);
-  s.hist2 = reinterpret_cast<uint32_t*>(base + o_h2);
-  s.ssum = reinterpret_cast<uint32_t*>(base + o_ssum);
-  s.head_words = (o_head_end - o_state) / sizeof(uint32_t);
-  s.flags = reinterpret_cast<uint64_t*>(base + o_flags);
+  s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
+  // kSegWords is even, so the flags stay 8-byte aligned
+  s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
   s.S = reinterpret_cast<uint32_t*>(base + o_S);
   s.chunk_off = reinterpret_cast<uint32_t*>(base + o_coff);
   s.partials = reinterpret_cast<double*>(base + o_part);
@@ -401,6 +473,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
   s.list = reinterpret_cast<uint2*>(base + o_list);
   s.vals = reinterpret_cast<float*>(base + o_vals);
+  s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
@@ -516,11 +589,15 @@ int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nse
   const PtrTable tab = make_table(one, 1);
   prof_begin(ctx);
   prof_mark(ctx, 1);
-  hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, ctx->stream, 0, ctx->s.leader_dev, (int32_t*)nullptr);
-  if (!seg_off) {
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
+  Plan flat;
+  const Plan* pl = &flat;
+  if (seg_off && nseg > 1) {
+    if ((rc = segmented_plan(ctx, n, nseg, seg_off, seg_k, &pl))) return rc;
+  } else {
+    flat = flat_plan(ctx, n, k);
   }
-  rc = enqueue_select_segments(ctx, tab, n, nseg, seg_off, seg_k, k, idx_out, false, 0);
+  if ((rc = enqueue_clear(ctx, *pl, 0, nullptr))) return rc;  // the single vector is "leader 0"
+  rc = enqueue_select(ctx, *pl, tab, n, idx_out, false, 0);
   prof_mark(ctx, 2);
   return rc;
 }
@@ -574,6 +651,14 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   const PtrTable gt = make_table(g, w);
   const PtrTable rt = make_table(residual, w);
   const bool segmented = seg_off != nullptr && nseg > 1;
+  Plan flat;
+  const Plan* pl = &flat;
+  if (segmented) {
+    if ((rc = segmented_plan(ctx, n, nseg, seg_off, seg_k, &pl))) return rc;
+  } else {
+    flat = flat_plan(ctx, n, k);
+  }
+  // pass A always works on whole-vector chunks; for a flat select they are the select's chunks too
   const ChunkGeom geom = make_geom(0, n);
   const dim3 grid(geom.nchunks, w), block(256);
   const bool nt = ctx->pass_a_nt;
@@ -590,7 +675,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     const PtrTable g1t = make_table(g1, 1), r1t = make_table(r1, 1);
     prof_begin(ctx);
     prof_mark(ctx, 0);
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n), L, leader_out))) return rc;
+    if ((rc = enqueue_clear(ctx, *pl, L, leader_out))) return rc;
     if (nt)
       hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
@@ -598,7 +683,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
       hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
                          st, g1t, r1t, n, geom, 0, s.S, s.partials);
     prof_mark(ctx, 1);
-    if ((rc = enqueue_select(ctx, rt, n, 0, n, k, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
+    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
     prof_mark(ctx, 2);
     if (w > 1) {
       if (nt)
@@ -611,7 +696,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_mark(ctx, 3);
     const int kblocks = (int)((k + 255) / 256);
     hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
-    hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
+    hipLaunchKernelGGL(k_sum_rows, dim3(kblocks), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
     if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
     prof_mark(ctx, 4);
@@ -622,10 +707,8 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   ctx->lvl1_b = 1;
   prof_begin(ctx);
   prof_mark(ctx, 0);
-  // the flat select reuses the histograms pass A builds; segments build their own
-  if (!segmented) {
-    if ((rc = enqueue_clear(ctx, tiles_of_range(0, n)))) return rc;
-  }
+  // the flat select reuses the histograms pass A builds; segments build their own afterwards
+  if ((rc = enqueue_clear(ctx, *pl))) return rc;
   int slot_by_leader = 0;
 #define LAUNCH_PASS_A(STATS, HIST, LEADER)                                                                 \
   do {                                                                                                     \
@@ -657,8 +740,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
 #undef LAUNCH_PASS_A
   HIP_TRY(ctx, hipGetLastError());
 
-  rc = enqueue_select_segments(ctx, rt, n, segmented ? nseg : 1, segmented ? seg_off : nullptr,
-                               segmented ? seg_k : nullptr, k, idx_out, !segmented, slot_by_leader);
+  rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, slot_by_leader);
   if (rc) return rc;
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;

@@ -71,6 +71,69 @@ constexpr uint32_t kErrWait = 2u;      // a bounded look-back wait expired
 constexpr uint32_t kErrSequence = 4u;  // a kernel found the state it needs missing
 constexpr uint32_t kErrIndex = 8u;     // an index outside [0, N) reached gather / scatter
 
+// Layout of one segment's zero-initialised scratch block (32-bit words).
+constexpr int kSegState = 0;                       // SelState (16 words)
+constexpr int kSegCounters = 16;                   // tile counters of the look-back passes (16 words)
+constexpr int kSegHist1 = 32;                      // next-digit histogram, digit 1
+constexpr int kSegHist2 = kSegHist1 + kHistBins;   // next-digit histogram, digit 2
+constexpr int kSegSsum = kSegHist2 + kHistBins;    // suffix sums of the top-digit histogram
+constexpr int kSegWords = kSegSsum + kHistBins;
+constexpr int kNumLookback = 4;                    // flag words per tile: array level 2, 3, list pass, spare
+
+struct ChunkGeom {
+  int64_t chunk0;       // first element of chunk 0 (a multiple of kTile, <= range start)
+  int64_t chunk_elems;  // elements per chunk (a multiple of kTile)
+  int32_t nchunks;
+};
+
+// One selection problem: the k largest magnitudes of x[e_lo, e_hi).
+struct SegDesc {
+  int64_t e_lo, e_hi;
+  ChunkGeom geom;      // chunk layout of the range
+  int64_t koff;        // first slot of this segment in idx_out (and in the leader's vals row)
+  int64_t list_base;   // first entry of this segment's survivor list (a multiple of 4)
+  int64_t flag_base;   // first look-back tile of this segment
+  int32_t chunk_begin; // first chunk slot of this segment in S / chunk_off
+  uint32_t k;          // entries wanted
+  uint32_t cap;        // survivor-list capacity of this segment
+  uint32_t pad;
+};
+
+// Everything the selection kernels need; blockIdx.y (blockIdx.z in k_reduce_hist)
+// picks the segment.  With table == nullptr there is one segment, `one`.
+struct SelParams {
+  PtrTable tab;
+  const int32_t* leader_dev;
+  int64_t n;               // length of the vector
+  uint32_t* zero_base;     // [segments][kSegWords]
+  uint64_t* flags;         // [tiles][kNumLookback]
+  uint32_t* S;             // [slot][kMaxChunks][4096] per-chunk suffix histograms
+  uint32_t* chunk_off;     // [chunks]
+  uint2* list;             // survivor lists
+  int32_t* idx_out;
+  float* vals_row;         // leader's row of gathered values, or nullptr
+  uint32_t* err;
+  const SegDesc* table;
+  int32_t slot_by_leader;  // S slot = *leader_dev (VAR, histograms of all workers) or 0
+  int32_t pad;
+  SegDesc one;
+};
+
+struct SegView {
+  SegDesc d;
+  SelState* st;
+  uint32_t* counters;
+  uint32_t* hist1;
+  uint32_t* hist2;
+  uint32_t* ssum;
+  uint64_t* flags;
+  uint32_t* S;
+  uint32_t* chunk_off;
+  uint2* list;
+  int32_t* idx_out;
+  float* vals_row;
+};
+
 // ---------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------
@@ -99,12 +162,6 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
 
 constexpr int kTile = 8192;       // chunk granularity = compaction tile (two pass-A tiles)
 constexpr int kMaxChunks = 1024;  // chunks per vector range
-
-struct ChunkGeom {
-  int64_t chunk0;       // first element of chunk 0 (a multiple of kTile, <= range start)
-  int64_t chunk_elems;  // elements per chunk (a multiple of kTile)
-  int32_t nchunks;
-};
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -158,6 +215,25 @@ __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, u
     q.w = v[4 * j + 3] + carry;
     reinterpret_cast<uint4*>(dst)[(BPT / 4) * t + j] = q;
   }
+}
+
+__device__ __forceinline__ SegView seg_view(const SelParams& p, int seg) {
+  SegView v;
+  v.d = p.table ? p.table[seg] : p.one;
+  uint32_t* zb = p.zero_base + (size_t)seg * kSegWords;
+  v.st = reinterpret_cast<SelState*>(zb + kSegState);
+  v.counters = zb + kSegCounters;
+  v.hist1 = zb + kSegHist1;
+  v.hist2 = zb + kSegHist2;
+  v.ssum = zb + kSegSsum;
+  v.flags = p.flags + (size_t)v.d.flag_base * kNumLookback;
+  const size_t slot = p.slot_by_leader ? (size_t)(*p.leader_dev) : 0;
+  v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
+  v.chunk_off = p.chunk_off + v.d.chunk_begin;
+  v.list = p.list + v.d.list_base;
+  v.idx_out = p.idx_out + v.d.koff;
+  v.vals_row = p.vals_row ? p.vals_row + v.d.koff : nullptr;
+  return v;
 }
 
 // ---------------------------------------------------------------------------
@@ -403,54 +479,67 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
 
 // ---------------------------------------------------------------------------
 // k_hist0 : per-chunk top-digit suffix histograms of |x[e_lo .. e_hi)| for the
-// leader's vector.  grid = nchunks, block = 256.  Whole aligned float4 groups
-// are read where they lie inside the chunk and the array, single elements at
-// the ragged ends of the range.
+// leader's vector.  grid = (max chunks of a segment, segments), block = 256.
+// Whole aligned float4 groups are read where they lie inside the array, single
+// elements at its ragged end; elements outside the chunk are masked out.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_hist0(PtrTable tab, const int32_t* __restrict__ leader_dev, int64_t n, int64_t e_lo, int64_t e_hi,
-        ChunkGeom geom, uint32_t* __restrict__ S) {
+k_hist0(SelParams p) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
   __shared__ uint32_t red_u[256];
-  const int tid = threadIdx.x;
+  const SegView sv = seg_view(p, blockIdx.y);
   const int c = blockIdx.x;
-  const float* __restrict__ xp = tab.p[*leader_dev];
+  if (c >= sv.d.geom.nchunks) return;
+  const int tid = threadIdx.x;
+  const float* __restrict__ xp = p.tab.p[*p.leader_dev];
   for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
   __syncthreads();
-  int64_t cs = geom.chunk0 + (int64_t)c * geom.chunk_elems;
-  int64_t ce = cs + geom.chunk_elems;
-  if (cs < e_lo) cs = e_lo;
-  if (ce > e_hi) ce = e_hi;
+  int64_t cs = sv.d.geom.chunk0 + (int64_t)c * sv.d.geom.chunk_elems;
+  int64_t ce = cs + sv.d.geom.chunk_elems;
+  if (cs < sv.d.e_lo) cs = sv.d.e_lo;
+  if (ce > sv.d.e_hi) ce = sv.d.e_hi;
+  const int64_t n_vec = p.n & ~(int64_t)3;
   const int64_t q_lo = cs >> 2;
   const int64_t q_hi = (ce + 3) >> 2;  // exclusive
-  for (int64_t q = q_lo + tid; q < q_hi; q += 256) {
-    const int64_t j = q << 2;
-    if (j >= cs && j + 4 <= ce) {
-      const uint4 v = *reinterpret_cast<const uint4*>(xp + j);
-      atomicAdd(&lh[(v.x & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(v.y & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(v.z & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(v.w & kKeyMask) >> 19], 1u);
-    } else {
+  for (int64_t q0 = q_lo + tid; q0 < q_hi; q0 += 256 * 4) {
+    uint4 v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int64_t je = j + e;
-        if (je >= cs && je < ce) atomicAdd(&lh[(__float_as_uint(xp[je]) & kKeyMask) >> 19], 1u);
+    for (int u = 0; u < 4; ++u) {  // whole groups inside the array are read as one vector
+      const int64_t j = (q0 + u * 256) << 2;
+      v[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (q0 + u * 256 < q_hi) {
+        if (j + 4 <= n_vec) {
+          v[u] = *reinterpret_cast<const uint4*>(xp + j);
+        } else {
+          v[u].x = (j + 0 < p.n) ? __float_as_uint(xp[j + 0]) : 0u;
+          v[u].y = (j + 1 < p.n) ? __float_as_uint(xp[j + 1]) : 0u;
+          v[u].z = (j + 2 < p.n) ? __float_as_uint(xp[j + 2]) : 0u;
+          v[u].w = (j + 3 < p.n) ? __float_as_uint(xp[j + 3]) : 0u;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t j = (q0 + u * 256) << 2;
+      if (q0 + u * 256 < q_hi) {
+        const uint32_t kk[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j + e >= cs && j + e < ce) atomicAdd(&lh[(kk[e] & kKeyMask) >> 19], 1u);
       }
     }
   }
-  flush_suffix_hist<256>(lh, red_u, S + (size_t)c * kHistBins);
+  flush_suffix_hist<256>(lh, red_u, sv.S + (size_t)c * kHistBins);
 }
 
 // ---------------------------------------------------------------------------
-// k_reduce_hist : Ssum[b] += sum over chunks of S[slot][c][b] for the leader's
-// slot.  grid = (16, ysplit), block = 256; Ssum must be zero on entry.
+// k_reduce_hist : ssum[b] += sum over the segment's chunks of S[c][b].
+// grid = (16, ysplit, segments), block = 256; ssum must be zero on entry.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_reduce_hist(const uint32_t* __restrict__ S, const int32_t* __restrict__ leader_dev, int slot_by_leader,
-              int nchunks, uint32_t* __restrict__ Ssum) {
-  const size_t slot = slot_by_leader ? (size_t)(*leader_dev) : 0;
-  const uint32_t* __restrict__ base = S + slot * kMaxChunks * kHistBins;
+k_reduce_hist(SelParams p) {
+  const SegView sv = seg_view(p, blockIdx.z);
+  const int nchunks = sv.d.geom.nchunks;
   const int bin = blockIdx.x * 256 + threadIdx.x;
   const int per = (nchunks + gridDim.y - 1) / gridDim.y;
   const int c0 = blockIdx.y * per;
@@ -458,59 +547,58 @@ k_reduce_hist(const uint32_t* __restrict__ S, const int32_t* __restrict__ leader
   if (c1 > nchunks) c1 = nchunks;
   uint32_t acc = 0u;
 #pragma unroll 8
-  for (int c = c0; c < c1; ++c) acc += base[(size_t)c * kHistBins + bin];
-  if (acc) atomicAdd(&Ssum[bin], acc);
+  for (int c = c0; c < c1; ++c) acc += sv.S[(size_t)c * kHistBins + bin];
+  if (acc) atomicAdd(&sv.ssum[bin], acc);
 }
 
 // ---------------------------------------------------------------------------
-// k_pick0 : one block of 1024 threads.  Initialises the selection state for a
-// range of n_range elements with k wanted, finds the threshold top digit b0 =
-// the largest b with Ssum[b] >= k, and gives every chunk the offset of its
-// survivors (keys with top digit >= b0) in the survivor list.
+// k_pick0 : one block of 1024 threads per segment.  Initialises the selection
+// state, finds the threshold top digit b0 = the largest b with ssum[b] >= k,
+// and gives every chunk of the segment the offset of its survivors (keys with
+// top digit >= b0) in the segment's survivor list.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
-k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uint32_t* __restrict__ S,
-        const int32_t* __restrict__ leader_dev, int slot_by_leader, int nchunks, uint32_t n_range, uint32_t k,
-        uint32_t* __restrict__ chunk_off, uint32_t* __restrict__ err) {
+k_pick0(SelParams p) {
   __shared__ uint32_t part[1024];
   __shared__ int b0_sh;
+  const SegView sv = seg_view(p, blockIdx.y);
+  const uint32_t k = sv.d.k;
+  const int nchunks = sv.d.geom.nchunks;
   const int t = threadIdx.x;
   if (t == 0) b0_sh = -1;
   __syncthreads();
-  uint32_t sv[5];
+  uint32_t sx[5];
 #pragma unroll
   for (int j = 0; j < 5; ++j) {
     const int b = 4 * t + j;
-    sv[j] = (b < kHistBins) ? Ssum[b] : 0u;
+    sx[j] = (b < kHistBins) ? sv.ssum[b] : 0u;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    if (sv[j] >= k && sv[j + 1] < k) b0_sh = 4 * t + j;  // Ssum is non-increasing: one hit
+    if (sx[j] >= k && sx[j + 1] < k) b0_sh = 4 * t + j;  // ssum is non-increasing: one hit
   }
   __syncthreads();
   const int b0 = b0_sh;
   if (b0 < 0) {
-    if (t == 0) atomicOr(err, kErrPick);
+    if (t == 0) atomicOr(p.err, kErrPick);
     return;
   }
   if (t == 0) {
     SelState st;
-    const uint32_t above = (b0 + 1 < kHistBins) ? Ssum[b0 + 1] : 0u;
+    const uint32_t above = (b0 + 1 < kHistBins) ? sv.ssum[b0 + 1] : 0u;
     st.lo = (uint32_t)b0 << 19;
     st.hi = st.lo | 0x7ffffu;
     st.n_gt = above;
     st.need = k - above;
-    st.cand = Ssum[b0] - above;
+    st.cand = sv.ssum[b0] - above;
     st.level = 1u;
     st.compact_level = 0u;
     st.list_count = 0u;
     for (int i = 0; i < 8; ++i) st.pad[i] = 0u;
-    st.pad[0] = n_range;
-    *stp = st;
+    *sv.st = st;
   }
   // exclusive scan of the per-chunk survivor counts
-  const size_t slot = slot_by_leader ? (size_t)(*leader_dev) : 0;
-  const uint32_t mine = (t < nchunks) ? S[(slot * kMaxChunks + (size_t)t) * kHistBins + b0] : 0u;
+  const uint32_t mine = (t < nchunks) ? sv.S[(size_t)t * kHistBins + b0] : 0u;
   part[t] = mine;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {  // inclusive prefix sums
@@ -519,7 +607,7 @@ k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uin
     part[t] += v;
     __syncthreads();
   }
-  if (t < nchunks) chunk_off[t] = part[t] - mine;
+  if (t < nchunks) sv.chunk_off[t] = part[t] - mine;
 }
 
 // ---------------------------------------------------------------------------
@@ -534,25 +622,31 @@ k_pick0(SelState* __restrict__ stp, const uint32_t* __restrict__ Ssum, const uin
 // ---------------------------------------------------------------------------
 template <int WAVES, int R, bool PF>
 __global__ void __launch_bounds__(64 * WAVES)
-k_compact1(PtrTable tab, const int32_t* __restrict__ leader_dev, const SelState* __restrict__ stp, int64_t n,
-           int64_t e_lo, int64_t e_hi, ChunkGeom geom, const uint32_t* __restrict__ chunk_off, uint32_t cap,
-           uint32_t* __restrict__ hist1, uint2* __restrict__ list, const uint32_t* __restrict__ err) {
+k_compact1(SelParams p) {
   constexpr int T = 64 * WAVES;
   constexpr int WSPAN = R * 256;       // consecutive elements one wave owns in a tile
   constexpr int TILE = WAVES * WSPAN;  // elements per block iteration
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint32_t wtot[2][WAVES];
 
+  const SegView sv = seg_view(p, blockIdx.y);
+  const int c = blockIdx.x;
+  if (c >= sv.d.geom.nchunks) return;
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
   const uint32_t lane = lane_id();
-  const int c = blockIdx.x;
+  const int64_t n = p.n, e_lo = sv.d.e_lo, e_hi = sv.d.e_hi;
+  const ChunkGeom geom = sv.d.geom;
+  const uint32_t cap = sv.d.cap;
+  const uint32_t* __restrict__ chunk_off = sv.chunk_off;
+  uint32_t* __restrict__ hist1 = sv.hist1;
+  uint2* __restrict__ list = sv.list;
 
-  const SelState st = *stp;
-  if (st.level != 1u || st.compact_level != 0u || *err) return;
+  const SelState st = *sv.st;
+  if (st.level != 1u || st.compact_level != 0u || *p.err) return;
   const bool write_out = (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
   const uint32_t klo = st.lo, khi = st.hi;
-  const float* __restrict__ xp = tab.p[*leader_dev];
+  const float* __restrict__ xp = p.tab.p[*p.leader_dev];
 
   for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
   __syncthreads();
@@ -692,12 +786,16 @@ __device__ __forceinline__ bool fits_list(const SelState& st, uint32_t cap) {
 }
 
 __global__ void __launch_bounds__(1024)
-k_pick(SelState* __restrict__ stp, const uint32_t* __restrict__ hist, int stage, uint32_t cap,
-       uint32_t* __restrict__ err) {
+k_pick(SelParams p, int stage) {
   __shared__ uint32_t part[1024];
   __shared__ SelState st;
   __shared__ int run_pick;
   __shared__ uint32_t found;
+  const SegView sv = seg_view(p, blockIdx.y);
+  SelState* __restrict__ stp = sv.st;
+  const uint32_t* __restrict__ hist = (stage == 1) ? sv.hist1 : sv.hist2;
+  const uint32_t cap = sv.d.cap;
+  uint32_t* __restrict__ err = p.err;
   const int t = threadIdx.x;
   if (t == 0) {
     st = *stp;
@@ -859,15 +957,27 @@ constexpr int kWaveSpan = 64 * 4 * kCompactRows;                  // 2048 elemen
 
 template <bool LIST>
 __global__ void __launch_bounds__(kCompactThreads)
-k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __restrict__ stp, int level,
-          int64_t n, int64_t e_lo, int64_t e_hi, uint32_t cap, uint32_t* __restrict__ hist_next,
-          uint64_t* __restrict__ flags, int flag_stride, uint32_t* __restrict__ tile_counter,
-          uint2* __restrict__ list, int32_t* __restrict__ idx_out, float* __restrict__ vals_row, uint32_t k_out,
-          uint32_t* __restrict__ err) {
+k_compact(SelParams p, int level, int launch_id) {
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint64_t wave_tot[8];
   __shared__ uint64_t tile_excl;
   __shared__ int64_t tile_sh;
+
+  const SegView sv = seg_view(p, blockIdx.y);
+  SelState* __restrict__ stp = sv.st;
+  int64_t n = p.n, e_lo = sv.d.e_lo, e_hi = sv.d.e_hi;
+  const uint32_t cap = sv.d.cap;
+  uint32_t* __restrict__ hist_next = sv.hist2;
+  uint64_t* __restrict__ flags = sv.flags + launch_id;
+  constexpr int flag_stride = kNumLookback;
+  uint32_t* __restrict__ tile_counter = sv.counters + launch_id;
+  uint2* __restrict__ list = sv.list;
+  int32_t* __restrict__ idx_out = sv.idx_out;
+  float* __restrict__ vals_row = sv.vals_row;
+  const uint32_t k_out = sv.d.k;
+  uint32_t* __restrict__ err = p.err;
+  const PtrTable& tab = p.tab;
+  const int32_t* __restrict__ leader_dev = p.leader_dev;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -1063,23 +1173,23 @@ k_compact(PtrTable tab, const int32_t* __restrict__ leader_dev, SelState* __rest
 // survivor list; runs only when the list was written at level 1.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_list_hist(const SelState* __restrict__ stp, const uint2* __restrict__ list,
-            uint32_t* __restrict__ hist2, const uint32_t* __restrict__ err) {
+k_list_hist(SelParams p) {
   __shared__ uint32_t lh[128];
-  const SelState st = *stp;
-  if (st.compact_level != 1u || st.level != 2u || *err) return;
+  const SegView sv = seg_view(p, blockIdx.y);
+  const SelState st = *sv.st;
+  if (st.compact_level != 1u || st.level != 2u || *p.err) return;
   const int tid = threadIdx.x;
   if (tid < 128) lh[tid] = 0u;
   __syncthreads();
   const uint32_t cnt = st.list_count;
-  for (uint32_t p = blockIdx.x * 256u + tid; p < cnt; p += gridDim.x * 256u) {
-    const uint32_t key = list[p].y & kKeyMask;
+  for (uint32_t q = blockIdx.x * 256u + tid; q < cnt; q += gridDim.x * 256u) {
+    const uint32_t key = sv.list[q].y & kKeyMask;
     if (key >= st.lo && key <= st.hi) atomicAdd(&lh[key & 0x7fu], 1u);
   }
   __syncthreads();
   if (tid < 128) {
     const uint32_t v = lh[tid];
-    if (v) atomicAdd(&hist2[tid], v);
+    if (v) atomicAdd(&sv.hist2[tid], v);
   }
 }
 
@@ -1219,19 +1329,19 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_sum_rows(const float* __restrict__ vals, int w_count, int64_t k, float* __restrict__ sum) {
-  const int64_t m0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (m0 >= k) return;
-  if (m0 + 4 <= k && (k & 3) == 0) {  // rows stay 16-byte aligned when k is a multiple of 4
-    v4f s = *reinterpret_cast<const v4f*>(vals + m0);
-    for (int w = 1; w < w_count; ++w) s = s + *reinterpret_cast<const v4f*>(vals + (size_t)w * (size_t)k + m0);
-    *reinterpret_cast<v4f*>(sum + m0) = s;
-  } else {
-    for (int64_t m = m0; m < m0 + 4 && m < k; ++m) {
-      float s = vals[m];
-      for (int w = 1; w < w_count; ++w) s = s + vals[(size_t)w * (size_t)k + (size_t)m];
-      sum[m] = s;
-    }
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= k) return;
+  float s = 0.0f;
+  for (int w0 = 0; w0 < w_count; w0 += 8) {  // eight independent loads in flight, then the ordered adds
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (w0 + j < w_count) v[j] = vals[(size_t)(w0 + j) * (size_t)k + (size_t)m];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (w0 + j < w_count) s = (w0 + j == 0) ? v[j] : (s + v[j]);
   }
+  sum[m] = s;
 }
 
 // ---------------------------------------------------------------------------
