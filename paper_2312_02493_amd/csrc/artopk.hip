@@ -345,9 +345,8 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   if (ysplit < 1) ysplit = 1;
   hipLaunchKernelGGL(k_reduce_hist, dim3(kHistBins / 256, ysplit, nseg), dim3(256), 0, st, p);
   hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p);
-  // 8 waves x 8 rows (64 KiB per block iteration), no prefetch: best of the shapes measured on the
-  // 138 M and 1 G workloads, though all of them lie within 5 %
-  hipLaunchKernelGGL((k_compact1<8, 8, false>), dim3(pl.max_chunks, nseg), dim3(512), 0, st, p);
+  // 4 waves, 16 consecutive elements per lane: best of the shapes measured on the 138 M and 1 G workloads
+  hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
   hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 1);
 
   // deeper array passes: they run only for segments whose level-1 survivors did not fit the list

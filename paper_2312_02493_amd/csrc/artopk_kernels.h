@@ -616,16 +616,20 @@ k_pick0(SelParams p) {
 // list in ascending element order at chunk_off[c] + rank inside the chunk;
 // candidates (top digit == b0) also feed the next-digit histogram hist1.
 // If the list cannot hold n_gt + cand entries nothing is written and only the
-// histogram is built.  block = WAVES waves; a tile is WAVES x R rows x 64 lanes
-// x 4 consecutive elements, each wave owning R*256 consecutive elements; with
-// PF the next tile is loaded while the current one is processed.
+// histogram is built.  block = WAVES waves; in a tile every lane owns 4 R
+// consecutive elements (lane-contiguous loads run at the same bandwidth as
+// row-coalesced ones here), so a survivor's rank is the lane's exclusive prefix
+// plus its position among the lane's own survivors: five or six ballots per
+// tile instead of one per element.
 // ---------------------------------------------------------------------------
-template <int WAVES, int R, bool PF>
+template <int WAVES, int R>
 __global__ void __launch_bounds__(64 * WAVES)
 k_compact1(SelParams p) {
   constexpr int T = 64 * WAVES;
-  constexpr int WSPAN = R * 256;       // consecutive elements one wave owns in a tile
+  constexpr int E = 4 * R;             // consecutive elements one lane owns in a tile
+  constexpr int WSPAN = 64 * E;        // consecutive elements one wave owns in a tile
   constexpr int TILE = WAVES * WSPAN;  // elements per block iteration
+  static_assert(E <= 32, "one 32-bit mask per lane");
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint32_t wtot[2][WAVES];
 
@@ -638,8 +642,6 @@ k_compact1(SelParams p) {
   const int64_t n = p.n, e_lo = sv.d.e_lo, e_hi = sv.d.e_hi;
   const ChunkGeom geom = sv.d.geom;
   const uint32_t cap = sv.d.cap;
-  const uint32_t* __restrict__ chunk_off = sv.chunk_off;
-  uint32_t* __restrict__ hist1 = sv.hist1;
   uint2* __restrict__ list = sv.list;
 
   const SelState st = *sv.st;
@@ -656,65 +658,58 @@ k_compact1(SelParams p) {
   const int64_t cs = c_begin > e_lo ? c_begin : e_lo;  // elements of the range owned by this chunk
   const int64_t ce = c_end < e_hi ? c_end : e_hi;
   const int64_t n_vec = n & ~(int64_t)3;
-  const int64_t lane_off = (int64_t)wave * WSPAN + (int64_t)lane * 4;
+  const int64_t lane_off = (int64_t)wave * WSPAN + (int64_t)lane * E;
 
-  // raw bits of this lane's R x 4 elements of the tile starting at element tb
-  // (groups that are not wholly inside the array are read element by element, absent ones as 0)
-  auto load_tile = [&](int64_t tb, uint4 (&v)[R]) {
-    const int64_t j0 = tb + lane_off;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int64_t j = j0 + r * 256;
-      if (j + 4 <= n_vec) {
-        v[r] = *reinterpret_cast<const uint4*>(xp + j);
-      } else {
-        v[r].x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
-        v[r].y = (j + 1 < n) ? __float_as_uint(xp[j + 1]) : 0u;
-        v[r].z = (j + 2 < n) ? __float_as_uint(xp[j + 2]) : 0u;
-        v[r].w = (j + 3 < n) ? __float_as_uint(xp[j + 3]) : 0u;
-      }
-    }
-  };
-
-  uint32_t run = write_out ? chunk_off[c] : 0u;  // list position of the next survivor of this chunk
+  uint32_t run = write_out ? sv.chunk_off[c] : 0u;  // list position of the next survivor of this chunk
   int buf = 0;
-  uint4 cur[R], nxt[R];
-  if (PF && c_begin < ce) load_tile(c_begin, cur);
 
   for (int64_t tb = c_begin; tb < ce; tb += TILE) {
-    if constexpr (PF) {
-      if (tb + TILE < ce) load_tile(tb + TILE, nxt);
-    } else {
-      load_tile(tb, cur);
+    const int64_t j0 = tb + lane_off;  // this lane's E consecutive elements start here
+    // raw bits; groups that are not wholly inside the array are read element by element, absent ones as 0
+    uint32_t raw[E];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t j = j0 + 4 * r;
+      uint4 v;
+      if (j + 4 <= n_vec) {
+        v = *reinterpret_cast<const uint4*>(xp + j);
+      } else {
+        v.x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
+        v.y = (j + 1 < n) ? __float_as_uint(xp[j + 1]) : 0u;
+        v.z = (j + 2 < n) ? __float_as_uint(xp[j + 2]) : 0u;
+        v.w = (j + 3 < n) ? __float_as_uint(xp[j + 3]) : 0u;
+      }
+      raw[4 * r + 0] = v.x;
+      raw[4 * r + 1] = v.y;
+      raw[4 * r + 2] = v.z;
+      raw[4 * r + 3] = v.w;
     }
-    const int64_t j0 = tb + lane_off;
     // every element of this tile belongs to the chunk and the range?
     const bool clean = (tb >= cs) && (tb + TILE <= ce);
 
-    // ---- count survivors (key >= klo); candidates (key <= khi) feed the next-digit histogram
-    uint32_t cnt = 0u;
+    // survivors (key >= klo) among this lane's elements, one bit each
+    uint32_t own = 0u;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const uint32_t kk[4] = {cur[r].x & kKeyMask, cur[r].y & kKeyMask, cur[r].z & kKeyMask, cur[r].w & kKeyMask};
+    for (int e = 0; e < E; ++e) {
+      bool ok = (raw[e] & kKeyMask) >= klo;
+      if (!clean) ok = ok && (j0 + e >= cs) && (j0 + e < ce);
+      own |= ok ? (1u << e) : 0u;
+    }
+    const uint32_t cnt = (uint32_t)__popc(own);
+    // exclusive prefix of cnt over the lanes and the wave total, from the bit planes of cnt
+    uint32_t before = 0u, wsum = 0u;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        bool ok = kk[e] >= klo;
-        if (!clean) {
-          const int64_t j = j0 + r * 256 + e;
-          ok = ok && j >= cs && j < ce;
-        }
-        const uint64_t m = __ballot(ok);
-        if (m != 0ull) {
-          cnt += (uint32_t)__popcll(m);
-          if (ok && kk[e] <= khi) atomicAdd(&lh[(kk[e] >> 7) & 0xfffu], 1u);
-        }
-      }
+    for (int b = 0; (1 << b) <= E; ++b) {
+      const uint64_t plane = __ballot((cnt >> b) & 1u);
+      before += popc_lt(plane) << b;
+      wsum += (uint32_t)__popcll(plane) << b;
     }
 
+    uint32_t base = 0u;
     if (write_out) {
-      if (lane == 0) wtot[buf][wave] = cnt;
+      if (lane == 0) wtot[buf][wave] = wsum;
       __syncthreads();
-      uint32_t base = run;
+      base = run;
 #pragma unroll
       for (int i = 0; i < WAVES; ++i) {
         const uint32_t wt = wtot[buf][i];
@@ -722,48 +717,26 @@ k_compact1(SelParams p) {
         run += wt;
       }
       buf ^= 1;
-      if (cnt != 0u) {
-        // ---- emit: survivors of lower lanes of a row come first, then this lane's own in slot order
+    }
+    if (own != 0u) {  // few lanes get here
+      uint32_t pos = base + before;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-          const uint32_t raw[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
-          uint64_t bm[4];
-          bool mine[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            bool ok = (raw[e] & kKeyMask) >= klo;
-            if (!clean) {
-              const int64_t j = j0 + r * 256 + e;
-              ok = ok && j >= cs && j < ce;
-            }
-            mine[e] = ok;
-            bm[e] = __ballot(ok);
-          }
-          if ((bm[0] | bm[1] | bm[2] | bm[3]) != 0ull) {
-            uint32_t pos = base + popc_lt(bm[0]) + popc_lt(bm[1]) + popc_lt(bm[2]) + popc_lt(bm[3]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              if (mine[e]) {
-                // (index, raw bits): the sign travels with the survivor
-                if (pos < cap) list[pos] = make_uint2((uint32_t)(j0 + r * 256 + e), raw[e]);
-                ++pos;
-              }
-            }
-            base += (uint32_t)(__popcll(bm[0]) + __popcll(bm[1]) + __popcll(bm[2]) + __popcll(bm[3]));
-          }
+      for (int e = 0; e < E; ++e) {
+        if ((own >> e) & 1u) {
+          const uint32_t kk = raw[e] & kKeyMask;
+          if (kk <= khi) atomicAdd(&lh[(kk >> 7) & 0xfffu], 1u);  // candidate: feeds the next digit
+          // (index, raw bits): the sign travels with the survivor
+          if (write_out && pos < cap) list[pos] = make_uint2((uint32_t)(j0 + e), raw[e]);
+          ++pos;
         }
       }
-    }
-    if constexpr (PF) {
-#pragma unroll
-      for (int r = 0; r < R; ++r) cur[r] = nxt[r];
     }
   }
 
   __syncthreads();
   for (int b = tid; b < kHistBins; b += T) {
     const uint32_t v = lh[b];
-    if (v) atomicAdd(&hist1[b], v);
+    if (v) atomicAdd(&sv.hist1[b], v);
   }
 }
 

@@ -238,3 +238,80 @@ def test_invalid_arguments_are_rejected():
     with pytest.raises(lib.ArTopkError):
         ctx.artopk_select_topk(x[0], 10, idx, seg_off=[0, 500, n], seg_k=[5, 6])   # sum(seg_k) != k
     ctx.status()
+
+
+# ------------------------------------------------------------------ segmented selection, edge cases
+def _segmented_select(x, seg_off, seg_k, max_segments=None):
+    import torch
+    import paper_2312_02493_amd as lib
+
+    dev = torch.device("cuda:0")
+    k = int(sum(seg_k))
+    ctx = lib.Context(1, x.size, k, max_segments=max_segments or len(seg_k))
+    xd = torch.from_numpy(x).to(dev)
+    idx = torch.full((k,), -1, dtype=torch.int32, device=dev)
+    ctx.artopk_select_topk(xd, k, idx, seg_off=[int(v) for v in seg_off], seg_k=[int(v) for v in seg_k])
+    ctx.status()
+    want = orc.topk_indices_segmented(x, seg_off, seg_k)
+    got = idx.cpu().numpy()
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"segmented idx differs first at {bad[:5]}: got {got[bad[:5]]} want {want[bad[:5]]}"
+    return ctx, xd, idx
+
+
+def test_segments_tiny_ragged_and_many():
+    rng = np.random.default_rng(21)
+    sizes = [1, 2, 3, 5, 1, 64, 63, 4097, 8191, 8193, 1, 30000, 7, 16385]
+    sizes += [int(v) for v in rng.integers(1, 300, 400)]            # several hundred small layers
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    x = rng.standard_normal(n).astype(np.float32)
+    x[rng.integers(0, n, n // 10)] = 0.5                             # planted ties
+    ks = [max(1, int(np.ceil(0.05 * s))) for s in sizes]
+    ks[7] = sizes[7]                                                 # one segment kept entirely
+    ks[9] = 1
+    _segmented_select(x, off, ks)
+
+
+def test_segments_with_degenerate_members():
+    """One all-equal segment larger than its survivor list (forces the deeper array passes for
+    that segment only), one all-zero segment, next to ordinary ones."""
+    rng = np.random.default_rng(22)
+    sizes = [50_000, 700_000, 123_457, 300_000, 9]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(off[-1])
+    x = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    x[off[1]:off[2]] = np.float32(-0.125)                            # all equal (sign ignored)
+    x[off[1] + 5:off[2]:3] = np.float32(0.125)
+    x[off[3]:off[4]] = 0.0                                           # all zero
+    ks = [500, 40_000, 1235, 17, 9]
+    ctx, xd, idx = _segmented_select(x, off, ks)
+    got = idx.cpu().numpy()
+    assert np.array_equal(got[500:40_500], np.arange(off[1], off[1] + 40_000, dtype=np.int32))
+    # the same context must serve a different layout afterwards (descriptor table is re-uploaded)
+    off2 = [0, 100_000, n]
+    ks2 = [10, 41_751]
+    idx.fill_(-1)
+    ctx.artopk_select_topk(xd, sum(ks2), idx, seg_off=off2, seg_k=ks2)
+    ctx.status()
+    assert np.array_equal(idx.cpu().numpy(), orc.topk_indices_segmented(x, off2, ks2))
+
+
+def test_segmented_step_star_fixed_leader():
+    rng = np.random.default_rng(23)
+    sizes = [3000, 1, 50_000, 20_001, 64]
+    off = [int(v) for v in np.concatenate([[0], np.cumsum(sizes)])]
+    n = off[-1]
+    ks = [30, 1, 777, 200, 64]
+    k = sum(ks)
+    w = 3
+    g = [rng.standard_normal(n).astype(np.float32) for _ in range(w)]
+    res = [(rng.standard_normal(n) * 0.3).astype(np.float32) for _ in range(w)]
+    run = GpuRunner(w, n, k, max_segments=len(ks))
+    for step_no in (1, 2):
+        run.load_g(g)
+        run.load_res(res)
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no, seg_off=off, seg_k=ks)
+        got = run.step(k, orc.MODE_STAR, step_no, seg_off=off, seg_k=ks)
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
