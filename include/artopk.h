@@ -167,6 +167,30 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
                 float* sum_out, float* update_out);
 
 /*
+ * Compression gain of every worker for the step just taken (the heuristic the
+ * paper quotes in Sec. II-C, "Statistical Efficiency in Gradient Compression":
+ * ||g_c||^2 / ||g_e||^2 with g_e the error-fed and g_c the compressed gradient).
+ * Because g_e = g_c + residual with disjoint supports, it is computed from the
+ * step's outputs as V / (V + R), V = sum vals_w^2, R = sum residual_w^2, in
+ * float64.  Reads 4*W*N + 4*W*k bytes.
+ *   residual host array of W device pointers: the residuals AFTER artopk_step
+ *   vals     device W*k float32, the step's vals_out
+ *   gain_out device W float64
+ */
+int artopk_compression_gain(artopk_ctx* ctx, const float* const* residual, int32_t w, int64_t n,
+                            const float* vals, int64_t k, double* gain_out);
+
+/*
+ * Sparse form of the model update of Alg. 1 (w <- w - eta * g~): only the k
+ * reduced positions change, weights[idx[m]] -= eta * sum[m] in float32 (one
+ * multiply, one subtract).  A caller that applies the update this way does not
+ * need the dense update_out of artopk_step.
+ *   weights device N float32, updated in place; idx, sum as produced by the step
+ */
+int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_t* idx,
+                        const float* sum, int64_t k, float eta);
+
+/*
  * Stage timing.  enable = 1 brackets only the dominant kernel of every
  * artopk_step (PASS_A, or GATHER when the leader is known up front) with two
  * HIP events on the context's stream; enable = 2 records

@@ -236,6 +236,29 @@ def step(g: Sequence[np.ndarray], residual: Sequence[np.ndarray], k: int,
 
 
 # --------------------------------------------------------------------------
+# neighbours of the step: compression gain and the sparse model update
+# --------------------------------------------------------------------------
+def compression_gain(acc: np.ndarray, idx: np.ndarray) -> float:
+    """||g_c||^2 / ||g_e||^2 for one worker (Sec. II-C, statistical efficiency
+    of compression): g_e is the error-fed gradient ``acc``, g_c keeps only the
+    communicated positions.  float64 sums of squares."""
+    a = np.asarray(acc, dtype=np.float32).astype(np.float64)
+    kept = a[np.asarray(idx, dtype=np.int64)]
+    total = float((a * a).sum())
+    return float((kept * kept).sum()) / total if total > 0.0 else 0.0
+
+
+def apply_update(weights: np.ndarray, idx: np.ndarray, summed: np.ndarray, eta: float) -> np.ndarray:
+    """Alg. 1 model update restricted to the communicated positions:
+    w[idx] = w[idx] - eta * g~ in float32 (product rounded, then difference)."""
+    w = np.array(weights, dtype=np.float32, copy=True)
+    i = np.asarray(idx, dtype=np.int64)
+    step = np.multiply(np.float32(eta), np.asarray(summed, np.float32), dtype=np.float32)
+    w[i] = np.subtract(w[i], step, dtype=np.float32)
+    return w
+
+
+# --------------------------------------------------------------------------
 # O(n) uniqueness certificate for a claimed Top-k index set
 # --------------------------------------------------------------------------
 def topk_certificate(acc: np.ndarray, idx: np.ndarray, k: int) -> Tuple[bool, str]:

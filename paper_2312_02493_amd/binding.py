@@ -18,7 +18,8 @@ PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 _SYMBOLS = (
     "artopk_create", "artopk_destroy", "artopk_last_error", "artopk_status", "artopk_variance",
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
-    "artopk_set_profile", "artopk_get_profile", "artopk_version",
+    "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
+    "artopk_apply_update",
 )
 
 
@@ -59,6 +60,8 @@ def load_library():
     lib.artopk_gather_sum.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_scatter_residual.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_step.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, i64, i32, u64, i32, vp, vp, vp, vp, vp, vp]
+    lib.artopk_compression_gain.argtypes = [vp, vp, i32, i64, vp, i64, vp]
+    lib.artopk_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, C.c_float]
     lib.artopk_set_profile.argtypes = [vp, i32]
     lib.artopk_get_profile.argtypes = [vp, C.POINTER(C.c_float), i32]
     lib.artopk_version.restype = i32
@@ -152,6 +155,15 @@ class Context:
         n = residual[0].numel()
         self._check(self._lib.artopk_scatter_residual(self._h, _ptr_table(residual), len(residual), n, _ptr(idx), k,
                                                       _ptr(summed), _ptr(update)))
+
+    def artopk_compression_gain(self, residual: Sequence, vals, k: int, gain_out):
+        n = residual[0].numel()
+        self._check(self._lib.artopk_compression_gain(self._h, _ptr_table(residual), len(residual), n, _ptr(vals),
+                                                      k, _ptr(gain_out)))
+
+    def artopk_apply_update(self, weights, idx, summed, k: int, eta: float):
+        self._check(self._lib.artopk_apply_update(self._h, _ptr(weights), weights.numel(), _ptr(idx), _ptr(summed),
+                                                  k, C.c_float(eta)))
 
     def artopk_step(self, g: Sequence, residual: Sequence, k: int, mode: int, step: int, idx_out, sum_out,
                     update_out, vals_out=None, leader_out=None, var_out=None, fixed_leader: int = 0,

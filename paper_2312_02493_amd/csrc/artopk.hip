@@ -571,7 +571,7 @@ int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n
   const PtrTable tab = make_table(x, w);
   const int nblk = stats_blocks(ctx, w, n);
   Scratch& s = ctx->s;
-  hipLaunchKernelGGL(k_stats, dim3(nblk, w), dim3(256), 0, ctx->stream, tab, n, s.partials);
+  hipLaunchKernelGGL((k_stats<true, true>), dim3(nblk, w), dim3(256), 0, ctx->stream, tab, n, s.partials);
   hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, ctx->stream, s.partials, (int)w, nblk, n, s.var_scratch,
                      var_out, s.leader_dev, argmax_out);
   HIP_TRY(ctx, hipGetLastError());
@@ -623,6 +623,44 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
   const int blocks = (int)((k + 255) / 256);
   hipLaunchKernelGGL(k_zero_at, dim3(blocks), dim3(256), 0, ctx->stream, tab, (int)w, n, idx, k, ctx->s.err_dev);
   return enqueue_update_fill(ctx, update, n, idx, sum, k);
+}
+
+int artopk_compression_gain(artopk_ctx* ctx, const float* const* residual, int32_t w, int64_t n,
+                            const float* vals, int64_t k, double* gain_out) {
+  int rc = check_common(ctx, w, n, k);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
+  if (!vals || !gain_out) return fail(ctx, ARTOPK_EINVAL, "vals or gain_out is NULL");
+  Scratch& s = ctx->s;
+  const PtrTable rtab = make_table(residual, w);
+  PtrTable vtab;
+  for (int i = 0; i < kMaxW; ++i) vtab.p[i] = (i < w) ? const_cast<float*>(vals) + (size_t)i * (size_t)k : nullptr;
+  const int nblk_res = stats_blocks(ctx, w, n);
+  int nblk_vals = (int)((k + 256 * 16 - 1) / (256 * 16));
+  if (nblk_vals < 1) nblk_vals = 1;
+  if (nblk_vals > kMaxChunks / 2) nblk_vals = kMaxChunks / 2;
+  // the two partial arrays share the variance scratch: residual partials first
+  double* part_res = s.partials;
+  double* part_vals = s.partials + (size_t)ctx->max_w * (kMaxChunks / 2) * 2;
+  const int nblk_res_c = nblk_res > kMaxChunks / 2 ? kMaxChunks / 2 : nblk_res;
+  hipLaunchKernelGGL((k_stats<false, true>), dim3(nblk_res_c, w), dim3(256), 0, ctx->stream, rtab, n, part_res);
+  hipLaunchKernelGGL((k_stats<false, false>), dim3(nblk_vals, w), dim3(256), 0, ctx->stream, vtab, k, part_vals);
+  hipLaunchKernelGGL(k_gain, dim3(1), dim3(1024), 0, ctx->stream, part_vals, nblk_vals, part_res, nblk_res_c, (int)w,
+                     gain_out);
+  HIP_TRY(ctx, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_t* idx, const float* sum,
+                        int64_t k, float eta) {
+  int rc = check_common(ctx, 1, n, k);
+  if (rc) return rc;
+  if (!weights || !idx || !sum) return fail(ctx, ARTOPK_EINVAL, "weights, idx or sum is NULL");
+  const int blocks = (int)((k + 255) / 256);
+  hipLaunchKernelGGL(k_apply_update, dim3(blocks), dim3(256), 0, ctx->stream, weights, n, idx, sum, k, eta,
+                     ctx->s.err_dev);
+  HIP_TRY(ctx, hipGetLastError());
+  return ARTOPK_OK;
 }
 
 int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w, int64_t n,

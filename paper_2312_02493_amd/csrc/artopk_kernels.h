@@ -380,47 +380,50 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 }
 
 // ---------------------------------------------------------------------------
-// k_stats : variance partials of read-only vectors.  grid = (nblk, W).
+// k_stats : per-block sums of (x - c) and (x - c)^2 of read-only vectors in
+// float64, c = x[0] with SHIFT (variance) or 0 (sum of squares).  grid = (nblk, W).
+// VEC reads float4 groups (rows must be 16-byte aligned).
 // ---------------------------------------------------------------------------
+template <bool SHIFT, bool VEC>
 __global__ void __launch_bounds__(256)
 k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
   __shared__ double red[2][4];
   const int w = blockIdx.y, bx = blockIdx.x, nblk = gridDim.x, tid = threadIdx.x;
   const float* __restrict__ xp = x.p[w];
-  const double c = (double)xp[0];
+  const double c = SHIFT ? (double)xp[0] : 0.0;
   double s = 0.0, ss = 0.0;
-  const int64_t n4 = n >> 2;
-  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
-  const int64_t tile = 256 * kPassAUnroll;
-  const int64_t ntile = (n4 + tile - 1) / tile;
-  for (int64_t t = bx; t < ntile; t += nblk) {
-    const int64_t q0 = t * tile + tid;
-    float4 a[kPassAUnroll];
+  const int64_t n4 = VEC ? (n >> 2) : 0;
+  if (VEC) {
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
+    const int64_t tile = 256 * kPassAUnroll;
+    const int64_t ntile = (n4 + tile - 1) / tile;
+    for (int64_t t = bx; t < ntile; t += nblk) {
+      const int64_t q0 = t * tile + tid;
+      float4 a[kPassAUnroll];
 #pragma unroll
-    for (int u = 0; u < kPassAUnroll; ++u) {
-      const int64_t q = q0 + u * 256;
-      if (q < n4) a[u] = x4[q];
-    }
+      for (int u = 0; u < kPassAUnroll; ++u) {
+        const int64_t q = q0 + u * 256;
+        if (q < n4) a[u] = x4[q];
+      }
 #pragma unroll
-    for (int u = 0; u < kPassAUnroll; ++u) {
-      const int64_t q = q0 + u * 256;
-      if (q < n4) {
-        double d0 = (double)a[u].x - c, d1 = (double)a[u].y - c, d2 = (double)a[u].z - c, d3 = (double)a[u].w - c;
-        s += (d0 + d1) + (d2 + d3);
-        ss = fma(d0, d0, ss);
-        ss = fma(d1, d1, ss);
-        ss = fma(d2, d2, ss);
-        ss = fma(d3, d3, ss);
+      for (int u = 0; u < kPassAUnroll; ++u) {
+        const int64_t q = q0 + u * 256;
+        if (q < n4) {
+          double d0 = (double)a[u].x - c, d1 = (double)a[u].y - c, d2 = (double)a[u].z - c, d3 = (double)a[u].w - c;
+          s += (d0 + d1) + (d2 + d3);
+          ss = fma(d0, d0, ss);
+          ss = fma(d1, d1, ss);
+          ss = fma(d2, d2, ss);
+          ss = fma(d3, d3, ss);
+        }
       }
     }
   }
-  if (bx == 0) {
-    const int64_t j = n4 * 4 + tid;
-    if (j < n) {
-      const double d = (double)xp[j] - c;
-      s += d;
-      ss = fma(d, d, ss);
-    }
+  // elements not covered by whole float4 groups (all of them when the row is not 16-byte aligned)
+  for (int64_t j = n4 * 4 + (int64_t)bx * 256 + tid; j < n; j += (int64_t)nblk * 256) {
+    const double d = (double)xp[j] - c;
+    s += d;
+    ss = fma(d, d, ss);
   }
   s = wave_sum(s);
   ss = wave_sum(ss);
@@ -433,6 +436,44 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
     partials[((size_t)w * nblk + bx) * 2 + 0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
     partials[((size_t)w * nblk + bx) * 2 + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
   }
+}
+
+// ---------------------------------------------------------------------------
+// k_gain : one block.  gain_w = V_w / (V_w + R_w) with V_w, R_w the sums of
+// squares (second partial of every block) of worker w's gathered values and of
+// its residual after the step; the two have disjoint support, so V_w + R_w is
+// the squared norm of the error-fed gradient.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_gain(const double* __restrict__ part_vals, int nblk_vals, const double* __restrict__ part_res, int nblk_res,
+       int w_count, double* __restrict__ gain_out) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int w = wave; w < w_count; w += 16) {
+    double v = 0.0, r = 0.0;
+    for (int b = lane; b < nblk_vals; b += 64) v += part_vals[((size_t)w * nblk_vals + b) * 2 + 1];
+    for (int b = lane; b < nblk_res; b += 64) r += part_res[((size_t)w * nblk_res + b) * 2 + 1];
+    v = wave_sum(v);
+    r = wave_sum(r);
+    if (lane == 0) gain_out[w] = (v + r > 0.0) ? v / (v + r) : 0.0;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_apply_update : w[idx[m]] = w[idx[m]] - eta * sum[m] (one float32 multiply,
+// one float32 subtract), the sparse form of the model update.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_apply_update(float* __restrict__ weights, int64_t n, const int32_t* __restrict__ idx,
+               const float* __restrict__ sum, int64_t k, float eta, uint32_t* __restrict__ err) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= k) return;
+  const int64_t i = (int64_t)idx[m];
+  if (i < 0 || i >= n) {
+    atomicOr(err, kErrIndex);
+    return;
+  }
+  const float step = eta * sum[m];
+  weights[i] = weights[i] - step;
 }
 
 // ---------------------------------------------------------------------------

@@ -315,3 +315,32 @@ def test_segmented_step_star_fixed_leader():
         got = run.step(k, orc.MODE_STAR, step_no, seg_off=off, seg_k=ks)
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
+
+
+# ------------------------------------------------------------------ neighbours of the step
+def test_compression_gain_and_sparse_update():
+    import torch
+
+    rng = np.random.default_rng(40)
+    w, n, k = 4, 600_013, 5001            # k odd: the rows of vals are not 16-byte aligned
+    g = [(rng.standard_normal(n) * (1 + r)).astype(np.float32) for r in range(w)]
+    res = [(rng.standard_normal(n) * 0.5).astype(np.float32) for _ in range(w)]
+    run = GpuRunner(w, n, k)
+    run.load_g(g)
+    run.load_res(res)
+    want = orc.step(g, res, k, orc.MODE_VAR, keep_acc=True)
+    got = run.step(k, orc.MODE_VAR, 0)
+    assert_step_matches(got, want, orc.MODE_VAR)
+    gain = torch.zeros(w, dtype=torch.float64, device=run.dev)
+    run.ctx.artopk_compression_gain(run.res, run.vals, k, gain)
+    run.ctx.status()
+    ref = np.array([orc.compression_gain(want.acc[r], want.idx) for r in range(w)])
+    # float64 sums of squares on both sides, summed in a different order
+    np.testing.assert_allclose(gain.cpu().numpy(), ref, rtol=1e-10)
+
+    weights_h = rng.standard_normal(n).astype(np.float32)
+    weights = torch.from_numpy(weights_h).to(run.dev)
+    eta = 0.0123
+    run.ctx.artopk_apply_update(weights, run.idx, run.sum, k, eta)
+    run.ctx.status()
+    assert np.array_equal(bits(weights.cpu().numpy()), bits(orc.apply_update(weights_h, want.idx, want.sum, eta)))

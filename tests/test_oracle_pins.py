@@ -306,3 +306,46 @@ def test_var_mode_picks_largest_spread():
     assert out.variances[1] == pytest.approx(np.var(g[1].astype(np.float64)), rel=1e-12)
     # selection was made on the leader: its row dominates its own leftovers
     assert np.array_equal(out.idx, orc.topk_indices(g[1], 10))
+
+
+# ---------------------------------------------------------------- gain / sparse update pins
+def test_gain_and_sparse_update_hand_values():
+    t = _load_trace()
+    acc0 = np.asarray(t["step1.g0"], np.float32)          # residual is zero at step 1
+    idx = np.asarray(t["step1.idx"], np.int32)
+    assert orc.compression_gain(acc0, idx) == pytest.approx(t["step1.gain0"][0], rel=1e-14)
+    w_after = orc.apply_update(np.asarray(t["step1.w_before"], np.float32), idx,
+                               np.asarray(t["step1.sum"], np.float32), t["step1.eta"][0])
+    assert w_after.tolist() == t["step1.w_after"]
+
+
+def test_gain_closed_forms():
+    n = 1000
+    x = np.where(np.arange(n) % 2 == 0, 2.0, -2.0).astype(np.float32)     # equal magnitudes
+    for k in (1, 10, n):
+        idx = orc.topk_indices(x, k)
+        assert orc.compression_gain(x, idx) == pytest.approx(k / n, rel=1e-14)
+    rng = np.random.default_rng(30)
+    y = rng.standard_normal(5000).astype(np.float32)
+    idx = orc.topk_indices(y, 50)
+    g = orc.compression_gain(y, idx)
+    kept = np.zeros_like(y)
+    kept[idx] = y[idx]
+    assert g == pytest.approx(np.linalg.norm(kept.astype(np.float64)) ** 2 / np.linalg.norm(y.astype(np.float64)) ** 2,
+                              rel=1e-12)
+    res = orc.residual_rewrite(y, idx)                     # gain from the step's outputs: V / (V + R)
+    v = float((y[idx].astype(np.float64) ** 2).sum())
+    r = float((res.astype(np.float64) ** 2).sum())
+    assert g == pytest.approx(v / (v + r), rel=1e-12)
+    assert 0.0 < g < 1.0 and orc.compression_gain(y, orc.topk_indices(y, 500)) > g   # grows with k
+
+
+def test_sparse_update_equals_dense_update():
+    rng = np.random.default_rng(31)
+    n, k, eta = 4000, 77, 0.037
+    w = rng.standard_normal(n).astype(np.float32)
+    idx = np.sort(rng.choice(n, k, replace=False)).astype(np.int32)
+    s = rng.standard_normal(k).astype(np.float32)
+    dense = np.subtract(w, np.multiply(np.float32(eta), orc.scatter_update(n, idx, s), dtype=np.float32),
+                        dtype=np.float32)
+    assert np.array_equal(_bits(orc.apply_update(w, idx, s, eta)), _bits(dense))
