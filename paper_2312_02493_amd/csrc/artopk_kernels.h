@@ -1343,19 +1343,24 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_sum_rows(const float* __restrict__ vals, int w_count, int64_t k, float* __restrict__ sum) {
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (m >= k) return;
-  float s = 0.0f;
-  for (int w0 = 0; w0 < w_count; w0 += 8) {  // eight independent loads in flight, then the ordered adds
-    float v[8];
+  const int64_t m0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;  // this thread: m0, m0+256, m0+512, m0+768
+  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int w0 = 0; w0 < w_count; w0 += 4) {  // sixteen independent loads in flight, then the ordered adds
+    float v[4][4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (w0 + j < w_count) v[j] = vals[(size_t)(w0 + j) * (size_t)k + (size_t)m];
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (w0 + j < w_count) s = (w0 + j == 0) ? v[j] : (s + v[j]);
+      for (int e = 0; e < 4; ++e)
+        if (w0 + j < w_count && m0 + e * 256 < k) v[j][e] = vals[(size_t)(w0 + j) * (size_t)k + (size_t)(m0 + e * 256)];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (w0 + j < w_count && m0 + e * 256 < k) s[e] = (w0 + j == 0) ? v[j][e] : (s[e] + v[j][e]);
   }
-  sum[m] = s;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (m0 + e * 256 < k) sum[m0 + e * 256] = s[e];
 }
 
 // ---------------------------------------------------------------------------
@@ -1409,10 +1414,12 @@ k_zero_at(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx,
 // k_update_fill : update = zeros(N) with update[idx[m]] = sum[m], every output
 // element written exactly once.  Block b owns a contiguous run of 8192-element
 // chunks; it locates its first index with a 256-way search, then per chunk
-// builds the chunk in LDS and streams it out.
+// builds the chunk in LDS (BATCH x 256 index/sum pairs per round, fetched ahead
+// of the buffer clear) and streams it out.
 // ---------------------------------------------------------------------------
 constexpr int kFillChunk = 8192;
 
+template <int BATCH>
 __global__ void __launch_bounds__(256)
 k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
               const float* __restrict__ sum, int64_t k) {
@@ -1459,17 +1466,41 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
     const int64_t lo = c * kFillChunk;
     const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
     float4* b4 = reinterpret_cast<float4*>(buf);
+    // the next BATCH x 256 (index, sum) pairs are fetched while the chunk buffer is cleared
+    int64_t ib[BATCH];
+    float sb[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const int64_t p = m + tid + j * 256;
+      ib[j] = hi;
+      sb[j] = 0.0f;
+      if (p < k) {
+        ib[j] = (int64_t)idx[p];
+        sb[j] = sum[p];
+      }
+    }
     for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
     while (true) {
-      const int64_t p = m + tid;
-      int64_t i = hi;
-      if (p < k) i = (int64_t)idx[p];
-      const bool in = i < hi;
-      if (in && i >= lo) buf[i - lo] = sum[p];  // i >= lo always holds for ascending idx
-      const int cnt = __syncthreads_count(in);
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const bool in = ib[j] < hi;
+        if (in && ib[j] >= lo) buf[ib[j] - lo] = sb[j];  // ib >= lo always holds for ascending idx
+        cnt += __syncthreads_count(in);
+      }
       m += cnt;
-      if (cnt < 256) break;
+      if (cnt < BATCH * 256) break;
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {  // a chunk with more kept entries than one batch
+        const int64_t p = m + tid + j * 256;
+        ib[j] = hi;
+        sb[j] = 0.0f;
+        if (p < k) {
+          ib[j] = (int64_t)idx[p];
+          sb[j] = sum[p];
+        }
+      }
     }
     // (the count barrier above also orders the LDS writes before the reads)
     const int64_t len = hi - lo;
