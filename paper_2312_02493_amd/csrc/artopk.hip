@@ -382,19 +382,26 @@ int enqueue_gather(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t n, con
   return ARTOPK_OK;
 }
 
+// zero_vec != nullptr: the pass also zeroes that vector at the indices.
 int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* idx, const float* sum,
-                        int64_t k) {
+                        int64_t k, float* zero_vec = nullptr) {
   const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
   int blocks = (int)(nchunk < (int64_t)c->num_cu * 4 ? nchunk : (int64_t)c->num_cu * 4);
   if (blocks < 1) blocks = 1;
   // kept entries expected per 8192-element chunk decide how many are fetched per round
   const double per_chunk = (double)k / (double)n * kFillChunk;
-  if (per_chunk <= 160.0)
-    hipLaunchKernelGGL(k_update_fill<1>, dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
-  else if (per_chunk <= 400.0)
-    hipLaunchKernelGGL(k_update_fill<2>, dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
-  else
-    hipLaunchKernelGGL(k_update_fill<4>, dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
+  if (zero_vec) {
+    if (per_chunk <= 400.0)
+      hipLaunchKernelGGL((k_update_fill<2, true>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+    else
+      hipLaunchKernelGGL((k_update_fill<4, true>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+  } else if (per_chunk <= 160.0) {
+    hipLaunchKernelGGL((k_update_fill<1, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+  } else if (per_chunk <= 400.0) {
+    hipLaunchKernelGGL((k_update_fill<2, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+  } else {
+    hipLaunchKernelGGL((k_update_fill<4, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+  }
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
 }
@@ -740,10 +747,15 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     }
     prof_mark(ctx, 3);
     const int kblocks = (int)((k + 255) / 256);
-    hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
+    // zeroing the leader's residual: scattered 4-byte writes while the kept entries are sparse,
+    // otherwise inside the streaming pass that writes the update
+    const bool zero_in_fill = (double)k * 32.0 >= (double)n;
+    if (!zero_in_fill)
+      hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
     hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
-    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k, zero_in_fill ? residual[L] : nullptr)))
+      return rc;
     prof_mark(ctx, 4);
     return ARTOPK_OK;
   }

@@ -1415,15 +1415,18 @@ k_zero_at(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx,
 // element written exactly once.  Block b owns a contiguous run of 8192-element
 // chunks; it locates its first index with a 256-way search, then per chunk
 // builds the chunk in LDS (BATCH x 256 index/sum pairs per round, fetched ahead
-// of the buffer clear) and streams it out.
+// of the buffer clear) and streams it out.  With ZERO the same pass also sets
+// zero_vec[idx[m]] = +0.0 (used for the leader's residual when so many entries
+// are kept that scattered 4-byte writes cost more than streaming the vector).
 // ---------------------------------------------------------------------------
 constexpr int kFillChunk = 8192;
 
-template <int BATCH>
+template <int BATCH, bool ZERO>
 __global__ void __launch_bounds__(256)
 k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
-              const float* __restrict__ sum, int64_t k) {
-  __shared__ float buf[kFillChunk];
+              const float* __restrict__ sum, int64_t k, float* __restrict__ zero_vec) {
+  __shared__ __attribute__((aligned(16))) float buf[kFillChunk];
+  __shared__ uint32_t mark[ZERO ? kFillChunk / 32 : 1];  // one bit per element of the chunk: is it a kept index
   __shared__ int64_t s_lo, s_hi;
   const int tid = threadIdx.x;
   const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
@@ -1462,9 +1465,12 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
   }
   int64_t m = s_lo;
 
+  constexpr int kGroups = kFillChunk / 4 / 256;  // float4 groups per thread and chunk
   for (int64_t c = c_begin; c < c_end; ++c) {
     const int64_t lo = c * kFillChunk;
     const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
+    const int64_t len = hi - lo;
+    const int64_t len4 = len >> 2;
     float4* b4 = reinterpret_cast<float4*>(buf);
     // the next BATCH x 256 (index, sum) pairs are fetched while the chunk buffer is cleared
     int64_t ib[BATCH];
@@ -1479,14 +1485,27 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
         sb[j] = sum[p];
       }
     }
+    float4 zv[ZERO ? kGroups : 1];  // this chunk of the vector whose kept positions are zeroed
+    if (ZERO) {
+#pragma unroll
+      for (int j = 0; j < kGroups; ++j) {
+        const int64_t i = tid + j * 256;
+        if (i < len4) zv[ZERO ? j : 0] = reinterpret_cast<const float4*>(zero_vec + lo)[i];
+      }
+    }
     for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ZERO) mark[ZERO ? tid : 0] = 0u;  // kFillChunk / 32 == 256 words
     __syncthreads();
     while (true) {
       int cnt = 0;
 #pragma unroll
       for (int j = 0; j < BATCH; ++j) {
         const bool in = ib[j] < hi;
-        if (in && ib[j] >= lo) buf[ib[j] - lo] = sb[j];  // ib >= lo always holds for ascending idx
+        if (in && ib[j] >= lo) {  // ib >= lo always holds for ascending idx
+          const int64_t off = ib[j] - lo;
+          buf[off] = sb[j];
+          if (ZERO) atomicOr(&mark[ZERO ? (off >> 5) : 0], 1u << (off & 31));
+        }
         cnt += __syncthreads_count(in);
       }
       m += cnt;
@@ -1503,11 +1522,29 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
       }
     }
     // (the count barrier above also orders the LDS writes before the reads)
-    const int64_t len = hi - lo;
     float* __restrict__ up = update + lo;
-    const int64_t len4 = len >> 2;
-    for (int64_t i = tid; i < len4; i += 256) reinterpret_cast<float4*>(up)[i] = b4[i];
-    for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];
+#pragma unroll
+    for (int j = 0; j < kGroups; ++j) {
+      const int64_t i = tid + j * 256;
+      if (i < len4) {
+        reinterpret_cast<float4*>(up)[i] = b4[i];
+        if (ZERO) {
+          const uint32_t bits4 = (mark[ZERO ? (i >> 3) : 0] >> ((i & 7) * 4)) & 0xfu;  // elements 4i .. 4i+3
+          if (bits4) {
+            float4 z = zv[ZERO ? j : 0];
+            if (bits4 & 1u) z.x = 0.0f;
+            if (bits4 & 2u) z.y = 0.0f;
+            if (bits4 & 4u) z.z = 0.0f;
+            if (bits4 & 8u) z.w = 0.0f;
+            reinterpret_cast<float4*>(zero_vec + lo)[i] = z;
+          }
+        }
+      }
+    }
+    for (int64_t i = len4 * 4 + tid; i < len; i += 256) {  // ragged end of the vector
+      up[i] = buf[i];
+      if (ZERO && ((mark[ZERO ? (i >> 5) : 0] >> (i & 31)) & 1u)) zero_vec[lo + i] = 0.0f;
+    }
     __syncthreads();
   }
 }
