@@ -53,8 +53,12 @@ enum {
   ARTOPK_ESTATE = -4  /* a kernel reported an internal inconsistency           */
 };
 
-/* Leader rule (Sec. III-B).  FIXED takes the leader from the caller. */
-enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2 };
+/* Leader rule (Sec. III-B).  FIXED takes the leader from the caller.  VAR uses
+ * the population variance of the dense error-fed vector.  VAR_TOPK is Alg. 1
+ * taken literally: every worker runs Top-k on its own vector and the worker
+ * whose k values have the largest squared norm leads (first maximum); its
+ * cost is W selections instead of one. */
+enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3 };
 
 #define ARTOPK_MAX_WORKERS 64
 
@@ -154,7 +158,9 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  *   step         the paper's iteration counter i
  *   fixed_leader used by ARTOPK_FIXED only
  *   leader_out   device int32 (may be NULL)
- *   var_out      device W float64, written in VAR mode only (may be NULL)
+ *   var_out      device W float64 (may be NULL): the per-worker variances in VAR
+ *                mode, the squared norms of each worker's own Top-k values in
+ *                VAR_TOPK mode; untouched otherwise
  *   idx_out      device k int32
  *   vals_out     device W*k float32 (may be NULL)
  *   sum_out      device k float32
@@ -165,6 +171,20 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
                 int64_t k, int32_t mode, uint64_t step, int32_t fixed_leader,
                 int32_t* leader_out, double* var_out, int32_t* idx_out, float* vals_out,
                 float* sum_out, float* update_out);
+
+/*
+ * Every worker's own exact Top-k (Alg. 1 calls Topk on each worker before the
+ * leader is chosen; the AllGather exchange of Sec. II-C sends exactly these
+ * values and indices).  Same ordering rules as artopk_select_topk.
+ *   acc        host array of W device pointers, each N float32 (read only)
+ *   idx_out    device W*k int32 row-major [w][m], each row ascending
+ *   vals_out   device W*k float32, vals_out[w][m] = acc_w[idx_out[w][m]]; may be NULL
+ *   sqnorm_out device W float64, sum of squares of each worker's k values
+ *              (the quantity Alg. 1 writes for the VAR leader); may be NULL
+ *   argmax_out device int32, first worker with the largest squared norm; may be NULL
+ */
+int artopk_topk_workers(artopk_ctx* ctx, const float* const* acc, int32_t w, int64_t n, int64_t k,
+                        int32_t* idx_out, float* vals_out, double* sqnorm_out, int32_t* argmax_out);
 
 /*
  * Compression gain of every worker for the step just taken (the heuristic the

@@ -47,6 +47,7 @@ import numpy as np
 MODE_STAR = 0
 MODE_VAR = 1
 MODE_FIXED = 2
+MODE_VAR_TOPK = 3
 
 _MAG_MASK = np.uint32(0x7FFFFFFF)
 
@@ -83,6 +84,13 @@ def variance(x: np.ndarray) -> float:
     mean = float(xd.sum() / n)          # pass 1
     dev = xd - mean
     return float((dev * dev).sum() / n)  # pass 2
+
+
+def topk_sqnorm(acc: np.ndarray, idx: np.ndarray) -> float:
+    """Squared 2-norm (float64) of the values a worker's own Top-k keeps -- the
+    scalar Alg. 1 writes into var[r] for the VAR-Topk leader choice."""
+    v = np.asarray(acc, np.float32)[np.asarray(idx, np.int64)].astype(np.float64)
+    return float((v * v).sum())
 
 
 def leader_star(step: int, w: int) -> int:
@@ -214,6 +222,12 @@ def step(g: Sequence[np.ndarray], residual: Sequence[np.ndarray], k: int,
         out.leader = leader_star(step_no, w)
     elif mode == MODE_VAR:
         out.variances = [variance(a) for a in accs]
+        out.leader = leader_var(out.variances)
+    elif mode == MODE_VAR_TOPK:
+        # Alg. 1 as printed: Topk on every worker first, the squared norm of each
+        # worker's own k values decides the leader (first maximum)
+        own = [topk_indices(a, k) for a in accs]
+        out.variances = [topk_sqnorm(a, i) for a, i in zip(accs, own)]
         out.leader = leader_var(out.variances)
     elif mode == MODE_FIXED:
         out.leader = int(fixed_leader)

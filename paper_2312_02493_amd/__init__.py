@@ -6,5 +6,5 @@ fallback: using the library without the built extension raises.
 """
 
 from .binding import (  # noqa: F401
-    ARTOPK_FIXED, ARTOPK_STAR, ARTOPK_VAR, ArTopkError, Context, exported_symbols, lib_path, load_library,
+    ARTOPK_FIXED, ARTOPK_STAR, ARTOPK_VAR, ARTOPK_VAR_TOPK, ArTopkError, Context, exported_symbols, lib_path, load_library,
 )

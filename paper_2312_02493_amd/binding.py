@@ -12,14 +12,14 @@ from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED = 0, 1, 2
+ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK = 0, 1, 2, 3
 PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 
 _SYMBOLS = (
     "artopk_create", "artopk_destroy", "artopk_last_error", "artopk_status", "artopk_variance",
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
-    "artopk_apply_update",
+    "artopk_apply_update", "artopk_topk_workers",
 )
 
 
@@ -60,6 +60,7 @@ def load_library():
     lib.artopk_gather_sum.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_scatter_residual.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_step.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, i64, i32, u64, i32, vp, vp, vp, vp, vp, vp]
+    lib.artopk_topk_workers.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp, vp]
     lib.artopk_compression_gain.argtypes = [vp, vp, i32, i64, vp, i64, vp]
     lib.artopk_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, C.c_float]
     lib.artopk_set_profile.argtypes = [vp, i32]
@@ -155,6 +156,11 @@ class Context:
         n = residual[0].numel()
         self._check(self._lib.artopk_scatter_residual(self._h, _ptr_table(residual), len(residual), n, _ptr(idx), k,
                                                       _ptr(summed), _ptr(update)))
+
+    def artopk_topk_workers(self, acc: Sequence, k: int, idx_out, vals_out=None, sqnorm_out=None, argmax_out=None):
+        n = acc[0].numel()
+        self._check(self._lib.artopk_topk_workers(self._h, _ptr_table(acc), len(acc), n, k, _ptr(idx_out),
+                                                  _ptr(vals_out), _ptr(sqnorm_out), _ptr(argmax_out)))
 
     def artopk_compression_gain(self, residual: Sequence, vals, k: int, gain_out):
         n = residual[0].numel()

@@ -39,6 +39,7 @@ struct Scratch {
   uint2* list = nullptr;          // survivor lists: (index, raw float bits)
   int64_t list_entries = 0;       // allocated entries
   float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
+  int32_t* idx_rows = nullptr;    // [max_w][max_k] every worker's own Top-k (literal Alg. 1 leader rule)
   SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
   uint32_t cap = 0;               // list capacity of a flat (one-segment) select
 };
@@ -214,7 +215,7 @@ int64_t seg_list_cap(int64_t n_s, int64_t k_s) {
 }
 
 // One segment covering the whole vector.
-Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k) {
+Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k, int32_t vec = -1) {
   Plan pl;
   pl.nseg = 1;
   SegDesc d{};
@@ -227,6 +228,7 @@ Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k) {
   d.chunk_begin = 0;
   d.k = (uint32_t)k;
   d.cap = c->s.cap < (uint64_t)n ? c->s.cap : (uint32_t)n;
+  d.vec = vec;
   pl.desc.push_back(d);
   pl.max_chunks = d.geom.nchunks;
   pl.max_tiles = pl.total_tiles = tiles_of_range(0, n);
@@ -266,6 +268,7 @@ int segmented_plan(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_of
       d.chunk_begin = chunk_begin;
       d.k = (uint32_t)seg_k[sgi];
       d.cap = (uint32_t)seg_list_cap(ns, seg_k[sgi]);
+      d.vec = -1;
       koff += seg_k[sgi];
       list_base += ((int64_t)d.cap + 3) / 4 * 4;
       const int64_t tiles = tiles_of_range(d.e_lo, d.e_hi);
@@ -406,6 +409,33 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
   return ARTOPK_OK;
 }
 
+
+// Every worker's own Top-k (indices ascending, values) and the squared norm of its k values;
+// argmax (first maximum) goes to leader_dev and, if given, argmax_out.  With hist_ready the
+// per-chunk histograms of all workers are already in S (pass A with histograms for every worker).
+int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t n, int64_t k, int32_t* idx_rows,
+                         float* val_rows, double* sqnorm_out, int32_t* argmax_out, bool hist_ready) {
+  Scratch& s = c->s;
+  for (int32_t r = 0; r < w; ++r) {
+    const Plan pl = flat_plan(c, n, k, r);
+    int rc = enqueue_clear(c, pl);
+    if (rc) return rc;
+    if ((rc = enqueue_select(c, pl, tab, n, idx_rows + (size_t)r * (size_t)k, hist_ready, 1,
+                             val_rows + (size_t)r * (size_t)k)))
+      return rc;
+  }
+  PtrTable vtab;
+  for (int i = 0; i < kMaxW; ++i) vtab.p[i] = (i < w) ? val_rows + (size_t)i * (size_t)k : nullptr;
+  int nblk = (int)((k + 256 * 16 - 1) / (256 * 16));
+  if (nblk < 1) nblk = 1;
+  if (nblk > kMaxChunks) nblk = kMaxChunks;
+  hipLaunchKernelGGL((k_stats<false, false>), dim3(nblk, w), dim3(256), 0, c->stream, vtab, k, s.partials);
+  hipLaunchKernelGGL(k_sqnorm, dim3(1), dim3(1024), 0, c->stream, s.partials, nblk, (int)w, s.var_scratch,
+                     sqnorm_out, s.leader_dev, argmax_out);
+  HIP_TRY(c, hipGetLastError());
+  return ARTOPK_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -467,6 +497,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_err = take(sizeof(uint32_t));
   const size_t o_list = take((size_t)s.list_entries * sizeof(uint2));
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
+  const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
   const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
   const size_t total = off;
 
@@ -487,6 +518,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
   s.list = reinterpret_cast<uint2*>(base + o_list);
   s.vals = reinterpret_cast<float*>(base + o_vals);
+  s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
   s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
 
   // leader and error words start at zero (stream-ordered before any later call)
@@ -639,6 +671,17 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
   return enqueue_update_fill(ctx, update, n, idx, sum, k);
 }
 
+int artopk_topk_workers(artopk_ctx* ctx, const float* const* acc, int32_t w, int64_t n, int64_t k,
+                        int32_t* idx_out, float* vals_out, double* sqnorm_out, int32_t* argmax_out) {
+  int rc = check_common(ctx, w, n, k);
+  if (rc) return rc;
+  if ((rc = check_ptr_table(ctx, acc, w, "acc"))) return rc;
+  if (!idx_out) return fail(ctx, ARTOPK_EINVAL, "idx_out is NULL");
+  const PtrTable tab = make_table(acc, w);
+  return enqueue_topk_workers(ctx, tab, w, n, k, idx_out, vals_out ? vals_out : ctx->s.vals, sqnorm_out,
+                              argmax_out, false);
+}
+
 int artopk_compression_gain(artopk_ctx* ctx, const float* const* residual, int32_t w, int64_t n,
                             const float* vals, int64_t k, double* gain_out) {
   int rc = check_common(ctx, w, n, k);
@@ -694,6 +737,9 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   } else if (mode == ARTOPK_FIXED) {
     if (fixed_leader < 0 || fixed_leader >= w) return fail(ctx, ARTOPK_EINVAL, "fixed_leader outside [0, W)");
     leader_host = fixed_leader;
+  } else if (mode == ARTOPK_VAR_TOPK) {
+    if (seg_off != nullptr && nseg > 1)
+      return fail(ctx, ARTOPK_EINVAL, "ARTOPK_VAR_TOPK is defined for the unsegmented selection only");
   } else if (mode != ARTOPK_VAR) {
     return fail(ctx, ARTOPK_EINVAL, "unknown mode %d", mode);
   }
@@ -714,6 +760,29 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   const ChunkGeom geom = make_geom(0, n);
   const dim3 grid(geom.nchunks, w), block(256);
   const bool nt = ctx->pass_a_nt;
+
+  if (mode == ARTOPK_VAR_TOPK) {
+    // Literal Alg. 1: Top-k on every worker, leader = largest squared norm of its own k values,
+    // then the leader's indices are the shared ones.
+    prof_begin(ctx);
+    prof_mark(ctx, 0);
+    if (nt)
+      hipLaunchKernelGGL((k_pass_a<false, 2, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
+                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.partials);
+    else
+      hipLaunchKernelGGL((k_pass_a<false, 2, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
+                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.partials);
+    prof_mark(ctx, 1);
+    if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true))) return rc;
+    hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
+                       idx_out);
+    prof_mark(ctx, 2);
+    if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;
+    prof_mark(ctx, 3);
+    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+    prof_mark(ctx, 4);
+    return ARTOPK_OK;
+  }
 
   if (mode != ARTOPK_VAR && !segmented && ctx->leader_first) {
     // The leader is known up front: run its pass and the selection first, then

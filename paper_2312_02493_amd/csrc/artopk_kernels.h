@@ -96,7 +96,7 @@ struct SegDesc {
   int32_t chunk_begin; // first chunk slot of this segment in S / chunk_off
   uint32_t k;          // entries wanted
   uint32_t cap;        // survivor-list capacity of this segment
-  uint32_t pad;
+  int32_t vec;         // which vector of the pointer table to select on; -1 = the leader's
 };
 
 // Everything the selection kernels need; blockIdx.y (blockIdx.z in k_reduce_hist)
@@ -114,13 +114,14 @@ struct SelParams {
   float* vals_row;         // leader's row of gathered values, or nullptr
   uint32_t* err;
   const SegDesc* table;
-  int32_t slot_by_leader;  // S slot = *leader_dev (VAR, histograms of all workers) or 0
+  int32_t slot_by_leader;  // S slot = index of the selected vector (histograms of all workers exist) or 0
   int32_t pad;
   SegDesc one;
 };
 
 struct SegView {
   SegDesc d;
+  const float* x;  // the vector this segment selects on
   SelState* st;
   uint32_t* counters;
   uint32_t* hist1;
@@ -227,7 +228,9 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg) {
   v.hist2 = zb + kSegHist2;
   v.ssum = zb + kSegSsum;
   v.flags = p.flags + (size_t)v.d.flag_base * kNumLookback;
-  const size_t slot = p.slot_by_leader ? (size_t)(*p.leader_dev) : 0;
+  const int vec = v.d.vec >= 0 ? v.d.vec : *p.leader_dev;
+  v.x = p.tab.p[vec];
+  const size_t slot = p.slot_by_leader ? (size_t)vec : 0;  // histogram slot: per vector, or the only one
   v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
   v.chunk_off = p.chunk_off + v.d.chunk_begin;
   v.list = p.list + v.d.list_base;
@@ -459,6 +462,40 @@ k_gain(const double* __restrict__ part_vals, int nblk_vals, const double* __rest
 }
 
 // ---------------------------------------------------------------------------
+// k_sqnorm : one block.  out[w] = sum of the second partials (sums of squares)
+// of vector w; argmax = first w with the largest value (also stored as leader).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_sqnorm(const double* __restrict__ part, int nblk, int w_count, double* __restrict__ scratch,
+         double* __restrict__ out, int32_t* __restrict__ leader_dev, int32_t* __restrict__ argmax_out) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int w = wave; w < w_count; w += 16) {
+    double v = 0.0;
+    for (int b = lane; b < nblk; b += 64) v += part[((size_t)w * nblk + b) * 2 + 1];
+    v = wave_sum(v);
+    if (lane == 0) {
+      scratch[w] = v;
+      if (out) out[w] = v;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int best = 0;
+    for (int w = 1; w < w_count; ++w)
+      if (scratch[w] > scratch[best]) best = w;
+    if (leader_dev) *leader_dev = best;
+    if (argmax_out) *argmax_out = best;
+  }
+}
+
+__global__ void __launch_bounds__(256)
+k_copy_i32(const int32_t* __restrict__ src_rows, const int32_t* __restrict__ row_dev, int64_t k,
+           int32_t* __restrict__ dst) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m < k) dst[m] = src_rows[(size_t)(*row_dev) * (size_t)k + (size_t)m];
+}
+
+// ---------------------------------------------------------------------------
 // k_apply_update : w[idx[m]] = w[idx[m]] - eta * sum[m] (one float32 multiply,
 // one float32 subtract), the sparse form of the model update.
 // ---------------------------------------------------------------------------
@@ -532,7 +569,7 @@ k_hist0(SelParams p) {
   const int c = blockIdx.x;
   if (c >= sv.d.geom.nchunks) return;
   const int tid = threadIdx.x;
-  const float* __restrict__ xp = p.tab.p[*p.leader_dev];
+  const float* __restrict__ xp = sv.x;
   for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
   __syncthreads();
   int64_t cs = sv.d.geom.chunk0 + (int64_t)c * sv.d.geom.chunk_elems;
@@ -689,7 +726,7 @@ k_compact1(SelParams p) {
   if (st.level != 1u || st.compact_level != 0u || *p.err) return;
   const bool write_out = (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
   const uint32_t klo = st.lo, khi = st.hi;
-  const float* __restrict__ xp = p.tab.p[*p.leader_dev];
+  const float* __restrict__ xp = sv.x;
 
   for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
   __syncthreads();
@@ -990,8 +1027,6 @@ k_compact(SelParams p, int level, int launch_id) {
   float* __restrict__ vals_row = sv.vals_row;
   const uint32_t k_out = sv.d.k;
   uint32_t* __restrict__ err = p.err;
-  const PtrTable& tab = p.tab;
-  const int32_t* __restrict__ leader_dev = p.leader_dev;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -1028,7 +1063,7 @@ k_compact(SelParams p, int level, int launch_id) {
   const int dshift = digit_shift(level < 3 ? level : 2);
   const uint32_t dmask = digit_mask(level < 3 ? level : 2);
 
-  const float* __restrict__ xp = LIST ? nullptr : tab.p[*leader_dev];
+  const float* __restrict__ xp = LIST ? nullptr : sv.x;
 
   if (do_hist) {
     for (int b = tid; b < kHistBins; b += kCompactThreads) lh[b] = 0u;

@@ -344,3 +344,42 @@ def test_compression_gain_and_sparse_update():
     run.ctx.artopk_apply_update(weights, run.idx, run.sum, k, eta)
     run.ctx.status()
     assert np.array_equal(bits(weights.cpu().numpy()), bits(orc.apply_update(weights_h, want.idx, want.sum, eta)))
+
+
+def test_topk_workers_and_literal_leader_rule():
+    import torch
+    import paper_2312_02493_amd as lib
+
+    rng = np.random.default_rng(41)
+    w, n, k = 5, 300_011, 2999
+    g = [(rng.standard_normal(n) * (1.0 + 0.1 * ((r * 3) % w))).astype(np.float32) for r in range(w)]
+    res = [(rng.standard_normal(n) * 0.2).astype(np.float32) for _ in range(w)]
+    acc = [orc.ef_add(a, b) for a, b in zip(g, res)]
+    dev = torch.device("cuda:0")
+    ctx = lib.Context(w, n, k)
+    acc_d = [torch.from_numpy(a).to(dev) for a in acc]
+    idx = torch.full((w * k,), -1, dtype=torch.int32, device=dev)
+    vals = torch.empty(w * k, dtype=torch.float32, device=dev)
+    sq = torch.zeros(w, dtype=torch.float64, device=dev)
+    am = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    ctx.artopk_topk_workers(acc_d, k, idx, vals, sq, am)
+    ctx.status()
+    want_idx = [orc.topk_indices(a, k) for a in acc]
+    want_sq = [orc.topk_sqnorm(a, i) for a, i in zip(acc, want_idx)]
+    got_idx = idx.cpu().numpy().reshape(w, k)
+    got_vals = vals.cpu().numpy().reshape(w, k)
+    for r in range(w):
+        assert np.array_equal(got_idx[r], want_idx[r]), f"worker {r} indices"
+        assert np.array_equal(bits(got_vals[r]), bits(acc[r][want_idx[r].astype(np.int64)])), f"worker {r} values"
+    np.testing.assert_allclose(sq.cpu().numpy(), want_sq, rtol=1e-12)
+    assert int(am.item()) == orc.leader_var(want_sq)
+
+    # the whole step with the literal leader rule
+    run = GpuRunner(w, n, k)
+    run.load_g(g)
+    run.load_res(res)
+    want = orc.step(g, res, k, orc.MODE_VAR_TOPK)
+    got = run.step(k, orc.MODE_VAR_TOPK, 0)
+    assert got["leader"] == want.leader
+    np.testing.assert_allclose(got["var"], want.variances, rtol=1e-12)
+    assert_step_matches(got, want, orc.MODE_FIXED)

@@ -349,3 +349,20 @@ def test_sparse_update_equals_dense_update():
     dense = np.subtract(w, np.multiply(np.float32(eta), orc.scatter_update(n, idx, s), dtype=np.float32),
                         dtype=np.float32)
     assert np.array_equal(_bits(orc.apply_update(w, idx, s, eta)), _bits(dense))
+
+
+def test_literal_alg1_leader_rule_hand_values():
+    t = _load_trace()
+    k = int(t["k"][0])
+    g = [np.asarray(t[f"step2.g{r}"], np.float32) for r in range(2)]
+    res = [np.asarray(t[f"step1.res{r}"], np.float32) for r in range(2)]
+    out = orc.step(g, res, k, orc.MODE_VAR_TOPK, step_no=2)
+    assert out.variances == [t["step2.topk_sqnorm0"][0], t["step2.topk_sqnorm1"][0]]
+    assert out.leader == int(t["step2.topk_leader"][0])
+    assert out.idx.tolist() == [int(v) for v in t["step2.topk_idx"]]
+    assert out.sum.tolist() == t["step2.topk_sum"]
+    # the squared norm of a worker's own Top-k is the largest any k-subset can have
+    rng = np.random.default_rng(50)
+    x = rng.standard_normal(12).astype(np.float32)
+    best = max(float((x[list(s)].astype(np.float64) ** 2).sum()) for s in itertools.combinations(range(12), 4))
+    assert orc.topk_sqnorm(x, orc.topk_indices(x, 4)) == pytest.approx(best, rel=1e-15)
