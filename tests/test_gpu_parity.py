@@ -383,3 +383,58 @@ def test_topk_workers_and_literal_leader_rule():
     assert got["leader"] == want.leader
     np.testing.assert_allclose(got["var"], want.variances, rtol=1e-12)
     assert_step_matches(got, want, orc.MODE_FIXED)
+
+
+def test_generic_path_with_host_known_leader(monkeypatch):
+    """STAR / FIXED normally take the leader-first pipeline; the library's switch back to the
+    generic pipeline (histogram for the leader only inside the all-worker pass, scattered gather)
+    must give the same bits."""
+    monkeypatch.setenv("ARTOPK_LEADER_FIRST", "0")
+    rng = np.random.default_rng(42)
+    w, n, k = 4, 450_003, 4500
+    g = [rng.standard_normal(n).astype(np.float32) for _ in range(w)]
+    res = [(rng.standard_normal(n) * 0.4).astype(np.float32) for _ in range(w)]
+    run = GpuRunner(w, n, k)            # the context reads the switch when it is created
+    monkeypatch.delenv("ARTOPK_LEADER_FIRST")
+    for step_no in (5, 6):
+        run.load_g(g)
+        run.load_res(res)
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
+        got = run.step(k, orc.MODE_STAR, step_no)
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
+
+
+def test_two_runs_give_identical_bits():
+    rng = np.random.default_rng(43)
+    w, n, k = 3, 700_001, 7000
+    g = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for _ in range(w)]
+    g[1][::3] = np.float32(2.0 ** -10)              # many ties at one magnitude
+    res = [np.zeros(n, np.float32) for _ in range(w)]
+    outs = []
+    for _ in range(2):
+        run = GpuRunner(w, n, k)
+        run.load_g(g)
+        run.load_res(res)
+        outs.append(run.step(k, orc.MODE_VAR, 1))
+    a, b = outs
+    assert a["leader"] == b["leader"] and np.array_equal(a["idx"], b["idx"])
+    assert np.array_equal(bits(a["sum"]), bits(b["sum"])) and np.array_equal(bits(a["update"]), bits(b["update"]))
+    assert np.array_equal(a["var"].view(np.uint64), b["var"].view(np.uint64))
+
+
+def test_bucketed_layout_16mi_elements():
+    """Fixed-size buckets (64 MB = 16 Mi float32 each, the granularity the paper's
+    communication measurements use) are just a segment table."""
+    wl = inp.workload(4, n=40_000_007, w=2)
+    bucket = 16 * 1024 * 1024
+    off = list(range(0, wl.n, bucket)) + [wl.n]
+    ks = [int(np.ceil(0.001 * (off[i + 1] - off[i]))) for i in range(len(off) - 1)]
+    k = sum(ks)
+    g = [wl.gen(1, r, threads=8) for r in range(2)]
+    res = [np.zeros(wl.n, np.float32) for _ in range(2)]
+    run = GpuRunner(2, wl.n, k, max_segments=len(ks))
+    run.load_g(g)
+    want = orc.step(g, res, k, orc.MODE_STAR, step_no=1, seg_off=off, seg_k=ks)
+    got = run.step(k, orc.MODE_STAR, 1, seg_off=off, seg_k=ks)
+    assert_step_matches(got, want, orc.MODE_STAR)
