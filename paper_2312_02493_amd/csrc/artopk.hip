@@ -26,6 +26,7 @@ constexpr int kPassRestThreads = 1024, kPassRestU = 8;
 
 struct Scratch {
   // zeroed before every select: one kSegWords block per segment, then the look-back flags
+  uint32_t* h_all = nullptr;      // [max_w][kHistReps][4096] top-digit histograms from the fused pass
   uint32_t* zero_base = nullptr;  // [max_seg][kSegWords]
   uint64_t* flags = nullptr;      // [max_tiles][kNumLookback], directly behind the blocks
   int64_t max_tiles = 0;
@@ -294,12 +295,13 @@ int segmented_plan(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_of
 }
 
 SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
-                      float* vals_row, int slot_by_leader) {
+                      float* vals_row, int slot_by_leader, bool hist_from_pass) {
   const Scratch& s = c->s;
   SelParams p;
   p.tab = tab;
   p.leader_dev = s.leader_dev;
   p.n = n;
+  p.h_all = hist_from_pass ? s.h_all : nullptr;
   p.zero_base = s.zero_base;
   p.flags = s.flags;
   p.S = s.S;
@@ -315,19 +317,22 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   return p;
 }
 
-// Clears the per-segment scratch blocks and the look-back flags of a plan.
+// Clears the per-segment scratch blocks and the look-back flags of a plan, and the
+// whole-vector histograms of the first hist_slots slots a fused pass is about to fill.
 // leader >= 0 also records a host-known leader (and copies it to leader_out).
-int enqueue_clear(artopk_ctx* c, const Plan& pl, int32_t leader = -1, int32_t* leader_out = nullptr) {
+int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader = -1,
+                  int32_t* leader_out = nullptr) {
   Scratch& s = c->s;
   const size_t words1 = (size_t)pl.nseg * kSegWords;
   const size_t words2 = (size_t)pl.total_tiles * kNumLookback * 2;
-  const size_t total = words1 + words2;
+  const size_t words3 = (size_t)hist_slots * kHistReps * kHistBins;
+  const size_t total = words1 + words2 + words3;
   int blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
   if (blocks < 1) blocks = 1;
   if (blocks > c->num_cu * 4) blocks = c->num_cu * 4;
   hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, c->stream, s.zero_base, words1,
-                     reinterpret_cast<uint32_t*>(s.flags), words2, leader, leader >= 0 ? s.leader_dev : nullptr,
-                     leader_out);
+                     reinterpret_cast<uint32_t*>(s.flags), words2, s.h_all, words3, leader,
+                     leader >= 0 ? s.leader_dev : nullptr, leader_out);
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
 }
@@ -338,34 +343,34 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int32_t leader = -1, int32_t* l
 // *leader_dev if slot_by_leader, else in slot 0).  vals_row, if given, receives
 // the leader's values at the selected indices.
 int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
-                   bool hist_ready, int slot_by_leader, float* vals_row = nullptr) {
+                   bool hist_ready, int slot_by_leader, float* vals_row = nullptr,
+                   const LeaderArgs* leader_args = nullptr) {
   hipStream_t st = c->stream;
   const unsigned nseg = (unsigned)pl.nseg;
-  const SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0);
+  const SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0, hist_ready);
+  LeaderArgs la{};
+  if (leader_args) la = *leader_args;
 
   if (!hist_ready) hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
-  int ysplit = pl.max_chunks / 32;
-  if (ysplit < 1) ysplit = 1;
-  hipLaunchKernelGGL(k_reduce_hist, dim3(kHistBins / 256, ysplit, nseg), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p);
+  hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
   // 4 waves, 16 consecutive elements per lane: best of the shapes measured on the 138 M and 1 G workloads
   hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 1);
 
+  // The remaining kernels take tiles from a counter (or stride over the list), so any grid works:
+  // about two blocks per compute unit over all segments together.
+  const int64_t per_seg = ((int64_t)c->num_cu * 2 + nseg - 1) / nseg;
   // deeper array passes: they run only for segments whose level-1 survivors did not fit the list
-  int cblocks = (int)(pl.max_tiles < (int64_t)c->num_cu * 2 ? pl.max_tiles : (int64_t)c->num_cu * 2);
+  int cblocks = (int)(pl.max_tiles < per_seg ? pl.max_tiles : per_seg);
   if (cblocks < 1) cblocks = 1;
   hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
-  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 2);
   hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 1);
 
-  int lblocks = (int)((pl.max_cap + 256 * 16 - 1) / (256 * 16));
+  int64_t lblocks = (pl.max_cap + 256 * 16 - 1) / (256 * 16);
+  if (lblocks > per_seg * 2) lblocks = per_seg * 2;
   if (lblocks < 1) lblocks = 1;
-  if (lblocks > c->num_cu * 4) lblocks = c->num_cu * 4;
-  hipLaunchKernelGGL(k_list_hist, dim3(lblocks, nseg), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_pick, dim3(1, nseg), dim3(1024), 0, st, p, 4);
+  hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p);
   int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
-  int fblocks = (int)(ltiles < (int64_t)c->num_cu * 2 ? ltiles : (int64_t)c->num_cu * 2);
+  int fblocks = (int)(ltiles < per_seg ? ltiles : per_seg);
   if (fblocks < 1) fblocks = 1;
   hipLaunchKernelGGL(k_compact<true>, dim3(fblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 2);
   HIP_TRY(c, hipGetLastError());
@@ -418,7 +423,7 @@ int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t 
   Scratch& s = c->s;
   for (int32_t r = 0; r < w; ++r) {
     const Plan pl = flat_plan(c, n, k, r);
-    int rc = enqueue_clear(c, pl);
+    int rc = enqueue_clear(c, pl, 0);
     if (rc) return rc;
     if ((rc = enqueue_select(c, pl, tab, n, idx_rows + (size_t)r * (size_t)k, hist_ready, 1,
                              val_rows + (size_t)r * (size_t)k)))
@@ -487,6 +492,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return o;
   };
   // zeroed region: one block per segment, then the look-back flags
+  const size_t o_hall = take((size_t)max_w * kHistReps * kHistBins * sizeof(uint32_t));
   const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
                              (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
   const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
@@ -507,6 +513,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return ARTOPK_ENOMEM;
   }
   char* base = static_cast<char*>(c->slab);
+  s.h_all = reinterpret_cast<uint32_t*>(base + o_hall);
   s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
   // kSegWords is even, so the flags stay 8-byte aligned
   s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
@@ -523,8 +530,8 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
-                     reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1, 0,
-                     (int32_t*)nullptr, (int32_t*)nullptr);
+                     reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1,
+                     (uint32_t*)nullptr, (size_t)0, 0, (int32_t*)nullptr, (int32_t*)nullptr);
   if (hipGetLastError() != hipSuccess) {
     (void)hipFree(c->slab);
     delete c;
@@ -642,7 +649,7 @@ int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nse
   } else {
     flat = flat_plan(ctx, n, k);
   }
-  if ((rc = enqueue_clear(ctx, *pl, 0, nullptr))) return rc;  // the single vector is "leader 0"
+  if ((rc = enqueue_clear(ctx, *pl, 0, 0, nullptr))) return rc;  // the single vector is "leader 0"
   rc = enqueue_select(ctx, *pl, tab, n, idx_out, false, 0);
   prof_mark(ctx, 2);
   return rc;
@@ -758,7 +765,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   }
   // pass A always works on whole-vector chunks; for a flat select they are the select's chunks too
   const ChunkGeom geom = make_geom(0, n);
-  const dim3 grid(geom.nchunks, w), block(256);
+  const dim3 grid(geom.nchunks, w);
   const bool nt = ctx->pass_a_nt;
 
   if (mode == ARTOPK_VAR_TOPK) {
@@ -766,12 +773,13 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     // then the leader's indices are the shared ones.
     prof_begin(ctx);
     prof_mark(ctx, 0);
+    if ((rc = enqueue_clear(ctx, *pl, (int)w))) return rc;
     if (nt)
       hipLaunchKernelGGL((k_pass_a<false, 2, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
-                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.partials);
+                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.h_all, s.partials);
     else
       hipLaunchKernelGGL((k_pass_a<false, 2, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
-                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.partials);
+                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.h_all, s.partials);
     prof_mark(ctx, 1);
     if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
@@ -796,13 +804,13 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     const PtrTable g1t = make_table(g1, 1), r1t = make_table(r1, 1);
     prof_begin(ctx);
     prof_mark(ctx, 0);
-    if ((rc = enqueue_clear(ctx, *pl, L, leader_out))) return rc;
+    if ((rc = enqueue_clear(ctx, *pl, 1, L, leader_out))) return rc;
     if (nt)
       hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
-                         st, g1t, r1t, n, geom, 0, s.S, s.partials);
+                         st, g1t, r1t, n, geom, 0, s.S, s.h_all, s.partials);
     else
       hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
-                         st, g1t, r1t, n, geom, 0, s.S, s.partials);
+                         st, g1t, r1t, n, geom, 0, s.S, s.h_all, s.partials);
     prof_mark(ctx, 1);
     if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
     prof_mark(ctx, 2);
@@ -834,16 +842,17 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   prof_begin(ctx);
   prof_mark(ctx, 0);
   // the flat select reuses the histograms pass A builds; segments build their own afterwards
-  if ((rc = enqueue_clear(ctx, *pl))) return rc;
+  if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : (mode == ARTOPK_VAR ? (int)w : 1)))) return rc;
   int slot_by_leader = 0;
+  LeaderArgs leader_args{};
 #define LAUNCH_PASS_A(STATS, HIST, LEADER)                                                                 \
   do {                                                                                                     \
     if (nt)                                                                                                \
       hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,   \
-                         gt, rt, n, geom, LEADER, s.S, s.partials);                                        \
+                         gt, rt, n, geom, LEADER, s.S, s.h_all, s.partials);                               \
     else                                                                                                   \
       hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,  \
-                         gt, rt, n, geom, LEADER, s.S, s.partials);                                        \
+                         gt, rt, n, geom, LEADER, s.S, s.h_all, s.partials);                               \
   } while (0)
   if (mode == ARTOPK_VAR) {
     if (segmented) {
@@ -853,8 +862,19 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
       slot_by_leader = 1;
     }
     prof_mark(ctx, 1);
-    hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, (int)geom.nchunks, n,
-                       s.var_scratch, var_out, s.leader_dev, leader_out);
+    if (segmented) {  // the segment histograms are built on the leader's vector, so it is needed now
+      hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, (int)geom.nchunks, n,
+                         s.var_scratch, var_out, s.leader_dev, leader_out);
+    } else {          // otherwise the selection's first kernel takes the leader itself
+      leader_args.partials = s.partials;
+      leader_args.w_count = (int)w;
+      leader_args.nblk = (int)geom.nchunks;
+      leader_args.n = n;
+      leader_args.var_scratch = s.var_scratch;
+      leader_args.var_out = var_out;
+      leader_args.leader_dev = s.leader_dev;
+      leader_args.leader_out = leader_out;
+    }
   } else {
     if (segmented)
       LAUNCH_PASS_A(false, 0, leader_host);
@@ -866,7 +886,8 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
 #undef LAUNCH_PASS_A
   HIP_TRY(ctx, hipGetLastError());
 
-  rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, slot_by_leader);
+  rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, slot_by_leader, nullptr,
+                      leader_args.partials ? &leader_args : nullptr);
   if (rc) return rc;
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;

@@ -7,11 +7,10 @@
 //   k_hist0          the same histograms alone (stand-alone select, segments)
 //   k_stats          variance partials alone (stand-alone variance)
 //   k_leader         finishes the variances and takes the first argmax
-//   k_reduce_hist    adds the leader's per-chunk histograms
-//   k_pick0          finds the threshold digit and every chunk's list offset
+//   k_pick0          (flat VAR: finishes the variances, takes the leader;) finds the
+//                    threshold digit and every chunk's list offset
 //   k_compact1       ordered compaction of the leader's survivors, one block
 //                    per chunk, no inter-block dependency
-//   k_pick           narrows the candidate key range by one more radix digit
 //   k_compact        ordered compaction with a decoupled look-back scan: the
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
@@ -42,6 +41,7 @@ namespace artopk {
 
 constexpr int kMaxW = 64;
 constexpr int kHistBins = 4096;          // 12-bit digits (the last digit uses 128 of them)
+constexpr int kHistReps = 16;            // partial copies of a whole-vector histogram (spreads the atomics)
 constexpr uint32_t kKeyMask = 0x7fffffffu;
 constexpr uint32_t kQuotaInf = 0x7fffffffu;
 
@@ -76,8 +76,8 @@ constexpr int kSegState = 0;                       // SelState (16 words)
 constexpr int kSegCounters = 16;                   // tile counters of the look-back passes (16 words)
 constexpr int kSegHist1 = 32;                      // next-digit histogram, digit 1
 constexpr int kSegHist2 = kSegHist1 + kHistBins;   // next-digit histogram, digit 2
-constexpr int kSegSsum = kSegHist2 + kHistBins;    // suffix sums of the top-digit histogram
-constexpr int kSegWords = kSegSsum + kHistBins;
+constexpr int kSegHtop = kSegHist2 + kHistBins;    // top-digit histogram (when built by k_hist0)
+constexpr int kSegWords = kSegHtop + kHistBins;
 constexpr int kNumLookback = 4;                    // flag words per tile: array level 2, 3, list pass, spare
 
 struct ChunkGeom {
@@ -105,6 +105,7 @@ struct SelParams {
   PtrTable tab;
   const int32_t* leader_dev;
   int64_t n;               // length of the vector
+  const uint32_t* h_all;   // [workers][kHistReps][4096] top-digit histograms from the fused pass, or nullptr
   uint32_t* zero_base;     // [segments][kSegWords]
   uint64_t* flags;         // [tiles][kNumLookback]
   uint32_t* S;             // [slot][kMaxChunks][4096] per-chunk suffix histograms
@@ -126,7 +127,8 @@ struct SegView {
   uint32_t* counters;
   uint32_t* hist1;
   uint32_t* hist2;
-  uint32_t* ssum;
+  uint32_t* htop;       // top-digit histogram of the selected vector's range: htop_reps partial copies to add up
+  int htop_reps;
   uint64_t* flags;
   uint32_t* S;
   uint32_t* chunk_off;
@@ -178,11 +180,12 @@ __device__ __forceinline__ void store4(float* p, v4f v) {
     *reinterpret_cast<v4f*>(p) = v;
 }
 
-// Turns the 4096-bin LDS histogram `lh` of a T-thread block into suffix sums
-// and writes them to dst[0..4096).  `red` is T words of LDS.  All threads of
-// the block must call it after their last histogram update.
+// Adds the 4096-bin LDS histogram `lh` of a T-thread block to total[0..4096)
+// and writes its suffix sums to dst[0..4096).  `red` is T words of LDS.  All
+// threads of the block must call it after their last histogram update.
 template <int T>
-__device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, uint32_t* __restrict__ dst) {
+__device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, uint32_t* __restrict__ dst,
+                                                  uint32_t* __restrict__ total) {
   constexpr int BPT = kHistBins / T;  // consecutive bins per thread (a multiple of 4)
   static_assert(BPT >= 4 && BPT % 4 == 0, "block size must divide 1024");
   const int t = threadIdx.x;
@@ -196,6 +199,10 @@ __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, u
     v[4 * j + 2] = q.z;
     v[4 * j + 3] = q.w;
   }
+  // the plain counts also go to the histogram of the whole range (few bins are occupied)
+#pragma unroll
+  for (int j = 0; j < BPT; ++j)
+    if (v[j]) atomicAdd(&total[BPT * t + j], v[j]);
 #pragma unroll
   for (int j = BPT - 2; j >= 0; --j) v[j] += v[j + 1];
   red[t] = v[0];
@@ -218,7 +225,8 @@ __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, u
   }
 }
 
-__device__ __forceinline__ SegView seg_view(const SelParams& p, int seg) {
+// leader >= 0 overrides the device-resident leader (used by the block that has just computed it)
+__device__ __forceinline__ SegView seg_view(const SelParams& p, int seg, int leader = -1) {
   SegView v;
   v.d = p.table ? p.table[seg] : p.one;
   uint32_t* zb = p.zero_base + (size_t)seg * kSegWords;
@@ -226,11 +234,12 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg) {
   v.counters = zb + kSegCounters;
   v.hist1 = zb + kSegHist1;
   v.hist2 = zb + kSegHist2;
-  v.ssum = zb + kSegSsum;
   v.flags = p.flags + (size_t)v.d.flag_base * kNumLookback;
-  const int vec = v.d.vec >= 0 ? v.d.vec : *p.leader_dev;
+  const int vec = v.d.vec >= 0 ? v.d.vec : (leader >= 0 ? leader : *p.leader_dev);
   v.x = p.tab.p[vec];
   const size_t slot = p.slot_by_leader ? (size_t)vec : 0;  // histogram slot: per vector, or the only one
+  v.htop = p.h_all ? const_cast<uint32_t*>(p.h_all) + slot * kHistReps * kHistBins : zb + kSegHtop;
+  v.htop_reps = p.h_all ? kHistReps : 1;
   v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
   v.chunk_off = p.chunk_off + v.d.chunk_begin;
   v.list = p.list + v.d.list_base;
@@ -240,12 +249,12 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg) {
 }
 
 // ---------------------------------------------------------------------------
-// k_fill_zero : clears two word ranges (either may be empty); if leader_dev is
+// k_fill_zero : clears three word ranges (any may be empty); if leader_dev is
 // given it also records a leader that the host already knows.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2, size_t words2,
-            int32_t leader, int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
+            uint32_t* __restrict__ p3, size_t words3, int32_t leader, int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
   if (leader_dev != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
     *leader_dev = leader;
     if (leader_out) *leader_out = leader;
@@ -253,6 +262,7 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words1; i += stride) p1[i] = 0u;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words2; i += stride) p2[i] = 0u;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words3; i += stride) p3[i] = 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -270,7 +280,7 @@ constexpr int kPassAUnroll = 4;
 template <bool STATS, int HIST, bool NT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
-         double* __restrict__ partials) {
+         uint32_t* __restrict__ h_all, double* __restrict__ partials) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[HIST ? kHistBins : 4];
   __shared__ uint32_t red_u[HIST ? T : 1];
   __shared__ double red[2][T / 64];
@@ -377,7 +387,9 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (HIST) {
     if (do_hist) {
       const size_t slot = (HIST == 2) ? (size_t)w : 0;
-      flush_suffix_hist<T>(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins);
+      // many blocks add to the same few hundred bins: spread them over kHistReps partial copies
+      flush_suffix_hist<T>(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins,
+                           h_all + (slot * kHistReps + (size_t)(c % kHistReps)) * kHistBins);
     }
   }
 }
@@ -607,73 +619,205 @@ k_hist0(SelParams p) {
       }
     }
   }
-  flush_suffix_hist<256>(lh, red_u, sv.S + (size_t)c * kHistBins);
+  flush_suffix_hist<256>(lh, red_u, sv.S + (size_t)c * kHistBins, sv.htop);
 }
 
 // ---------------------------------------------------------------------------
-// k_reduce_hist : ssum[b] += sum over the segment's chunks of S[c][b].
-// grid = (16, ysplit, segments), block = 256; ssum must be zero on entry.
+// Selection state machine.  k_pick0 writes the state after the top digit (level
+// 1) and decides whether the level-1 survivors fit the list.  Nothing else
+// writes the state: later kernels replay the remaining digit picks from the
+// next-digit histograms in their prologue (derive_state), every block for
+// itself -- the result is a pure function of hist1 / hist2, so all blocks agree
+// and no extra launches are needed.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_reduce_hist(SelParams p) {
-  const SegView sv = seg_view(p, blockIdx.z);
-  const int nchunks = sv.d.geom.nchunks;
-  const int bin = blockIdx.x * 256 + threadIdx.x;
-  const int per = (nchunks + gridDim.y - 1) / gridDim.y;
-  const int c0 = blockIdx.y * per;
-  int c1 = c0 + per;
-  if (c1 > nchunks) c1 = nchunks;
-  uint32_t acc = 0u;
-#pragma unroll 8
-  for (int c = c0; c < c1; ++c) acc += sv.S[(size_t)c * kHistBins + bin];
-  if (acc) atomicAdd(&sv.ssum[bin], acc);
+__device__ __forceinline__ bool fits_list(const SelState& st, uint32_t cap) {
+  return (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
+}
+
+// Narrows st (in shared memory) by digit `digit` (1 or 2) using the histogram of
+// that digit over the current candidates.  All T threads of the block call it;
+// `part` is T words of shared memory.
+template <int T>
+__device__ void block_pick(SelState& st, const uint32_t* __restrict__ hist, int digit, uint32_t* part,
+                           uint32_t* __restrict__ err) {
+  constexpr int BPT = kHistBins / T;
+  const int t = threadIdx.x;
+  const int nbins = (int)digit_mask(digit) + 1;
+  uint32_t h[BPT];
+  uint32_t tot = 0u;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) {
+    const int b = BPT * t + j;
+    h[j] = (b < nbins) ? hist[b] : 0u;
+    tot += h[j];
+  }
+  __syncthreads();  // st is stable and `part` is free
+  part[t] = tot;
+  __syncthreads();
+  for (int off = 1; off < T; off <<= 1) {  // inclusive suffix sums
+    const uint32_t v = (t + off < T) ? part[t + off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  uint32_t above = (t + 1 < T) ? part[t + 1] : 0u;
+  const uint32_t total = part[0];
+  const uint32_t need = st.need;
+  int hit = -1;
+  uint32_t hit_above = 0u, hit_cnt = 0u;
+#pragma unroll
+  for (int j = BPT - 1; j >= 0; --j) {
+    if (hit < 0 && above < need && need <= above + h[j]) {
+      hit = BPT * t + j;
+      hit_above = above;
+      hit_cnt = h[j];
+    }
+    above += h[j];
+  }
+  __syncthreads();  // every thread has read st.need
+  if (hit >= 0) {   // exactly one thread when the histogram holds >= need keys
+    const int sh = digit_shift(digit);
+    st.lo = st.lo | ((uint32_t)hit << sh);
+    st.hi = st.lo | ((1u << sh) - 1u);
+    st.n_gt += hit_above;
+    st.need -= hit_above;
+    st.cand = hit_cnt;
+    st.level = (uint32_t)digit + 1u;
+  }
+  if (t == 0 && total < need) atomicOr(err, kErrPick);  // histogram does not cover `need`
+  __syncthreads();
+}
+
+// State at `want_level` (2 or 3) in st (shared).  st.compact_level = the level
+// whose pass writes the survivor list (1, 2 or 3), st.list_count its size.
+template <int T>
+__device__ void derive_state(const SegView& sv, SelState& st, int want_level, uint32_t* part,
+                             uint32_t* __restrict__ err) {
+  if (threadIdx.x == 0) st = *sv.st;  // level 1; compact_level = 1 if the level-1 survivors fit
+  __syncthreads();
+  block_pick<T>(st, sv.hist1, 1, part, err);
+  if (threadIdx.x == 0 && st.compact_level == 0u) {
+    if (fits_list(st, sv.d.cap)) {
+      st.compact_level = 2u;
+      st.list_count = st.n_gt + st.cand;
+    } else {
+      st.compact_level = 3u;
+    }
+  }
+  __syncthreads();
+  if (want_level >= 3) {
+    block_pick<T>(st, sv.hist2, 2, part, err);
+    if (threadIdx.x == 0 && st.compact_level == 3u) st.list_count = st.n_gt + (st.cand < st.need ? st.cand : st.need);
+    __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------------------------
-// k_pick0 : one block of 1024 threads per segment.  Initialises the selection
-// state, finds the threshold top digit b0 = the largest b with ssum[b] >= k,
-// and gives every chunk of the segment the offset of its survivors (keys with
-// top digit >= b0) in the segment's survivor list.
+// k_pick0 : one block of 1024 threads per segment.  Optionally first finishes
+// the per-worker variances and takes the leader (flat VAR step).  Then: suffix
+// sums of the top-digit histogram, threshold digit b0 = the largest b with at
+// least k keys at or above it, the level-1 state, and for every chunk of the
+// segment the offset of its survivors (keys with top digit >= b0) in the list.
 // ---------------------------------------------------------------------------
+struct LeaderArgs {
+  const double* partials;  // nullptr: the leader is already in leader_dev
+  int w_count, nblk;
+  int64_t n;
+  double* var_scratch;
+  double* var_out;
+  int32_t* leader_dev;
+  int32_t* leader_out;
+};
+
 __global__ void __launch_bounds__(1024)
-k_pick0(SelParams p) {
+k_pick0(SelParams p, LeaderArgs la) {
   __shared__ uint32_t part[1024];
   __shared__ int b0_sh;
-  const SegView sv = seg_view(p, blockIdx.y);
+  __shared__ int lead_sh;
+  const int t = threadIdx.x;
+  if (t == 0) {
+    b0_sh = -1;
+    lead_sh = -1;
+  }
+  if (la.partials != nullptr) {  // same arithmetic as k_leader
+    const int wave = t >> 6, lane = t & 63;
+    for (int w = wave; w < la.w_count; w += 16) {
+      double s = 0.0, ss = 0.0;
+      for (int b = lane; b < la.nblk; b += 64) {
+        s += la.partials[((size_t)w * la.nblk + b) * 2 + 0];
+        ss += la.partials[((size_t)w * la.nblk + b) * 2 + 1];
+      }
+      s = wave_sum(s);
+      ss = wave_sum(ss);
+      if (lane == 0) {
+        const double dn = (double)la.n;
+        double v = (ss - s * s / dn) / dn;
+        if (!(v > 0.0)) v = (v != v) ? v : 0.0;
+        la.var_scratch[w] = v;
+        if (la.var_out) la.var_out[w] = v;
+      }
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (t == 0) {
+      int best = 0;
+      for (int w = 1; w < la.w_count; ++w)
+        if (la.var_scratch[w] > la.var_scratch[best]) best = w;
+      *la.leader_dev = best;
+      if (la.leader_out) *la.leader_out = best;
+      lead_sh = best;
+    }
+  }
+  __syncthreads();
+  const SegView sv = seg_view(p, blockIdx.y, lead_sh);
   const uint32_t k = sv.d.k;
   const int nchunks = sv.d.geom.nchunks;
-  const int t = threadIdx.x;
-  if (t == 0) b0_sh = -1;
-  __syncthreads();
-  uint32_t sx[5];
+
+  // suffix sums of the top-digit histogram: sx[j] = keys with digit >= 4t+j
+  uint32_t h[4];
 #pragma unroll
-  for (int j = 0; j < 5; ++j) {
-    const int b = 4 * t + j;
-    sx[j] = (b < kHistBins) ? sv.ssum[b] : 0u;
+  for (int j = 0; j < 4; ++j) h[j] = 0u;
+  for (int r = 0; r < sv.htop_reps; ++r) {
+    const uint4 q = reinterpret_cast<const uint4*>(sv.htop + (size_t)r * kHistBins)[t];
+    h[0] += q.x;
+    h[1] += q.y;
+    h[2] += q.z;
+    h[3] += q.w;
   }
+  part[t] = h[0] + h[1] + h[2] + h[3];
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const uint32_t v = (t + off < 1024) ? part[t + off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  uint32_t sx[5];
+  sx[4] = (t + 1 < 1024) ? part[t + 1] : 0u;
+#pragma unroll
+  for (int j = 3; j >= 0; --j) sx[j] = sx[j + 1] + h[j];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    if (sx[j] >= k && sx[j + 1] < k) b0_sh = 4 * t + j;  // ssum is non-increasing: one hit
+    if (sx[j] >= k && sx[j + 1] < k) {  // the suffix sums are non-increasing: one hit
+      b0_sh = 4 * t + j;
+      SelState st;
+      st.lo = (uint32_t)(4 * t + j) << 19;
+      st.hi = st.lo | 0x7ffffu;
+      st.n_gt = sx[j + 1];
+      st.need = k - sx[j + 1];
+      st.cand = sx[j] - sx[j + 1];
+      st.level = 1u;
+      st.compact_level = fits_list(st, sv.d.cap) ? 1u : 0u;
+      st.list_count = st.compact_level ? st.n_gt + st.cand : 0u;
+      for (int i = 0; i < 8; ++i) st.pad[i] = 0u;
+      *sv.st = st;
+    }
   }
   __syncthreads();
   const int b0 = b0_sh;
   if (b0 < 0) {
     if (t == 0) atomicOr(p.err, kErrPick);
     return;
-  }
-  if (t == 0) {
-    SelState st;
-    const uint32_t above = (b0 + 1 < kHistBins) ? sv.ssum[b0 + 1] : 0u;
-    st.lo = (uint32_t)b0 << 19;
-    st.hi = st.lo | 0x7ffffu;
-    st.n_gt = above;
-    st.need = k - above;
-    st.cand = sv.ssum[b0] - above;
-    st.level = 1u;
-    st.compact_level = 0u;
-    st.list_count = 0u;
-    for (int i = 0; i < 8; ++i) st.pad[i] = 0u;
-    *sv.st = st;
   }
   // exclusive scan of the per-chunk survivor counts
   const uint32_t mine = (t < nchunks) ? sv.S[(size_t)t * kHistBins + b0] : 0u;
@@ -723,8 +867,8 @@ k_compact1(SelParams p) {
   uint2* __restrict__ list = sv.list;
 
   const SelState st = *sv.st;
-  if (st.level != 1u || st.compact_level != 0u || *p.err) return;
-  const bool write_out = (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
+  if (st.level != 1u || *p.err) return;
+  const bool write_out = st.compact_level == 1u;  // the level-1 survivors fit the list
   const uint32_t klo = st.lo, khi = st.hi;
   const float* __restrict__ xp = sv.x;
 
@@ -819,107 +963,6 @@ k_compact1(SelParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// k_pick : one block of 1024 threads narrows the candidate range by one digit.
-//
-//   stage 1 (after k_compact1): record whether that pass wrote the list, then
-//             resolve digit 1 from hist1.
-//   stage 2 (after the level-2 array compaction): if the list has not been
-//             written and state.level == 2, record whether that pass wrote it,
-//             then resolve digit 2.
-//   stage 4 (after the level-3 array compaction and the list histogram): record
-//             the list if the level-3 pass wrote it; resolve digit 2 if the
-//             list was written at level 1.
-// The decision "did the compaction at this level write the list" is the same
-// expression the compaction kernel evaluates: n_gt + cand <= cap.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ bool fits_list(const SelState& st, uint32_t cap) {
-  return (uint64_t)st.n_gt + (uint64_t)st.cand <= (uint64_t)cap;
-}
-
-__global__ void __launch_bounds__(1024)
-k_pick(SelParams p, int stage) {
-  __shared__ uint32_t part[1024];
-  __shared__ SelState st;
-  __shared__ int run_pick;
-  __shared__ uint32_t found;
-  const SegView sv = seg_view(p, blockIdx.y);
-  SelState* __restrict__ stp = sv.st;
-  const uint32_t* __restrict__ hist = (stage == 1) ? sv.hist1 : sv.hist2;
-  const uint32_t cap = sv.d.cap;
-  uint32_t* __restrict__ err = p.err;
-  const int t = threadIdx.x;
-  if (t == 0) {
-    st = *stp;
-    found = 0u;
-    int digit = -1;
-    if (stage == 1 || stage == 2) {
-      if (st.compact_level == 0u && st.level == (uint32_t)stage) {
-        if (fits_list(st, cap)) {
-          st.compact_level = (uint32_t)stage;
-          st.list_count = st.n_gt + st.cand;
-        }
-        digit = stage;
-      }
-    } else {  // stage 4
-      if (st.compact_level == 0u && st.level == 3u) {  // the level-3 array pass wrote the list
-        st.compact_level = 3u;
-        st.list_count = st.n_gt + (st.cand < st.need ? st.cand : st.need);
-      } else if (st.compact_level == 1u && st.level == 2u) {
-        digit = 2;
-      }
-    }
-    run_pick = digit;
-  }
-  __syncthreads();
-  const int digit = run_pick;
-  if (digit >= 0) {
-    const int nbins = (int)digit_mask(digit) + 1;
-    uint32_t h[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int b = 4 * t + j;
-      h[j] = (b < nbins) ? hist[b] : 0u;
-    }
-    part[t] = h[0] + h[1] + h[2] + h[3];
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {  // inclusive suffix sums
-      const uint32_t v = (t + off < 1024) ? part[t + off] : 0u;
-      __syncthreads();
-      part[t] += v;
-      __syncthreads();
-    }
-    uint32_t above = (t + 1 < 1024) ? part[t + 1] : 0u;
-    const uint32_t need = st.need;
-    int hit = -1;
-    uint32_t hit_above = 0u, hit_cnt = 0u;
-#pragma unroll
-    for (int j = 3; j >= 0; --j) {
-      if (hit < 0 && above < need && need <= above + h[j]) {
-        hit = 4 * t + j;
-        hit_above = above;
-        hit_cnt = h[j];
-      }
-      above += h[j];
-    }
-    __syncthreads();
-    if (hit >= 0) {  // exactly one thread when the histogram holds >= need keys
-      const int sh = digit_shift(digit);
-      st.lo = st.lo | ((uint32_t)hit << sh);
-      st.hi = st.lo | ((1u << sh) - 1u);
-      st.n_gt += hit_above;
-      st.need -= hit_above;
-      st.cand = hit_cnt;
-      st.level = (uint32_t)digit + 1u;
-      found = 1u;
-    }
-    __syncthreads();
-    if (t == 0 && !found) atomicOr(err, kErrPick);  // histogram does not cover `need`
-  }
-  __syncthreads();
-  if (t == 0) *stp = st;
-}
-
-// ---------------------------------------------------------------------------
 // Decoupled look-back over tiles.  Each tile publishes a 64-bit word
 //   [63:62] status (0 none, 1 tile aggregate, 2 inclusive prefix)
 //   [61:31] count A (keys above the range)      [30:0] count B (keys inside)
@@ -989,10 +1032,11 @@ __device__ uint64_t lookback_exclusive(uint64_t* __restrict__ flags, int flag_st
 //        (#A before it) + min(#B before it, quota)
 //   which is ascending in element order.  quota = infinity below level 3.
 //
-//   SRC_ARRAY (LIST = false): elements are x[e_lo .. e_hi) of the leader's
-//     vector, kept entries go to the survivor list as (index, key).  Runs only
-//     if the list has not been written and st.level == level; writes the list
-//     only if it fits (otherwise the pass only feeds the next digit histogram).
+//   SRC_ARRAY (LIST = false): elements are x[e_lo .. e_hi) of the selected
+//     vector, kept entries go to the survivor list as (index, bits).  Level 2
+//     runs when the level-1 survivors did not fit the list, level 3 when the
+//     level-2 ones did not either; a pass writes the list only if it fits
+//     (otherwise it only feeds the next digit histogram).
 //   SRC_LIST (LIST = true): elements are the survivor list, kept entries'
 //     indices go to idx_out[0 .. k) and, if vals_row is given, their values
 //     (the list carries the raw float bits) to vals_row[0 .. k).  Requires
@@ -1032,21 +1076,28 @@ k_compact(SelParams p, int level, int launch_id) {
   const int wave = tid >> 6;
   const uint32_t lane = lane_id();
 
-  const SelState st = *stp;
+  // the level-1 survivors fitted the list: the deeper array passes have nothing to do
+  if (!LIST && (stp->compact_level == 1u || *err)) return;
+  if (LIST && *err) return;
+  // tiles are handed out by a counter, so blocks beyond the number of list tiles are not needed
+  if (LIST && stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
+  __shared__ SelState st;
+  __shared__ uint32_t pick_part[kCompactThreads];
+  derive_state<kCompactThreads>(sv, st, LIST ? 3 : level, pick_part, err);
   bool write_out;
   bool do_hist;
   uint32_t quota;
   int64_t first_tile, ntiles;
   if (!LIST) {
-    if (st.compact_level != 0u || st.level != (uint32_t)level || *err) return;
+    // level 2 runs whenever level 1 did not fit; level 3 only if level 2 did not fit either
+    if (level == 3 && st.compact_level != 3u) return;
     quota = (level == 3) ? st.need : kQuotaInf;
-    const uint32_t takeB = st.cand < quota ? st.cand : quota;
-    write_out = (uint64_t)st.n_gt + takeB <= (uint64_t)cap;
+    write_out = st.compact_level == (uint32_t)level;
     do_hist = level < 3;
     first_tile = e_lo / kCompactTile;
     ntiles = (e_hi + kCompactTile - 1) / kCompactTile - first_tile;
   } else {
-    if (st.compact_level == 0u || st.level != 3u || *err) {
+    if (st.level != 3u) {
       if (tid == 0 && blockIdx.x == 0) atomicOr(err, kErrSequence);
       return;
     }
@@ -1219,21 +1270,26 @@ k_compact(SelParams p, int level, int launch_id) {
 
 // ---------------------------------------------------------------------------
 // k_list_hist : histogram of the last digit (7 bits) over the candidates in the
-// survivor list; runs only when the list was written at level 1.
+// survivor list; runs only when the list was written at level 1 (digit 1 is
+// replayed from hist1 in the prologue).
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_list_hist(SelParams p) {
   __shared__ uint32_t lh[128];
+  __shared__ SelState st;
+  __shared__ uint32_t pick_part[256];
   const SegView sv = seg_view(p, blockIdx.y);
-  const SelState st = *sv.st;
-  if (st.compact_level != 1u || st.level != 2u || *p.err) return;
+  if (sv.st->compact_level != 1u || *p.err) return;  // only a list written at level 1 still lacks digit 2
   const int tid = threadIdx.x;
+  const uint32_t cnt = sv.st->list_count;
+  if ((uint64_t)blockIdx.x * 256u >= cnt) return;     // nothing of the list for this block
+  derive_state<256>(sv, st, 2, pick_part, p.err);
   if (tid < 128) lh[tid] = 0u;
   __syncthreads();
-  const uint32_t cnt = st.list_count;
+  const uint32_t klo = st.lo, khi = st.hi;
   for (uint32_t q = blockIdx.x * 256u + tid; q < cnt; q += gridDim.x * 256u) {
     const uint32_t key = sv.list[q].y & kKeyMask;
-    if (key >= st.lo && key <= st.hi) atomicAdd(&lh[key & 0x7fu], 1u);
+    if (key >= klo && key <= khi) atomicAdd(&lh[key & 0x7fu], 1u);
   }
   __syncthreads();
   if (tid < 128) {
