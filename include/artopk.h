@@ -222,6 +222,22 @@ int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_
 int artopk_set_profile(artopk_ctx* ctx, int32_t enable);
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count);
 
+/*
+ * How the last artopk_step ran its selection (Sec. III-B leaves the Top-k
+ * method open; this only reports which of the library's equivalent routes was
+ * taken, for tests and tuning).  Synchronises the stream and writes up to
+ * `count` host int32 values:
+ *   [0] 1 if the step sampled a threshold guess before its fused pass
+ *   [1] 1 if the survivor list was then written from the fused pass' bit mask
+ *       (0 with [0] = 1: the guess did not hold and the full route was taken)
+ *   [2] entries in the survivor list
+ *   [3] radix level at which the list was written (1..3)
+ *   [4] workers the dominant streaming kernel covered (W, or W-1 when the
+ *       leader is known up front)
+ * Flat (one-segment) steps only; segmented steps report [0] = [1] = 0.
+ */
+int artopk_select_info(artopk_ctx* ctx, int32_t* info_out, int32_t count);
+
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t artopk_version(void);
 

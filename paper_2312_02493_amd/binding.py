@@ -19,7 +19,7 @@ _SYMBOLS = (
     "artopk_create", "artopk_destroy", "artopk_last_error", "artopk_status", "artopk_variance",
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
-    "artopk_apply_update", "artopk_topk_workers",
+    "artopk_apply_update", "artopk_topk_workers", "artopk_select_info",
 )
 
 
@@ -131,6 +131,12 @@ class Context:
     def set_profile(self, level: int):
         """0 off, 1 events around pass A only, 2 events at every stage boundary."""
         self._check(self._lib.artopk_set_profile(self._h, int(level)))
+
+    def select_info(self) -> dict:
+        buf = (C.c_int32 * 5)()
+        self._check(self._lib.artopk_select_info(self._h, buf, 5))
+        return {"guessed": int(buf[0]), "from_mask": int(buf[1]), "list_count": int(buf[2]),
+                "list_level": int(buf[3]), "dominant_workers": int(buf[4])}
 
     def get_profile(self) -> dict:
         buf = (C.c_float * len(PROF_NAMES))()

@@ -8,6 +8,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -26,7 +27,10 @@ constexpr int kPassRestThreads = 1024, kPassRestU = 8;
 
 struct Scratch {
   // zeroed before every select: one kSegWords block per segment, then the look-back flags
-  uint32_t* h_all = nullptr;      // [max_w][kHistReps][4096] top-digit histograms from the fused pass
+  uint32_t* h_all = nullptr;      // [max_w][kSlotWords] whole-vector histograms of the fused pass, guess sample
+  uint64_t* mask = nullptr;       // [max_w][mask_stride] survivor bit masks of the fused pass (if guessing is on)
+  int64_t mask_stride = 0;        // 64-bit words per worker
+  uint32_t* mcount = nullptr;     // [max_w][kMaxChunks] marked elements per chunk
   uint32_t* zero_base = nullptr;  // [max_seg][kSegWords]
   uint64_t* flags = nullptr;      // [max_tiles][kNumLookback], directly behind the blocks
   int64_t max_tiles = 0;
@@ -68,8 +72,13 @@ struct artopk_ctx {
   int32_t max_seg = 0;
   bool pass_a_nt = true;   // non-temporal g loads / acc stores in pass A
   bool leader_first = true;  // STAR / FIXED: leader pass + select first, then one fused pass over the rest
+  // vectors of at least this many elements get a sampled threshold guess before the fused pass, which
+  // then counts and marks only the keys that reach it (the selection no longer re-reads the vector)
+  int64_t guess_min_n = (int64_t)1 << 25;
   void* slab = nullptr;
   Scratch s;
+  // how the last step ran (artopk_select_info)
+  int32_t last_guessed = 0, last_dom_workers = 0;
   // descriptors of the last segmented layout uploaded to table_dev
   std::vector<int64_t> cached_off, cached_k;
   int64_t cached_n = -1;
@@ -302,6 +311,11 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.leader_dev = s.leader_dev;
   p.n = n;
   p.h_all = hist_from_pass ? s.h_all : nullptr;
+  p.mask = nullptr;
+  p.mask_stride = s.mask_stride;
+  p.mcount = nullptr;
+  p.from_list = 0;
+  p.only_if_need_full = 0;
   p.zero_base = s.zero_base;
   p.flags = s.flags;
   p.S = s.S;
@@ -312,7 +326,6 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.err = s.err_dev;
   p.table = pl.use_table ? s.table_dev : nullptr;
   p.slot_by_leader = slot_by_leader;
-  p.pad = 0;
   p.one = pl.desc[0];
   return p;
 }
@@ -325,7 +338,7 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
   Scratch& s = c->s;
   const size_t words1 = (size_t)pl.nseg * kSegWords;
   const size_t words2 = (size_t)pl.total_tiles * kNumLookback * 2;
-  const size_t words3 = (size_t)hist_slots * kHistReps * kHistBins;
+  const size_t words3 = (size_t)hist_slots * kSlotWords;
   const size_t total = words1 + words2 + words3;
   int blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
   if (blocks < 1) blocks = 1;
@@ -337,6 +350,66 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
   return ARTOPK_OK;
 }
 
+// Launches the fused pass over grid.y workers with the wanted options.
+template <bool STATS, int HIST, bool MASK>
+void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
+                     const ChunkGeom& geom, int hist_worker) {
+  Scratch& s = c->s;
+  if (c->pass_a_nt)
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, MASK, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+                       stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
+                       s.partials);
+  else
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, MASK, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+                       stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
+                       s.partials);
+}
+
+void launch_pass_a(artopk_ctx* c, bool stats, int hist, bool mask, dim3 grid, const PtrTable& g, const PtrTable& r,
+                   int64_t n, const ChunkGeom& geom, int hist_worker, hipStream_t stream = nullptr) {
+  if (stream == nullptr) stream = c->stream;
+#define PASS_A_CASE(S_, H_, M_)                     \
+  if (stats == S_ && hist == H_ && mask == M_)      \
+  return launch_pass_a_t<S_, H_, M_>(c, stream, grid, g, r, n, geom, hist_worker)
+  PASS_A_CASE(false, 0, false);
+  PASS_A_CASE(false, 1, false);
+  PASS_A_CASE(false, 1, true);
+  PASS_A_CASE(false, 2, false);
+  PASS_A_CASE(true, 0, false);
+  PASS_A_CASE(true, 2, false);
+  PASS_A_CASE(true, 2, true);
+#undef PASS_A_CASE
+}
+
+// Whether a flat step on n elements keeping k uses the sampled threshold guess.
+struct GuessPlan {
+  bool on = false;
+  int runs = 0;
+  int64_t stride = 0;
+  uint32_t m_hi = 0;
+};
+
+GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k) {
+  GuessPlan gp;
+  if (c->s.mask == nullptr || n < c->guess_min_n || k * 32 > n) return gp;
+  int64_t runs = n / (4 * kGuessRun);  // at most a quarter of the vector
+  if (runs > 16384) runs = 16384;
+  if (runs < 256) return gp;
+  gp.runs = (int)runs;
+  gp.stride = n / runs;
+  // keys of the sample expected above the true threshold, plus six standard deviations and a few
+  const double expect = (double)k * (double)(runs * kGuessRun) / (double)n;
+  gp.m_hi = (uint32_t)std::ceil(expect + 6.0 * std::sqrt(expect) + 8.0);
+  gp.on = (int64_t)gp.m_hi <= runs * kGuessRun;
+  return gp;
+}
+
+// Samples the first nvec vectors of (g + residual) into slots 0 .. nvec-1 (cleared beforehand).
+void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const PtrTable& res, int nvec) {
+  hipLaunchKernelGGL(k_guess, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs, gp.stride,
+                     gp.m_hi);
+}
+
 // Top-k of every segment of the plan on the vector tab.p[*leader_dev]; the
 // scratch must have been cleared.  If hist_ready the per-chunk suffix
 // histograms are already in S (flat plans only: pass A built them, in slot
@@ -344,15 +417,34 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
 // the leader's values at the selected indices.
 int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
                    bool hist_ready, int slot_by_leader, float* vals_row = nullptr,
-                   const LeaderArgs* leader_args = nullptr) {
+                   const LeaderArgs* leader_args = nullptr, bool guessed = false) {
   hipStream_t st = c->stream;
   const unsigned nseg = (unsigned)pl.nseg;
-  const SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0, hist_ready);
+  SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0, hist_ready);
   LeaderArgs la{};
   if (leader_args) la = *leader_args;
 
-  if (!hist_ready) hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
+  if (guessed && hist_ready) {
+    // The fused pass marked and counted the keys reaching a guessed bound.  If the bound works out
+    // the list is written from the mask and the threshold digit taken from the list; otherwise the
+    // state says need_full, the next two kernels build the histogram of every key and pick from
+    // that, and the selection goes on as without a guess.  Kernels of the other case return at once.
+    p.mask = c->s.mask;
+    p.mcount = c->s.mcount;
+    hipLaunchKernelGGL(k_pick_mask, dim3(1, nseg), dim3(1024), 0, st, p, la);
+    SelParams pf = p;
+    pf.h_all = nullptr;
+    pf.only_if_need_full = 1;
+    hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, pf);
+    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pf, LeaderArgs{});
+    hipLaunchKernelGGL((k_compact_mask<4>), dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
+    SelParams pl0 = p;
+    pl0.from_list = 1;
+    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pl0, LeaderArgs{});
+  } else {
+    if (!hist_ready) hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
+  }
   // 4 waves, 16 consecutive elements per lane: best of the shapes measured on the 138 M and 1 G workloads
   hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
 
@@ -368,7 +460,8 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   int64_t lblocks = (pl.max_cap + 256 * 16 - 1) / (256 * 16);
   if (lblocks > per_seg * 2) lblocks = per_seg * 2;
   if (lblocks < 1) lblocks = 1;
-  hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p);
+  if (guessed && hist_ready) hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 1);
+  hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 2);
   int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < per_seg ? ltiles : per_seg);
   if (fblocks < 1) fblocks = 1;
@@ -472,6 +565,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   c->num_cu = cus > 0 ? cus : 256;
   if (const char* e_nt = getenv("ARTOPK_PASS_A_NT")) c->pass_a_nt = atoi(e_nt) != 0;
   if (const char* e_lf = getenv("ARTOPK_LEADER_FIRST")) c->leader_first = atoi(e_lf) != 0;
+  if (const char* e_g = getenv("ARTOPK_GUESS_MIN_N")) c->guess_min_n = atoll(e_g);
 
   Scratch& s = c->s;
   // list capacity: every key above the range (< k of them) plus a generous share of candidates
@@ -492,7 +586,11 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return o;
   };
   // zeroed region: one block per segment, then the look-back flags
-  const size_t o_hall = take((size_t)max_w * kHistReps * kHistBins * sizeof(uint32_t));
+  const size_t o_hall = take((size_t)max_w * kSlotWords * sizeof(uint32_t));
+  // one bit per element and worker, in rows of 256 elements, if the vectors are long enough to guess on
+  s.mask_stride = max_n >= c->guess_min_n ? (max_n + 255) / 256 * 4 : 0;
+  const size_t o_mask = take((size_t)max_w * (size_t)s.mask_stride * sizeof(uint64_t));
+  const size_t o_mcount = take((size_t)max_w * kMaxChunks * sizeof(uint32_t));
   const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
                              (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
   const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
@@ -514,6 +612,8 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   }
   char* base = static_cast<char*>(c->slab);
   s.h_all = reinterpret_cast<uint32_t*>(base + o_hall);
+  s.mask = s.mask_stride ? reinterpret_cast<uint64_t*>(base + o_mask) : nullptr;
+  s.mcount = reinterpret_cast<uint32_t*>(base + o_mcount);
   s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
   // kSegWords is even, so the flags stay 8-byte aligned
   s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
@@ -582,6 +682,17 @@ int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
 
 // Averages every stage over the calls recorded since profiling was enabled
 // (at most the kRing most recent ones).
+int artopk_select_info(artopk_ctx* ctx, int32_t* info_out, int32_t count) {
+  if (!ctx || !info_out || count < 0) return ARTOPK_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  SelState st{};
+  HIP_TRY(ctx, hipMemcpy(&st, ctx->s.zero_base + kSegState, sizeof(st), hipMemcpyDeviceToHost));
+  const int32_t v[5] = {ctx->last_guessed, ctx->last_guessed ? (int32_t)st.use_mask : 0, (int32_t)st.list_count,
+                        (int32_t)st.compact_level, ctx->last_dom_workers};
+  for (int i = 0; i < count && i < 5; ++i) info_out[i] = v[i];
+  return ARTOPK_OK;
+}
+
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count) {
   if (!ctx || !ms_out || count < 0) return ARTOPK_EINVAL;
   if (!ctx->ev_created) return fail(ctx, ARTOPK_EINVAL, "profiling was never enabled");
@@ -766,20 +877,16 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   // pass A always works on whole-vector chunks; for a flat select they are the select's chunks too
   const ChunkGeom geom = make_geom(0, n);
   const dim3 grid(geom.nchunks, w);
-  const bool nt = ctx->pass_a_nt;
 
+  ctx->last_guessed = 0;
+  ctx->last_dom_workers = w;
   if (mode == ARTOPK_VAR_TOPK) {
     // Literal Alg. 1: Top-k on every worker, leader = largest squared norm of its own k values,
     // then the leader's indices are the shared ones.
     prof_begin(ctx);
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, *pl, (int)w))) return rc;
-    if (nt)
-      hipLaunchKernelGGL((k_pass_a<false, 2, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
-                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.h_all, s.partials);
-    else
-      hipLaunchKernelGGL((k_pass_a<false, 2, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, w),
-                         dim3(kPassAThreads), 0, st, gt, rt, n, geom, -1, s.S, s.h_all, s.partials);
+    launch_pass_a(ctx, false, 2, false, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
     prof_mark(ctx, 1);
     if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
@@ -805,21 +912,22 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_begin(ctx);
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, *pl, 1, L, leader_out))) return rc;
-    if (nt)
-      hipLaunchKernelGGL((k_pass_a<false, 1, true, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
-                         st, g1t, r1t, n, geom, 0, s.S, s.h_all, s.partials);
-    else
-      hipLaunchKernelGGL((k_pass_a<false, 1, false, kPassAThreads, kPassAU>), dim3(geom.nchunks, 1), dim3(kPassAThreads), 0,
-                         st, g1t, r1t, n, geom, 0, s.S, s.h_all, s.partials);
+    const GuessPlan gp = plan_guess(ctx, n, k);
+    ctx->last_guessed = gp.on ? 1 : 0;
+    ctx->last_dom_workers = w > 1 ? w - 1 : 1;
+    if (gp.on) enqueue_guess(ctx, gp, g1t, r1t, 1);
+    launch_pass_a(ctx, false, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
     prof_mark(ctx, 1);
-    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k))) return rc;
+    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on)))
+      return rc;
     prof_mark(ctx, 2);
-    if (w > 1) {
-      if (nt)
-        hipLaunchKernelGGL((k_pass_rest<true, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
+    const int rest = (int)w - 1;
+    if (rest > 0) {
+      if (ctx->pass_a_nt)
+        hipLaunchKernelGGL((k_pass_rest<true, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, rest), dim3(kPassRestThreads),
                            0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
       else
-        hipLaunchKernelGGL((k_pass_rest<false, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, w - 1), dim3(kPassRestThreads),
+        hipLaunchKernelGGL((k_pass_rest<false, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, rest), dim3(kPassRestThreads),
                            0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
     }
     prof_mark(ctx, 3);
@@ -845,20 +953,15 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : (mode == ARTOPK_VAR ? (int)w : 1)))) return rc;
   int slot_by_leader = 0;
   LeaderArgs leader_args{};
-#define LAUNCH_PASS_A(STATS, HIST, LEADER)                                                                 \
-  do {                                                                                                     \
-    if (nt)                                                                                                \
-      hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,   \
-                         gt, rt, n, geom, LEADER, s.S, s.h_all, s.partials);                               \
-    else                                                                                                   \
-      hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, st,  \
-                         gt, rt, n, geom, LEADER, s.S, s.h_all, s.partials);                               \
-  } while (0)
+  GuessPlan gp;
   if (mode == ARTOPK_VAR) {
     if (segmented) {
-      LAUNCH_PASS_A(true, 0, -1);
+      launch_pass_a(ctx, true, 0, false, grid, gt, rt, n, geom, -1);
     } else {
-      LAUNCH_PASS_A(true, 2, -1);
+      gp = plan_guess(ctx, n, k);
+      ctx->last_guessed = gp.on ? 1 : 0;
+      if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
+      launch_pass_a(ctx, true, 2, gp.on, grid, gt, rt, n, geom, -1);
       slot_by_leader = 1;
     }
     prof_mark(ctx, 1);
@@ -876,18 +979,14 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
       leader_args.leader_out = leader_out;
     }
   } else {
-    if (segmented)
-      LAUNCH_PASS_A(false, 0, leader_host);
-    else
-      LAUNCH_PASS_A(false, 1, leader_host);
+    launch_pass_a(ctx, false, segmented ? 0 : 1, false, grid, gt, rt, n, geom, leader_host);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
   }
-#undef LAUNCH_PASS_A
   HIP_TRY(ctx, hipGetLastError());
 
   rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, slot_by_leader, nullptr,
-                      leader_args.partials ? &leader_args : nullptr);
+                      leader_args.partials ? &leader_args : nullptr, gp.on);
   if (rc) return rc;
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;

@@ -35,6 +35,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 namespace artopk {
@@ -42,6 +44,13 @@ namespace artopk {
 constexpr int kMaxW = 64;
 constexpr int kHistBins = 4096;          // 12-bit digits (the last digit uses 128 of them)
 constexpr int kHistReps = 16;            // partial copies of a whole-vector histogram (spreads the atomics)
+// One slot of whole-vector scratch (32-bit words): the partial histogram copies, then the
+// histogram of the threshold-guess sample, then its control words.
+constexpr int kSlotGuessHist = kHistReps * kHistBins;
+constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound
+constexpr int kSlotWords = kSlotCtrl + 16;
+constexpr uint32_t kNoGuess = 0xffffffffu;             // no key reaches this bound
+constexpr int kGuessRun = 16;                          // consecutive elements per sample run
 constexpr uint32_t kKeyMask = 0x7fffffffu;
 constexpr uint32_t kQuotaInf = 0x7fffffffu;
 
@@ -62,7 +71,10 @@ struct SelState {
   uint32_t level;          // radix digits resolved so far (0..3)
   uint32_t compact_level;  // level at which the survivor list was written (0 = not yet)
   uint32_t list_count;     // entries in the survivor list
-  uint32_t pad[8];
+  uint32_t use_mask;       // the list is written from the survivor bit mask of the fused pass
+  uint32_t need_full;      // the guessed bound did not work out: the top-digit histogram of every key is needed
+  uint32_t list_lo;        // with use_mask: the list holds every key >= list_lo (<= lo)
+  uint32_t pad[5];
 };
 
 // Bits of the sticky device-side error word.
@@ -105,7 +117,12 @@ struct SelParams {
   PtrTable tab;
   const int32_t* leader_dev;
   int64_t n;               // length of the vector
-  const uint32_t* h_all;   // [workers][kHistReps][4096] top-digit histograms from the fused pass, or nullptr
+  const uint32_t* h_all;   // [workers][kSlotWords] whole-vector histograms from the fused pass, or nullptr
+  const uint64_t* mask;    // [workers][mask_stride] survivor bit masks from the fused pass, or nullptr
+  int64_t mask_stride;     // 64-bit words per worker
+  const uint32_t* mcount;  // [workers][kMaxChunks] marked elements per chunk, or nullptr
+  int32_t from_list;       // k_pick0: the top-digit histogram covers the survivor list written from the mask
+  int32_t only_if_need_full;  // this launch runs only for segments whose state says need_full
   uint32_t* zero_base;     // [segments][kSegWords]
   uint64_t* flags;         // [tiles][kNumLookback]
   uint32_t* S;             // [slot][kMaxChunks][4096] per-chunk suffix histograms
@@ -129,6 +146,9 @@ struct SegView {
   uint32_t* hist2;
   uint32_t* htop;       // top-digit histogram of the selected vector's range: htop_reps partial copies to add up
   int htop_reps;
+  const uint32_t* ctrl;  // control words of the vector's slot (guessed bound), or nullptr
+  const uint64_t* mask;  // survivor bit mask of the vector, or nullptr
+  const uint32_t* mcount;  // marked elements per chunk of the vector, or nullptr
   uint64_t* flags;
   uint32_t* S;
   uint32_t* chunk_off;
@@ -238,8 +258,11 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg, int lea
   const int vec = v.d.vec >= 0 ? v.d.vec : (leader >= 0 ? leader : *p.leader_dev);
   v.x = p.tab.p[vec];
   const size_t slot = p.slot_by_leader ? (size_t)vec : 0;  // histogram slot: per vector, or the only one
-  v.htop = p.h_all ? const_cast<uint32_t*>(p.h_all) + slot * kHistReps * kHistBins : zb + kSegHtop;
+  v.htop = p.h_all ? const_cast<uint32_t*>(p.h_all) + slot * kSlotWords : zb + kSegHtop;
   v.htop_reps = p.h_all ? kHistReps : 1;
+  v.ctrl = p.h_all ? p.h_all + slot * kSlotWords + kSlotCtrl : nullptr;
+  v.mask = p.mask ? p.mask + slot * (size_t)p.mask_stride : nullptr;
+  v.mcount = p.mcount ? p.mcount + slot * kMaxChunks : nullptr;
   v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
   v.chunk_off = p.chunk_off + v.d.chunk_begin;
   v.list = p.list + v.d.list_base;
@@ -267,37 +290,61 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 
 // ---------------------------------------------------------------------------
 // k_pass_a : acc = g + residual (in place over residual), variance partials,
-//            per-chunk top-digit suffix histograms.
-//   grid = (nchunks, W), block = 256; block (c, w) owns chunk c of worker w.
-//   HIST: 0 none, 1 only worker `hist_worker` (into S[0][c]), 2 every worker
-//         (into S[w][c]).
+//            and what the selection needs from this pass.
+//   grid = (nchunks, W), block = T; block (c, w) owns chunk c of worker w.
+//   HIST: 0 nothing for the selection, 1 only for worker `hist_worker` (slot 0),
+//         2 for every worker (worker w in slot w).
+//   MASK = false: per-chunk top-digit suffix histograms S[slot][c] and the
+//         whole-vector histogram of the slot.
+//   MASK = true: no histogram; elements whose key reaches the guessed bound of
+//         the slot are marked in the slot's bit mask and counted per chunk.  For
+//         every row of 64 float4 groups four 64-bit words are written: word e,
+//         bit l <=> element 4 (64 row + l) + e is marked.  The n mod 4 elements
+//         behind the last whole group are counted but have no mask bit.
 //   Variance partials use the shift c_w = g_w[0]: per block the sums of
 //   (acc - c_w) and (acc - c_w)^2 in float64, written to partials[w][c][0..1].
 //   NT: non-temporal loads of g and stores of acc.
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST, bool NT, int T, int U>
+template <bool STATS, int HIST, bool NT, bool MASK, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
-         uint32_t* __restrict__ h_all, double* __restrict__ partials) {
-  __shared__ __attribute__((aligned(16))) uint32_t lh[HIST ? kHistBins : 4];
-  __shared__ uint32_t red_u[HIST ? T : 1];
+         uint32_t* __restrict__ h_all, uint64_t* __restrict__ mask, int64_t mask_stride,
+         uint32_t* __restrict__ mcount, double* __restrict__ partials) {
+  static_assert(!MASK || HIST != 0, "the mask belongs to a slot");
+  constexpr bool LH = HIST != 0 && !MASK;  // an LDS histogram is built
+  __shared__ __attribute__((aligned(16))) uint32_t lh[LH ? kHistBins : 4];
+  __shared__ uint32_t red_u[LH ? T : 1];
   __shared__ double red[2][T / 64];
+  __shared__ uint32_t marked_sh;
 
-  // with a known leader its blocks (the only ones that build histograms) are dispatched first
+  // with a known leader its blocks (the only ones that work for the selection) are dispatched first
   const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
   const int c = blockIdx.x;
   const int nblk = gridDim.x;
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
   const float* __restrict__ gp = g.p[w];
   float* __restrict__ rp = res.p[w];
   const bool do_hist = (HIST == 2) || (HIST == 1 && w == hist_worker);
+  const size_t slot = (HIST == 2) ? (size_t)w : 0;
 
-  if (HIST) {
+  if (LH) {
     if (do_hist)
       for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
-    __syncthreads();
+  }
+  if (MASK && tid == 0) marked_sh = 0u;
+  if (LH || MASK) __syncthreads();
+  // Marked <=> not (|acc| < bound): the same as key >= bound on the magnitude bits, NaNs included.
+  uint32_t gkey = kNoGuess;
+  float gf = __builtin_inff();
+  uint64_t* __restrict__ mrow = nullptr;
+  uint32_t marked = 0u;  // per wave
+  if (MASK) {
+    if (do_hist) gkey = h_all[slot * kSlotWords + kSlotCtrl + 1];
+    if (gkey != kNoGuess) gf = __uint_as_float(gkey);
+    mrow = mask + slot * (size_t)mask_stride;
   }
 
   double cshift = 0.0, s = 0.0, ss = 0.0;
@@ -308,21 +355,25 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (c_hi > n) c_hi = n;
   const int64_t q_hi = c_hi >> 2;  // whole float4 groups of this chunk
 
-  for (int64_t q0 = (c_lo >> 2) + tid; q0 < q_hi; q0 += T * U) {
+  // One tile: U rows of T float4 groups; the wave's rows start at group qw (a multiple of 64).
+  // FULL: every group of the wave's rows lies inside the chunk, so nothing is predicated.
+  auto tile = [&](const int64_t qw, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     v4f a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t q = q0 + u * T;
-      if (q < q_hi) {
+      const int64_t q = qw + lane + u * T;
+      if (FULL || q < q_hi) {
         a[u] = load4<NT>(gp + 4 * q);
         b[u] = load4<NT>(rp + 4 * q);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t q = q0 + u * T;
-      if (q < q_hi) {
-        v4f v;
+      const int64_t q = qw + lane + u * T;
+      const bool valid = FULL || q < q_hi;
+      v4f v = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
         v.x = a[u].x + b[u].x;
         v.y = a[u].y + b[u].y;
         v.z = a[u].z + b[u].z;
@@ -337,7 +388,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
           ss = fma(d2, d2, ss);
           ss = fma(d3, d3, ss);
         }
-        if (HIST) {
+        if (LH) {
           if (do_hist) {
             atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
             atomicAdd(&lh[(__float_as_uint(v.y) & kKeyMask) >> 19], 1u);
@@ -346,8 +397,26 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
           }
         }
       }
+      if (MASK) {
+        if (do_hist) {
+          const uint64_t m0 = __ballot(valid && !(__builtin_fabsf(v.x) < gf));
+          const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
+          const uint64_t m2 = __ballot(valid && !(__builtin_fabsf(v.z) < gf));
+          const uint64_t m3 = __ballot(valid && !(__builtin_fabsf(v.w) < gf));
+          marked += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+          const int64_t qrow = qw + u * T;  // first group of this wave's row
+          if ((FULL || qrow < q_hi) && lane < 4)
+            mrow[(qrow >> 6) * 4 + lane] = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
+        }
+      }
     }
-  }
+  };
+
+  // the loop runs on the wave's first group, so all 64 lanes stay together (the masks need that)
+  const int64_t qw0 = (c_lo >> 2) + __builtin_amdgcn_readfirstlane(tid - lane);
+  int64_t qw = qw0;
+  for (; qw + (int64_t)(U - 1) * T + 64 <= q_hi; qw += T * U) tile(qw, std::true_type{});
+  if (qw < q_hi) tile(qw, std::false_type{});
   // scalar tail (n not a multiple of 4): the block that owns the last chunk
   if (c_hi == n) {
     const int64_t j = (n >> 2) * 4 + tid;
@@ -359,10 +428,16 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
         s += d;
         ss = fma(d, d, ss);
       }
-      if (HIST) {
+      if (LH) {
         if (do_hist) atomicAdd(&lh[(__float_as_uint(v) & kKeyMask) >> 19], 1u);
       }
+      if (MASK) {
+        if (do_hist && !(__builtin_fabsf(v) < gf)) atomicAdd(&marked_sh, 1u);
+      }
     }
+  }
+  if (MASK) {
+    if (do_hist && lane == 0 && marked != 0u) atomicAdd(&marked_sh, marked);
   }
 
   if (STATS) {
@@ -384,12 +459,14 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     partials[((size_t)w * nblk + c) * 2 + 0] = S1;
     partials[((size_t)w * nblk + c) * 2 + 1] = S2;
   }
-  if (HIST) {
+  if (MASK) {
+    if (do_hist && tid == 0) mcount[slot * kMaxChunks + (size_t)c] = marked_sh;
+  }
+  if (LH) {
     if (do_hist) {
-      const size_t slot = (HIST == 2) ? (size_t)w : 0;
       // many blocks add to the same few hundred bins: spread them over kHistReps partial copies
       flush_suffix_hist<T>(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins,
-                           h_all + (slot * kHistReps + (size_t)(c % kHistReps)) * kHistBins);
+                           h_all + slot * kSlotWords + (size_t)(c % kHistReps) * kHistBins);
     }
   }
 }
@@ -568,6 +645,88 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
 }
 
 // ---------------------------------------------------------------------------
+// k_guess : a lower bound on the key of the k-th largest |g + residual| of each
+// vector, from a sample, before the fused pass runs.  grid = (blocks, vectors),
+// block = 256; vector y uses slot y.  The sample is `runs` runs of kGuessRun
+// consecutive elements, run r starting at (r stride) rounded down to a multiple
+// of kGuessRun.  The last block to finish takes the top digit d of the sample's
+// m_hi-th largest key and publishes d << 19 (kNoGuess if the sample is smaller
+// than m_hi).  The bound is only a guess: whoever uses it checks that at least
+// k keys of the whole vector reach it.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_t stride, uint32_t m_hi) {
+  __shared__ uint32_t lh[kHistBins];
+  __shared__ uint32_t wsum[4];
+  __shared__ int last_sh, hit_sh;
+  const int tid = threadIdx.x;
+  const int v = blockIdx.y;
+  const float* __restrict__ gp = g.p[v];
+  const float* __restrict__ rp = res.p[v];
+  uint32_t* __restrict__ ghist = slots + (size_t)v * kSlotWords + kSlotGuessHist;
+  uint32_t* __restrict__ ctrl = slots + (size_t)v * kSlotWords + kSlotCtrl;
+  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  __syncthreads();
+  for (int r = blockIdx.x * 256 + tid; r < runs; r += gridDim.x * 256) {
+    const int64_t e0 = ((int64_t)r * stride) & ~(int64_t)(kGuessRun - 1);
+    float4 a[kGuessRun / 4], b[kGuessRun / 4];
+#pragma unroll
+    for (int i = 0; i < kGuessRun / 4; ++i) {
+      a[i] = *reinterpret_cast<const float4*>(gp + e0 + 4 * i);
+      b[i] = *reinterpret_cast<const float4*>(rp + e0 + 4 * i);
+    }
+#pragma unroll
+    for (int i = 0; i < kGuessRun / 4; ++i) {
+      atomicAdd(&lh[(__float_as_uint(a[i].x + b[i].x) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(a[i].y + b[i].y) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(a[i].z + b[i].z) & kKeyMask) >> 19], 1u);
+      atomicAdd(&lh[(__float_as_uint(a[i].w + b[i].w) & kKeyMask) >> 19], 1u);
+    }
+  }
+  __syncthreads();
+  for (int b = tid; b < kHistBins; b += 256) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&ghist[b], c);
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    last_sh = atomicAdd(&ctrl[0], 1u) == gridDim.x - 1 ? 1 : 0;
+    hit_sh = -1;
+  }
+  __syncthreads();
+  if (!last_sh) return;
+  __threadfence();
+  // the last block: suffix sums over the sample histogram, 16 consecutive bins per thread
+  uint32_t h[16];
+  uint32_t tot = 0u;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    h[j] = __hip_atomic_load(&ghist[16 * tid + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    tot += h[j];
+  }
+  // inclusive suffix sum of tot over the 64 lanes, then over the 4 waves
+  uint32_t suf = tot;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t x = __shfl_down(suf, off, 64);
+    if ((tid & 63) + off < 64) suf += x;
+  }
+  if ((tid & 63) == 0) wsum[tid >> 6] = suf;
+  __syncthreads();
+  uint32_t above = suf - tot;  // bins of higher threads in this wave
+  for (int i = (tid >> 6) + 1; i < 4; ++i) above += wsum[i];
+#pragma unroll
+  for (int j = 15; j >= 0; --j) {
+    if (above < m_hi && above + h[j] >= m_hi) hit_sh = 16 * tid + j;  // one thread, one bin
+    above += h[j];
+  }
+  __syncthreads();
+  // bounds above infinity's digit would not survive the floating-point comparison of the fused pass
+  if (tid == 0) ctrl[1] = hit_sh >= 0 ? (uint32_t)(hit_sh < 0xff0 ? hit_sh : 0xff0) << 19 : kNoGuess;
+}
+
+// ---------------------------------------------------------------------------
 // k_hist0 : per-chunk top-digit suffix histograms of |x[e_lo .. e_hi)| for the
 // leader's vector.  grid = (max chunks of a segment, segments), block = 256.
 // Whole aligned float4 groups are read where they lie inside the array, single
@@ -580,6 +739,7 @@ k_hist0(SelParams p) {
   const SegView sv = seg_view(p, blockIdx.y);
   const int c = blockIdx.x;
   if (c >= sv.d.geom.nchunks) return;
+  if (p.only_if_need_full && sv.st->need_full == 0u) return;
   const int tid = threadIdx.x;
   const float* __restrict__ xp = sv.x;
   for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
@@ -729,6 +889,40 @@ struct LeaderArgs {
   int32_t* leader_out;
 };
 
+// Finishes the per-worker variances from the fused pass' partials and takes the first
+// worker of largest variance (same arithmetic as k_leader).  All 1024 threads of the
+// block call it; returns the leader in thread 0 only.
+__device__ int block_take_leader(const LeaderArgs& la) {
+  const int t = threadIdx.x;
+  const int wave = t >> 6, lane = t & 63;
+  for (int w = wave; w < la.w_count; w += 16) {
+    double s = 0.0, ss = 0.0;
+    for (int b = lane; b < la.nblk; b += 64) {
+      s += la.partials[((size_t)w * la.nblk + b) * 2 + 0];
+      ss += la.partials[((size_t)w * la.nblk + b) * 2 + 1];
+    }
+    s = wave_sum(s);
+    ss = wave_sum(ss);
+    if (lane == 0) {
+      const double dn = (double)la.n;
+      double v = (ss - s * s / dn) / dn;
+      if (!(v > 0.0)) v = (v != v) ? v : 0.0;
+      la.var_scratch[w] = v;
+      if (la.var_out) la.var_out[w] = v;
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+  int best = 0;
+  if (t == 0) {
+    for (int w = 1; w < la.w_count; ++w)
+      if (la.var_scratch[w] > la.var_scratch[best]) best = w;
+    *la.leader_dev = best;
+    if (la.leader_out) *la.leader_out = best;
+  }
+  return best;
+}
+
 __global__ void __launch_bounds__(1024)
 k_pick0(SelParams p, LeaderArgs la) {
   __shared__ uint32_t part[1024];
@@ -739,37 +933,15 @@ k_pick0(SelParams p, LeaderArgs la) {
     b0_sh = -1;
     lead_sh = -1;
   }
-  if (la.partials != nullptr) {  // same arithmetic as k_leader
-    const int wave = t >> 6, lane = t & 63;
-    for (int w = wave; w < la.w_count; w += 16) {
-      double s = 0.0, ss = 0.0;
-      for (int b = lane; b < la.nblk; b += 64) {
-        s += la.partials[((size_t)w * la.nblk + b) * 2 + 0];
-        ss += la.partials[((size_t)w * la.nblk + b) * 2 + 1];
-      }
-      s = wave_sum(s);
-      ss = wave_sum(ss);
-      if (lane == 0) {
-        const double dn = (double)la.n;
-        double v = (ss - s * s / dn) / dn;
-        if (!(v > 0.0)) v = (v != v) ? v : 0.0;
-        la.var_scratch[w] = v;
-        if (la.var_out) la.var_out[w] = v;
-      }
-    }
-    __threadfence_block();
-    __syncthreads();
-    if (t == 0) {
-      int best = 0;
-      for (int w = 1; w < la.w_count; ++w)
-        if (la.var_scratch[w] > la.var_scratch[best]) best = w;
-      *la.leader_dev = best;
-      if (la.leader_out) *la.leader_out = best;
-      lead_sh = best;
-    }
+  if (la.partials != nullptr) {
+    const int best = block_take_leader(la);
+    if (t == 0) lead_sh = best;
   }
   __syncthreads();
   const SegView sv = seg_view(p, blockIdx.y, lead_sh);
+  if (p.only_if_need_full && sv.st->need_full == 0u) return;
+  if (p.from_list && sv.st->use_mask == 0u) return;
+  const SelState prev = *sv.st;  // from_list: says how long the list is
   const uint32_t k = sv.d.k;
   const int nchunks = sv.d.geom.nchunks;
 
@@ -777,12 +949,25 @@ k_pick0(SelParams p, LeaderArgs la) {
   uint32_t h[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) h[j] = 0u;
-  for (int r = 0; r < sv.htop_reps; ++r) {
-    const uint4 q = reinterpret_cast<const uint4*>(sv.htop + (size_t)r * kHistBins)[t];
-    h[0] += q.x;
-    h[1] += q.y;
-    h[2] += q.z;
-    h[3] += q.w;
+  if (sv.htop_reps == kHistReps) {  // sixteen loads in flight together
+    for (int r0 = 0; r0 < kHistReps; r0 += 16) {
+      uint4 q[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) q[r] = reinterpret_cast<const uint4*>(sv.htop + (size_t)(r0 + r) * kHistBins)[t];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        h[0] += q[r].x;
+        h[1] += q[r].y;
+        h[2] += q[r].z;
+        h[3] += q[r].w;
+      }
+    }
+  } else {
+    const uint4 q = reinterpret_cast<const uint4*>(sv.htop)[t];
+    h[0] = q.x;
+    h[1] = q.y;
+    h[2] = q.z;
+    h[3] = q.w;
   }
   part[t] = h[0] + h[1] + h[2] + h[3];
   __syncthreads();
@@ -800,16 +985,22 @@ k_pick0(SelParams p, LeaderArgs la) {
   for (int j = 0; j < 4; ++j) {
     if (sx[j] >= k && sx[j + 1] < k) {  // the suffix sums are non-increasing: one hit
       b0_sh = 4 * t + j;
-      SelState st;
+      SelState st{};
       st.lo = (uint32_t)(4 * t + j) << 19;
       st.hi = st.lo | 0x7ffffu;
       st.n_gt = sx[j + 1];
       st.need = k - sx[j + 1];
       st.cand = sx[j] - sx[j + 1];
       st.level = 1u;
-      st.compact_level = fits_list(st, sv.d.cap) ? 1u : 0u;
-      st.list_count = st.compact_level ? st.n_gt + st.cand : 0u;
-      for (int i = 0; i < 8; ++i) st.pad[i] = 0u;
+      if (p.from_list) {  // the list exists already and holds every key >= list_lo
+        st.compact_level = 1u;
+        st.use_mask = 1u;
+        st.list_lo = prev.list_lo;
+        st.list_count = prev.list_count;
+      } else {
+        st.compact_level = fits_list(st, sv.d.cap) ? 1u : 0u;
+        st.list_count = st.compact_level ? st.n_gt + st.cand : 0u;
+      }
       *sv.st = st;
     }
   }
@@ -819,6 +1010,7 @@ k_pick0(SelParams p, LeaderArgs la) {
     if (t == 0) atomicOr(p.err, kErrPick);
     return;
   }
+  if (p.from_list) return;
   // exclusive scan of the per-chunk survivor counts
   const uint32_t mine = (t < nchunks) ? sv.S[(size_t)t * kHistBins + b0] : 0u;
   part[t] = mine;
@@ -830,6 +1022,59 @@ k_pick0(SelParams p, LeaderArgs la) {
     __syncthreads();
   }
   if (t < nchunks) sv.chunk_off[t] = part[t] - mine;
+}
+
+// ---------------------------------------------------------------------------
+// k_pick_mask : first selection kernel after a fused pass that marked the keys
+// reaching a guessed bound.  One block of 1024 threads (flat selections only).
+// Optionally takes the leader first.  Adds up the per-chunk counts of marked
+// elements; if the bound holds at least k and at most `cap` keys, every marked
+// element will become a list entry (chunk offsets are written, the state stays
+// at level 0 with use_mask set); otherwise the state asks for the histogram of
+// every key (need_full).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_pick_mask(SelParams p, LeaderArgs la) {
+  __shared__ uint32_t part[1024];
+  __shared__ int lead_sh;
+  const int t = threadIdx.x;
+  if (t == 0) lead_sh = -1;
+  if (la.partials != nullptr) {
+    const int best = block_take_leader(la);
+    if (t == 0) lead_sh = best;
+  }
+  __syncthreads();
+  const SegView sv = seg_view(p, blockIdx.y, lead_sh);
+  const uint32_t k = sv.d.k;
+  const int nchunks = sv.d.geom.nchunks;
+  const uint32_t gkey = sv.ctrl[1];
+  const uint32_t mine = (t < nchunks) ? sv.mcount[t] : 0u;
+  part[t] = mine;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {  // inclusive prefix sums
+    const uint32_t v = (t >= off) ? part[t - off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  const uint32_t total = part[1023];
+  const bool ok = gkey != kNoGuess && total >= k && total <= sv.d.cap;
+  if (ok && t < nchunks) sv.chunk_off[t] = part[t] - mine;
+  if (t == 0) {
+    SelState st{};
+    if (ok) {
+      st.hi = kKeyMask;
+      st.need = k;
+      st.cand = total;
+      st.compact_level = 1u;
+      st.use_mask = 1u;
+      st.list_lo = gkey;
+      st.list_count = total;
+    } else {
+      st.need_full = 1u;
+    }
+    *sv.st = st;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -867,7 +1112,7 @@ k_compact1(SelParams p) {
   uint2* __restrict__ list = sv.list;
 
   const SelState st = *sv.st;
-  if (st.level != 1u || *p.err) return;
+  if (st.level != 1u || st.use_mask != 0u || *p.err) return;
   const bool write_out = st.compact_level == 1u;  // the level-1 survivors fit the list
   const uint32_t klo = st.lo, khi = st.hi;
   const float* __restrict__ xp = sv.x;
@@ -959,6 +1204,142 @@ k_compact1(SelParams p) {
   for (int b = tid; b < kHistBins; b += T) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&sv.hist1[b], v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_compact_mask : writes the survivor list from the bit mask the fused pass
+// left behind instead of re-reading the vector; one block of 1024 threads per
+// chunk, runs only if the state says use_mask.  Every marked element (key >=
+// list_lo) becomes a list entry, in ascending element order, starting at
+// chunk_off[c]; only the marked elements' values are fetched.  The top digits
+// of all entries are counted into the slot's partial whole-vector histograms
+// (copy c mod kHistReps), from which k_pick0 then takes the threshold digit.
+//   Per slab of 1024 mask rows (256 elements each), two steps.  First thread t
+//   owns row t: a block scan of the rows' popcounts gives the row's list
+//   offset, and the thread writes the indices of its marked elements into the
+//   list entries.  Then the block walks the slab's entries with one entry per
+//   thread, UB of them in flight, fetching the values to complete the entries.
+// ---------------------------------------------------------------------------
+template <int UB>
+__global__ void __launch_bounds__(1024)
+k_compact_mask(SelParams p) {
+  constexpr int T = 1024, WAVES = 16;
+  __shared__ uint32_t wtot[WAVES];
+  __shared__ uint32_t lh[kHistBins];
+
+  const SegView sv = seg_view(p, blockIdx.y);
+  const int c = blockIdx.x;
+  if (c >= sv.d.geom.nchunks) return;
+  const SelState st = *sv.st;
+  if (st.use_mask == 0u || sv.mask == nullptr || *p.err) return;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const uint32_t lane = lane_id();
+  const int64_t n = p.n;
+  const ChunkGeom geom = sv.d.geom;
+  const uint32_t cap = sv.d.cap;
+  const uint32_t list_lo = st.list_lo;
+  const float* __restrict__ xp = sv.x;
+  const uint64_t* __restrict__ mk = sv.mask;
+  uint2* list = sv.list;
+
+  for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
+  __syncthreads();
+
+  const int64_t c_begin = geom.chunk0 + (int64_t)c * geom.chunk_elems;  // a multiple of 256
+  int64_t c_end = c_begin + geom.chunk_elems;
+  if (c_end > n) c_end = n;
+  const int64_t n_vec = n & ~(int64_t)3;                      // marked elements end here
+  const int64_t v_end = c_end < n_vec ? c_end : n_vec;
+  const int64_t row_lo = c_begin >> 8;
+  const int64_t row_hi = (v_end + 255) >> 8;                  // exclusive
+
+  uint32_t run = sv.chunk_off[c];  // list position of the next entry of this chunk
+  for (int64_t slab = row_lo; slab < row_hi; slab += T) {
+    const int64_t row = slab + tid;
+    uint64_t m[4] = {0ull, 0ull, 0ull, 0ull};
+    if (row < row_hi) {
+      const uint4 lo2 = reinterpret_cast<const uint4*>(mk + row * 4)[0];
+      const uint4 hi2 = reinterpret_cast<const uint4*>(mk + row * 4)[1];
+      m[0] = ((uint64_t)lo2.y << 32) | lo2.x;
+      m[1] = ((uint64_t)lo2.w << 32) | lo2.z;
+      m[2] = ((uint64_t)hi2.y << 32) | hi2.x;
+      m[3] = ((uint64_t)hi2.w << 32) | hi2.z;
+    }
+    const uint32_t cnt = (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+    // exclusive prefix of cnt (<= 256) over the lanes and the wave total, from the bit planes of cnt
+    uint32_t before = 0u, wsum = 0u;
+#pragma unroll
+    for (int b = 0; b <= 8; ++b) {
+      const uint64_t plane = __ballot((cnt >> b) & 1u);
+      before += popc_lt(plane) << b;
+      wsum += (uint32_t)__popcll(plane) << b;
+    }
+    if (lane == 0) wtot[wave] = wsum;
+    __syncthreads();
+    uint32_t pos = run + before, total = 0u;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      const uint32_t wt = wtot[i];
+      if (i < wave) pos += wt;
+      total += wt;
+    }
+    // the row's marked elements in ascending order: by group, then by position in the group
+    uint64_t any = m[0] | m[1] | m[2] | m[3];
+    while (any) {
+      const int g = __builtin_ctzll(any);
+      const uint64_t bit = 1ull << g;
+      any &= ~bit;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (m[e] & bit) {
+          if (pos < cap) list[pos].x = (uint32_t)(row * 256 + 4 * g + e);
+          ++pos;
+        }
+      }
+    }
+    __threadfence_block();  // the indices are written before any thread of the block reads them
+    __syncthreads();
+    for (uint32_t e0 = (uint32_t)tid; e0 < total; e0 += T * UB) {
+      uint32_t j[UB], raw[UB];
+      bool ok[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const uint32_t e = e0 + (uint32_t)u * T;
+        ok[u] = e < total && run + e < cap;
+        j[u] = ok[u] ? list[run + e].x : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) raw[u] = __float_as_uint(xp[j[u]]);
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (ok[u]) {
+          list[run + e0 + (uint32_t)u * T].y = raw[u];
+          atomicAdd(&lh[(raw[u] & kKeyMask) >> 19], 1u);
+        }
+      }
+    }
+    run += total;
+  }
+  // the elements behind the last whole group of four are not in the mask
+  if (c_end == n && n_vec < n && tid == 0) {
+    for (int64_t j = n_vec; j < n; ++j) {
+      const uint32_t raw = __float_as_uint(xp[j]);
+      const uint32_t kk = raw & kKeyMask;
+      if (kk >= list_lo) {
+        atomicAdd(&lh[kk >> 19], 1u);
+        if (run < cap) list[run] = make_uint2((uint32_t)j, raw);
+        ++run;
+      }
+    }
+  }
+
+  __syncthreads();
+  uint32_t* __restrict__ htop = sv.htop + (size_t)(c % sv.htop_reps) * kHistBins;
+  for (int b = tid; b < kHistBins; b += T) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&htop[b], v);
   }
 }
 
@@ -1269,32 +1650,54 @@ k_compact(SelParams p, int level, int launch_id) {
 }
 
 // ---------------------------------------------------------------------------
-// k_list_hist : histogram of the last digit (7 bits) over the candidates in the
-// survivor list; runs only when the list was written at level 1 (digit 1 is
-// replayed from hist1 in the prologue).
+// k_list_hist : histogram of digit `digit` (1 or 2) over the candidates in the
+// survivor list; runs only when the list was written at level 1 or from the
+// mask.  Digit 1 is needed only for a list written from the mask (k_compact1
+// counts it on the way); for digit 2 the digit-1 pick is replayed from hist1 in
+// the prologue.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_list_hist(SelParams p) {
-  __shared__ uint32_t lh[128];
+k_list_hist(SelParams p, int digit) {
+  __shared__ uint32_t lh[kHistBins];
   __shared__ SelState st;
   __shared__ uint32_t pick_part[256];
   const SegView sv = seg_view(p, blockIdx.y);
-  if (sv.st->compact_level != 1u || *p.err) return;  // only a list written at level 1 still lacks digit 2
+  if (sv.st->compact_level != 1u || *p.err) return;
+  if (digit == 1 && sv.st->use_mask == 0u) return;
   const int tid = threadIdx.x;
   const uint32_t cnt = sv.st->list_count;
-  if ((uint64_t)blockIdx.x * 256u >= cnt) return;     // nothing of the list for this block
-  derive_state<256>(sv, st, 2, pick_part, p.err);
-  if (tid < 128) lh[tid] = 0u;
+  // 8192 entries per block and round; no more blocks than that needs
+  uint32_t nb = (cnt + 8191u) / 8192u;
+  if (nb > gridDim.x) nb = gridDim.x;
+  if (blockIdx.x >= nb) return;
+  if (digit == 2) {
+    derive_state<256>(sv, st, 2, pick_part, p.err);
+  } else {
+    if (tid == 0) st = *sv.st;
+    __syncthreads();
+  }
+  const int nbins = (int)digit_mask(digit) + 1;
+  for (int b = tid; b < nbins; b += 256) lh[b] = 0u;
   __syncthreads();
   const uint32_t klo = st.lo, khi = st.hi;
-  for (uint32_t q = blockIdx.x * 256u + tid; q < cnt; q += gridDim.x * 256u) {
-    const uint32_t key = sv.list[q].y & kKeyMask;
-    if (key >= klo && key <= khi) atomicAdd(&lh[key & 0x7fu], 1u);
+  const int sh = digit_shift(digit);
+  const uint32_t dm = digit_mask(digit);
+  for (uint64_t base = (uint64_t)blockIdx.x * 8192u; base < cnt; base += (uint64_t)nb * 8192u) {
+    uint32_t key[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const uint64_t q = base + (uint64_t)i * 256u + tid;
+      key[i] = q < cnt ? (sv.list[q].y & kKeyMask) : 0xffffffffu;  // the filler is above every range
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+      if (key[i] >= klo && key[i] <= khi) atomicAdd(&lh[(key[i] >> sh) & dm], 1u);
   }
   __syncthreads();
-  if (tid < 128) {
-    const uint32_t v = lh[tid];
-    if (v) atomicAdd(&sv.hist2[tid], v);
+  uint32_t* __restrict__ dst = digit == 1 ? sv.hist1 : sv.hist2;
+  for (int b = tid; b < nbins; b += 256) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&dst[b], v);
   }
 }
 
@@ -1485,7 +1888,7 @@ k_gather(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx, 
       }
     }
   }
-  sum[m] = s;
+  if (sum) sum[m] = s;
 }
 
 __global__ void __launch_bounds__(256)
