@@ -180,6 +180,10 @@ ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks)
   int64_t ce = (span + max_chunks - 1) / max_chunks;
   ce = (ce + kTile - 1) / kTile * kTile;
   if (ce < kTile) ce = kTile;
+  // chunks longer than one tile of the fused pass are whole tiles of it, so that only the last
+  // chunk of a vector has a ragged tile
+  constexpr int64_t pass_tile = (int64_t)kPassAThreads * kPassAU * 4;
+  if (ce > kTile) ce = (ce + pass_tile - 1) / pass_tile * pass_tile;
   g.chunk_elems = ce;
   g.nchunks = (int32_t)((span + ce - 1) / ce);
   if (g.nchunks < 1) g.nchunks = 1;

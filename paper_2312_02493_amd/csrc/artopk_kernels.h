@@ -362,11 +362,12 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     v4f a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      // groups outside the chunk re-read its last group (unused): no branch between the loads,
+      // so that all of them are in flight together
       const int64_t q = qw + lane + u * T;
-      if (FULL || q < q_hi) {
-        a[u] = load4<NT>(gp + 4 * q);
-        b[u] = load4<NT>(rp + 4 * q);
-      }
+      const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
+      a[u] = load4<NT>(gp + 4 * ql);
+      b[u] = load4<NT>(rp + 4 * ql);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {

@@ -53,7 +53,8 @@ def _run_steps(runner, gen, w, n, k, mode, steps, expect_mask, fixed_leader=0):
         info = runner.ctx.select_info()
         assert info["guessed"] == 1, info
         if expect_mask is not None:
-            assert info["from_mask"] == expect_mask, info
+            want_mask = expect_mask[step_no - 1] if isinstance(expect_mask, (list, tuple)) else expect_mask
+            assert info["from_mask"] == want_mask, (step_no, info)
         assert_step_matches(got, want, mode)
         res = want.residual
 
@@ -73,6 +74,29 @@ def test_guess_var_workers_of_different_scale(guess_on):
     k = wl.k(0.01)
     runner = GpuRunner(w, n, k)
     _run_steps(runner, lambda s, r: wl.gen(s, r), w, n, k, orc.MODE_VAR, 3, expect_mask=1)
+
+
+def test_guess_var_leader_changes_every_step(guess_on):
+    n, w = 600_000, 4
+    wl = inp.workload(1, n=n, w=w)
+    k = wl.k(0.01)
+    runner = GpuRunner(w, n, k)
+
+    def gen(step_no, r):
+        scale = np.float32(3.0 if r == (step_no * 3) % w else 1.0)
+        return wl.gen(step_no, r) * scale
+
+    _run_steps(runner, gen, w, n, k, orc.MODE_VAR, 4, expect_mask=1)
+
+
+def test_guess_sample_too_small_for_a_bound(guess_on):
+    # k so close to n / 32 that the wanted sample rank still fits, on a vector barely long enough
+    # to be sampled: exercises the route where a slot may end up without a bound
+    n, w = 16_384, 2
+    wl = inp.workload(1, n=n, w=w)
+    k = n // 32
+    runner = GpuRunner(w, n, k)
+    _run_steps(runner, lambda s, r: wl.gen(s, r), w, n, k, orc.MODE_STAR, 2, expect_mask=None)
 
 
 def test_guess_heavy_tails_fixed_leader(guess_on):
