@@ -2,19 +2,26 @@
 //
 // Kernels (in the order one step runs them):
 //   k_fill_zero      clears the per-call scratch (histograms, scan flags, ...)
+//   k_guess          (long flat vectors) samples g + residual and guesses a lower
+//                    bound on the key of the k-th largest magnitude
 //   k_pass_a         acc = g + residual in place, per-worker variance
-//                    partials, per-chunk 12-bit top-digit histograms of |acc|
-//   k_hist0          the same histograms alone (stand-alone select, segments)
+//                    partials, and either per-chunk 12-bit top-digit histograms
+//                    of |acc| or a bit mask of the keys reaching the guessed bound
+//   k_hist0          the same histograms alone (stand-alone select, segments,
+//                    after a guess that did not hold)
 //   k_stats          variance partials alone (stand-alone variance)
 //   k_leader         finishes the variances and takes the first argmax
 //   k_pick0          (flat VAR: finishes the variances, takes the leader;) finds the
 //                    threshold digit and every chunk's list offset
+//   k_pick_mask      the same first step when the fused pass left a mask: accepts
+//                    the guessed bound or asks for the histogram route
 //   k_compact1       ordered compaction of the leader's survivors, one block
 //                    per chunk, no inter-block dependency
+//   k_compact_mask   the survivor list written from the mask instead
 //   k_compact        ordered compaction with a decoupled look-back scan: the
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
-//   k_list_hist      last-digit histogram over the survivor list
+//   k_list_hist      digit histograms over the survivor list
 //   k_pass_rest      (leader known up front) EF add + gather + residual zeroing
 //                    of all other workers in one streaming pass
 //   k_sum_rows       ordered sum over the workers' gathered rows
@@ -26,7 +33,7 @@
 // order on keys is the order of |x|.  The radix digits are 12 + 12 + 7 bits.
 //
 // Chunks.  A vector range is cut into at most kMaxChunks contiguous chunks, each
-// a whole number of 4096-element tiles.  The histogram pass stores, per chunk,
+// a whole number of 8192-element tiles.  The histogram pass stores, per chunk,
 // the SUFFIX sums of its top-digit histogram: S[c][b] = number of keys of chunk
 // c whose top digit is >= b.  Once the threshold digit b0 is known, S[c][b0] is
 // exactly the number of survivors chunk c will emit, so an exclusive scan over
