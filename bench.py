@@ -38,9 +38,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, n, k, with_vals):
+def algorithmic_bytes(w, n, k, with_vals, g_bytes=4):
     """Bytes one step must move (fp32, 4-byte granularity for the k-sized terms)."""
-    pass_a = 12 * w * n                 # read g, read residual, write acc
+    pass_a = (8 + g_bytes) * w * n      # read g, read residual, write acc
     select = 4 * n                      # one re-read of the leader after the threshold digit is known
     update = 4 * n                      # dense update written once
     ksized = k * (8 * w + (4 * w if with_vals else 0) + 20)
@@ -62,7 +62,10 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     host = np.empty(wl.n, dtype=np.float32)
     for r in range(wl.w):
         wl.gen_into(host, 1, r, threads=args.gen_threads)
-        g.append(torch.from_numpy(host).to(dev))
+        t = torch.from_numpy(host).to(dev)
+        if args.g16:  # 16-bit gradient storage: rounded once here, outside the timed region
+            t = t.to(torch.bfloat16 if args.g16 == "bf16" else torch.float16)
+        g.append(t)
         res.append(torch.zeros(wl.n, dtype=torch.float32, device=dev))
         log(f"[bench]   worker {r} generated and uploaded ({time.perf_counter() - t0:.1f} s)")
     del host
@@ -73,9 +76,16 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     leader = torch.zeros(1, dtype=torch.int32, device=dev)
     var = torch.zeros(wl.w, dtype=torch.float64, device=dev)
 
+    g_bytes = 2 if args.g16 else 4
+    g_type = {None: pkg.ARTOPK_G_F32, "bf16": pkg.ARTOPK_G_BF16, "f16": pkg.ARTOPK_G_F16}[args.g16]
+
     def one(step_no):
-        ctx.artopk_step(g, res, k, mode, step_no, idx, summed, update, leader_out=leader, var_out=var,
-                        seg_off=seg_off, seg_k=seg_k)
+        if args.g16:
+            ctx.artopk_step_g16(g, g_type, res, k, mode, step_no, idx, summed, update, leader_out=leader,
+                                var_out=var, seg_off=seg_off, seg_k=seg_k)
+        else:
+            ctx.artopk_step(g, res, k, mode, step_no, idx, summed, update, leader_out=leader, var_out=var,
+                            seg_off=seg_off, seg_k=seg_k)
 
     step_no = 1
     for _ in range(warmup):
@@ -108,8 +118,8 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     ctx.status()
     ms_per_step = 1e3 * t_total / steps
     pa = sum(pass_a_ms) / len(pass_a_ms)
-    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False)
-    b_pass_a = 12 * dom_workers * wl.n
+    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes)
+    b_pass_a = (8 + g_bytes) * dom_workers * wl.n
     out = {
         "wl": wl, "k": k, "rho": rho, "ms_per_step": ms_per_step,
         "gelem_per_s": wl.w * wl.n / (ms_per_step * 1e-3) / 1e9,
@@ -162,6 +172,8 @@ def main():
     ap.add_argument("--rho", type=float, default=None)
     ap.add_argument("--gen-threads", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--g16", choices=["bf16", "f16"], default=None,
+                    help="store the gradients in 16 bits (artopk_step_g16); not the headline configuration")
     ap.add_argument("--also-c4", action="store_true", help="append the 138M workload's numbers under 'other'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the rocprofv3 "
@@ -206,7 +218,7 @@ def main():
 
     base = None if args.no_cpu_baseline else cpu_baseline(cfg, rho, inp)
 
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, rho))
+    traffic = None if args.g16 else MEASURED_TRAFFIC_BYTES.get((args.workload, rho))
     line = {
         "metric": "compressed gradient elements/s per AR-Topk step (1 GPU)",
         "value": round(r["gelem_per_s"], 3),
@@ -218,10 +230,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32" if not args.g16 else f"f32 (gradients stored as {args.g16})",
         "data": "synthetic (seeded recipe of the workload; step-1 gradients reused every step, residual carried)",
         "config": {"workload": wl0.name, "N": wl0.n, "W": wl0.w, "rho": rho, "k": r["k"],
-                   "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR"},
+                   "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR",
+                   **({"gradient_storage": args.g16} if args.g16 else {})},
         "roofline": {"bound": "hbm", "kernel": r["dom_name"], "achieved": round(r["pass_a_gbps"], 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r["pass_a_gbps"] / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": r["b_pass_a"],

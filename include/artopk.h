@@ -60,6 +60,9 @@ enum {
  * cost is W selections instead of one. */
 enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3 };
 
+/* Element type of the gradients handed to artopk_step_g16. */
+enum { ARTOPK_G_F32 = 0, ARTOPK_G_BF16 = 1, ARTOPK_G_F16 = 2 };
+
 #define ARTOPK_MAX_WORKERS 64
 
 /* Stages whose duration artopk_get_profile() reports (milliseconds).  With the
@@ -171,6 +174,24 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
                 int64_t k, int32_t mode, uint64_t step, int32_t fixed_leader,
                 int32_t* leader_out, double* var_out, int32_t* idx_out, float* vals_out,
                 float* sum_out, float* update_out);
+
+/*
+ * artopk_step for gradients stored in 16 bits (the residual, and everything
+ * derived from it, stays float32: the error-feedback state of Sec. II-C must
+ * not lose what compression leaves behind).  Each gradient value is widened
+ * exactly to float32 -- bfloat16: its bits become the upper half of the
+ * float32; float16: the IEEE conversion, subnormals included -- and the step is
+ * then the one artopk_step defines, bit for bit.  The fused pass reads 2 bytes
+ * per gradient element instead of 4.
+ *   g       host array of W device pointers, each N 16-bit elements, 8-byte aligned
+ *   g_type  ARTOPK_G_BF16 or ARTOPK_G_F16
+ * All other arguments, outputs and errors as for artopk_step.
+ */
+int artopk_step_g16(artopk_ctx* ctx, const void* const* g, int32_t g_type, float* const* residual,
+                    int32_t w, int64_t n, int32_t nseg, const int64_t* seg_off,
+                    const int64_t* seg_k, int64_t k, int32_t mode, uint64_t step,
+                    int32_t fixed_leader, int32_t* leader_out, double* var_out, int32_t* idx_out,
+                    float* vals_out, float* sum_out, float* update_out);
 
 /*
  * Every worker's own exact Top-k (Alg. 1 calls Topk on each worker before the

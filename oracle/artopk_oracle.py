@@ -18,6 +18,9 @@ definition:
                                     workers in rank order 0..W-1
 * dense update                   -- Alg. 1 (model update consumes g~ on the
                                     full parameter vector)
+* 16-bit gradient storage        -- not in the paper: a gradient stored as
+                                    bfloat16 / float16 is widened exactly to
+                                    float32 and the step above applies
 
 Readings taken where the paper leaves a choice open (each also listed in the
 design notes of the repository):
@@ -50,6 +53,25 @@ MODE_FIXED = 2
 MODE_VAR_TOPK = 3
 
 _MAG_MASK = np.uint32(0x7FFFFFFF)
+
+
+# --------------------------------------------------------------------------
+# Gradients stored in 16 bits: exact widening to float32 before anything else
+# --------------------------------------------------------------------------
+def widen_gradient(bits16: np.ndarray, kind: str) -> np.ndarray:
+    """float32 values of 16-bit gradient storage given as uint16 bit patterns.
+
+    'bf16': the 16 bits are the upper half of the float32 (sign, 8 exponent
+    bits, 7 mantissa bits), the lower half is zero.  'f16': IEEE binary16,
+    every value of which (subnormals included) is a float32 value; NumPy's
+    conversion is used as the step.
+    """
+    b = np.ascontiguousarray(bits16, dtype=np.uint16)
+    if kind == "bf16":
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    if kind == "f16":
+        return b.view(np.float16).astype(np.float32)
+    raise ValueError("kind must be 'bf16' or 'f16'")
 
 
 # --------------------------------------------------------------------------

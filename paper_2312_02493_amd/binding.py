@@ -13,13 +13,14 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK = 0, 1, 2, 3
+ARTOPK_G_F32, ARTOPK_G_BF16, ARTOPK_G_F16 = 0, 1, 2
 PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 
 _SYMBOLS = (
     "artopk_create", "artopk_destroy", "artopk_last_error", "artopk_status", "artopk_variance",
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
-    "artopk_apply_update", "artopk_topk_workers", "artopk_select_info",
+    "artopk_apply_update", "artopk_topk_workers", "artopk_select_info", "artopk_step_g16",
 )
 
 
@@ -60,6 +61,8 @@ def load_library():
     lib.artopk_gather_sum.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_scatter_residual.argtypes = [vp, vp, i32, i64, vp, i64, vp, vp]
     lib.artopk_step.argtypes = [vp, vp, vp, i32, i64, i32, vp, vp, i64, i32, u64, i32, vp, vp, vp, vp, vp, vp]
+    lib.artopk_step_g16.argtypes = [vp, vp, i32, vp, i32, i64, i32, vp, vp, i64, i32, u64, i32, vp, vp, vp, vp, vp,
+                                    vp]
     lib.artopk_topk_workers.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp, vp]
     lib.artopk_compression_gain.argtypes = [vp, vp, i32, i64, vp, i64, vp]
     lib.artopk_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, C.c_float]
@@ -186,3 +189,13 @@ class Context:
                                           _i64_array(seg_off), _i64_array(seg_k), k, mode, step, fixed_leader,
                                           _ptr(leader_out), _ptr(var_out), _ptr(idx_out), _ptr(vals_out),
                                           _ptr(sum_out), _ptr(update_out)))
+
+    def artopk_step_g16(self, g: Sequence, g_type: int, residual: Sequence, k: int, mode: int, step: int, idx_out,
+                        sum_out, update_out, vals_out=None, leader_out=None, var_out=None, fixed_leader: int = 0,
+                        seg_off=None, seg_k=None):
+        n = g[0].numel()
+        nseg = 1 if seg_off is None else len(seg_k)
+        self._check(self._lib.artopk_step_g16(self._h, _ptr_table(g), g_type, _ptr_table(residual), len(g), n, nseg,
+                                              _i64_array(seg_off), _i64_array(seg_k), k, mode, step, fixed_leader,
+                                              _ptr(leader_out), _ptr(var_out), _ptr(idx_out), _ptr(vals_out),
+                                              _ptr(sum_out), _ptr(update_out)))

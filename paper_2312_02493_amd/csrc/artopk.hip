@@ -79,6 +79,7 @@ struct artopk_ctx {
   Scratch s;
   // how the last step ran (artopk_select_info)
   int32_t last_guessed = 0, last_dom_workers = 0;
+  int g_type = ARTOPK_G_F32;  // element type of the gradients of the step being enqueued
   // descriptors of the last segmented layout uploaded to table_dev
   std::vector<int64_t> cached_off, cached_k;
   int64_t cached_n = -1;
@@ -124,11 +125,12 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_ptr_table(artopk_ctx* c, const float* const* tab, int32_t w, const char* name) {
+int check_ptr_table(artopk_ctx* c, const float* const* tab, int32_t w, const char* name, int align = 16) {
   if (!tab) return fail(c, ARTOPK_EINVAL, "%s is NULL", name);
   for (int i = 0; i < w; ++i) {
     if (!tab[i]) return fail(c, ARTOPK_EINVAL, "%s[%d] is NULL", name, i);
-    if (!aligned16(tab[i])) return fail(c, ARTOPK_EINVAL, "%s[%d] is not 16-byte aligned", name, i);
+    if (reinterpret_cast<uintptr_t>(tab[i]) % (uintptr_t)align)
+      return fail(c, ARTOPK_EINVAL, "%s[%d] is not %d-byte aligned", name, i, align);
   }
   return ARTOPK_OK;
 }
@@ -355,18 +357,29 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
 }
 
 // Launches the fused pass over grid.y workers with the wanted options.
-template <bool STATS, int HIST, bool MASK>
-void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
+template <bool STATS, int HIST, bool MASK, int GT>
+void launch_pass_a_g(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
                      const ChunkGeom& geom, int hist_worker) {
   Scratch& s = c->s;
   if (c->pass_a_nt)
-    hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, MASK, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, MASK, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
                        stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
                        s.partials);
   else
-    hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, MASK, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, MASK, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
                        stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
                        s.partials);
+}
+
+template <bool STATS, int HIST, bool MASK>
+void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
+                     const ChunkGeom& geom, int hist_worker) {
+  if (c->g_type == ARTOPK_G_BF16)
+    launch_pass_a_g<STATS, HIST, MASK, kGBF16>(c, stream, grid, g, r, n, geom, hist_worker);
+  else if (c->g_type == ARTOPK_G_F16)
+    launch_pass_a_g<STATS, HIST, MASK, kGF16>(c, stream, grid, g, r, n, geom, hist_worker);
+  else
+    launch_pass_a_g<STATS, HIST, MASK, kGF32>(c, stream, grid, g, r, n, geom, hist_worker);
 }
 
 void launch_pass_a(artopk_ctx* c, bool stats, int hist, bool mask, dim3 grid, const PtrTable& g, const PtrTable& r,
@@ -383,6 +396,27 @@ void launch_pass_a(artopk_ctx* c, bool stats, int hist, bool mask, dim3 grid, co
   PASS_A_CASE(true, 2, false);
   PASS_A_CASE(true, 2, true);
 #undef PASS_A_CASE
+}
+
+template <int GT>
+void launch_pass_rest_g(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
+                        const ChunkGeom& geom, const int32_t* idx, int64_t k, float* vals) {
+  if (c->pass_a_nt)
+    hipLaunchKernelGGL((k_pass_rest<true, GT, kPassRestThreads, kPassRestU>), grid, dim3(kPassRestThreads), 0, c->stream,
+                       g, r, w, leader, n, geom, idx, k, vals);
+  else
+    hipLaunchKernelGGL((k_pass_rest<false, GT, kPassRestThreads, kPassRestU>), grid, dim3(kPassRestThreads), 0, c->stream,
+                       g, r, w, leader, n, geom, idx, k, vals);
+}
+
+void launch_pass_rest(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
+                      const ChunkGeom& geom, const int32_t* idx, int64_t k, float* vals) {
+  if (c->g_type == ARTOPK_G_BF16)
+    launch_pass_rest_g<kGBF16>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
+  else if (c->g_type == ARTOPK_G_F16)
+    launch_pass_rest_g<kGF16>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
+  else
+    launch_pass_rest_g<kGF32>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
 }
 
 // Whether a flat step on n elements keeping k uses the sampled threshold guess.
@@ -410,8 +444,15 @@ GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k) {
 
 // Samples the first nvec vectors of (g + residual) into slots 0 .. nvec-1 (cleared beforehand).
 void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const PtrTable& res, int nvec) {
-  hipLaunchKernelGGL(k_guess, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs, gp.stride,
-                     gp.m_hi);
+  if (c->g_type == ARTOPK_G_BF16)
+    hipLaunchKernelGGL(k_guess<kGBF16>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+                       gp.stride, gp.m_hi);
+  else if (c->g_type == ARTOPK_G_F16)
+    hipLaunchKernelGGL(k_guess<kGF16>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+                       gp.stride, gp.m_hi);
+  else
+    hipLaunchKernelGGL(k_guess<kGF32>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+                       gp.stride, gp.m_hi);
 }
 
 // Top-k of every segment of the plan on the vector tab.p[*leader_dev]; the
@@ -842,13 +883,20 @@ int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_
   return ARTOPK_OK;
 }
 
-int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w, int64_t n,
-                int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t mode,
-                uint64_t step, int32_t fixed_leader, int32_t* leader_out, double* var_out, int32_t* idx_out,
-                float* vals_out, float* sum_out, float* update_out) {
+namespace {
+
+// One step; the g rows hold elements of type g_type (float32 rows are passed as they are, 16-bit
+// rows behind the same pointer type).
+int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* const* residual, int32_t w, int64_t n,
+              int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t mode,
+              uint64_t step, int32_t fixed_leader, int32_t* leader_out, double* var_out, int32_t* idx_out,
+              float* vals_out, float* sum_out, float* update_out) {
   int rc = check_common(ctx, w, n, k);
   if (rc) return rc;
-  if ((rc = check_ptr_table(ctx, g, w, "g"))) return rc;
+  if (g_type != ARTOPK_G_F32 && g_type != ARTOPK_G_BF16 && g_type != ARTOPK_G_F16)
+    return fail(ctx, ARTOPK_EINVAL, "unknown gradient element type %d", g_type);
+  ctx->g_type = g_type;
+  if ((rc = check_ptr_table(ctx, g, w, "g", g_type == ARTOPK_G_F32 ? 16 : 8))) return rc;
   if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
   if (!idx_out || !sum_out || !update_out) return fail(ctx, ARTOPK_EINVAL, "idx_out, sum_out or update_out is NULL");
   if (!aligned16(update_out)) return fail(ctx, ARTOPK_EINVAL, "update_out is not 16-byte aligned");
@@ -927,12 +975,7 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;
     if (rest > 0) {
-      if (ctx->pass_a_nt)
-        hipLaunchKernelGGL((k_pass_rest<true, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, rest), dim3(kPassRestThreads),
-                           0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
-      else
-        hipLaunchKernelGGL((k_pass_rest<false, kPassRestThreads, kPassRestU>), dim3(geom.nchunks, rest), dim3(kPassRestThreads),
-                           0, st, gt, rt, (int)w, L, n, geom, idx_out, k, vals);
+      launch_pass_rest(ctx, dim3(geom.nchunks, rest), gt, rt, (int)w, L, n, geom, idx_out, k, vals);
     }
     prof_mark(ctx, 3);
     const int kblocks = (int)((k + 255) / 256);
@@ -998,6 +1041,26 @@ int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, 
   if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
   prof_mark(ctx, 4);
   return ARTOPK_OK;
+}
+
+}  // namespace
+
+int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w, int64_t n,
+                int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t mode,
+                uint64_t step, int32_t fixed_leader, int32_t* leader_out, double* var_out, int32_t* idx_out,
+                float* vals_out, float* sum_out, float* update_out) {
+  return step_impl(ctx, g, ARTOPK_G_F32, residual, w, n, nseg, seg_off, seg_k, k, mode, step, fixed_leader,
+                   leader_out, var_out, idx_out, vals_out, sum_out, update_out);
+}
+
+int artopk_step_g16(artopk_ctx* ctx, const void* const* g, int32_t g_type, float* const* residual, int32_t w,
+                    int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k,
+                    int32_t mode, uint64_t step, int32_t fixed_leader, int32_t* leader_out, double* var_out,
+                    int32_t* idx_out, float* vals_out, float* sum_out, float* update_out) {
+  if (ctx && g_type != ARTOPK_G_BF16 && g_type != ARTOPK_G_F16)
+    return fail(ctx, ARTOPK_EINVAL, "artopk_step_g16 takes ARTOPK_G_BF16 or ARTOPK_G_F16 gradients");
+  return step_impl(ctx, reinterpret_cast<const float* const*>(g), g_type, residual, w, n, nseg, seg_off, seg_k, k,
+                   mode, step, fixed_leader, leader_out, var_out, idx_out, vals_out, sum_out, update_out);
 }
 
 }  // extern "C"

@@ -207,6 +207,37 @@ __device__ __forceinline__ void store4(float* p, v4f v) {
     *reinterpret_cast<v4f*>(p) = v;
 }
 
+// Gradient element types: float32, or 16 bits widened exactly to float32 before use
+// (bfloat16: the bits become the upper half of the float32; float16: hardware conversion).
+constexpr int kGF32 = 0, kGBF16 = 1, kGF16 = 2;
+
+template <int GT>
+__device__ __forceinline__ float widen16(uint32_t h) {  // h: the 16 bits in the low half
+  if (GT == kGBF16) return __uint_as_float(h << 16);
+  return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+
+// Four consecutive gradient elements starting at element index e (a multiple of 4).
+template <bool NT, int GT>
+__device__ __forceinline__ v4f load4g(const float* base, int64_t e) {
+  if (GT == kGF32) return load4<NT>(base + e);
+  typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+  const v2u* p = reinterpret_cast<const v2u*>(reinterpret_cast<const unsigned short*>(base) + e);
+  const v2u r = NT ? __builtin_nontemporal_load(p) : *p;
+  v4f v;
+  v.x = widen16<GT>(r.x & 0xffffu);
+  v.y = widen16<GT>(r.x >> 16);
+  v.z = widen16<GT>(r.y & 0xffffu);
+  v.w = widen16<GT>(r.y >> 16);
+  return v;
+}
+
+template <int GT>
+__device__ __forceinline__ float load1g(const float* base, int64_t e) {
+  if (GT == kGF32) return base[e];
+  return widen16<GT>(reinterpret_cast<const unsigned short*>(base)[e]);
+}
+
 // Adds the 4096-bin LDS histogram `lh` of a T-thread block to total[0..4096)
 // and writes its suffix sums to dst[0..4096).  `red` is T words of LDS.  All
 // threads of the block must call it after their last histogram update.
@@ -314,7 +345,7 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST, bool NT, bool MASK, int T, int U>
+template <bool STATS, int HIST, bool NT, bool MASK, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
          uint32_t* __restrict__ h_all, uint64_t* __restrict__ mask, int64_t mask_stride,
@@ -355,7 +386,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   }
 
   double cshift = 0.0, s = 0.0, ss = 0.0;
-  if (STATS) cshift = (double)gp[0];  // g is never written, so every block sees the same shift
+  if (STATS) cshift = (double)load1g<GT>(gp, 0);  // g is never written, so every block sees the same shift
 
   const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
   int64_t c_hi = c_lo + geom.chunk_elems;
@@ -373,7 +404,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       // so that all of them are in flight together
       const int64_t q = qw + lane + u * T;
       const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
-      a[u] = load4<NT>(gp + 4 * ql);
+      a[u] = load4g<NT, GT>(gp, 4 * ql);
       b[u] = load4<NT>(rp + 4 * ql);
     }
 #pragma unroll
@@ -429,7 +460,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (c_hi == n) {
     const int64_t j = (n >> 2) * 4 + tid;
     if (j < n) {
-      const float v = gp[j] + rp[j];
+      const float v = load1g<GT>(gp, j) + rp[j];
       rp[j] = v;
       if (STATS) {
         const double d = (double)v - cshift;
@@ -662,6 +693,7 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
 // than m_hi).  The bound is only a guess: whoever uses it checks that at least
 // k keys of the whole vector reach it.
 // ---------------------------------------------------------------------------
+template <int GT>
 __global__ void __launch_bounds__(256)
 k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_t stride, uint32_t m_hi) {
   __shared__ uint32_t lh[kHistBins];
@@ -677,11 +709,11 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
   __syncthreads();
   for (int r = blockIdx.x * 256 + tid; r < runs; r += gridDim.x * 256) {
     const int64_t e0 = ((int64_t)r * stride) & ~(int64_t)(kGuessRun - 1);
-    float4 a[kGuessRun / 4], b[kGuessRun / 4];
+    v4f a[kGuessRun / 4], b[kGuessRun / 4];
 #pragma unroll
     for (int i = 0; i < kGuessRun / 4; ++i) {
-      a[i] = *reinterpret_cast<const float4*>(gp + e0 + 4 * i);
-      b[i] = *reinterpret_cast<const float4*>(rp + e0 + 4 * i);
+      a[i] = load4g<false, GT>(gp, e0 + 4 * i);
+      b[i] = load4<false>(rp + e0 + 4 * i);
     }
 #pragma unroll
     for (int i = 0; i < kGuessRun / 4; ++i) {
@@ -1719,7 +1751,7 @@ k_list_hist(SelParams p, int digit) {
 // finds its first index with a T-way search; per tile of 16 T elements it marks
 // the kept positions in an LDS slot table while the tile's loads are in flight.
 // ---------------------------------------------------------------------------
-template <bool NT, int T, int U>
+template <bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkGeom geom,
             const int32_t* __restrict__ idx, int64_t k, float* __restrict__ vals) {
@@ -1777,7 +1809,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
     for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
       if (q < q_end) {
-        a[u] = load4<NT>(gp + 4 * q);
+        a[u] = load4g<NT, GT>(gp, 4 * q);
         b[u] = load4<NT>(rp + 4 * q);
       }
     }
@@ -1824,7 +1856,7 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
   if (c_hi == n) {
     const int64_t j = (n >> 2) * 4 + tid;
     if (j < n) {
-      float v = gp[j] + rp[j];
+      float v = load1g<GT>(gp, j) + rp[j];
       int64_t lo = 0, hi = k;  // binary search for j among the indices
       while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;

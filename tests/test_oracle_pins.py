@@ -366,3 +366,37 @@ def test_literal_alg1_leader_rule_hand_values():
     x = rng.standard_normal(12).astype(np.float32)
     best = max(float((x[list(s)].astype(np.float64) ** 2).sum()) for s in itertools.combinations(range(12), 4))
     assert orc.topk_sqnorm(x, orc.topk_indices(x, 4)) == pytest.approx(best, rel=1e-15)
+
+
+# --------------------------------------------------------------------------
+# 16-bit gradient storage: the widening is pinned by decoding the fields by hand
+# --------------------------------------------------------------------------
+def test_widen_f16_all_bit_patterns_against_field_decoding():
+    bits = np.arange(1 << 16, dtype=np.uint32)
+    sign = np.where(bits >> 15, -1.0, 1.0)
+    e = (bits >> 10) & 0x1F
+    m = (bits & 0x3FF).astype(np.float64)
+    normal = sign * np.ldexp(1.0 + m / 1024.0, e.astype(np.int64) - 15)
+    sub = sign * np.ldexp(m / 1024.0, -14)
+    want = np.where(e == 0, sub, normal)
+    got = orc.widen_gradient(bits.astype(np.uint16), "f16")
+    finite = e != 31
+    assert got.dtype == np.float32
+    assert np.array_equal(got[finite].astype(np.float64), want[finite])       # exact, subnormals included
+    assert np.array_equal(np.signbit(got[finite]), bits[finite] >> 15 == 1)   # -0.0 keeps its sign
+    inf = (e == 31) & (bits & 0x3FF == 0)
+    assert np.all(np.isinf(got[inf])) and np.array_equal(got[inf] < 0, bits[inf] >> 15 == 1)
+    assert np.all(np.isnan(got[(e == 31) & (bits & 0x3FF != 0)]))
+
+
+def test_widen_bf16_known_values_and_round_trip():
+    known = {0x3F80: 1.0, 0xC000: -2.0, 0x0000: 0.0, 0x3DCC: 0.099609375, 0x7F80: np.inf, 0xFF80: -np.inf,
+             0x0001: 2.0 ** -133, 0x0080: 2.0 ** -126, 0x7F7F: (2.0 - 2.0 ** -7) * 2.0 ** 127}
+    b = np.array(list(known), dtype=np.uint16)
+    got = orc.widen_gradient(b, "bf16")
+    assert got.dtype == np.float32
+    assert np.array_equal(got.astype(np.float64), np.array(list(known.values())))
+    every = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    wide = orc.widen_gradient(every, "bf16")
+    assert np.array_equal(wide.view(np.uint32) >> 16, every.astype(np.uint32))  # the bits are the upper half
+    assert np.all(wide.view(np.uint32) & 0xFFFF == 0)                             # nothing is invented below
