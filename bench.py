@@ -135,7 +135,7 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     return out
 
 
-def cpu_baseline(cfg, rho, inp, budget_s=20.0):
+def cpu_baseline(cfg, rho, inp, budget_s=15.0):
     """The oracle, as it stands, on a bounded sample of the workload (one thread)."""
     import numpy as np
     from oracle import artopk_oracle as orc
@@ -149,7 +149,7 @@ def cpu_baseline(cfg, rho, inp, budget_s=20.0):
     mode = orc.MODE_STAR if wl.mode == inp.MODE_STAR else orc.MODE_VAR
     res = [np.zeros(n, np.float32) for _ in range(wl.w)]
     steps, spent = 0, 0.0
-    while spent < budget_s and steps < 4:
+    while spent < budget_s and steps < 12:
         g = [wl.gen(steps + 1, r) for r in range(wl.w)]
         t0 = time.perf_counter()
         out = orc.step(g, res, k, mode, step_no=steps + 1, seg_off=seg_off, seg_k=seg_k)
