@@ -168,6 +168,12 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  *   vals_out     device W*k float32 (may be NULL)
  *   sum_out      device k float32
  *   update_out   device N float32
+ * The call only enqueues kernels on the context's stream: it allocates nothing,
+ * issues no memset and does not synchronise (a segmented layout is copied to
+ * the device the first time it is seen, so make one call with it before
+ * recording).  With stage timing off it can therefore be recorded into a HIP
+ * graph and replayed; in VAR mode the leader is taken on the device at every
+ * replay, in STAR / FIXED mode the recorded leader is replayed.
  */
 int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w,
                 int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k,

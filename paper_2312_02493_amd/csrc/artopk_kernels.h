@@ -190,7 +190,7 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
   return v;  // the total, in every lane
 }
 
-constexpr int kTile = 8192;       // chunk granularity = compaction tile (two pass-A tiles)
+constexpr int kTile = 8192;       // chunk granularity (a quarter of a tile of the fused pass)
 constexpr int kMaxChunks = 1024;  // chunks per vector range
 
 typedef float v4f __attribute__((ext_vector_type(4)));

@@ -438,3 +438,62 @@ def test_bucketed_layout_16mi_elements():
     want = orc.step(g, res, k, orc.MODE_STAR, step_no=1, seg_off=off, seg_k=ks)
     got = run.step(k, orc.MODE_STAR, 1, seg_off=off, seg_k=ks)
     assert_step_matches(got, want, orc.MODE_STAR)
+
+
+def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
+    """One VAR step recorded into a HIP graph (through torch's capture) and replayed three times,
+    with host work and synchronisation between the replays: every replay must be the next step
+    of the oracle, residual carried.  The step allocates nothing, clears its scratch with a fill
+    kernel (no memset nodes) and takes every data-dependent decision on the device."""
+    import torch
+    import paper_2312_02493_amd as lib
+
+    n, w = 200_003, 4
+    wl = inp.workload(2, n=n, w=w)
+    k = wl.k(0.01)
+    dev = torch.device("cuda:0")
+    side = torch.cuda.Stream()
+    g_np = [wl.gen(1, r) for r in range(w)]
+    with torch.cuda.stream(side):
+        ctx = lib.Context(w, n, k, 1, stream=side.cuda_stream)
+        g = [torch.from_numpy(a).to(dev) for a in g_np]
+        res = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(w)]
+        idx = torch.empty(k, dtype=torch.int32, device=dev)
+        summed = torch.empty(k, dtype=torch.float32, device=dev)
+        update = torch.empty(n, dtype=torch.float32, device=dev)
+        vals = torch.empty(w * k, dtype=torch.float32, device=dev)
+        leader = torch.zeros(1, dtype=torch.int32, device=dev)
+        var = torch.zeros(w, dtype=torch.float64, device=dev)
+
+        def step():
+            ctx.artopk_step(g, res, k, lib.ARTOPK_VAR, 1, idx, summed, update, vals_out=vals, leader_out=leader,
+                            var_out=var)
+
+        step()  # warm-up outside the capture
+        side.synchronize()
+        ctx.status()
+        for r in res:
+            r.zero_()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for r in res:
+            r.zero_()
+        side.synchronize()
+
+        want_res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+        for replay in range(3):
+            want = orc.step(g_np, want_res, k, orc.MODE_VAR, step_no=1)
+            assert top_two_gap(want.variances) > 1e-4
+            graph.replay()
+            side.synchronize()
+            ctx.status()
+            got = {
+                "leader": int(leader.item()), "var": var.cpu().numpy().copy(), "idx": idx.cpu().numpy(),
+                "sum": summed.cpu().numpy(), "update": update.cpu().numpy(),
+                "residual": [r.cpu().numpy() for r in res], "vals": vals.cpu().numpy().reshape(w, k),
+            }
+            assert_step_matches(got, want, orc.MODE_VAR)
+            want_res = want.residual
+            _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
