@@ -114,6 +114,10 @@ def test_c4_full_star(rho):
         run.load_g(g)
         _say(f"c4 rho={rho} step={s}: inputs ready")
         res = _check_step_by_definition(f"c4 rho={rho} step={s}", run, g, res, k, orc.MODE_STAR, s)
+        # vectors this long take the sampled-guess route whenever 32 k <= N, and on this data the guess holds
+        info = run.ctx.select_info()
+        assert info["guessed"] == (1 if 32 * k <= wl.n else 0), info
+        assert info["from_mask"] == info["guessed"], info
 
 
 def test_c5_full_var():
@@ -132,3 +136,5 @@ def test_c5_full_var():
             g.append(x)
             _say(f"c5 step={s}: worker {r} generated, var={variances[-1]:.6e}")
         res = _check_step_by_definition(f"c5 step={s}", run, g, res, k, orc.MODE_VAR, s, variances=variances)
+        info = run.ctx.select_info()
+        assert info["guessed"] == 1 and info["from_mask"] == 1, info
