@@ -329,6 +329,7 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.list = s.list;
   p.idx_out = idx_out;
   p.vals_row = vals_row;
+  p.zero_vec = nullptr;
   p.err = s.err_dev;
   p.table = pl.use_table ? s.table_dev : nullptr;
   p.slot_by_leader = slot_by_leader;
@@ -462,10 +463,11 @@ void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const 
 // the leader's values at the selected indices.
 int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
                    bool hist_ready, int slot_by_leader, float* vals_row = nullptr,
-                   const LeaderArgs* leader_args = nullptr, bool guessed = false) {
+                   const LeaderArgs* leader_args = nullptr, bool guessed = false, float* zero_vec = nullptr) {
   hipStream_t st = c->stream;
   const unsigned nseg = (unsigned)pl.nseg;
   SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0, hist_ready);
+  p.zero_vec = zero_vec;
   LeaderArgs la{};
   if (leader_args) la = *leader_args;
 
@@ -528,25 +530,19 @@ int enqueue_gather(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t n, con
   return ARTOPK_OK;
 }
 
-// zero_vec != nullptr: the pass also zeroes that vector at the indices.
 int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* idx, const float* sum,
-                        int64_t k, float* zero_vec = nullptr) {
+                        int64_t k) {
   const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
   int blocks = (int)(nchunk < (int64_t)c->num_cu * 4 ? nchunk : (int64_t)c->num_cu * 4);
   if (blocks < 1) blocks = 1;
   // kept entries expected per 8192-element chunk decide how many are fetched per round
   const double per_chunk = (double)k / (double)n * kFillChunk;
-  if (zero_vec) {
-    if (per_chunk <= 400.0)
-      hipLaunchKernelGGL((k_update_fill<2, true>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
-    else
-      hipLaunchKernelGGL((k_update_fill<4, true>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
-  } else if (per_chunk <= 160.0) {
-    hipLaunchKernelGGL((k_update_fill<1, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+  if (per_chunk <= 160.0) {
+    hipLaunchKernelGGL((k_update_fill<1>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
   } else if (per_chunk <= 400.0) {
-    hipLaunchKernelGGL((k_update_fill<2, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+    hipLaunchKernelGGL((k_update_fill<2>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
   } else {
-    hipLaunchKernelGGL((k_update_fill<4, false>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k, zero_vec);
+    hipLaunchKernelGGL((k_update_fill<4>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
   }
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
@@ -970,7 +966,11 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     if (gp.on) enqueue_guess(ctx, gp, g1t, r1t, 1);
     launch_pass_a(ctx, false, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
     prof_mark(ctx, 1);
-    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on)))
+    // With many kept entries (32 k >= N) the leader's residual is zeroed inside the selection, which
+    // has its values in registers anyway; with few, by scattered 4-byte writes afterwards.
+    const bool zero_in_select = (double)k * 32.0 >= (double)n;
+    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on,
+                             zero_in_select ? residual[L] : nullptr)))
       return rc;
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;
@@ -979,15 +979,11 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     }
     prof_mark(ctx, 3);
     const int kblocks = (int)((k + 255) / 256);
-    // zeroing the leader's residual: scattered 4-byte writes while the kept entries are sparse,
-    // otherwise inside the streaming pass that writes the update
-    const bool zero_in_fill = (double)k * 32.0 >= (double)n;
-    if (!zero_in_fill)
+    if (!zero_in_select)
       hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
     hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
-    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k, zero_in_fill ? residual[L] : nullptr)))
-      return rc;
+    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
     prof_mark(ctx, 4);
     return ARTOPK_OK;
   }

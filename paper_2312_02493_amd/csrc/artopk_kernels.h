@@ -137,6 +137,7 @@ struct SelParams {
   uint2* list;             // survivor lists
   int32_t* idx_out;
   float* vals_row;         // leader's row of gathered values, or nullptr
+  float* zero_vec;         // the selected vector itself if its kept entries are to become +0.0 on the way, or nullptr
   uint32_t* err;
   const SegDesc* table;
   int32_t slot_by_leader;  // S slot = index of the selected vector (histograms of all workers exist) or 0
@@ -1154,6 +1155,7 @@ k_compact1(SelParams p) {
   const SelState st = *sv.st;
   if (st.level != 1u || st.use_mask != 0u || *p.err) return;
   const bool write_out = st.compact_level == 1u;  // the level-1 survivors fit the list
+  const bool zero_out = write_out && p.zero_vec != nullptr;
   const uint32_t klo = st.lo, khi = st.hi;
   const float* __restrict__ xp = sv.x;
 
@@ -1235,6 +1237,32 @@ k_compact1(SelParams p) {
           // (index, raw bits): the sign travels with the survivor
           if (write_out && pos < cap) list[pos] = make_uint2((uint32_t)(j0 + e), raw[e]);
           ++pos;
+        }
+      }
+      // Keys above the threshold digit are kept whatever the later digits say: if asked to, put
+      // +0.0 there now, while the group is in registers (the list carries the values on).  Only
+      // when the list is written here, because the deeper array passes would re-read the vector.
+      if (zero_out) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          uint32_t z[4];
+          uint32_t hit = 0u;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bool a = ((own >> (4 * r + e)) & 1u) && (raw[4 * r + e] & kKeyMask) > khi;
+            z[e] = a ? 0u : raw[4 * r + e];
+            hit |= a ? (1u << e) : 0u;
+          }
+          if (hit) {  // (rewriting the lane's whole 64 bytes instead was measured slower)
+            const int64_t j = j0 + 4 * r;
+            if (clean && j + 4 <= n_vec) {
+              *reinterpret_cast<uint4*>(p.zero_vec + j) = make_uint4(z[0], z[1], z[2], z[3]);
+            } else {  // at a chunk's edge a group may hold a neighbour's elements
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if ((hit >> e) & 1u) p.zero_vec[j + e] = 0.0f;
+            }
+          }
         }
       }
     }
@@ -1497,6 +1525,10 @@ k_compact(SelParams p, int level, int launch_id) {
   const int wave = tid >> 6;
   const uint32_t lane = lane_id();
 
+  // With zeroing on the way: the level-1 pass zeroed the keys above its range if it wrote the
+  // list (stored compact_level 1); the final pass zeroes the kept rest, or all of them otherwise.
+  float* __restrict__ zero_vec = LIST ? p.zero_vec : nullptr;
+  const uint32_t zero_below = (stp->compact_level == 1u && stp->use_mask == 0u) ? stp->hi : kKeyMask;
   // the level-1 survivors fitted the list: the deeper array passes have nothing to do
   if (!LIST && (stp->compact_level == 1u || *err)) return;
   if (LIST && *err) return;
@@ -1665,6 +1697,11 @@ k_compact(SelParams p, int level, int launch_id) {
                   if (pos < k_out) {
                     idx_out[pos] = pay[LIST ? r : 0][e];
                     if (vals_row) vals_row[pos] = __uint_as_float(key[r][e]);
+                    // kept entries that the level-1 pass has not already put to +0.0
+                    if (zero_vec && ((key[r][e] & kKeyMask) <= zero_below)) {
+                      const int32_t zi = pay[LIST ? r : 0][e];
+                      if (zi >= 0 && (int64_t)zi < p.n) zero_vec[zi] = 0.0f;
+                    }
                   }
                 }
               }
@@ -1949,18 +1986,15 @@ k_zero_at(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx,
 // element written exactly once.  Block b owns a contiguous run of 8192-element
 // chunks; it locates its first index with a 256-way search, then per chunk
 // builds the chunk in LDS (BATCH x 256 index/sum pairs per round, fetched ahead
-// of the buffer clear) and streams it out.  With ZERO the same pass also sets
-// zero_vec[idx[m]] = +0.0 (used for the leader's residual when so many entries
-// are kept that scattered 4-byte writes cost more than streaming the vector).
+// of the buffer clear) and streams it out.
 // ---------------------------------------------------------------------------
 constexpr int kFillChunk = 8192;
 
-template <int BATCH, bool ZERO>
+template <int BATCH>
 __global__ void __launch_bounds__(256)
 k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
-              const float* __restrict__ sum, int64_t k, float* __restrict__ zero_vec) {
+              const float* __restrict__ sum, int64_t k) {
   __shared__ __attribute__((aligned(16))) float buf[kFillChunk];
-  __shared__ uint32_t mark[ZERO ? kFillChunk / 32 : 1];  // one bit per element of the chunk: is it a kept index
   __shared__ int64_t s_lo, s_hi;
   const int tid = threadIdx.x;
   const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
@@ -2019,16 +2053,7 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
         sb[j] = sum[p];
       }
     }
-    float4 zv[ZERO ? kGroups : 1];  // this chunk of the vector whose kept positions are zeroed
-    if (ZERO) {
-#pragma unroll
-      for (int j = 0; j < kGroups; ++j) {
-        const int64_t i = tid + j * 256;
-        if (i < len4) zv[ZERO ? j : 0] = reinterpret_cast<const float4*>(zero_vec + lo)[i];
-      }
-    }
     for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (ZERO) mark[ZERO ? tid : 0] = 0u;  // kFillChunk / 32 == 256 words
     __syncthreads();
     while (true) {
       int cnt = 0;
@@ -2038,7 +2063,6 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
         if (in && ib[j] >= lo) {  // ib >= lo always holds for ascending idx
           const int64_t off = ib[j] - lo;
           buf[off] = sb[j];
-          if (ZERO) atomicOr(&mark[ZERO ? (off >> 5) : 0], 1u << (off & 31));
         }
         cnt += __syncthreads_count(in);
       }
@@ -2060,25 +2084,9 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
 #pragma unroll
     for (int j = 0; j < kGroups; ++j) {
       const int64_t i = tid + j * 256;
-      if (i < len4) {
-        reinterpret_cast<float4*>(up)[i] = b4[i];
-        if (ZERO) {
-          const uint32_t bits4 = (mark[ZERO ? (i >> 3) : 0] >> ((i & 7) * 4)) & 0xfu;  // elements 4i .. 4i+3
-          if (bits4) {
-            float4 z = zv[ZERO ? j : 0];
-            if (bits4 & 1u) z.x = 0.0f;
-            if (bits4 & 2u) z.y = 0.0f;
-            if (bits4 & 4u) z.z = 0.0f;
-            if (bits4 & 8u) z.w = 0.0f;
-            reinterpret_cast<float4*>(zero_vec + lo)[i] = z;
-          }
-        }
-      }
+      if (i < len4) reinterpret_cast<float4*>(up)[i] = b4[i];
     }
-    for (int64_t i = len4 * 4 + tid; i < len; i += 256) {  // ragged end of the vector
-      up[i] = buf[i];
-      if (ZERO && ((mark[ZERO ? (i >> 5) : 0] >> (i & 31)) & 1u)) zero_vec[lo + i] = 0.0f;
-    }
+    for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];  // ragged end of the vector
     __syncthreads();
   }
 }
