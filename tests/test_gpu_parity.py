@@ -497,3 +497,31 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
             assert_step_matches(got, want, orc.MODE_VAR)
             want_res = want.residual
             _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
+
+
+@pytest.mark.parametrize("case", ["all_equal", "two_valued", "normal"])
+def test_many_kept_entries_zeroed_inside_the_selection(case):
+    """With 32 k >= N and the leader known up front the leader's residual is zeroed inside the
+    selection kernels.  all_equal: the level-1 survivors overflow the list, so the deeper array
+    passes run and the final pass does all the zeroing; two_valued: a large tie class sits in the
+    threshold digit; normal: the usual split between the two kernels."""
+    n, w, k = 200_003, 3, 50_000
+    rng = np.random.default_rng(5)
+
+    def gen():
+        if case == "all_equal":
+            return np.full(n, -0.5, dtype=np.float32)
+        if case == "two_valued":
+            x = np.where(rng.random(n) < 0.2, 2.0, 1.0).astype(np.float32)   # 40 k large, 10 k of the ties kept
+            return x * np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+        return rng.standard_normal(n).astype(np.float32)
+
+    run = GpuRunner(w, n, k)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (1, 2, 3):
+        g = [gen() for _ in range(w)]
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
+        run.load_g(g)
+        got = run.step(k, orc.MODE_STAR, step_no)
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
