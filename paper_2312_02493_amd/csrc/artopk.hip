@@ -966,11 +966,10 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     if (gp.on) enqueue_guess(ctx, gp, g1t, r1t, 1);
     launch_pass_a(ctx, false, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
     prof_mark(ctx, 1);
-    // With many kept entries (32 k >= N) the leader's residual is zeroed inside the selection, which
-    // has its values in registers anyway; with few, by scattered 4-byte writes afterwards.
-    const bool zero_in_select = (double)k * 32.0 >= (double)n;
+    // The leader's residual is zeroed inside the selection: its kernels have the kept values in
+    // registers (level-1 compaction) or write the kept indices anyway (final list pass).
     if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on,
-                             zero_in_select ? residual[L] : nullptr)))
+                             residual[L])))
       return rc;
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;
@@ -978,9 +977,6 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
       launch_pass_rest(ctx, dim3(geom.nchunks, rest), gt, rt, (int)w, L, n, geom, idx_out, k, vals);
     }
     prof_mark(ctx, 3);
-    const int kblocks = (int)((k + 255) / 256);
-    if (!zero_in_select)
-      hipLaunchKernelGGL(k_zero_at, dim3(kblocks), dim3(256), 0, st, r1t, 1, n, idx_out, k, s.err_dev);
     hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
     if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
