@@ -61,15 +61,20 @@ def test_c3_full_segmented():
         res = want.residual
 
 
-def _check_step_by_definition(tag, run, g, res_prev, k, mode, step_no, want_leader=None, variances=None):
-    """One GPU step verified against the definitions, O(N) per worker."""
+def _check_step_by_definition(tag, run, g, res_prev, k, mode, step_no, want_leader=None, variances=None, g16=None):
+    """One GPU step verified against the definitions, O(N) per worker.  g16 = (tensors, type) runs
+    the 16-bit entry point on those gradient tensors; g then holds their widened values."""
     torch = run.torch
     w, n = run.w, run.n
     run.idx.fill_(-1)
     run.sum.fill_(float("nan"))
     run.update.fill_(float("nan"))
-    run.ctx.artopk_step(run.g, run.res, k, mode, step_no, run.idx, run.sum, run.update, vals_out=run.vals,
-                        leader_out=run.leader, var_out=run.var)
+    if g16 is not None:
+        run.ctx.artopk_step_g16(g16[0], g16[1], run.res, k, mode, step_no, run.idx, run.sum, run.update,
+                                vals_out=run.vals, leader_out=run.leader, var_out=run.var)
+    else:
+        run.ctx.artopk_step(run.g, run.res, k, mode, step_no, run.idx, run.sum, run.update, vals_out=run.vals,
+                            leader_out=run.leader, var_out=run.var)
     run.ctx.status()
     torch.cuda.synchronize()
     leader = int(run.leader.item())
@@ -118,6 +123,29 @@ def test_c4_full_star(rho):
         info = run.ctx.select_info()
         assert info["guessed"] == (1 if 32 * k <= wl.n else 0), info
         assert info["from_mask"] == info["guessed"], info
+
+
+def test_c4_full_star_bfloat16_gradients():
+    """The 138 M x 4 workload with the gradients stored as bfloat16 (upper halves of the float32 draws)."""
+    import paper_2312_02493_amd as lib
+
+    wl = inp.workload(4)
+    k = wl.k(0.01)
+    run = GpuRunner(wl.w, wl.n, k)
+    t = run.torch
+    g16 = [t.empty(wl.n, dtype=t.bfloat16, device=run.dev) for _ in range(wl.w)]
+    res = [np.zeros(wl.n, np.float32) for _ in range(wl.w)]
+    for s in (1, 2):
+        g = []
+        for r in range(wl.w):
+            b = (wl.gen(s, r, threads=THREADS).view(np.uint32) >> 16).astype(np.uint16)
+            g16[r].copy_(t.from_numpy(b.view(np.int16)).view(t.bfloat16))
+            g.append(orc.widen_gradient(b, "bf16"))
+        _say(f"c4 bf16 step={s}: inputs ready")
+        res = _check_step_by_definition(f"c4 bf16 step={s}", run, g, res, k, orc.MODE_STAR, s,
+                                        g16=(g16, lib.ARTOPK_G_BF16))
+        info = run.ctx.select_info()
+        assert info["guessed"] == 1 and info["from_mask"] == 1, info
 
 
 def test_c5_full_var():
