@@ -85,7 +85,18 @@ enum {
  * Create a context bound to `hip_stream` (a hipStream_t; NULL = the default
  * stream) on the current device and allocate its scratch for problems up to
  * max_w workers, max_n elements, max_k kept entries and max_segments segments.
- * *out is set only on success.
+ * *out is set only on success.  Scratch size: about 16.3 MiB per worker plus
+ * 8 (max_k + max_n / 8) bytes of survivor list plus 8 max_w max_k bytes, and,
+ * for max_n >= 2^25, max_n / 8 bytes per worker of survivor bit masks.
+ *
+ * Three environment variables, read here, switch between routes that give
+ * identical results (for tests and measurements; unset = the defaults):
+ *   ARTOPK_GUESS_MIN_N   shortest vector that gets the sampled threshold guess
+ *                        before its fused pass (default 33554432)
+ *   ARTOPK_LEADER_FIRST  0: also with a leader known up front, run the fused
+ *                        pass over all workers first and gather entry by entry
+ *   ARTOPK_PASS_A_NT     0: ordinary instead of non-temporal loads and stores
+ *                        in the streaming passes
  */
 int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
                   int32_t max_segments, void* hip_stream);

@@ -118,7 +118,7 @@ struct SegDesc {
   int32_t vec;         // which vector of the pointer table to select on; -1 = the leader's
 };
 
-// Everything the selection kernels need; blockIdx.y (blockIdx.z in k_reduce_hist)
+// Everything the selection kernels need; blockIdx.y
 // picks the segment.  With table == nullptr there is one segment, `one`.
 struct SelParams {
   PtrTable tab;
