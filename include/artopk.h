@@ -57,8 +57,10 @@ enum {
  * the population variance of the dense error-fed vector.  VAR_TOPK is Alg. 1
  * taken literally: every worker runs Top-k on its own vector and the worker
  * whose k values have the largest squared norm leads (first maximum); its
- * cost is W selections instead of one. */
-enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3 };
+ * cost is W selections instead of one.  VAR_G reads "largest gradient
+ * variance" as the variance of the raw gradient g_w, before the residual is
+ * added; everything else is as in VAR (same kernels, same cost). */
+enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3, ARTOPK_VAR_G = 4 };
 
 /* Element type of the gradients handed to artopk_step_g16. */
 enum { ARTOPK_G_F32 = 0, ARTOPK_G_BF16 = 1, ARTOPK_G_F16 = 2 };

@@ -26,7 +26,9 @@ Readings taken where the paper leaves a choice open (each also listed in the
 design notes of the repository):
 
 * "variance" of a worker is the population variance (divide by n) of its
-  dense error-fed vector, accumulated in float64 in two passes;
+  dense error-fed vector, accumulated in float64 in two passes (MODE_VAR_G
+  takes it of the raw gradient instead; MODE_VAR_TOPK is Alg. 1's printed
+  squared norm of the worker's own Top-k values);
 * Top-k ranks by |value| using the raw 31 magnitude bits, ties go to the
   lowest index, and the k indices are reported in ascending order;
 * the VAR leader is the first (lowest-rank) worker attaining the maximum;
@@ -51,6 +53,7 @@ MODE_STAR = 0
 MODE_VAR = 1
 MODE_FIXED = 2
 MODE_VAR_TOPK = 3
+MODE_VAR_G = 4
 
 _MAG_MASK = np.uint32(0x7FFFFFFF)
 
@@ -244,6 +247,11 @@ def step(g: Sequence[np.ndarray], residual: Sequence[np.ndarray], k: int,
         out.leader = leader_star(step_no, w)
     elif mode == MODE_VAR:
         out.variances = [variance(a) for a in accs]
+        out.leader = leader_var(out.variances)
+    elif mode == MODE_VAR_G:
+        # the other reading of "largest gradient variance" (Sec. III-B): the variance of the
+        # raw gradient, before the residual is added
+        out.variances = [variance(np.asarray(x, dtype=np.float32)) for x in g]
         out.leader = leader_var(out.variances)
     elif mode == MODE_VAR_TOPK:
         # Alg. 1 as printed: Topk on every worker first, the squared norm of each

@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK = 0, 1, 2, 3
+ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK, ARTOPK_VAR_G = 0, 1, 2, 3, 4
 ARTOPK_G_F32, ARTOPK_G_BF16, ARTOPK_G_F16 = 0, 1, 2
 PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 

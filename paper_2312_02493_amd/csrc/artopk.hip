@@ -358,7 +358,7 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
 }
 
 // Launches the fused pass over grid.y workers with the wanted options.
-template <bool STATS, int HIST, bool MASK, int GT>
+template <int STATS, int HIST, bool MASK, int GT>
 void launch_pass_a_g(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
                      const ChunkGeom& geom, int hist_worker) {
   Scratch& s = c->s;
@@ -372,7 +372,7 @@ void launch_pass_a_g(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTabl
                        s.partials);
 }
 
-template <bool STATS, int HIST, bool MASK>
+template <int STATS, int HIST, bool MASK>
 void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
                      const ChunkGeom& geom, int hist_worker) {
   if (c->g_type == ARTOPK_G_BF16)
@@ -383,19 +383,22 @@ void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTabl
     launch_pass_a_g<STATS, HIST, MASK, kGF32>(c, stream, grid, g, r, n, geom, hist_worker);
 }
 
-void launch_pass_a(artopk_ctx* c, bool stats, int hist, bool mask, dim3 grid, const PtrTable& g, const PtrTable& r,
+void launch_pass_a(artopk_ctx* c, int stats, int hist, bool mask, dim3 grid, const PtrTable& g, const PtrTable& r,
                    int64_t n, const ChunkGeom& geom, int hist_worker, hipStream_t stream = nullptr) {
   if (stream == nullptr) stream = c->stream;
 #define PASS_A_CASE(S_, H_, M_)                     \
   if (stats == S_ && hist == H_ && mask == M_)      \
   return launch_pass_a_t<S_, H_, M_>(c, stream, grid, g, r, n, geom, hist_worker)
-  PASS_A_CASE(false, 0, false);
-  PASS_A_CASE(false, 1, false);
-  PASS_A_CASE(false, 1, true);
-  PASS_A_CASE(false, 2, false);
-  PASS_A_CASE(true, 0, false);
-  PASS_A_CASE(true, 2, false);
-  PASS_A_CASE(true, 2, true);
+  PASS_A_CASE(0, 0, false);
+  PASS_A_CASE(0, 1, false);
+  PASS_A_CASE(0, 1, true);
+  PASS_A_CASE(0, 2, false);
+  PASS_A_CASE(1, 0, false);
+  PASS_A_CASE(1, 2, false);
+  PASS_A_CASE(1, 2, true);
+  PASS_A_CASE(2, 0, false);
+  PASS_A_CASE(2, 2, false);
+  PASS_A_CASE(2, 2, true);
 #undef PASS_A_CASE
 }
 
@@ -906,7 +909,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   } else if (mode == ARTOPK_VAR_TOPK) {
     if (seg_off != nullptr && nseg > 1)
       return fail(ctx, ARTOPK_EINVAL, "ARTOPK_VAR_TOPK is defined for the unsegmented selection only");
-  } else if (mode != ARTOPK_VAR) {
+  } else if (mode != ARTOPK_VAR && mode != ARTOPK_VAR_G) {
     return fail(ctx, ARTOPK_EINVAL, "unknown mode %d", mode);
   }
 
@@ -934,7 +937,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_begin(ctx);
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, *pl, (int)w))) return rc;
-    launch_pass_a(ctx, false, 2, false, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
+    launch_pass_a(ctx, 0, 2, false, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
     prof_mark(ctx, 1);
     if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
@@ -947,7 +950,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     return ARTOPK_OK;
   }
 
-  if (mode != ARTOPK_VAR && !segmented && ctx->leader_first) {
+  if (mode != ARTOPK_VAR && mode != ARTOPK_VAR_G && !segmented && ctx->leader_first) {
     // The leader is known up front: run its pass and the selection first, then
     // stream over the other workers once, gathering and zeroing on the way.
     const int L = leader_host;
@@ -964,7 +967,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     ctx->last_guessed = gp.on ? 1 : 0;
     ctx->last_dom_workers = w > 1 ? w - 1 : 1;
     if (gp.on) enqueue_guess(ctx, gp, g1t, r1t, 1);
-    launch_pass_a(ctx, false, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
+    launch_pass_a(ctx, 0, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
     prof_mark(ctx, 1);
     // The leader's residual is zeroed inside the selection: its kernels have the kept values in
     // registers (level-1 compaction) or write the kept indices anyway (final list pass).
@@ -989,18 +992,20 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   prof_begin(ctx);
   prof_mark(ctx, 0);
   // the flat select reuses the histograms pass A builds; segments build their own afterwards
-  if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : (mode == ARTOPK_VAR ? (int)w : 1)))) return rc;
+  if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : ((mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) ? (int)w : 1))))
+    return rc;
   int slot_by_leader = 0;
   LeaderArgs leader_args{};
   GuessPlan gp;
-  if (mode == ARTOPK_VAR) {
+  if (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) {
+    const int stats = mode == ARTOPK_VAR_G ? 2 : 1;  // variance of the raw gradient, or of g + residual
     if (segmented) {
-      launch_pass_a(ctx, true, 0, false, grid, gt, rt, n, geom, -1);
+      launch_pass_a(ctx, stats, 0, false, grid, gt, rt, n, geom, -1);
     } else {
       gp = plan_guess(ctx, n, k);
       ctx->last_guessed = gp.on ? 1 : 0;
       if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
-      launch_pass_a(ctx, true, 2, gp.on, grid, gt, rt, n, geom, -1);
+      launch_pass_a(ctx, stats, 2, gp.on, grid, gt, rt, n, geom, -1);
       slot_by_leader = 1;
     }
     prof_mark(ctx, 1);
@@ -1018,7 +1023,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
       leader_args.leader_out = leader_out;
     }
   } else {
-    launch_pass_a(ctx, false, segmented ? 0 : 1, false, grid, gt, rt, n, geom, leader_host);
+    launch_pass_a(ctx, 0, segmented ? 0 : 1, false, grid, gt, rt, n, geom, leader_host);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
   }

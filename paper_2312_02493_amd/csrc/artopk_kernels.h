@@ -340,13 +340,14 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 //         every row of 64 float4 groups four 64-bit words are written: word e,
 //         bit l <=> element 4 (64 row + l) + e is marked.  The n mod 4 elements
 //         behind the last whole group are counted but have no mask bit.
-//   Variance partials use the shift c_w = g_w[0]: per block the sums of
-//   (acc - c_w) and (acc - c_w)^2 in float64, written to partials[w][c][0..1].
+//   STATS: 0 none, 1 variance partials of acc, 2 of the raw gradient g.  They
+//   use the shift c_w = g_w[0]: per block the sums of (x - c_w) and (x - c_w)^2
+//   in float64, written to partials[w][c][0..1].
 //   NT: non-temporal loads of g and stores of acc.
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <bool STATS, int HIST, bool NT, bool MASK, int GT, int T, int U>
+template <int STATS, int HIST, bool NT, bool MASK, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
          uint32_t* __restrict__ h_all, uint64_t* __restrict__ mask, int64_t mask_stride,
@@ -420,8 +421,9 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
         v.w = a[u].w + b[u].w;
         store4<NT>(rp + 4 * q, v);
         if (STATS) {
-          double d0 = (double)v.x - cshift, d1 = (double)v.y - cshift, d2 = (double)v.z - cshift,
-                 d3 = (double)v.w - cshift;
+          const v4f t = STATS == 2 ? a[u] : v;  // the raw gradient, or the error-fed value
+          double d0 = (double)t.x - cshift, d1 = (double)t.y - cshift, d2 = (double)t.z - cshift,
+                 d3 = (double)t.w - cshift;
           s += (d0 + d1) + (d2 + d3);
           ss = fma(d0, d0, ss);
           ss = fma(d1, d1, ss);
@@ -461,10 +463,11 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (c_hi == n) {
     const int64_t j = (n >> 2) * 4 + tid;
     if (j < n) {
-      const float v = load1g<GT>(gp, j) + rp[j];
+      const float gj = load1g<GT>(gp, j);
+      const float v = gj + rp[j];
       rp[j] = v;
       if (STATS) {
-        const double d = (double)v - cshift;
+        const double d = (double)(STATS == 2 ? gj : v) - cshift;
         s += d;
         ss = fma(d, d, ss);
       }

@@ -66,7 +66,7 @@ class GpuRunner:
 def assert_step_matches(got, want: "orc.StepResult", mode, var_rtol=1e-5):
     """Bit-exact comparison of one GPU step with the oracle's."""
     assert got["leader"] == want.leader, (got["leader"], want.leader, got["var"], want.variances)
-    if mode == orc.MODE_VAR:
+    if mode in (orc.MODE_VAR, orc.MODE_VAR_G):
         ref = np.asarray(want.variances)
         # variance within 1e-5 relative (both sides fp64; the GPU sums in one shifted pass)
         np.testing.assert_allclose(got["var"], ref, rtol=var_rtol, atol=0.0)

@@ -525,3 +525,38 @@ def test_many_kept_entries_zeroed_inside_the_selection(case):
         got = run.step(k, orc.MODE_STAR, step_no)
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
+
+
+@pytest.mark.parametrize("layout", ["flat", "segmented", "flat_guess"])
+def test_leader_by_variance_of_the_raw_gradient(layout, monkeypatch):
+    """Mode VAR_G: the leader is the worker whose raw gradient varies most (the other reading of
+    Sec. III-B's "largest gradient variance").  Gradient scales rotate over the steps while the
+    residuals go stale, so the raw-gradient rule and the error-fed rule disagree on the way."""
+    if layout == "flat_guess":
+        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    n, w = 120_001, 4
+    wl = inp.workload(1, n=n, w=w)
+    seg_off = seg_k = None
+    k = wl.k(0.01)
+    if layout == "segmented":
+        seg_off = np.array([0, 30_000, 30_007, 90_000, n], dtype=np.int64)
+        seg_k = np.array([300, 3, 600, 301], dtype=np.int64)
+        k = int(seg_k.sum())
+    run = GpuRunner(w, n, k, 1 if seg_k is None else len(seg_k))
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    res[2] = wl.gen(99, 2) * np.float32(6.0)  # worker 2 starts with a large stale residual
+    run.load_res(res)
+    disagreements = 0
+    for step_no in range(1, 6):
+        g = [wl.gen(step_no, r) * np.float32(1.0 + 0.5 * ((r + step_no) % w)) for r in range(w)]
+        want = orc.step(g, res, k, orc.MODE_VAR_G, step_no=step_no, seg_off=seg_off, seg_k=seg_k)
+        other = orc.step(g, res, k, orc.MODE_VAR, step_no=step_no, seg_off=seg_off, seg_k=seg_k)
+        disagreements += int(want.leader != other.leader)
+        assert top_two_gap(want.variances) > 1e-4
+        run.load_g(g)
+        got = run.step(k, orc.MODE_VAR_G, step_no,
+                       seg_off=None if seg_off is None else [int(v) for v in seg_off],
+                       seg_k=None if seg_k is None else [int(v) for v in seg_k])
+        assert_step_matches(got, want, orc.MODE_VAR_G)
+        res = want.residual
+    assert disagreements >= 1

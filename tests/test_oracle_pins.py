@@ -400,3 +400,18 @@ def test_widen_bf16_known_values_and_round_trip():
     wide = orc.widen_gradient(every, "bf16")
     assert np.array_equal(wide.view(np.uint32) >> 16, every.astype(np.uint32))  # the bits are the upper half
     assert np.all(wide.view(np.uint32) & 0xFFFF == 0)                             # nothing is invented below
+
+
+def test_raw_gradient_variance_rule_differs_from_the_error_fed_one():
+    # worker 0: small gradient, large stale residual; worker 1: larger gradient, no residual.
+    # The error-fed vector of worker 0 varies more, the raw gradient of worker 1 does.
+    g = [np.array([0.1, -0.1, 0.1, -0.1], np.float32), np.array([1.0, -1.0, 1.0, -1.0], np.float32)]
+    res = [np.array([5.0, -5.0, 0.0, 0.0], np.float32), np.zeros(4, np.float32)]
+    a = orc.step(g, res, 1, orc.MODE_VAR)
+    b = orc.step(g, res, 1, orc.MODE_VAR_G)
+    assert a.leader == 0 and b.leader == 1
+    # population variances by hand: g0 -> 0.01, g1 -> 1 (float32 0.1 is not exact, hence the tolerance)
+    assert abs(b.variances[0] - 0.01) < 1e-8 and b.variances[1] == 1.0
+    # everything after the leader choice is the same machinery: index of the largest |acc| of the leader
+    assert list(a.idx) == [0] and list(b.idx) == [0]
+    assert a.sum[0] == np.float32(np.float32(0.1) + np.float32(5.0)) + np.float32(1.0)
