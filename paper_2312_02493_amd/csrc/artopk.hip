@@ -393,6 +393,7 @@ void launch_pass_a(artopk_ctx* c, int stats, int hist, bool mask, dim3 grid, con
   PASS_A_CASE(0, 1, false);
   PASS_A_CASE(0, 1, true);
   PASS_A_CASE(0, 2, false);
+  PASS_A_CASE(0, 2, true);
   PASS_A_CASE(1, 0, false);
   PASS_A_CASE(1, 2, false);
   PASS_A_CASE(1, 2, true);
@@ -556,14 +557,15 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
 // argmax (first maximum) goes to leader_dev and, if given, argmax_out.  With hist_ready the
 // per-chunk histograms of all workers are already in S (pass A with histograms for every worker).
 int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t n, int64_t k, int32_t* idx_rows,
-                         float* val_rows, double* sqnorm_out, int32_t* argmax_out, bool hist_ready) {
+                         float* val_rows, double* sqnorm_out, int32_t* argmax_out, bool hist_ready,
+                         bool guessed = false) {
   Scratch& s = c->s;
   for (int32_t r = 0; r < w; ++r) {
     const Plan pl = flat_plan(c, n, k, r);
     int rc = enqueue_clear(c, pl, 0);
     if (rc) return rc;
     if ((rc = enqueue_select(c, pl, tab, n, idx_rows + (size_t)r * (size_t)k, hist_ready, 1,
-                             val_rows + (size_t)r * (size_t)k)))
+                             val_rows + (size_t)r * (size_t)k, nullptr, guessed)))
       return rc;
   }
   PtrTable vtab;
@@ -937,9 +939,14 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_begin(ctx);
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, *pl, (int)w))) return rc;
-    launch_pass_a(ctx, 0, 2, false, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
+    // every worker selects on its own vector: on long vectors every worker gets a guessed bound and
+    // leaves a mask, as under the variance rule
+    const GuessPlan gp = plan_guess(ctx, n, k);
+    ctx->last_guessed = gp.on ? 1 : 0;
+    if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
+    launch_pass_a(ctx, 0, 2, gp.on, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
     prof_mark(ctx, 1);
-    if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true))) return rc;
+    if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true, gp.on))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
                        idx_out);
     prof_mark(ctx, 2);

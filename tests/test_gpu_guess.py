@@ -196,3 +196,13 @@ def test_guess_is_off_for_short_vectors_by_default():
     runner.load_g(g)
     runner.step(k, orc.MODE_STAR, 1)
     assert runner.ctx.select_info()["guessed"] == 0
+
+
+def test_guess_literal_leader_rule_every_worker_selects_from_its_mask(guess_on):
+    """Alg. 1 as printed (every worker runs Top-k, the largest squared norm of the own k values
+    leads) on the guess route: every worker's list comes from its own mask."""
+    n, w = 400_003, 5
+    wl = inp.workload(2, n=n, w=w)
+    k = wl.k(0.01)
+    runner = GpuRunner(w, n, k)
+    _run_steps(runner, lambda s, r: wl.gen(s, r), w, n, k, orc.MODE_VAR_TOPK, 3, expect_mask=1)
