@@ -68,3 +68,50 @@ def test_random_problem(seed, monkeypatch):
                        seg_k=None if seg_k is None else [int(v) for v in seg_k])
         assert_step_matches(got, want, mode)
         res = want.residual
+
+
+def test_one_context_reused_for_problems_of_many_shapes(monkeypatch):
+    """A single context sized for the largest problem runs a sequence of smaller and larger ones
+    (other N, W, k, leader rule, segment layout, route): nothing a call leaves in the scratch may
+    leak into the next."""
+    import torch
+    import paper_2312_02493_amd as lib
+
+    monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    max_w, max_n, max_seg = 6, 300_007, 8
+    dev = torch.device("cuda:0")
+    ctx = lib.Context(max_w, max_n, max_n, max_seg)
+    gbuf = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(max_w)]
+    rbuf = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(max_w)]
+    idx = torch.empty(max_n, dtype=torch.int32, device=dev)
+    summed = torch.empty(max_n, dtype=torch.float32, device=dev)
+    update = torch.empty(max_n, dtype=torch.float32, device=dev)
+    vals = torch.empty(max_w * max_n, dtype=torch.float32, device=dev)
+    leader = torch.zeros(1, dtype=torch.int32, device=dev)
+    var = torch.zeros(max_w, dtype=torch.float64, device=dev)
+    for seed in range(24):
+        rng, n, w, mode, kind, k, seg_off, seg_k = _problem(seed * 2 + (seed % 3 == 0))
+        g = [(_values(rng, n, kind) * np.float32(1.0 + 0.3 * r)) for r in range(w)]
+        res = [(_values(rng, n, 0) * np.float32(0.1)) for _ in range(w)]
+        fixed = int(rng.integers(0, w))
+        want = orc.step(g, res, k, mode, step_no=seed, fixed_leader=fixed, seg_off=seg_off, seg_k=seg_k)
+        if mode == orc.MODE_VAR and w > 1 and top_two_gap(want.variances) <= 1e-4:
+            continue
+        for r in range(w):
+            gbuf[r][:n].copy_(torch.from_numpy(g[r]))
+            rbuf[r][:n].copy_(torch.from_numpy(res[r]))
+        idx.fill_(-1)
+        summed.fill_(float("nan"))
+        update.fill_(float("nan"))
+        ctx.artopk_step([t[:n] for t in gbuf[:w]], [t[:n] for t in rbuf[:w]], k, mode, seed, idx[:k], summed[:k],
+                        update[:n], vals_out=vals[: w * k], leader_out=leader, var_out=var[:w], fixed_leader=fixed,
+                        seg_off=None if seg_off is None else [int(v) for v in seg_off],
+                        seg_k=None if seg_k is None else [int(v) for v in seg_k])
+        ctx.status()
+        got = {
+            "leader": int(leader.item()), "var": var[:w].cpu().numpy().copy(), "idx": idx[:k].cpu().numpy(),
+            "sum": summed[:k].cpu().numpy(), "update": update[:n].cpu().numpy(),
+            "residual": [t[:n].cpu().numpy() for t in rbuf[:w]],
+            "vals": vals[: w * k].cpu().numpy().reshape(w, k),
+        }
+        assert_step_matches(got, want, mode)
