@@ -486,14 +486,14 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
     SelParams pf = p;
     pf.h_all = nullptr;
     pf.only_if_need_full = 1;
-    hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, pf);
+    hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, pf);
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pf, LeaderArgs{});
     hipLaunchKernelGGL((k_compact_mask<4>), dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
     SelParams pl0 = p;
     pl0.from_list = 1;
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pl0, LeaderArgs{});
   } else {
-    if (!hist_ready) hipLaunchKernelGGL(k_hist0, dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+    if (!hist_ready) hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
   }
   // 4 waves, 16 consecutive elements per lane: best of the shapes measured on the 138 M and 1 G workloads

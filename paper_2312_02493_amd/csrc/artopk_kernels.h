@@ -772,21 +772,23 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
 
 // ---------------------------------------------------------------------------
 // k_hist0 : per-chunk top-digit suffix histograms of |x[e_lo .. e_hi)| for the
-// leader's vector.  grid = (max chunks of a segment, segments), block = 256.
+// leader's vector.  grid = (max chunks of a segment, segments), block = T (1024:
+// there are at most about a thousand blocks, so a block must keep many loads in flight).
 // Whole aligned float4 groups are read where they lie inside the array, single
 // elements at its ragged end; elements outside the chunk are masked out.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+template <int T>
+__global__ void __launch_bounds__(T)
 k_hist0(SelParams p) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
-  __shared__ uint32_t red_u[256];
+  __shared__ uint32_t red_u[T];
   const SegView sv = seg_view(p, blockIdx.y);
   const int c = blockIdx.x;
   if (c >= sv.d.geom.nchunks) return;
   if (p.only_if_need_full && sv.st->need_full == 0u) return;
   const int tid = threadIdx.x;
   const float* __restrict__ xp = sv.x;
-  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
   __syncthreads();
   int64_t cs = sv.d.geom.chunk0 + (int64_t)c * sv.d.geom.chunk_elems;
   int64_t ce = cs + sv.d.geom.chunk_elems;
@@ -795,13 +797,13 @@ k_hist0(SelParams p) {
   const int64_t n_vec = p.n & ~(int64_t)3;
   const int64_t q_lo = cs >> 2;
   const int64_t q_hi = (ce + 3) >> 2;  // exclusive
-  for (int64_t q0 = q_lo + tid; q0 < q_hi; q0 += 256 * 4) {
+  for (int64_t q0 = q_lo + tid; q0 < q_hi; q0 += T * 4) {
     uint4 v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // whole groups inside the array are read as one vector
-      const int64_t j = (q0 + u * 256) << 2;
+      const int64_t j = (q0 + u * T) << 2;
       v[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (q0 + u * 256 < q_hi) {
+      if (q0 + u * T < q_hi) {
         if (j + 4 <= n_vec) {
           v[u] = *reinterpret_cast<const uint4*>(xp + j);
         } else {
@@ -814,8 +816,8 @@ k_hist0(SelParams p) {
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t j = (q0 + u * 256) << 2;
-      if (q0 + u * 256 < q_hi) {
+      const int64_t j = (q0 + u * T) << 2;
+      if (q0 + u * T < q_hi) {
         const uint32_t kk[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -823,7 +825,7 @@ k_hist0(SelParams p) {
       }
     }
   }
-  flush_suffix_hist<256>(lh, red_u, sv.S + (size_t)c * kHistBins, sv.htop);
+  flush_suffix_hist<T>(lh, red_u, sv.S + (size_t)c * kHistBins, sv.htop);
 }
 
 // ---------------------------------------------------------------------------
