@@ -87,7 +87,9 @@ enum {
  * Create a context bound to `hip_stream` (a hipStream_t; NULL = the default
  * stream) on the current device and allocate its scratch for problems up to
  * max_w workers, max_n elements, max_k kept entries and max_segments segments.
- * *out is set only on success.  Scratch size: about 16.3 MiB per worker plus
+ * *out is set only on success.  A context serialises nothing by itself: calls
+ * on one context must not overlap (its scratch is shared between them), and
+ * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.3 MiB per worker plus
  * 8 (max_k + max_n / 8) bytes of survivor list plus 8 max_w max_k bytes, and,
  * for max_n >= 2^25, max_n / 8 bytes per worker of survivor bit masks.
  *
