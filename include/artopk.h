@@ -90,7 +90,7 @@ enum {
  * *out is set only on success.  A context serialises nothing by itself: calls
  * on one context must not overlap (its scratch is shared between them), and
  * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.3 MiB per worker plus
- * 8 (max_k + max_n / 8) bytes of survivor list plus 8 max_w max_k bytes, and,
+ * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes, and,
  * for max_n >= 2^25, max_n / 8 bytes per worker of survivor bit masks.
  *
  * Three environment variables, read here, switch between routes that give
@@ -273,7 +273,8 @@ int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count);
  *   [1] 1 if the survivor list was then written from the fused pass' bit mask
  *       (0 with [0] = 1: the guess did not hold and the full route was taken)
  *   [2] entries in the survivor list
- *   [3] radix level at which the list was written (1..3)
+ *   [3] 1 if the list was written after the first radix digit (or from the
+ *       mask), 0 if that did not fit and the deeper array passes wrote it
  *   [4] workers the dominant streaming kernel covered (W, or W-1 when the
  *       leader is known up front)
  * Flat (one-segment) steps only; segmented steps report [0] = [1] = 0.

@@ -502,11 +502,15 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   // The remaining kernels take tiles from a counter (or stride over the list), so any grid works:
   // about two blocks per compute unit over all segments together.
   const int64_t per_seg = ((int64_t)c->num_cu * 2 + nseg - 1) / nseg;
-  // deeper array passes: they run only for segments whose level-1 survivors did not fit the list
-  int cblocks = (int)(pl.max_tiles < per_seg ? pl.max_tiles : per_seg);
-  if (cblocks < 1) cblocks = 1;
-  hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
-  hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 1);
+  // deeper array passes: they run only for segments whose level-1 survivors did not fit the list,
+  // which cannot happen if the list takes the whole range
+  const bool always_fits = nseg == 1 && (int64_t)pl.desc[0].cap >= pl.desc[0].e_hi - pl.desc[0].e_lo;
+  if (!always_fits) {
+    int cblocks = (int)(pl.max_tiles < per_seg ? pl.max_tiles : per_seg);
+    if (cblocks < 1) cblocks = 1;
+    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
+    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 1);
+  }
 
   int64_t lblocks = (pl.max_cap + 256 * 16 - 1) / (256 * 16);
   if (lblocks > per_seg * 2) lblocks = per_seg * 2;
@@ -615,8 +619,10 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
 
   Scratch& s = c->s;
   // list capacity: every key above the range (< k of them) plus a generous share of candidates
+  // (vectors of up to 4 Mi elements fit the list whole: their selection never needs the deeper
+  // array passes, which are then not even launched)
   int64_t cand_share = max_n / 8;
-  if (cand_share < 65536) cand_share = 65536;
+  if (cand_share < ((int64_t)1 << 22)) cand_share = (int64_t)1 << 22;
   int64_t cap = max_k + cand_share;
   if (cap > max_n) cap = max_n;
   s.cap = (uint32_t)cap;

@@ -1074,8 +1074,8 @@ k_pick0(SelParams p, LeaderArgs la) {
 // k_pick_mask : first selection kernel after a fused pass that marked the keys
 // reaching a guessed bound.  One block of 1024 threads (flat selections only).
 // Optionally takes the leader first.  Adds up the per-chunk counts of marked
-// elements; if the bound holds at least k and at most `cap` keys, every marked
-// element will become a list entry (chunk offsets are written, the state stays
+// elements; if the bound holds at least k and at most min(cap, k + n/8) keys, every
+// marked element will become a list entry (chunk offsets are written, the state stays
 // at level 0 with use_mask set); otherwise the state asks for the histogram of
 // every key (need_full).
 // ---------------------------------------------------------------------------
@@ -1104,7 +1104,12 @@ k_pick_mask(SelParams p, LeaderArgs la) {
     __syncthreads();
   }
   const uint32_t total = part[1023];
-  const bool ok = gkey != kNoGuess && total >= k && total <= sv.d.cap;
+  // accepted if the bound holds at least k keys and not more than the list takes; a list far
+  // longer than k (beyond k + n/8) is not worth fetching entry by entry either
+  const uint64_t span = (uint64_t)(sv.d.e_hi - sv.d.e_lo);
+  uint64_t limit = (uint64_t)k + (span >> 3);
+  if (limit > sv.d.cap) limit = sv.d.cap;
+  const bool ok = gkey != kNoGuess && total >= k && total <= limit;
   if (ok && t < nchunks) sv.chunk_off[t] = part[t] - mine;
   if (t == 0) {
     SelState st{};

@@ -560,3 +560,29 @@ def test_leader_by_variance_of_the_raw_gradient(layout, monkeypatch):
         assert_step_matches(got, want, orc.MODE_VAR_G)
         res = want.residual
     assert disagreements >= 1
+
+
+@pytest.mark.parametrize("case", ["all_equal", "two_valued_many_ties"])
+def test_deeper_array_passes_on_a_long_degenerate_vector(case):
+    """Vectors short enough to fit the survivor list whole never take the deeper array passes, so
+    they are exercised here on a vector of 5 M elements whose level-1 survivors overflow the list."""
+    n, w, k = 5_000_003, 2, 60_000
+    rng = np.random.default_rng(77)
+
+    def gen():
+        if case == "all_equal":
+            return np.full(n, 0.75, dtype=np.float32)
+        x = np.where(rng.random(n) < 0.004, 3.0, 1.0).astype(np.float32)  # ~20 k large, 40 k of 4.98 M ties kept
+        return x * np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+
+    run = GpuRunner(w, n, k)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (1, 2):
+        g = [gen() for _ in range(w)]
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
+        run.load_g(g)
+        got = run.step(k, orc.MODE_STAR, step_no)
+        if step_no == 1:  # (at step 2 the residual has split the tie class and the list fits again)
+            assert run.ctx.select_info()["list_level"] == 0   # the deeper array passes wrote the list
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
