@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 1 GiB
 # device copy (profiles/artopk_step_<workload>_rho<rho>.md); None where it was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5", 0.001): 97160.0e6,   # k_pass_a, all 8 workers: 64.0 GB fetched + 33.2 GB written (1 GB of it bit masks)
-    ("c4", 0.01): 5033.1e6,     # k_pass_rest, 3 workers: 3.36 GB fetched + 1.68 GB written
+    ("c5", 0.001): 97159.3e6,   # k_pass_a, all 8 workers: 64.0 GB fetched + 33.2 GB written (1 GB of it bit masks)
+    ("c4", 0.01): 5029.0e6,     # k_pass_rest, 3 workers: 3.36 GB fetched + 1.68 GB written
 }
 
 
