@@ -115,3 +115,21 @@ def test_one_context_reused_for_problems_of_many_shapes(monkeypatch):
             "vals": vals[: w * k].cpu().numpy().reshape(w, k),
         }
         assert_step_matches(got, want, mode)
+
+
+@pytest.mark.parametrize("mode", [orc.MODE_STAR, orc.MODE_VAR, orc.MODE_VAR_TOPK])
+def test_sixty_four_workers(mode):
+    """The largest worker count the library takes (ARTOPK_MAX_WORKERS)."""
+    n, w, k = 40_003, 64, 400
+    rng = np.random.default_rng(64)
+    run = GpuRunner(w, n, k)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (63, 64, 65):
+        g = [(rng.standard_normal(n) * (1.0 + 0.05 * ((r * 7 + step_no) % w))).astype(np.float32) for r in range(w)]
+        want = orc.step(g, res, k, mode, step_no=step_no)
+        if mode != orc.MODE_STAR:
+            assert top_two_gap(want.variances) > 1e-4
+        run.load_g(g)
+        got = run.step(k, mode, step_no)
+        assert_step_matches(got, want, mode)
+        res = want.residual
