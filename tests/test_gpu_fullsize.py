@@ -166,3 +166,26 @@ def test_c5_full_var():
         res = _check_step_by_definition(f"c5 step={s}", run, g, res, k, orc.MODE_VAR, s, variances=variances)
         info = run.ctx.select_info()
         assert info["guessed"] == 1 and info["from_mask"] == 1, info
+
+
+def test_longest_vector_the_library_takes():
+    """N = 2^31 - 5 (just under the limit, 3 elements behind the last whole group of four), two
+    workers, one step: every 32-bit quantity on the path (indices, counts, list positions) is at
+    its largest here.  Checked by definition and with the Top-k certificate."""
+    n, w = (1 << 31) - 5, 2
+    wl = inp.workload(1, n=n, w=w)
+    k = wl.k(0.001)
+    run = GpuRunner(w, n, k)
+    res = [np.zeros(n, np.float32) for _ in range(w)]
+    g = []
+    for r in range(w):
+        x = wl.gen(1, r, threads=THREADS)
+        x[-3:] = np.float32(1.0 + r)        # the last three elements are kept entries
+        g.append(x)
+        _say(f"2^31-5: worker {r} generated")
+    run.load_g(g)
+    _check_step_by_definition("2^31-5", run, g, res, k, orc.MODE_STAR, 1)
+    idx = run.idx[:k].cpu().numpy()
+    assert idx[-3:].tolist() == [n - 3, n - 2, n - 1]
+    info = run.ctx.select_info()
+    assert info["guessed"] == 1 and info["from_mask"] == 1, info
