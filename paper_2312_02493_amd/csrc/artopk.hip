@@ -321,6 +321,7 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.mask_stride = s.mask_stride;
   p.mcount = nullptr;
   p.from_list = 0;
+  p.after_mask = 0;
   p.only_if_need_full = 0;
   p.zero_base = s.zero_base;
   p.flags = s.flags;
@@ -478,20 +479,18 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   if (guessed && hist_ready) {
     // The fused pass marked and counted the keys reaching a guessed bound.  If the bound works out
     // the list is written from the mask and the threshold digit taken from the list; otherwise the
-    // state says need_full, the next two kernels build the histogram of every key and pick from
-    // that, and the selection goes on as without a guess.  Kernels of the other case return at once.
+    // state says need_full, and the same two launches build the histogram of every key and pick
+    // from that, after which the selection goes on as without a guess.
     p.mask = c->s.mask;
     p.mcount = c->s.mcount;
     hipLaunchKernelGGL(k_pick_mask, dim3(1, nseg), dim3(1024), 0, st, p, la);
     SelParams pf = p;
     pf.h_all = nullptr;
     pf.only_if_need_full = 1;
-    hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, pf);
-    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pf, LeaderArgs{});
-    hipLaunchKernelGGL((k_compact_mask<4>), dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
-    SelParams pl0 = p;
-    pl0.from_list = 1;
-    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pl0, LeaderArgs{});
+    hipLaunchKernelGGL((k_mask_or_hist<4>), dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p, pf);
+    SelParams pa = p;
+    pa.after_mask = 1;
+    hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pa, LeaderArgs{});
   } else {
     if (!hist_ready) hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);

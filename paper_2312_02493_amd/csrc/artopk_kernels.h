@@ -17,7 +17,8 @@
 //                    the guessed bound or asks for the histogram route
 //   k_compact1       ordered compaction of the leader's survivors, one block
 //                    per chunk, no inter-block dependency
-//   k_compact_mask   the survivor list written from the mask instead
+//   k_mask_or_hist   the survivor list written from the mask instead; or, after
+//                    a guess that did not hold, k_hist0's work in the same launch
 //   k_compact        ordered compaction with a decoupled look-back scan: the
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
@@ -129,6 +130,7 @@ struct SelParams {
   int64_t mask_stride;     // 64-bit words per worker
   const uint32_t* mcount;  // [workers][kMaxChunks] marked elements per chunk, or nullptr
   int32_t from_list;       // k_pick0: the top-digit histogram covers the survivor list written from the mask
+  int32_t after_mask;      // k_pick0 behind k_mask_or_hist: from_list if the mask was used, else the full pick
   int32_t only_if_need_full;  // this launch runs only for segments whose state says need_full
   uint32_t* zero_base;     // [segments][kSegWords]
   uint64_t* flags;         // [tiles][kNumLookback]
@@ -154,6 +156,7 @@ struct SegView {
   uint32_t* hist2;
   uint32_t* htop;       // top-digit histogram of the selected vector's range: htop_reps partial copies to add up
   int htop_reps;
+  uint32_t* hseg;       // the segment's own top-digit histogram (single copy), what k_hist0 fills without h_all
   const uint32_t* ctrl;  // control words of the vector's slot (guessed bound), or nullptr
   const uint64_t* mask;  // survivor bit mask of the vector, or nullptr
   const uint32_t* mcount;  // marked elements per chunk of the vector, or nullptr
@@ -299,6 +302,7 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg, int lea
   const size_t slot = p.slot_by_leader ? (size_t)vec : 0;  // histogram slot: per vector, or the only one
   v.htop = p.h_all ? const_cast<uint32_t*>(p.h_all) + slot * kSlotWords : zb + kSegHtop;
   v.htop_reps = p.h_all ? kHistReps : 1;
+  v.hseg = zb + kSegHtop;
   v.ctrl = p.h_all ? p.h_all + slot * kSlotWords + kSlotCtrl : nullptr;
   v.mask = p.mask ? p.mask + slot * (size_t)p.mask_stride : nullptr;
   v.mcount = p.mcount ? p.mcount + slot * kMaxChunks : nullptr;
@@ -778,8 +782,7 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
 // elements at its ragged end; elements outside the chunk are masked out.
 // ---------------------------------------------------------------------------
 template <int T>
-__global__ void __launch_bounds__(T)
-k_hist0(SelParams p) {
+__device__ __forceinline__ void hist0_body(const SelParams& p) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
   __shared__ uint32_t red_u[T];
   const SegView sv = seg_view(p, blockIdx.y);
@@ -826,6 +829,12 @@ k_hist0(SelParams p) {
     }
   }
   flush_suffix_hist<T>(lh, red_u, sv.S + (size_t)c * kHistBins, sv.htop);
+}
+
+template <int T>
+__global__ void __launch_bounds__(T)
+k_hist0(SelParams p) {
+  hist0_body<T>(p);
 }
 
 // ---------------------------------------------------------------------------
@@ -988,6 +997,19 @@ k_pick0(SelParams p, LeaderArgs la) {
   if (p.only_if_need_full && sv.st->need_full == 0u) return;
   if (p.from_list && sv.st->use_mask == 0u) return;
   const SelState prev = *sv.st;  // from_list: says how long the list is
+  bool from_list = p.from_list != 0;
+  const uint32_t* __restrict__ htop = sv.htop;
+  int htop_reps = sv.htop_reps;
+  if (p.after_mask) {  // the list was written from the mask, or k_hist0's work has just been done instead
+    if (prev.use_mask != 0u) {
+      from_list = true;
+    } else if (prev.need_full != 0u) {
+      htop = sv.hseg;
+      htop_reps = 1;
+    } else {
+      return;
+    }
+  }
   const uint32_t k = sv.d.k;
   const int nchunks = sv.d.geom.nchunks;
 
@@ -995,11 +1017,11 @@ k_pick0(SelParams p, LeaderArgs la) {
   uint32_t h[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) h[j] = 0u;
-  if (sv.htop_reps == kHistReps) {  // sixteen loads in flight together
+  if (htop_reps == kHistReps) {  // sixteen loads in flight together
     for (int r0 = 0; r0 < kHistReps; r0 += 16) {
       uint4 q[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) q[r] = reinterpret_cast<const uint4*>(sv.htop + (size_t)(r0 + r) * kHistBins)[t];
+      for (int r = 0; r < 16; ++r) q[r] = reinterpret_cast<const uint4*>(htop + (size_t)(r0 + r) * kHistBins)[t];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         h[0] += q[r].x;
@@ -1009,7 +1031,7 @@ k_pick0(SelParams p, LeaderArgs la) {
       }
     }
   } else {
-    const uint4 q = reinterpret_cast<const uint4*>(sv.htop)[t];
+    const uint4 q = reinterpret_cast<const uint4*>(htop)[t];
     h[0] = q.x;
     h[1] = q.y;
     h[2] = q.z;
@@ -1038,7 +1060,7 @@ k_pick0(SelParams p, LeaderArgs la) {
       st.need = k - sx[j + 1];
       st.cand = sx[j] - sx[j + 1];
       st.level = 1u;
-      if (p.from_list) {  // the list exists already and holds every key >= list_lo
+      if (from_list) {  // the list exists already and holds every key >= list_lo
         st.compact_level = 1u;
         st.use_mask = 1u;
         st.list_lo = prev.list_lo;
@@ -1056,7 +1078,7 @@ k_pick0(SelParams p, LeaderArgs la) {
     if (t == 0) atomicOr(p.err, kErrPick);
     return;
   }
-  if (p.from_list) return;
+  if (from_list) return;
   // exclusive scan of the per-chunk survivor counts
   const uint32_t mine = (t < nchunks) ? sv.S[(size_t)t * kHistBins + b0] : 0u;
   part[t] = mine;
@@ -1286,9 +1308,9 @@ k_compact1(SelParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// k_compact_mask : writes the survivor list from the bit mask the fused pass
-// left behind instead of re-reading the vector; one block of 1024 threads per
-// chunk, runs only if the state says use_mask.  Every marked element (key >=
+// compact_mask_body (first job of k_mask_or_hist) : writes the survivor list from the
+// bit mask the fused pass left behind instead of re-reading the vector; one block of
+// 1024 threads per chunk, runs only if the state says use_mask.  Every marked element (key >=
 // list_lo) becomes a list entry, in ascending element order, starting at
 // chunk_off[c]; only the marked elements' values are fetched.  The top digits
 // of all entries are counted into the slot's partial whole-vector histograms
@@ -1300,8 +1322,7 @@ k_compact1(SelParams p) {
 //   thread, UB of them in flight, fetching the values to complete the entries.
 // ---------------------------------------------------------------------------
 template <int UB>
-__global__ void __launch_bounds__(1024)
-k_compact_mask(SelParams p) {
+__device__ __forceinline__ void compact_mask_body(const SelParams& p) {
   constexpr int T = 1024, WAVES = 16;
   __shared__ uint32_t wtot[WAVES];
   __shared__ uint32_t lh[kHistBins];
@@ -1418,6 +1439,22 @@ k_compact_mask(SelParams p) {
   for (int b = tid; b < kHistBins; b += T) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&htop[b], v);
+  }
+}
+
+// k_mask_or_hist : the kernel behind k_pick_mask.  Per segment it does whichever of the two
+// jobs the state asks for: the list from the mask (use_mask), or, after a guess that did not
+// hold, the per-chunk histograms of every key (need_full; p_full are the parameters of that
+// route: own top-digit histogram, only_if_need_full set).  Both are one 1024-thread block per
+// chunk, so they share a launch.
+template <int UB>
+__global__ void __launch_bounds__(1024)
+k_mask_or_hist(SelParams p, SelParams p_full) {
+  const SelState* st = seg_view(p, blockIdx.y).st;
+  if (st->use_mask != 0u) {
+    compact_mask_body<UB>(p);
+  } else if (st->need_full != 0u) {
+    hist0_body<1024>(p_full);
   }
 }
 
