@@ -105,7 +105,8 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     t_total = time.perf_counter() - t_start
     # level-1 events bracket the dominant kernel: the fused pass over all workers (VAR) or,
     # when the leader is known up front, the fused pass over the W-1 other workers
-    star = mode != pkg.ARTOPK_VAR and seg_k is None and wl.w > 1
+    # (the library says which of the two it ran: an environment switch can turn the second off)
+    star = ctx.select_info()["dominant_workers"] == wl.w - 1 and wl.w > 1
     dom_name, dom_stage, dom_workers = ("k_pass_rest", "gather", wl.w - 1) if star else ("k_pass_a", "pass_a", wl.w)
     pass_a_ms = [ctx.get_profile()[dom_stage]]  # averaged over the timed steps
     # stage breakdown from a few extra, untimed steps (an event at every stage boundary)

@@ -172,7 +172,8 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  *                place (holds residual_{i-1} on entry, residual_i on exit)
  *   nseg/seg_off/seg_k/k  as in artopk_select_topk (one leader per step even
  *                when the selection is per segment)
- *   mode         ARTOPK_STAR (leader = step mod W), ARTOPK_VAR, ARTOPK_FIXED
+ *   mode         ARTOPK_STAR (leader = step mod W), ARTOPK_VAR, ARTOPK_FIXED,
+ *                ARTOPK_VAR_TOPK or ARTOPK_VAR_G (see the enum)
  *   step         the paper's iteration counter i
  *   fixed_leader used by ARTOPK_FIXED only
  *   leader_out   device int32 (may be NULL)

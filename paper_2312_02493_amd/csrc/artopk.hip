@@ -731,8 +731,7 @@ int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
   return ARTOPK_OK;
 }
 
-// Averages every stage over the calls recorded since profiling was enabled
-// (at most the kRing most recent ones).
+// Reads back the selection state of segment 0 as the last step left it.
 int artopk_select_info(artopk_ctx* ctx, int32_t* info_out, int32_t count) {
   if (!ctx || !info_out || count < 0) return ARTOPK_EINVAL;
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -744,6 +743,8 @@ int artopk_select_info(artopk_ctx* ctx, int32_t* info_out, int32_t count) {
   return ARTOPK_OK;
 }
 
+// Averages every stage over the calls recorded since profiling was enabled
+// (at most the kRing most recent ones).
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count) {
   if (!ctx || !ms_out || count < 0) return ARTOPK_EINVAL;
   if (!ctx->ev_created) return fail(ctx, ARTOPK_EINVAL, "profiling was never enabled");
