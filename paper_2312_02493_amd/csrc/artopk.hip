@@ -30,14 +30,13 @@ struct Scratch {
   uint32_t* h_all = nullptr;      // [max_w][kSlotWords] whole-vector histograms of the fused pass, guess sample
   uint64_t* mask = nullptr;       // [max_w][mask_stride] survivor bit masks of the fused pass (if guessing is on)
   int64_t mask_stride = 0;        // 64-bit words per worker
-  uint32_t* mcount = nullptr;     // [max_w][kMaxChunks] marked elements per chunk
   uint32_t* zero_base = nullptr;  // [max_seg][kSegWords]
   uint64_t* flags = nullptr;      // [max_tiles][kNumLookback], directly behind the blocks
   int64_t max_tiles = 0;
   // not zeroed
   uint32_t* S = nullptr;          // [max_w * kMaxChunks + max_seg][4096] per-chunk suffix histograms
   uint32_t* chunk_off = nullptr;  // [kMaxChunks + max_seg]
-  double* partials = nullptr;     // [max_w][kMaxChunks][2]
+  double* partials = nullptr;     // [max_w][kMaxPassBlocks][2]
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
   uint32_t* err_dev = nullptr;
@@ -45,6 +44,7 @@ struct Scratch {
   int64_t list_entries = 0;       // allocated entries
   float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
   int32_t* idx_rows = nullptr;    // [max_w][max_k] every worker's own Top-k (literal Alg. 1 leader rule)
+  int32_t* tile_start = nullptr;  // [max_n / kPassTile + 2] kept indices below every tile of the streaming pass
   SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
   uint32_t cap = 0;               // list capacity of a flat (one-segment) select
 };
@@ -175,7 +175,7 @@ PtrTable make_table(const float* const* tab, int32_t w) {
 
 // Chunk layout of the element range [e_lo, e_hi): at most max_chunks chunks of
 // whole tiles, chunk 0 starting at the tile boundary at or below e_lo.
-ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks) {
+ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks, bool whole_pass_tiles = false) {
   ChunkGeom g;
   g.chunk0 = e_lo / kTile * kTile;
   const int64_t span = e_hi - g.chunk0;
@@ -184,8 +184,10 @@ ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks)
   if (ce < kTile) ce = kTile;
   // chunks longer than one tile of the fused pass are whole tiles of it, so that only the last
   // chunk of a vector has a ragged tile
+  // (and always, if the pass strides over its tiles and counts per chunk)
   constexpr int64_t pass_tile = (int64_t)kPassAThreads * kPassAU * 4;
-  if (ce > kTile) ce = (ce + pass_tile - 1) / pass_tile * pass_tile;
+  static_assert(pass_tile == kPassTile, "the kernels' tile");
+  if (ce > kTile || whole_pass_tiles) ce = (ce + pass_tile - 1) / pass_tile * pass_tile;
   g.chunk_elems = ce;
   g.nchunks = (int32_t)((span + ce - 1) / ce);
   if (g.nchunks < 1) g.nchunks = 1;
@@ -231,13 +233,13 @@ int64_t seg_list_cap(int64_t n_s, int64_t k_s) {
 }
 
 // One segment covering the whole vector.
-Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k, int32_t vec = -1) {
+Plan flat_plan(const artopk_ctx* c, int64_t n, int64_t k, int32_t vec = -1, bool whole_pass_tiles = false) {
   Plan pl;
   pl.nseg = 1;
   SegDesc d{};
   d.e_lo = 0;
   d.e_hi = n;
-  d.geom = make_geom(0, n);
+  d.geom = make_geom(0, n, kMaxChunks, whole_pass_tiles);
   d.koff = 0;
   d.list_base = 0;
   d.flag_base = 0;
@@ -319,7 +321,7 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.h_all = hist_from_pass ? s.h_all : nullptr;
   p.mask = nullptr;
   p.mask_stride = s.mask_stride;
-  p.mcount = nullptr;
+  p.use_mcount = 0;
   p.from_list = 0;
   p.after_mask = 0;
   p.only_if_need_full = 0;
@@ -359,70 +361,105 @@ int enqueue_clear(artopk_ctx* c, const Plan& pl, int hist_slots, int32_t leader 
 }
 
 // Launches the fused pass over grid.y workers with the wanted options.
-template <int STATS, int HIST, bool MASK, int GT>
-void launch_pass_a_g(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
-                     const ChunkGeom& geom, int hist_worker) {
+template <int STATS, int HIST, int GT>
+void launch_pass_a_g(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n, const ChunkGeom& geom,
+                     int hist_worker) {
   Scratch& s = c->s;
   if (c->pass_a_nt)
-    hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, MASK, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
-                       stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
-                       s.partials);
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, true, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.partials);
   else
-    hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, MASK, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
-                       stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.mask, s.mask_stride, s.mcount,
-                       s.partials);
+    hipLaunchKernelGGL((k_pass_a<STATS, HIST, false, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, geom, hist_worker, s.S, s.h_all, s.partials);
 }
 
-template <int STATS, int HIST, bool MASK>
-void launch_pass_a_t(artopk_ctx* c, hipStream_t stream, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
-                     const ChunkGeom& geom, int hist_worker) {
+template <int STATS, int HIST>
+void launch_pass_a_t(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n, const ChunkGeom& geom,
+                     int hist_worker) {
   if (c->g_type == ARTOPK_G_BF16)
-    launch_pass_a_g<STATS, HIST, MASK, kGBF16>(c, stream, grid, g, r, n, geom, hist_worker);
+    launch_pass_a_g<STATS, HIST, kGBF16>(c, grid, g, r, n, geom, hist_worker);
   else if (c->g_type == ARTOPK_G_F16)
-    launch_pass_a_g<STATS, HIST, MASK, kGF16>(c, stream, grid, g, r, n, geom, hist_worker);
+    launch_pass_a_g<STATS, HIST, kGF16>(c, grid, g, r, n, geom, hist_worker);
   else
-    launch_pass_a_g<STATS, HIST, MASK, kGF32>(c, stream, grid, g, r, n, geom, hist_worker);
+    launch_pass_a_g<STATS, HIST, kGF32>(c, grid, g, r, n, geom, hist_worker);
 }
 
-void launch_pass_a(artopk_ctx* c, int stats, int hist, bool mask, dim3 grid, const PtrTable& g, const PtrTable& r,
-                   int64_t n, const ChunkGeom& geom, int hist_worker, hipStream_t stream = nullptr) {
-  if (stream == nullptr) stream = c->stream;
-#define PASS_A_CASE(S_, H_, M_)                     \
-  if (stats == S_ && hist == H_ && mask == M_)      \
-  return launch_pass_a_t<S_, H_, M_>(c, stream, grid, g, r, n, geom, hist_worker)
-  PASS_A_CASE(0, 0, false);
-  PASS_A_CASE(0, 1, false);
-  PASS_A_CASE(0, 1, true);
-  PASS_A_CASE(0, 2, false);
-  PASS_A_CASE(0, 2, true);
-  PASS_A_CASE(1, 0, false);
-  PASS_A_CASE(1, 2, false);
-  PASS_A_CASE(1, 2, true);
-  PASS_A_CASE(2, 0, false);
-  PASS_A_CASE(2, 2, false);
-  PASS_A_CASE(2, 2, true);
+void launch_pass_a(artopk_ctx* c, int stats, int hist, dim3 grid, const PtrTable& g, const PtrTable& r, int64_t n,
+                   const ChunkGeom& geom, int hist_worker) {
+#define PASS_A_CASE(S_, H_) \
+  if (stats == S_ && hist == H_) return launch_pass_a_t<S_, H_>(c, grid, g, r, n, geom, hist_worker)
+  PASS_A_CASE(0, 0);
+  PASS_A_CASE(0, 1);
+  PASS_A_CASE(0, 2);
+  PASS_A_CASE(1, 0);
+  PASS_A_CASE(1, 2);
+  PASS_A_CASE(2, 0);
+  PASS_A_CASE(2, 2);
 #undef PASS_A_CASE
+}
+
+// Blocks per worker of a streaming pass that strides over the tiles of n elements.
+int pass_blocks(int64_t n) {
+  const int64_t ntiles = (n + kPassTile - 1) / kPassTile;
+  return (int)(ntiles < kMaxPassBlocks ? ntiles : kMaxPassBlocks);
+}
+
+// The fused pass of the guess route over the first nw workers of the tables (worker y in slot y).
+template <int STATS, int GT>
+void launch_pass_mark_g(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems) {
+  Scratch& s = c->s;
+  const dim3 grid(pass_blocks(n), nw);
+  if (c->pass_a_nt)
+    hipLaunchKernelGGL((k_pass_mark<STATS, true, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, c->stream,
+                       g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials);
+  else
+    hipLaunchKernelGGL((k_pass_mark<STATS, false, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, c->stream,
+                       g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials);
+}
+
+template <int STATS>
+void launch_pass_mark_t(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems) {
+  if (c->g_type == ARTOPK_G_BF16)
+    launch_pass_mark_g<STATS, kGBF16>(c, nw, g, r, n, chunk_elems);
+  else if (c->g_type == ARTOPK_G_F16)
+    launch_pass_mark_g<STATS, kGF16>(c, nw, g, r, n, chunk_elems);
+  else
+    launch_pass_mark_g<STATS, kGF32>(c, nw, g, r, n, chunk_elems);
+}
+
+void launch_pass_mark(artopk_ctx* c, int stats, int nw, const PtrTable& g, const PtrTable& r, int64_t n,
+                      int64_t chunk_elems) {
+  if (stats == 0) return launch_pass_mark_t<0>(c, nw, g, r, n, chunk_elems);
+  if (stats == 1) return launch_pass_mark_t<1>(c, nw, g, r, n, chunk_elems);
+  return launch_pass_mark_t<2>(c, nw, g, r, n, chunk_elems);
 }
 
 template <int GT>
 void launch_pass_rest_g(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
-                        const ChunkGeom& geom, const int32_t* idx, int64_t k, float* vals) {
+                        const int32_t* idx, int64_t k, float* vals) {
+  Scratch& s = c->s;
   if (c->pass_a_nt)
     hipLaunchKernelGGL((k_pass_rest<true, GT, kPassRestThreads, kPassRestU>), grid, dim3(kPassRestThreads), 0, c->stream,
-                       g, r, w, leader, n, geom, idx, k, vals);
+                       g, r, w, leader, n, idx, k, vals, s.tile_start, s.err_dev);
   else
     hipLaunchKernelGGL((k_pass_rest<false, GT, kPassRestThreads, kPassRestU>), grid, dim3(kPassRestThreads), 0, c->stream,
-                       g, r, w, leader, n, geom, idx, k, vals);
+                       g, r, w, leader, n, idx, k, vals, s.tile_start, s.err_dev);
 }
 
-void launch_pass_rest(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
-                      const ChunkGeom& geom, const int32_t* idx, int64_t k, float* vals) {
+// The other workers' streaming pass (leader known, idx final): first the number of kept indices
+// below every tile, then the pass itself, striding over the tiles.
+void launch_pass_rest(artopk_ctx* c, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
+                      const int32_t* idx, int64_t k, float* vals) {
+  const int32_t ntiles = (int32_t)((n + kPassTile - 1) / kPassTile);
+  hipLaunchKernelGGL(k_tile_starts, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, c->stream, idx, k, ntiles,
+                     c->s.tile_start);
+  const dim3 grid(pass_blocks(n), w - 1);
   if (c->g_type == ARTOPK_G_BF16)
-    launch_pass_rest_g<kGBF16>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
+    launch_pass_rest_g<kGBF16>(c, grid, g, r, w, leader, n, idx, k, vals);
   else if (c->g_type == ARTOPK_G_F16)
-    launch_pass_rest_g<kGF16>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
+    launch_pass_rest_g<kGF16>(c, grid, g, r, w, leader, n, idx, k, vals);
   else
-    launch_pass_rest_g<kGF32>(c, grid, g, r, w, leader, n, geom, idx, k, vals);
+    launch_pass_rest_g<kGF32>(c, grid, g, r, w, leader, n, idx, k, vals);
 }
 
 // Whether a flat step on n elements keeping k uses the sampled threshold guess.
@@ -482,7 +519,7 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
     // state says need_full, and the same two launches build the histogram of every key and pick
     // from that, after which the selection goes on as without a guess.
     p.mask = c->s.mask;
-    p.mcount = c->s.mcount;
+    p.use_mcount = 1;
     hipLaunchKernelGGL(k_pick_mask, dim3(1, nseg), dim3(1024), 0, st, p, la);
     SelParams pf = p;
     pf.h_all = nullptr;
@@ -564,7 +601,7 @@ int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t 
                          bool guessed = false) {
   Scratch& s = c->s;
   for (int32_t r = 0; r < w; ++r) {
-    const Plan pl = flat_plan(c, n, k, r);
+    const Plan pl = flat_plan(c, n, k, r, guessed);
     int rc = enqueue_clear(c, pl, 0);
     if (rc) return rc;
     if ((rc = enqueue_select(c, pl, tab, n, idx_rows + (size_t)r * (size_t)k, hist_ready, 1,
@@ -641,12 +678,11 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   // one bit per element and worker, in rows of 256 elements, if the vectors are long enough to guess on
   s.mask_stride = max_n >= c->guess_min_n ? (max_n + 255) / 256 * 4 : 0;
   const size_t o_mask = take((size_t)max_w * (size_t)s.mask_stride * sizeof(uint64_t));
-  const size_t o_mcount = take((size_t)max_w * kMaxChunks * sizeof(uint32_t));
   const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
                              (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
   const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
   const size_t o_coff = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
-  const size_t o_part = take((size_t)max_w * kMaxChunks * 2 * sizeof(double));
+  const size_t o_part = take((size_t)max_w * kMaxPassBlocks * 2 * sizeof(double));
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
@@ -654,6 +690,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
   const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
   const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
+  const size_t o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
   const size_t total = off;
 
   e = hipMalloc(&c->slab, total);
@@ -664,7 +701,6 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   char* base = static_cast<char*>(c->slab);
   s.h_all = reinterpret_cast<uint32_t*>(base + o_hall);
   s.mask = s.mask_stride ? reinterpret_cast<uint64_t*>(base + o_mask) : nullptr;
-  s.mcount = reinterpret_cast<uint32_t*>(base + o_mcount);
   s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
   // kSegWords is even, so the flags stay 8-byte aligned
   s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
@@ -678,6 +714,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.vals = reinterpret_cast<float*>(base + o_vals);
   s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
   s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
+  s.tile_start = reinterpret_cast<int32_t*>(base + o_tstart);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
@@ -926,15 +963,18 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   const PtrTable gt = make_table(g, w);
   const PtrTable rt = make_table(residual, w);
   const bool segmented = seg_off != nullptr && nseg > 1;
+  // a flat selection on a long vector samples a threshold guess first; its chunks are then whole
+  // tiles of the fused pass, which strides over the tiles and counts per chunk
+  const GuessPlan gp = segmented ? GuessPlan{} : plan_guess(ctx, n, k);
   Plan flat;
   const Plan* pl = &flat;
   if (segmented) {
     if ((rc = segmented_plan(ctx, n, nseg, seg_off, seg_k, &pl))) return rc;
   } else {
-    flat = flat_plan(ctx, n, k);
+    flat = flat_plan(ctx, n, k, -1, gp.on);
   }
   // pass A always works on whole-vector chunks; for a flat select they are the select's chunks too
-  const ChunkGeom geom = make_geom(0, n);
+  const ChunkGeom geom = make_geom(0, n, kMaxChunks, gp.on);
   const dim3 grid(geom.nchunks, w);
 
   ctx->last_guessed = 0;
@@ -947,10 +987,13 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     if ((rc = enqueue_clear(ctx, *pl, (int)w))) return rc;
     // every worker selects on its own vector: on long vectors every worker gets a guessed bound and
     // leaves a mask, as under the variance rule
-    const GuessPlan gp = plan_guess(ctx, n, k);
     ctx->last_guessed = gp.on ? 1 : 0;
-    if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
-    launch_pass_a(ctx, 0, 2, gp.on, dim3(geom.nchunks, w), gt, rt, n, geom, -1);
+    if (gp.on) {
+      enqueue_guess(ctx, gp, gt, rt, (int)w);
+      launch_pass_mark(ctx, 0, (int)w, gt, rt, n, geom.chunk_elems);
+    } else {
+      launch_pass_a(ctx, 0, 2, grid, gt, rt, n, geom, -1);
+    }
     prof_mark(ctx, 1);
     if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true, gp.on))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
@@ -976,11 +1019,14 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_begin(ctx);
     prof_mark(ctx, 0);
     if ((rc = enqueue_clear(ctx, *pl, 1, L, leader_out))) return rc;
-    const GuessPlan gp = plan_guess(ctx, n, k);
     ctx->last_guessed = gp.on ? 1 : 0;
     ctx->last_dom_workers = w > 1 ? w - 1 : 1;
-    if (gp.on) enqueue_guess(ctx, gp, g1t, r1t, 1);
-    launch_pass_a(ctx, 0, 1, gp.on, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
+    if (gp.on) {
+      enqueue_guess(ctx, gp, g1t, r1t, 1);
+      launch_pass_mark(ctx, 0, 1, g1t, r1t, n, geom.chunk_elems);
+    } else {
+      launch_pass_a(ctx, 0, 1, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
+    }
     prof_mark(ctx, 1);
     // The leader's residual is zeroed inside the selection: its kernels have the kept values in
     // registers (level-1 compaction) or write the kept indices anyway (final list pass).
@@ -990,7 +1036,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;
     if (rest > 0) {
-      launch_pass_rest(ctx, dim3(geom.nchunks, rest), gt, rt, (int)w, L, n, geom, idx_out, k, vals);
+      launch_pass_rest(ctx, gt, rt, (int)w, L, n, idx_out, k, vals);
     }
     prof_mark(ctx, 3);
     hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
@@ -1009,16 +1055,19 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     return rc;
   int slot_by_leader = 0;
   LeaderArgs leader_args{};
-  GuessPlan gp;
+  const bool marking = gp.on && (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G);
   if (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) {
     const int stats = mode == ARTOPK_VAR_G ? 2 : 1;  // variance of the raw gradient, or of g + residual
     if (segmented) {
-      launch_pass_a(ctx, stats, 0, false, grid, gt, rt, n, geom, -1);
+      launch_pass_a(ctx, stats, 0, grid, gt, rt, n, geom, -1);
     } else {
-      gp = plan_guess(ctx, n, k);
       ctx->last_guessed = gp.on ? 1 : 0;
-      if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
-      launch_pass_a(ctx, stats, 2, gp.on, grid, gt, rt, n, geom, -1);
+      if (gp.on) {
+        enqueue_guess(ctx, gp, gt, rt, (int)w);
+        launch_pass_mark(ctx, stats, (int)w, gt, rt, n, geom.chunk_elems);
+      } else {
+        launch_pass_a(ctx, stats, 2, grid, gt, rt, n, geom, -1);
+      }
       slot_by_leader = 1;
     }
     prof_mark(ctx, 1);
@@ -1028,7 +1077,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     } else {          // otherwise the selection's first kernel takes the leader itself
       leader_args.partials = s.partials;
       leader_args.w_count = (int)w;
-      leader_args.nblk = (int)geom.nchunks;
+      leader_args.nblk = marking ? pass_blocks(n) : (int)geom.nchunks;
       leader_args.n = n;
       leader_args.var_scratch = s.var_scratch;
       leader_args.var_out = var_out;
@@ -1036,14 +1085,14 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
       leader_args.leader_out = leader_out;
     }
   } else {
-    launch_pass_a(ctx, 0, segmented ? 0 : 1, false, grid, gt, rt, n, geom, leader_host);
+    launch_pass_a(ctx, 0, segmented ? 0 : 1, grid, gt, rt, n, geom, leader_host);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
   }
   HIP_TRY(ctx, hipGetLastError());
 
   rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, slot_by_leader, nullptr,
-                      leader_args.partials ? &leader_args : nullptr, gp.on);
+                      leader_args.partials ? &leader_args : nullptr, marking);
   if (rc) return rc;
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;

@@ -56,7 +56,8 @@ constexpr int kHistReps = 16;            // partial copies of a whole-vector his
 // histogram of the threshold-guess sample, then its control words.
 constexpr int kSlotGuessHist = kHistReps * kHistBins;
 constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound
-constexpr int kSlotWords = kSlotCtrl + 16;
+constexpr int kSlotMcount = kSlotCtrl + 16;            // marked elements per chunk (kMaxChunks words)
+constexpr int kSlotWords = kSlotMcount + 1024;
 constexpr uint32_t kNoGuess = 0xffffffffu;             // no key reaches this bound
 constexpr int kGuessRun = 16;                          // consecutive elements per sample run
 constexpr uint32_t kKeyMask = 0x7fffffffu;
@@ -128,7 +129,7 @@ struct SelParams {
   const uint32_t* h_all;   // [workers][kSlotWords] whole-vector histograms from the fused pass, or nullptr
   const uint64_t* mask;    // [workers][mask_stride] survivor bit masks from the fused pass, or nullptr
   int64_t mask_stride;     // 64-bit words per worker
-  const uint32_t* mcount;  // [workers][kMaxChunks] marked elements per chunk, or nullptr
+  int32_t use_mcount;      // the slots' per-chunk counts of marked elements are valid
   int32_t from_list;       // k_pick0: the top-digit histogram covers the survivor list written from the mask
   int32_t after_mask;      // k_pick0 behind k_mask_or_hist: from_list if the mask was used, else the full pick
   int32_t only_if_need_full;  // this launch runs only for segments whose state says need_full
@@ -196,6 +197,9 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
 
 constexpr int kTile = 8192;       // chunk granularity (a quarter of a tile of the fused pass)
 constexpr int kMaxChunks = 1024;  // chunks per vector range
+static_assert(kSlotWords == kSlotMcount + kMaxChunks, "a slot ends with one count per chunk");
+constexpr int kPassTile = 32768;      // elements per block iteration of the streaming passes (1024 threads x 8 float4)
+constexpr int kMaxPassBlocks = 2048;  // blocks per worker of a streaming pass that strides over tiles
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -305,7 +309,7 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg, int lea
   v.hseg = zb + kSegHtop;
   v.ctrl = p.h_all ? p.h_all + slot * kSlotWords + kSlotCtrl : nullptr;
   v.mask = p.mask ? p.mask + slot * (size_t)p.mask_stride : nullptr;
-  v.mcount = p.mcount ? p.mcount + slot * kMaxChunks : nullptr;
+  v.mcount = (p.h_all && p.use_mcount) ? p.h_all + slot * kSlotWords + kSlotMcount : nullptr;
   v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
   v.chunk_off = p.chunk_off + v.d.chunk_begin;
   v.list = p.list + v.d.list_base;
@@ -333,17 +337,11 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 
 // ---------------------------------------------------------------------------
 // k_pass_a : acc = g + residual (in place over residual), variance partials,
-//            and what the selection needs from this pass.
+//            and the histograms the selection needs from this pass.
 //   grid = (nchunks, W), block = T; block (c, w) owns chunk c of worker w.
 //   HIST: 0 nothing for the selection, 1 only for worker `hist_worker` (slot 0),
-//         2 for every worker (worker w in slot w).
-//   MASK = false: per-chunk top-digit suffix histograms S[slot][c] and the
-//         whole-vector histogram of the slot.
-//   MASK = true: no histogram; elements whose key reaches the guessed bound of
-//         the slot are marked in the slot's bit mask and counted per chunk.  For
-//         every row of 64 float4 groups four 64-bit words are written: word e,
-//         bit l <=> element 4 (64 row + l) + e is marked.  The n mod 4 elements
-//         behind the last whole group are counted but have no mask bit.
+//         2 for every worker (worker w in slot w): per-chunk top-digit suffix
+//         histograms S[slot][c] and the whole-vector histogram of the slot.
 //   STATS: 0 none, 1 variance partials of acc, 2 of the raw gradient g.  They
 //   use the shift c_w = g_w[0]: per block the sums of (x - c_w) and (x - c_w)^2
 //   in float64, written to partials[w][c][0..1].
@@ -351,17 +349,14 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
 
-template <int STATS, int HIST, bool NT, bool MASK, int GT, int T, int U>
+template <int STATS, int HIST, bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, uint32_t* __restrict__ S,
-         uint32_t* __restrict__ h_all, uint64_t* __restrict__ mask, int64_t mask_stride,
-         uint32_t* __restrict__ mcount, double* __restrict__ partials) {
-  static_assert(!MASK || HIST != 0, "the mask belongs to a slot");
-  constexpr bool LH = HIST != 0 && !MASK;  // an LDS histogram is built
+         uint32_t* __restrict__ h_all, double* __restrict__ partials) {
+  constexpr bool LH = HIST != 0;  // an LDS histogram is built
   __shared__ __attribute__((aligned(16))) uint32_t lh[LH ? kHistBins : 4];
   __shared__ uint32_t red_u[LH ? T : 1];
   __shared__ double red[2][T / 64];
-  __shared__ uint32_t marked_sh;
 
   // with a known leader its blocks (the only ones that work for the selection) are dispatched first
   const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
@@ -377,18 +372,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   if (LH) {
     if (do_hist)
       for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
-  }
-  if (MASK && tid == 0) marked_sh = 0u;
-  if (LH || MASK) __syncthreads();
-  // Marked <=> not (|acc| < bound): the same as key >= bound on the magnitude bits, NaNs included.
-  uint32_t gkey = kNoGuess;
-  float gf = __builtin_inff();
-  uint64_t* __restrict__ mrow = nullptr;
-  uint32_t marked = 0u;  // per wave
-  if (MASK) {
-    if (do_hist) gkey = h_all[slot * kSlotWords + kSlotCtrl + 1];
-    if (gkey != kNoGuess) gf = __uint_as_float(gkey);
-    mrow = mask + slot * (size_t)mask_stride;
+    __syncthreads();
   }
 
   double cshift = 0.0, s = 0.0, ss = 0.0;
@@ -417,8 +401,8 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     for (int u = 0; u < U; ++u) {
       const int64_t q = qw + lane + u * T;
       const bool valid = FULL || q < q_hi;
-      v4f v = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
+        v4f v;
         v.x = a[u].x + b[u].x;
         v.y = a[u].y + b[u].y;
         v.z = a[u].z + b[u].z;
@@ -443,22 +427,10 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
           }
         }
       }
-      if (MASK) {
-        if (do_hist) {
-          const uint64_t m0 = __ballot(valid && !(__builtin_fabsf(v.x) < gf));
-          const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
-          const uint64_t m2 = __ballot(valid && !(__builtin_fabsf(v.z) < gf));
-          const uint64_t m3 = __ballot(valid && !(__builtin_fabsf(v.w) < gf));
-          marked += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
-          const int64_t qrow = qw + u * T;  // first group of this wave's row
-          if ((FULL || qrow < q_hi) && lane < 4)
-            mrow[(qrow >> 6) * 4 + lane] = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
-        }
-      }
     }
   };
 
-  // the loop runs on the wave's first group, so all 64 lanes stay together (the masks need that)
+  // the loop runs on the wave's first group, so all 64 lanes stay together
   const int64_t qw0 = (c_lo >> 2) + __builtin_amdgcn_readfirstlane(tid - lane);
   int64_t qw = qw0;
   for (; qw + (int64_t)(U - 1) * T + 64 <= q_hi; qw += T * U) tile(qw, std::true_type{});
@@ -478,13 +450,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       if (LH) {
         if (do_hist) atomicAdd(&lh[(__float_as_uint(v) & kKeyMask) >> 19], 1u);
       }
-      if (MASK) {
-        if (do_hist && !(__builtin_fabsf(v) < gf)) atomicAdd(&marked_sh, 1u);
-      }
     }
-  }
-  if (MASK) {
-    if (do_hist && lane == 0 && marked != 0u) atomicAdd(&marked_sh, marked);
   }
 
   if (STATS) {
@@ -506,14 +472,147 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     partials[((size_t)w * nblk + c) * 2 + 0] = S1;
     partials[((size_t)w * nblk + c) * 2 + 1] = S2;
   }
-  if (MASK) {
-    if (do_hist && tid == 0) mcount[slot * kMaxChunks + (size_t)c] = marked_sh;
-  }
   if (LH) {
     if (do_hist) {
       // many blocks add to the same few hundred bins: spread them over kHistReps partial copies
       flush_suffix_hist<T>(lh, red_u, S + (slot * kMaxChunks + (size_t)c) * kHistBins,
                            h_all + slot * kSlotWords + (size_t)(c % kHistReps) * kHistBins);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_pass_mark : the fused pass of the route with a guessed threshold bound:
+//   acc = g + residual (in place over residual), variance partials (STATS as in
+//   k_pass_a), and, instead of histograms, one bit per element: elements whose
+//   key reaches the guessed bound of the worker's slot are marked in the slot's
+//   bit mask and counted per chunk of the selection's chunk layout.
+//   grid = (gx, W'), block = T; block (b, y) works on worker y (slot y) and takes
+//   the tiles b, b + gx, b + 2 gx, ... of T U float4 groups, so that at any time
+//   the blocks in flight read and write one contiguous window of each array
+//   (measured 4 to 10 % faster than one contiguous chunk per block).
+//   Mask layout: for every row of 64 float4 groups four 64-bit words, word e,
+//   bit l <=> element 4 (64 row + l) + e is marked.  The n mod 4 elements behind
+//   the last whole group are counted (in the last chunk) but have no mask bit.
+//   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
+//   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
+//   Variance partials go to partials[y][b][0..1].
+// ---------------------------------------------------------------------------
+template <int STATS, bool NT, int GT, int T, int U>
+__global__ void __launch_bounds__(T)
+k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
+            uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials) {
+  __shared__ double red[2][T / 64];
+  const int w = blockIdx.y;
+  const int bx = blockIdx.x;
+  const int nblk = gridDim.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const float* __restrict__ gp = g.p[w];
+  float* __restrict__ rp = res.p[w];
+  uint32_t* __restrict__ slot = h_all + (size_t)w * kSlotWords;
+  uint32_t* __restrict__ mcount = slot + kSlotMcount;
+  uint64_t* __restrict__ mrow = mask + (size_t)w * (size_t)mask_stride;
+
+  // Marked <=> not (|acc| < bound): the same as key >= bound on the magnitude bits, NaNs included.
+  const uint32_t gkey = slot[kSlotCtrl + 1];
+  const float gf = gkey != kNoGuess ? __uint_as_float(gkey) : __builtin_inff();
+
+  double cshift = 0.0, s = 0.0, ss = 0.0;
+  if (STATS) cshift = (double)load1g<GT>(gp, 0);  // g is never written, so every block sees the same shift
+
+  const int64_t q_hi = n >> 2;  // whole float4 groups of the vector
+  constexpr int64_t TQ = (int64_t)T * U;  // groups per tile
+  const int64_t ntiles = (q_hi + TQ - 1) / TQ;
+  const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
+
+  // One tile: U rows of T float4 groups; the wave's rows start at group qw (a multiple of 64).
+  // FULL: every group of the tile lies inside the vector, so nothing is predicated.
+  auto tile = [&](const int64_t qw, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    v4f a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // groups outside the vector re-read its last group (unused): no branch between the loads,
+      // so that all of them are in flight together
+      const int64_t q = qw + lane + u * T;
+      const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
+      a[u] = load4g<NT, GT>(gp, 4 * ql);
+      b[u] = load4<NT>(rp + 4 * ql);
+    }
+    uint32_t marked = 0u;  // of this wave in this tile
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = qw + lane + u * T;
+      const bool valid = FULL || q < q_hi;
+      v4f v = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
+        v.x = a[u].x + b[u].x;
+        v.y = a[u].y + b[u].y;
+        v.z = a[u].z + b[u].z;
+        v.w = a[u].w + b[u].w;
+        store4<NT>(rp + 4 * q, v);
+        if (STATS) {
+          const v4f t = STATS == 2 ? a[u] : v;  // the raw gradient, or the error-fed value
+          double d0 = (double)t.x - cshift, d1 = (double)t.y - cshift, d2 = (double)t.z - cshift,
+                 d3 = (double)t.w - cshift;
+          s += (d0 + d1) + (d2 + d3);
+          ss = fma(d0, d0, ss);
+          ss = fma(d1, d1, ss);
+          ss = fma(d2, d2, ss);
+          ss = fma(d3, d3, ss);
+        }
+      }
+      const uint64_t m0 = __ballot(valid && !(__builtin_fabsf(v.x) < gf));
+      const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
+      const uint64_t m2 = __ballot(valid && !(__builtin_fabsf(v.z) < gf));
+      const uint64_t m3 = __ballot(valid && !(__builtin_fabsf(v.w) < gf));
+      marked += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+      const int64_t qrow = qw + u * T;  // first group of this wave's row
+      if ((FULL || qrow < q_hi) && lane < 4)
+        mrow[(qrow >> 6) * 4 + lane] = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
+    }
+    return marked;
+  };
+
+  for (int64_t ti = bx; ti < ntiles; ti += nblk) {
+    const int64_t qw = ti * TQ + wave_first;  // wave-uniform, so all 64 lanes stay together (the masks need that)
+    const uint32_t marked = (ti + 1) * TQ <= q_hi ? tile(qw, std::true_type{}) : tile(qw, std::false_type{});
+    if (lane == 0 && marked != 0u) atomicAdd(&mcount[(ti * TQ * 4) / chunk_elems], marked);
+  }
+  // scalar tail (n not a multiple of 4): the first block
+  if (bx == 0) {
+    const int64_t j = q_hi * 4 + tid;
+    if (j < n) {
+      const float gj = load1g<GT>(gp, j);
+      const float v = gj + rp[j];
+      rp[j] = v;
+      if (STATS) {
+        const double d = (double)(STATS == 2 ? gj : v) - cshift;
+        s += d;
+        ss = fma(d, d, ss);
+      }
+      if (!(__builtin_fabsf(v) < gf)) atomicAdd(&mcount[(n - 1) / chunk_elems], 1u);
+    }
+  }
+
+  if (STATS) {
+    s = wave_sum(s);
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) {
+      red[0][tid >> 6] = s;
+      red[1][tid >> 6] = ss;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      double S1 = 0.0, S2 = 0.0;
+#pragma unroll
+      for (int i = 0; i < T / 64; ++i) {
+        S1 += red[0][i];
+        S2 += red[1][i];
+      }
+      partials[((size_t)w * nblk + bx) * 2 + 0] = S1;
+      partials[((size_t)w * nblk + bx) * 2 + 1] = S2;
     }
   }
 }
@@ -1204,27 +1303,48 @@ k_compact1(SelParams p) {
   uint32_t run = write_out ? sv.chunk_off[c] : 0u;  // list position of the next survivor of this chunk
   int buf = 0;
 
+  // raw bits of one tile; a tile that is wholly inside the array is read with R unconditional loads
+  // (conditions around the loads make the compiler wait for each before issuing the next), in the
+  // last tile groups are read element by element where needed, absent elements as 0
+  auto load_tile = [&](int64_t tb, uint32_t (&out)[E]) {
+    const int64_t j0 = tb + lane_off;
+    if (tb + TILE <= n_vec) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xp + j0 + 4 * r);
+        out[4 * r + 0] = v.x;
+        out[4 * r + 1] = v.y;
+        out[4 * r + 2] = v.z;
+        out[4 * r + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int64_t j = j0 + 4 * r;
+        uint4 v;
+        if (j + 4 <= n_vec) {
+          v = *reinterpret_cast<const uint4*>(xp + j);
+        } else {
+          v.x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
+          v.y = (j + 1 < n) ? __float_as_uint(xp[j + 1]) : 0u;
+          v.z = (j + 2 < n) ? __float_as_uint(xp[j + 2]) : 0u;
+          v.w = (j + 3 < n) ? __float_as_uint(xp[j + 3]) : 0u;
+        }
+        out[4 * r + 0] = v.x;
+        out[4 * r + 1] = v.y;
+        out[4 * r + 2] = v.z;
+        out[4 * r + 3] = v.w;
+      }
+    }
+  };
+
+  // the next tile's loads are issued before this tile is worked on
+  uint32_t raw[E], nxt[E];
+  if (c_begin < ce) load_tile(c_begin, raw);
   for (int64_t tb = c_begin; tb < ce; tb += TILE) {
     const int64_t j0 = tb + lane_off;  // this lane's E consecutive elements start here
-    // raw bits; groups that are not wholly inside the array are read element by element, absent ones as 0
-    uint32_t raw[E];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int64_t j = j0 + 4 * r;
-      uint4 v;
-      if (j + 4 <= n_vec) {
-        v = *reinterpret_cast<const uint4*>(xp + j);
-      } else {
-        v.x = (j + 0 < n) ? __float_as_uint(xp[j + 0]) : 0u;
-        v.y = (j + 1 < n) ? __float_as_uint(xp[j + 1]) : 0u;
-        v.z = (j + 2 < n) ? __float_as_uint(xp[j + 2]) : 0u;
-        v.w = (j + 3 < n) ? __float_as_uint(xp[j + 3]) : 0u;
-      }
-      raw[4 * r + 0] = v.x;
-      raw[4 * r + 1] = v.y;
-      raw[4 * r + 2] = v.z;
-      raw[4 * r + 3] = v.w;
-    }
+    const bool more = tb + TILE < ce;
+    if (more) load_tile(tb + TILE, nxt);
     // every element of this tile belongs to the chunk and the range?
     const bool clean = (tb >= cs) && (tb + TILE <= ce);
 
@@ -1297,6 +1417,10 @@ k_compact1(SelParams p) {
           }
         }
       }
+    }
+    if (more) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) raw[e] = nxt[e];
     }
   }
 
@@ -1826,97 +1950,125 @@ k_list_hist(SelParams p, int digit) {
 }
 
 // ---------------------------------------------------------------------------
+// k_tile_starts : tile_start[t] = number of kept indices below t * kPassTile, for
+// t = 0 .. ntiles (so tile_start[ntiles] = k), from the ascending index list.
+// One thread per index: idx[p] owns the entries of the tiles that begin between
+// idx[p-1] and idx[p], the last index also the rest; the 64 lanes of a wave fill
+// each owner's entries together, so a long run of empty tiles costs its length / 64.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_tile_starts(const int32_t* __restrict__ idx, int64_t k, int32_t ntiles, int32_t* __restrict__ tile_start) {
+  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  int32_t t0 = 1, t1 = 0, t_last = -1;  // [t0, t1] = entries this index owns (empty by default)
+  if (p < k) {
+    const int64_t i = (int64_t)idx[p];
+    const int64_t prev = p > 0 ? (int64_t)idx[p - 1] : -1;
+    if (i >= 0 && i >= prev) {  // otherwise not an ascending index list: k_pass_rest reports what is left unset
+      const int64_t t = i / kPassTile;
+      t1 = (int32_t)(t < ntiles ? t : ntiles);
+      t0 = prev < 0 ? 0 : (int32_t)(prev / kPassTile) + 1;
+      if (p == k - 1) t_last = t1;
+    }
+  }
+  uint64_t todo = __ballot(t0 <= t1);
+  while (todo != 0ull) {
+    const int src = __ffsll((unsigned long long)todo) - 1;
+    todo &= todo - 1;
+    const int32_t a = __shfl(t0, src, 64), b = __shfl(t1, src, 64);
+    const int32_t v = (int32_t)(p - lane + src);
+    for (int32_t t = a + lane; t <= b; t += 64) tile_start[t] = v;
+  }
+  const uint64_t fin = __ballot(t_last >= 0);
+  if (fin != 0ull) {
+    const int src = __ffsll((unsigned long long)fin) - 1;
+    const int32_t a = __shfl(t_last, src, 64) + 1;
+    for (int32_t t = a + lane; t <= ntiles; t += 64) tile_start[t] = (int32_t)k;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // k_pass_rest : for every worker except the leader, in one streaming pass:
 //   acc = g + residual; at the kept indices vals[w][m] = acc and the residual
 //   becomes +0.0, elsewhere the residual becomes acc.
 // Used when the leader is known before the step starts (its own pass and the
-// selection have already run, so idx is final).  grid = (nchunks, W-1), block =
-// T; block (c, y) owns chunk c of worker (leader + 1 + y) mod W.  The block
-// finds its first index with a T-way search; per tile of 16 T elements it marks
-// the kept positions in an LDS slot table while the tile's loads are in flight.
+// selection have already run, so idx is final and k_tile_starts has run).
+// grid = (gx, W-1), block = T; block (b, y) works on worker (leader + 1 + y) mod W
+// and takes the tiles b, b + gx, ... of T U float4 groups (see k_pass_mark).  Per
+// tile it marks the kept positions, idx[tile_start[t] .. tile_start[t+1]), in an
+// LDS slot table while the tile's loads are in flight.
 // ---------------------------------------------------------------------------
 template <bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
-k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkGeom geom,
-            const int32_t* __restrict__ idx, int64_t k, float* __restrict__ vals) {
+k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, const int32_t* __restrict__ idx, int64_t k,
+            float* __restrict__ vals, const int32_t* __restrict__ tile_start, uint32_t* __restrict__ err) {
   constexpr int TILE = T * 4 * U;  // elements per tile: T threads x U float4
+  static_assert(TILE == kPassTile, "tile_start is laid out for this tile");
   static_assert(TILE <= 32768, "slot entries are 16-bit offsets from the tile's first index");
   __shared__ __attribute__((aligned(16))) int16_t slot[TILE];
-  __shared__ int64_t s_lo, s_hi;
   const int tid = threadIdx.x;
-  const int c = blockIdx.x;
   const int w = (int)(((unsigned)leader + 1u + blockIdx.y) % (unsigned)w_count);
   const float* __restrict__ gp = g.p[w];
   float* __restrict__ rp = res.p[w];
   float* __restrict__ vrow = vals + (size_t)w * (size_t)k;
+  uint2* s2 = reinterpret_cast<uint2*>(slot);  // four 16-bit slots: one float4 group
 
-  const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
-  int64_t c_hi = c_lo + geom.chunk_elems;
-  if (c_hi > n) c_hi = n;
-  if (c_lo >= c_hi) return;
-
-  // m = number of indices below c_lo (T-way search)
-  if (tid == 0) {
-    s_lo = 0;
-    s_hi = k;
+  const int64_t q_end = n >> 2;  // whole float4 groups end here
+  const int64_t ntiles = q_end > 0 ? (n + TILE - 1) / TILE : 0;  // fewer than four elements: only the scalar tail
+  // The counter that loads are waited on counts them in issue order, so whatever is needed early
+  // is issued early: the bounds of the NEXT tile's indices one tile ahead, this tile's indices
+  // before its big loads; the slot table is then filled while those are in flight.
+  int64_t ti = blockIdx.x;
+  int32_t m0 = 0, m1 = 0;
+  if (ti < ntiles) {
+    m0 = tile_start[ti];
+    m1 = tile_start[ti + 1];
   }
-  __syncthreads();
-  while (true) {
-    const int64_t lo = s_lo, hi = s_hi;
-    const int64_t span = hi - lo;
-    if (span <= 0) break;
-    const int64_t stepw = (span + T - 1) / T;
-    const int64_t p = lo + (int64_t)tid * stepw;
-    const bool below = (p < hi) && ((int64_t)idx[p] < c_lo);
-    const int cnt = __syncthreads_count(below);
-    if (tid == 0) {
-      if (cnt == 0) {
-        s_hi = lo;
-      } else {
-        const int64_t nlo = lo + (int64_t)(cnt - 1) * stepw + 1;
-        int64_t nhi = lo + (int64_t)cnt * stepw;
-        if (nhi > hi) nhi = hi;
-        s_lo = nlo;
-        s_hi = nhi;
-      }
+  for (; ti < ntiles; ti += gridDim.x) {
+    const int64_t ti_next = ti + gridDim.x;
+    int32_t n0 = 0, n1 = 0;
+    if (ti_next < ntiles) {
+      n0 = tile_start[ti_next];
+      n1 = tile_start[ti_next + 1];
     }
-    __syncthreads();
-  }
-  int64_t m = s_lo;
-
-  const int64_t q_end = c_hi >> 2;  // whole float4 groups end here
-  for (int64_t lo = c_lo; lo < c_hi; lo += TILE) {
-    const int64_t hi = (lo + TILE < c_hi) ? lo + TILE : c_hi;
+    int64_t m_base = (int64_t)m0, m_end = (int64_t)m1;
+    if (m_base < 0 || m_end > k || m_end < m_base || m_end - m_base > TILE) {  // idx was not ascending
+      if (tid == 0) atomicOr(err, kErrIndex);
+      m_end = m_base = 0;
+    }
+    const int64_t lo = ti * TILE;
+    // (no branch around the load: beyond the tile's indices it re-reads the last index, unused)
+    const int64_t p0 = m_base + tid;
+    const int32_t i0 = idx[p0 < m_end ? p0 : k - 1];
     const int64_t q0 = (lo >> 2) + tid;
+    const bool full = lo + TILE <= 4 * q_end;
     v4f a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      // groups behind the vector re-read its last group (unused): no branch between or around the
+      // loads, or the compiler would wait for all of them before the first use of an index
       const int64_t q = q0 + u * T;
-      if (q < q_end) {
-        a[u] = load4g<NT, GT>(gp, 4 * q);
-        b[u] = load4<NT>(rp + 4 * q);
-      }
+      const int64_t ql = (full || q < q_end) ? q : q_end - 1;
+      a[u] = load4g<NT, GT>(gp, 4 * ql);
+      b[u] = load4<NT>(rp + 4 * ql);
     }
     // slot[j] = (position in idx) - m_base for a kept element j of this tile, else -1
-    const int64_t m_base = m;
-    uint2* s2 = reinterpret_cast<uint2*>(slot);  // four 16-bit slots
 #pragma unroll
     for (int u = 0; u < U; ++u) s2[tid + u * T] = make_uint2(0xffffffffu, 0xffffffffu);
     __syncthreads();
-    while (true) {
-      const int64_t p = m + tid;
-      int64_t i = hi;
-      if (p < k) i = (int64_t)idx[p];
-      const bool in = i < hi;
-      if (in && i >= lo) slot[i - lo] = (int16_t)(p - m_base);
-      const int cnt = __syncthreads_count(in);
-      m += cnt;
-      if (cnt < T) break;
+    {
+      const int64_t i = (int64_t)i0 - lo;
+      if (p0 < m_end && i >= 0 && i < TILE) slot[i] = (int16_t)tid;
     }
+    for (int64_t p = p0 + T; p < m_end; p += T) {  // dense tiles only (more than T kept of 32 T elements)
+      const int64_t i = (int64_t)idx[p] - lo;
+      if (i >= 0 && i < TILE) slot[i] = (int16_t)(p - m_base);
+    }
+    __syncthreads();
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * T;
-      if (q < q_end) {
+      if (full || q < q_end) {
         const uint2 sl = s2[tid + u * T];
         v4f v;
         v.x = a[u].x + b[u].x;
@@ -1935,9 +2087,11 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, ChunkG
       }
     }
     __syncthreads();  // the slot table is rebuilt for the next tile
+    m0 = n0;
+    m1 = n1;
   }
-  // scalar tail of the vector (n not a multiple of 4): the block that owns the last chunk
-  if (c_hi == n) {
+  // scalar tail of the vector (n not a multiple of 4): the first block
+  if (blockIdx.x == 0) {
     const int64_t j = (n >> 2) * 4 + tid;
     if (j < n) {
       float v = load1g<GT>(gp, j) + rp[j];
