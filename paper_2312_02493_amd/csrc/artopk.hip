@@ -676,7 +676,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   // zeroed region: one block per segment, then the look-back flags
   const size_t o_hall = take((size_t)max_w * kSlotWords * sizeof(uint32_t));
   // one bit per element and worker, in rows of 256 elements, if the vectors are long enough to guess on
-  s.mask_stride = max_n >= c->guess_min_n ? (max_n + 255) / 256 * 4 : 0;
+  s.mask_stride = max_n >= c->guess_min_n ? (max_n + kPassTile - 1) / kPassTile * (kPassTile / 64) : 0;
   const size_t o_mask = take((size_t)max_w * (size_t)s.mask_stride * sizeof(uint64_t));
   const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
                              (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));

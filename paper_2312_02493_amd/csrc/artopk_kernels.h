@@ -492,12 +492,21 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   the blocks in flight read and write one contiguous window of each array
 //   (measured 4 to 10 % faster than one contiguous chunk per block).
 //   Mask layout: for every row of 64 float4 groups four 64-bit words, word e,
-//   bit l <=> element 4 (64 row + l) + e is marked.  The n mod 4 elements behind
-//   the last whole group are counted (in the last chunk) but have no mask bit.
+//   bit l <=> element 4 (64 row + l) + e is marked; the words of a tile are
+//   ordered so that each wave writes the 32 words of its 8 rows as one 256-byte
+//   piece (mask_word() gives the place; 32-byte pieces per row cost the pass 4 %).
+//   The n mod 4 elements behind the last whole group are counted (in the last
+//   chunk) but have no mask bit.
 //   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
 //   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
 //   Variance partials go to partials[y][b][0..1].
 // ---------------------------------------------------------------------------
+// First of the four mask words of row `row` (256 elements) of a vector: tiles of 128 rows, inside a
+// tile row r belongs to wave r mod 16 as its (r / 16)-th row.
+__device__ __forceinline__ int64_t mask_word(int64_t row) {
+  return (row >> 7) * 512 + (row & 15) * 32 + ((row >> 4) & 7) * 4;
+}
+
 template <int STATS, bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
@@ -525,6 +534,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
   constexpr int64_t TQ = (int64_t)T * U;  // groups per tile
   const int64_t ntiles = (q_hi + TQ - 1) / TQ;
   const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
+  static_assert(T == 1024 && U == 8, "mask_word() is laid out for 16 waves x 8 rows");
 
   // One tile: U rows of T float4 groups; the wave's rows start at group qw (a multiple of 64).
   // FULL: every group of the tile lies inside the vector, so nothing is predicated.
@@ -541,6 +551,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       b[u] = load4<NT>(rp + 4 * ql);
     }
     uint32_t marked = 0u;  // of this wave in this tile
+    uint64_t mine = 0ull;  // lane 4 u + e keeps word e of the wave's row u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t q = qw + lane + u * T;
@@ -568,10 +579,13 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       const uint64_t m2 = __ballot(valid && !(__builtin_fabsf(v.z) < gf));
       const uint64_t m3 = __ballot(valid && !(__builtin_fabsf(v.w) < gf));
       marked += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
-      const int64_t qrow = qw + u * T;  // first group of this wave's row
-      if ((FULL || qrow < q_hi) && lane < 4)
-        mrow[(qrow >> 6) * 4 + lane] = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : m3;
+      mine = lane == 4 * u + 0 ? m0 : mine;
+      mine = lane == 4 * u + 1 ? m1 : mine;
+      mine = lane == 4 * u + 2 ? m2 : mine;
+      mine = lane == 4 * u + 3 ? m3 : mine;
     }
+    // rows behind the vector's end get zero words: the mask holds whole tiles
+    if (lane < 4 * U) mrow[mask_word(qw >> 6) + lane] = mine;
     return marked;
   };
 
@@ -1483,8 +1497,8 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
     const int64_t row = slab + tid;
     uint64_t m[4] = {0ull, 0ull, 0ull, 0ull};
     if (row < row_hi) {
-      const uint4 lo2 = reinterpret_cast<const uint4*>(mk + row * 4)[0];
-      const uint4 hi2 = reinterpret_cast<const uint4*>(mk + row * 4)[1];
+      const uint4 lo2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[0];
+      const uint4 hi2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[1];
       m[0] = ((uint64_t)lo2.y << 32) | lo2.x;
       m[1] = ((uint64_t)lo2.w << 32) | lo2.z;
       m[2] = ((uint64_t)hi2.y << 32) | hi2.x;
