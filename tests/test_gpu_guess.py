@@ -206,3 +206,20 @@ def test_guess_literal_leader_rule_every_worker_selects_from_its_mask(guess_on):
     k = wl.k(0.01)
     runner = GpuRunner(w, n, k)
     _run_steps(runner, lambda s, r: wl.gen(s, r), w, n, k, orc.MODE_VAR_TOPK, 3, expect_mask=1)
+
+
+@pytest.mark.parametrize("mode", ["star", "var"])
+def test_guess_kept_elements_clustered_in_two_tiles(guess_on, mode):
+    """All large magnitudes sit in one stretch across a tile border of the fused pass: most tiles
+    mark nothing, two mark thousands, and the sample sees the stretch in a few of its runs only."""
+    n, w, k = 40 * 32768 + 3, 4, 5_000
+    rng = np.random.default_rng(22)
+
+    def gen(step_no, r):
+        x = (1e-3 * (1.0 + 0.3 * r) * rng.standard_normal(n)).astype(np.float32)
+        lo = 18 * 32768 - 2500
+        x[lo:lo + 5200] = (1.0 + rng.random(5200)).astype(np.float32)
+        return x
+
+    runner = GpuRunner(w, n, k)
+    _run_steps(runner, gen, w, n, k, orc.MODE_STAR if mode == "star" else orc.MODE_VAR, 2, expect_mask=None)

@@ -586,3 +586,41 @@ def test_deeper_array_passes_on_a_long_degenerate_vector(case):
             assert run.ctx.select_info()["list_level"] == 0   # the deeper array passes wrote the list
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
+
+
+@pytest.mark.parametrize("where", ["front", "middle", "back", "two_islands", "one_dense_tile"])
+def test_kept_indices_clustered_in_few_tiles(where):
+    """The other workers' streaming pass takes the kept indices tile by tile (32768 elements).
+    Here all of them sit in one or two places, so most tiles have none, some have more indices
+    than the block has threads, and the runs of empty tiles before, between and behind are long;
+    the vector ends in a ragged group whose elements are kept in the `back` case."""
+    n, w = 40 * 32768 + 3, 4
+    rng = np.random.default_rng(21)
+    k = {"front": 900, "middle": 5_000, "back": 700, "two_islands": 2_600, "one_dense_tile": 30_000}[where]
+
+    def gen():
+        x = (1e-3 * rng.standard_normal(n)).astype(np.float32)
+        big = lambda m: (1.0 + rng.random(m)).astype(np.float32) * np.where(rng.random(m) < 0.5, -1.0, 1.0).astype(np.float32)
+        if where == "front":
+            x[:1000] = big(1000)
+        elif where == "middle":                      # straddles the border of tiles 17 and 18
+            lo = 18 * 32768 - 2500
+            x[lo:lo + 5200] = big(5200)
+        elif where == "back":
+            x[-800:] = big(800)
+        elif where == "two_islands":
+            x[5 * 32768 + 100:5 * 32768 + 1500] = big(1400)
+            x[33 * 32768 - 700:33 * 32768 + 700] = big(1400)
+        else:                                        # nearly every element of tile 9 is kept
+            x[9 * 32768 + 50:9 * 32768 + 50 + 31_000] = big(31_000)
+        return x
+
+    run = GpuRunner(w, n, k)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (1, 2):
+        g = [gen() for _ in range(w)]
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
+        run.load_g(g)
+        got = run.step(k, orc.MODE_STAR, step_no)
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
