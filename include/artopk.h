@@ -93,10 +93,14 @@ enum {
  * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes, and,
  * for max_n >= 2^25, max_n / 8 bytes per worker of survivor bit masks.
  *
- * Three environment variables, read here, switch between routes that give
+ * Four environment variables, read here, switch between routes that give
  * identical results (for tests and measurements; unset = the defaults):
  *   ARTOPK_GUESS_MIN_N   shortest vector that gets the sampled threshold guess
  *                        before its fused pass (default 33554432)
+ *   ARTOPK_UPDATE_TILES_MIN_N  shortest vector whose dense update is streamed
+ *                        tile by tile with the values stored behind the zeros
+ *                        (default 4194304); shorter ones are built chunk by
+ *                        chunk in on-chip memory
  *   ARTOPK_LEADER_FIRST  0: also with a leader known up front, run the fused
  *                        pass over all workers first and gather entry by entry
  *   ARTOPK_PASS_A_NT     0: ordinary instead of non-temporal loads and stores

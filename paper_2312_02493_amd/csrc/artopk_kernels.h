@@ -46,6 +46,7 @@
 
 #include <type_traits>
 #include <stdint.h>
+#include <limits.h>
 
 namespace artopk {
 
@@ -2249,25 +2250,30 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
   int64_t m = s_lo;
 
   constexpr int kGroups = kFillChunk / 4 / 256;  // float4 groups per thread and chunk
+  constexpr int64_t kNone = INT64_MAX;           // no index: beyond every chunk
+  // The (index, sum) pairs a chunk starts with are fetched one chunk ahead, before the previous
+  // chunk is streamed out, so that their latency is not part of the chunk's own chain.
+  int64_t ib[BATCH];
+  float sb[BATCH];
+  auto fetch = [&](int64_t from) {
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      // (no branch around the loads: behind the list they re-read its last entry, unused)
+      const int64_t p = from + tid + j * 256;
+      const int64_t pc = p < k ? p : k - 1;
+      const int32_t iv = idx[pc];
+      const float sv = sum[pc];
+      ib[j] = p < k ? (int64_t)iv : kNone;
+      sb[j] = sv;
+    }
+  };
+  fetch(m);
   for (int64_t c = c_begin; c < c_end; ++c) {
     const int64_t lo = c * kFillChunk;
     const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
     const int64_t len = hi - lo;
     const int64_t len4 = len >> 2;
     float4* b4 = reinterpret_cast<float4*>(buf);
-    // the next BATCH x 256 (index, sum) pairs are fetched while the chunk buffer is cleared
-    int64_t ib[BATCH];
-    float sb[BATCH];
-#pragma unroll
-    for (int j = 0; j < BATCH; ++j) {
-      const int64_t p = m + tid + j * 256;
-      ib[j] = hi;
-      sb[j] = 0.0f;
-      if (p < k) {
-        ib[j] = (int64_t)idx[p];
-        sb[j] = sum[p];
-      }
-    }
     for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
     while (true) {
@@ -2282,17 +2288,8 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
         cnt += __syncthreads_count(in);
       }
       m += cnt;
+      fetch(m);  // the next chunk's first pairs, or the rest of this chunk's
       if (cnt < BATCH * 256) break;
-#pragma unroll
-      for (int j = 0; j < BATCH; ++j) {  // a chunk with more kept entries than one batch
-        const int64_t p = m + tid + j * 256;
-        ib[j] = hi;
-        sb[j] = 0.0f;
-        if (p < k) {
-          ib[j] = (int64_t)idx[p];
-          sb[j] = sum[p];
-        }
-      }
     }
     // (the count barrier above also orders the LDS writes before the reads)
     float* __restrict__ up = update + lo;
@@ -2303,6 +2300,74 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
     }
     for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];  // ragged end of the vector
     __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_update_tiles : the same dense update for long vectors: zeros streamed out tile
+// by tile (kPassTile elements, blocks striding over the tiles as in k_pass_mark), and
+// behind a tile's zeros the same block stores sum[m] at the tile's kept indices,
+// idx[tile_start[t] .. tile_start[t+1]) (k_tile_starts has run).  The barrier between
+// the two orders them for the block's stores to one address; the lines are still in
+// the cache when the second store arrives, so memory sees each line once.
+// ---------------------------------------------------------------------------
+template <int T, int U>
+__global__ void __launch_bounds__(T)
+k_update_tiles(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx, const float* __restrict__ sum,
+               int64_t k, const int32_t* __restrict__ tile_start, uint32_t* __restrict__ err) {
+  constexpr int TILE = T * 4 * U;
+  static_assert(TILE == kPassTile, "tile_start is laid out for this tile");
+  const int tid = threadIdx.x;
+  const int64_t q_end = n >> 2;  // whole float4 groups
+  const int64_t ntiles = (n + TILE - 1) / TILE;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  int64_t ti = blockIdx.x;
+  int32_t m0 = 0, m1 = 0;
+  if (ti < ntiles) {
+    m0 = tile_start[ti];
+    m1 = tile_start[ti + 1];
+  }
+  for (; ti < ntiles; ti += gridDim.x) {
+    const int64_t ti_next = ti + gridDim.x;
+    int32_t n0 = 0, n1 = 0;
+    if (ti_next < ntiles) {  // the next tile's bounds, one tile ahead
+      n0 = tile_start[ti_next];
+      n1 = tile_start[ti_next + 1];
+    }
+    int64_t m_base = (int64_t)m0, m_end = (int64_t)m1;
+    if (m_base < 0 || m_end > k || m_end < m_base || m_end - m_base > TILE) {  // idx was not ascending
+      if (tid == 0) atomicOr(err, kErrIndex);
+      m_end = m_base = 0;
+    }
+    const int64_t lo = ti * TILE;
+    // this tile's first T (index, sum) pairs, fetched while the zeros go out
+    // (no branch around the loads: behind the tile's pairs they re-read the last pair, unused)
+    const int64_t p0 = m_base + tid;
+    const int64_t pc = p0 < m_end ? p0 : k - 1;
+    const int32_t i0 = idx[pc];
+    const float s0 = sum[pc];
+    const int64_t q0 = (lo >> 2) + tid;
+    if (lo + TILE <= 4 * q_end) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) store4<false>(update + 4 * (q0 + u * T), zero);
+    } else {  // the last tile: whole groups, then the ragged end
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (q0 + u * T < q_end) store4<false>(update + 4 * (q0 + u * T), zero);
+      const int64_t j = 4 * q_end + tid;
+      if (j < n) update[j] = 0.0f;
+    }
+    __syncthreads();  // the block's zeros are ordered before its values
+    if (p0 < m_end) {
+      const int64_t i = (int64_t)i0 - lo;
+      if (i >= 0 && i < TILE && lo + i < n) update[lo + i] = s0;
+    }
+    for (int64_t p = p0 + T; p < m_end; p += T) {  // dense tiles only
+      const int64_t i = (int64_t)idx[p] - lo;
+      if (i >= 0 && i < TILE && lo + i < n) update[lo + i] = sum[p];
+    }
+    m0 = n0;
+    m1 = n1;
   }
 }
 

@@ -624,3 +624,45 @@ def test_kept_indices_clustered_in_few_tiles(where):
         got = run.step(k, orc.MODE_STAR, step_no)
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
+
+
+@pytest.mark.parametrize("n", [3, 32768, 32769, 5 * 32768 + 2, 300_001])
+def test_dense_update_streamed_tile_by_tile(n, monkeypatch):
+    """The dense update of long, sparsely kept vectors is written as zeros tile by tile with the
+    values stored behind them; switched on here for short vectors.  Covers a vector shorter than
+    a group of four, exact and ragged tile ends, kept entries on tile borders and at both ends,
+    under a rule that gathers entry by entry (VAR) and one that streams the other workers (STAR);
+    also the stand-alone scatter entry point."""
+    import torch
+    monkeypatch.setenv("ARTOPK_UPDATE_TILES_MIN_N", "1")
+    w = 3
+    rng = np.random.default_rng(31)
+    kk = min(n, max(n // 200, 12)) if n > 12 else 2   # few enough kept entries for the streamed form when n is not tiny
+
+    def gen(scale):
+        x = (scale * rng.standard_normal(n)).astype(np.float32)
+        x[0] = 9.0
+        x[n - 1] = -8.0
+        for border in range(32768, n, 32768):
+            x[border - 1] = 7.0
+            if border < n:
+                x[border] = -7.5
+        return x
+
+    for mode in (orc.MODE_VAR, orc.MODE_STAR):
+        run = GpuRunner(w, n, kk)
+        res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+        for step_no in (1, 2):
+            g = [gen(1.0 + 0.5 * r) for r in range(w)]
+            want = orc.step(g, res, kk, mode, step_no=step_no)
+            if mode == orc.MODE_VAR:
+                assert top_two_gap(want.variances) > 1e-4
+            run.load_g(g)
+            got = run.step(kk, mode, step_no)
+            assert_step_matches(got, want, mode)
+            res = want.residual
+        # stand-alone: residual rewrite + dense update from the step's own idx and sum
+        upd = torch.full((n,), float("nan"), dtype=torch.float32, device=run.dev)
+        run.ctx.artopk_scatter_residual(run.res, run.idx[:kk], kk, run.sum[:kk], upd)
+        run.ctx.status()
+        assert np.array_equal(bits(upd.cpu().numpy()), bits(want.update))
