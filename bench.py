@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 1 GiB
 # device copy (profiles/artopk_step_<workload>_rho<rho>.md); None where it was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5", 0.001): 97159.3e6,   # k_pass_a, all 8 workers: 64.0 GB fetched + 33.2 GB written (1 GB of it bit masks)
-    ("c4", 0.01): 5029.0e6,     # k_pass_rest, 3 workers: 3.36 GB fetched + 1.68 GB written
+    ("c5", 0.001): 97127.0e6,   # k_pass_mark, all 8 workers: 64.0 GB fetched + 33.1 GB written (1 GB of it bit masks)
+    ("c4", 0.01): 5006.4e6,     # k_pass_rest, 3 workers: 3.33 GB fetched + 1.68 GB written
 }
 
 
@@ -106,8 +106,10 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     # level-1 events bracket the dominant kernel: the fused pass over all workers (VAR) or,
     # when the leader is known up front, the fused pass over the W-1 other workers
     # (the library says which of the two it ran: an environment switch can turn the second off)
-    star = ctx.select_info()["dominant_workers"] == wl.w - 1 and wl.w > 1
-    dom_name, dom_stage, dom_workers = ("k_pass_rest", "gather", wl.w - 1) if star else ("k_pass_a", "pass_a", wl.w)
+    info = ctx.select_info()
+    star = info["dominant_workers"] == wl.w - 1 and wl.w > 1
+    fused = "k_pass_mark" if info["guessed"] else "k_pass_a"   # the fused pass of the guess / histogram route
+    dom_name, dom_stage, dom_workers = ("k_pass_rest", "gather", wl.w - 1) if star else (fused, "pass_a", wl.w)
     pass_a_ms = [ctx.get_profile()[dom_stage]]  # averaged over the timed steps
     # stage breakdown from a few extra, untimed steps (an event at every stage boundary)
     ctx.set_profile(2)
