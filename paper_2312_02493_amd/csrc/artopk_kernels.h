@@ -5,8 +5,10 @@
 //   k_guess          (long flat vectors) samples g + residual and guesses a lower
 //                    bound on the key of the k-th largest magnitude
 //   k_pass_a         acc = g + residual in place, per-worker variance
-//                    partials, and either per-chunk 12-bit top-digit histograms
-//                    of |acc| or a bit mask of the keys reaching the guessed bound
+//                    partials, and per-chunk 12-bit top-digit histograms of |acc|
+//   k_pass_mark      the same pass behind k_guess: instead of histograms a bit
+//                    mask of the keys reaching the guessed bound; its blocks
+//                    stride over the tiles of the vector
 //   k_hist0          the same histograms alone (stand-alone select, segments,
 //                    after a guess that did not hold)
 //   k_stats          variance partials alone (stand-alone variance)
@@ -23,12 +25,15 @@
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
 //   k_list_hist      digit histograms over the survivor list
+//   k_tile_starts    number of kept indices below every tile of a streaming pass
 //   k_pass_rest      (leader known up front) EF add + gather + residual zeroing
-//                    of all other workers in one streaming pass
+//                    of all other workers in one streaming pass over the tiles
 //   k_sum_rows       ordered sum over the workers' gathered rows
 //   k_gather         vals / ordered sum / residual zeroing at the k indices
 //   k_zero_at        residual zeroing alone
 //   k_update_fill    dense update = zeros + k scattered sums, written once
+//   k_update_tiles   the same for long, sparsely kept vectors: zeros streamed tile
+//                    by tile, the sums stored behind them
 //
 // Keys are the 31 magnitude bits of the float32 (sign cleared), so integer
 // order on keys is the order of |x|.  The radix digits are 12 + 12 + 7 bits.

@@ -666,3 +666,28 @@ def test_dense_update_streamed_tile_by_tile(n, monkeypatch):
         run.ctx.artopk_scatter_residual(run.res, run.idx[:kk], kk, run.sum[:kk], upd)
         run.ctx.status()
         assert np.array_equal(bits(upd.cpu().numpy()), bits(want.update))
+
+
+@pytest.mark.parametrize("guess", [False, True])
+def test_ordinary_loads_and_stores_give_the_same_bits(guess, monkeypatch):
+    """The streaming passes use non-temporal loads and stores by default; the library's switch to
+    ordinary ones must not change a bit, on either selection route and under either kind of leader."""
+    monkeypatch.setenv("ARTOPK_PASS_A_NT", "0")
+    if guess:
+        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    w, n = 3, 6 * 32768 + 77
+    wl = inp.workload(2, n=n, w=w)
+    k = wl.k(0.01)
+    for mode in (orc.MODE_VAR, orc.MODE_STAR):
+        run = GpuRunner(w, n, k)
+        res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+        for step_no in (1, 2):
+            g = [wl.gen(step_no, r) for r in range(w)]
+            want = orc.step(g, res, k, mode, step_no=step_no)
+            if mode == orc.MODE_VAR:
+                assert top_two_gap(want.variances) > 1e-4
+            run.load_g(g)
+            got = run.step(k, mode, step_no)
+            assert run.ctx.select_info()["guessed"] == (1 if guess else 0)
+            assert_step_matches(got, want, mode)
+            res = want.residual
