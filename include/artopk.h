@@ -258,13 +258,15 @@ int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_
                         const float* sum, int64_t k, float eta);
 
 /*
- * Stage timing.  enable = 1 brackets only the dominant kernel of every
- * artopk_step (PASS_A, or GATHER when the leader is known up front) with two
- * HIP events on the context's stream; enable = 2 records
- * an event at every stage boundary; 0 switches it off.  artopk_get_profile synchronises the
- * stream and writes up to `count` stage durations in milliseconds (order: the
- * ARTOPK_PROF_* enum; stages that did not run report 0), each averaged over
- * the calls made since profiling was enabled (at most the 64 most recent).
+ * Stage timing.  enable = 1 records two HIP events on the context's stream
+ * directly around the launch of the dominant kernel of every artopk_step (the
+ * fused pass over all workers, reported as PASS_A; or, when the leader is known
+ * up front, the fused pass over the other workers, reported as GATHER) and
+ * nothing else; enable = 2 records an event at every stage boundary; 0
+ * switches it off.  artopk_get_profile synchronises the stream and writes up
+ * to `count` stage durations in milliseconds (order: the ARTOPK_PROF_* enum;
+ * stages that did not run, or were not bracketed, report 0), each averaged
+ * over the calls made since profiling was enabled (at most the 64 most recent).
  */
 int artopk_set_profile(artopk_ctx* ctx, int32_t enable);
 int artopk_get_profile(artopk_ctx* ctx, float* ms_out, int32_t count);

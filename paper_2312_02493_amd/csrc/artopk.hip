@@ -209,9 +209,17 @@ int stats_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
   return (int)nblk;
 }
 
+// A stage boundary (level 2 only).
 void prof_mark(artopk_ctx* c, int mark) {
-  if (!c->profile) return;
-  if (c->profile_level < 2 && !(mark == c->lvl1_a || mark == c->lvl1_b)) return;  // level 1: dominant kernel only
+  if (!c->profile || c->profile_level < 2) return;
+  if (hipEventRecord(c->ev[c->cur][mark], c->stream) == hipSuccess) c->ev_valid[c->cur][mark] = true;
+}
+
+// Level 1: the two events directly around the launch of the step's dominant kernel, stored as the
+// marks lvl1_a / lvl1_b so that they read as that kernel's stage.
+void prof_dom(artopk_ctx* c, bool end) {
+  if (!c->profile || c->profile_level != 1) return;
+  const int mark = end ? c->lvl1_b : c->lvl1_a;
   if (hipEventRecord(c->ev[c->cur][mark], c->stream) == hipSuccess) c->ev_valid[c->cur][mark] = true;
 }
 
@@ -1005,12 +1013,16 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     // every worker selects on its own vector: on long vectors every worker gets a guessed bound and
     // leaves a mask, as under the variance rule
     ctx->last_guessed = gp.on ? 1 : 0;
+    ctx->lvl1_a = 0;
+    ctx->lvl1_b = 1;
+    if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
+    prof_dom(ctx, false);
     if (gp.on) {
-      enqueue_guess(ctx, gp, gt, rt, (int)w);
       launch_pass_mark(ctx, 0, (int)w, gt, rt, n, geom.chunk_elems);
     } else {
       launch_pass_a(ctx, 0, 2, grid, gt, rt, n, geom, -1);
     }
+    prof_dom(ctx, true);
     prof_mark(ctx, 1);
     if ((rc = enqueue_topk_workers(ctx, rt, w, n, k, s.idx_rows, s.vals, var_out, leader_out, true, gp.on))) return rc;
     hipLaunchKernelGGL(k_copy_i32, dim3((int)((k + 255) / 256)), dim3(256), 0, st, s.idx_rows, s.leader_dev, k,
@@ -1053,9 +1065,11 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;
     enqueue_tile_starts(ctx, idx_out, n, k);
+    prof_dom(ctx, false);
     if (rest > 0) {
       launch_pass_rest(ctx, gt, rt, (int)w, L, n, idx_out, k, vals);
     }
+    prof_dom(ctx, true);
     prof_mark(ctx, 3);
     hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
     HIP_TRY(ctx, hipGetLastError());
@@ -1077,17 +1091,20 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   if (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) {
     const int stats = mode == ARTOPK_VAR_G ? 2 : 1;  // variance of the raw gradient, or of g + residual
     if (segmented) {
+      prof_dom(ctx, false);
       launch_pass_a(ctx, stats, 0, grid, gt, rt, n, geom, -1);
     } else {
       ctx->last_guessed = gp.on ? 1 : 0;
+      if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
+      prof_dom(ctx, false);
       if (gp.on) {
-        enqueue_guess(ctx, gp, gt, rt, (int)w);
         launch_pass_mark(ctx, stats, (int)w, gt, rt, n, geom.chunk_elems);
       } else {
         launch_pass_a(ctx, stats, 2, grid, gt, rt, n, geom, -1);
       }
       slot_by_leader = 1;
     }
+    prof_dom(ctx, true);
     prof_mark(ctx, 1);
     if (segmented) {  // the segment histograms are built on the leader's vector, so it is needed now
       hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, (int)geom.nchunks, n,
@@ -1103,7 +1120,9 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
       leader_args.leader_out = leader_out;
     }
   } else {
+    prof_dom(ctx, false);
     launch_pass_a(ctx, 0, segmented ? 0 : 1, grid, gt, rt, n, geom, leader_host);
+    prof_dom(ctx, true);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);
   }
