@@ -440,14 +440,22 @@ def test_bucketed_layout_16mi_elements():
     assert_step_matches(got, want, orc.MODE_STAR)
 
 
-def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
-    """One VAR step recorded into a HIP graph (through torch's capture) and replayed three times,
+@pytest.mark.parametrize("rule,route", [("var", "histogram"), ("var", "guess"), ("star", "histogram"), ("star", "guess")])
+def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monkeypatch):
+    """One step recorded into a HIP graph (through torch's capture) and replayed three times,
     with host work and synchronisation between the replays: every replay must be the next step
     of the oracle, residual carried.  The step allocates nothing, clears its scratch with a fill
-    kernel (no memset nodes) and takes every data-dependent decision on the device."""
+    kernel (no memset nodes) and takes every data-dependent decision on the device.  Under the
+    round-robin rule the recorded leader (step 1 -> worker 1) is the one every replay uses; the
+    dense update is written in its tile-by-tile form on the guess route."""
     import torch
     import paper_2312_02493_amd as lib
 
+    if route == "guess":
+        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+        monkeypatch.setenv("ARTOPK_UPDATE_TILES_MIN_N", "1")
+    mode_lib = lib.ARTOPK_VAR if rule == "var" else lib.ARTOPK_STAR
+    mode_orc = orc.MODE_VAR if rule == "var" else orc.MODE_STAR
     n, w = 200_003, 4
     wl = inp.workload(2, n=n, w=w)
     k = wl.k(0.01)
@@ -466,7 +474,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
         var = torch.zeros(w, dtype=torch.float64, device=dev)
 
         def step():
-            ctx.artopk_step(g, res, k, lib.ARTOPK_VAR, 1, idx, summed, update, vals_out=vals, leader_out=leader,
+            ctx.artopk_step(g, res, k, mode_lib, 1, idx, summed, update, vals_out=vals, leader_out=leader,
                             var_out=var)
 
         step()  # warm-up outside the capture
@@ -484,8 +492,9 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
 
         want_res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
         for replay in range(3):
-            want = orc.step(g_np, want_res, k, orc.MODE_VAR, step_no=1)
-            assert top_two_gap(want.variances) > 1e-4
+            want = orc.step(g_np, want_res, k, mode_orc, step_no=1)
+            if rule == "var":
+                assert top_two_gap(want.variances) > 1e-4
             graph.replay()
             side.synchronize()
             ctx.status()
@@ -494,7 +503,8 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps():
                 "sum": summed.cpu().numpy(), "update": update.cpu().numpy(),
                 "residual": [r.cpu().numpy() for r in res], "vals": vals.cpu().numpy().reshape(w, k),
             }
-            assert_step_matches(got, want, orc.MODE_VAR)
+            assert_step_matches(got, want, mode_orc)
+            assert ctx.select_info()["guessed"] == (1 if route == "guess" else 0)
             want_res = want.residual
             _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
 
