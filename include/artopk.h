@@ -163,6 +163,10 @@ int artopk_gather_sum(artopk_ctx* ctx, const float* const* acc, int32_t w, int64
  * that consumes the reduced values; second EF equation of Sec. II-C).
  *   residual host array of W device pointers; each holds acc_w on entry and on
  *            exit differs only at the idx positions, which become +0.0
+ *   idx      device, k int32, strictly ascending, each in [0, N) (as the
+ *            selection writes them); a list that is not leaves update
+ *            unspecified and is reported by artopk_status as ARTOPK_ESTATE
+ *            where a kernel notices it
  *   sum      device, k float32
  *   update   device, N float32, fully overwritten: zeros, and sum[m] at idx[m]
  */
