@@ -501,14 +501,19 @@ GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k) {
 
 // Samples the first nvec vectors of (g + residual) into slots 0 .. nvec-1 (cleared beforehand).
 void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const PtrTable& res, int nvec) {
+  // about 128 blocks over all vectors (measured: 8 vectors take 70 us with 64 blocks each, 32 us
+  // with 16; one vector 15 us with 64 blocks, 19 us with 16)
+  int gblocks = 128 / nvec;
+  if (gblocks > 64) gblocks = 64;
+  if (gblocks < 8) gblocks = 8;
   if (c->g_type == ARTOPK_G_BF16)
-    hipLaunchKernelGGL(k_guess<kGBF16>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+    hipLaunchKernelGGL(k_guess<kGBF16>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
                        gp.stride, gp.m_hi);
   else if (c->g_type == ARTOPK_G_F16)
-    hipLaunchKernelGGL(k_guess<kGF16>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+    hipLaunchKernelGGL(k_guess<kGF16>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
                        gp.stride, gp.m_hi);
   else
-    hipLaunchKernelGGL(k_guess<kGF32>, dim3(64, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
+    hipLaunchKernelGGL(k_guess<kGF32>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
                        gp.stride, gp.m_hi);
 }
 
