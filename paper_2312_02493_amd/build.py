@@ -34,7 +34,26 @@ def build(verbose: bool = False) -> str:
     if verbose and proc.stderr.strip():
         sys.stderr.write(proc.stderr)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
+    build_abi_client(hipcc, verbose)
     return LIB_PATH
+
+
+ABI_CLIENT_SRC = os.path.join(ROOT, "tests", "abi_client", "abi_client.cpp")
+ABI_CLIENT_BIN = os.path.join(ROOT, "tests", "abi_client", "abi_client")
+
+
+def build_abi_client(hipcc: str, verbose: bool = False) -> str:
+    """The plain C++ client of the C ABI that tests/test_gpu_abi_client.py runs (no Python, no PyTorch)."""
+    cmd = [hipcc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"), ABI_CLIENT_SRC,
+           "-L", HERE, "-lartopk", "-Wl,-rpath,$ORIGIN/../../paper_2312_02493_amd", "-o", ABI_CLIENT_BIN + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        sys.stderr.write(proc.stdout + proc.stderr)
+        raise RuntimeError("hipcc failed building the ABI client")
+    os.replace(ABI_CLIENT_BIN + ".tmp", ABI_CLIENT_BIN)
+    return ABI_CLIENT_BIN
 
 
 if __name__ == "__main__":
