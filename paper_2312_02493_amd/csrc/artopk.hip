@@ -551,8 +551,6 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
     if (!hist_ready) hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
   }
-  // 4 waves, 16 consecutive elements per lane: best of the shapes measured on the 138 M and 1 G workloads
-  hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
 
   // The remaining kernels take tiles from a counter (or stride over the list), so any grid works:
   // about two blocks per compute unit over all segments together.
@@ -560,22 +558,43 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   // deeper array passes: they run only for segments whose level-1 survivors did not fit the list,
   // which cannot happen if the list takes the whole range
   const bool always_fits = nseg == 1 && (int64_t)pl.desc[0].cap >= pl.desc[0].e_hi - pl.desc[0].e_lo;
-  if (!always_fits) {
-    int cblocks = (int)(pl.max_tiles < per_seg ? pl.max_tiles : per_seg);
-    if (cblocks < 1) cblocks = 1;
-    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
-    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 1);
-  }
+  int cblocks = (int)(pl.max_tiles < per_seg ? pl.max_tiles : per_seg);
+  if (cblocks < 1) cblocks = 1;
 
   int64_t lblocks = (pl.max_cap + 256 * 16 - 1) / (256 * 16);
   if (lblocks > per_seg * 2) lblocks = per_seg * 2;
   if (lblocks < 1) lblocks = 1;
-  if (guessed && hist_ready) hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 1);
-  hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 2);
+  // level 1: ordered compaction of the array (4 waves, 16 consecutive elements per lane: best of the
+  // shapes measured on the 138 M and 1 G workloads); on the guess route the same launch counts
+  // the second digit over a list that was written from the mask
+  if (guessed && hist_ready) {
+    const int64_t b1 = lblocks > pl.max_chunks ? lblocks : pl.max_chunks;
+    hipLaunchKernelGGL(k_level1, dim3((unsigned)b1, nseg), dim3(256), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+  }
+  // A list of many millions of entries (one element in 32 kept, or more) is counted faster by the
+  // lean kernel of its own (99 vs 66 us on 15 M entries: the merged one carries the array pass'
+  // registers), which is worth the launch of an array pass that has nothing to do.
+  const bool long_list = nseg == 1 && (int64_t)pl.desc[0].k * 32 > n;
+  if (always_fits) {
+    hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 2);
+  } else if (long_list) {
+    hipLaunchKernelGGL(k_compact<false>, dim3(cblocks, nseg), dim3(kCompactThreads), 0, st, p, 2, 0);
+    hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 2);
+  } else {  // the same launch is the level-2 array pass where the level-1 survivors did not fit the list
+    const int64_t b2 = lblocks > cblocks ? lblocks : cblocks;
+    hipLaunchKernelGGL(k_level2, dim3((unsigned)b2, nseg), dim3(kCompactThreads), 0, st, p);
+  }
   int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < per_seg ? ltiles : per_seg);
   if (fblocks < 1) fblocks = 1;
-  hipLaunchKernelGGL(k_compact<true>, dim3(fblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 2);
+  if (always_fits) {
+    hipLaunchKernelGGL(k_compact<true>, dim3(fblocks, nseg), dim3(kCompactThreads), 0, st, p, 3, 2);
+  } else {  // the same launch is the level-3 array pass where no list could be written
+    if (fblocks < cblocks) fblocks = cblocks;
+    hipLaunchKernelGGL(k_final, dim3(fblocks, nseg), dim3(kCompactThreads), 0, st, p);
+  }
   HIP_TRY(c, hipGetLastError());
   return ARTOPK_OK;
 }

@@ -25,6 +25,11 @@
 //                    rarely needed deeper array passes and the final pass over
 //                    the survivor list
 //   k_list_hist      digit histograms over the survivor list
+//   k_level1 / k_level2 / k_final   the launches behind the first pick where
+//                    alternatives exist: each does whichever of two jobs the state
+//                    asks for (list histogram or array pass; final pass over the
+//                    list or level-3 array pass writing the outputs), so that the
+//                    rarely needed array passes cost no launches of their own
 //   k_tile_starts    number of kept indices below every tile of a streaming pass
 //   k_pass_rest      (leader known up front) EF add + gather + residual zeroing
 //                    of all other workers in one streaming pass over the tiles
@@ -1282,8 +1287,7 @@ k_pick_mask(SelParams p, LeaderArgs la) {
 // tile instead of one per element.
 // ---------------------------------------------------------------------------
 template <int WAVES, int R>
-__global__ void __launch_bounds__(64 * WAVES)
-k_compact1(SelParams p) {
+__device__ __forceinline__ void compact1_body(const SelParams& p) {
   constexpr int T = 64 * WAVES;
   constexpr int E = 4 * R;             // consecutive elements one lane owns in a tile
   constexpr int WSPAN = 64 * E;        // consecutive elements one wave owns in a tile
@@ -1690,16 +1694,18 @@ constexpr int kCompactRows = 8;
 constexpr int kCompactTile = kCompactThreads * 4 * kCompactRows;  // 16384 elements
 constexpr int kWaveSpan = 64 * 4 * kCompactRows;                  // 2048 elements
 
-template <bool LIST>
-__global__ void __launch_bounds__(kCompactThreads)
-k_compact(SelParams p, int level, int launch_id) {
-  __shared__ uint32_t lh[kHistBins];
+// The pass itself; st is the state derived for it (in shared memory, the same in every thread).
+// DIRECT (array source, level 3): the kept entries go straight to idx_out / vals_row (and are put
+// to +0.0 in zero_vec) instead of into the list, so no pass over the list has to follow.
+template <bool LIST, bool DIRECT>
+__device__ __forceinline__ void compact_body(const SelParams& p, const SegView& sv, const SelState& st, int level,
+                                             int launch_id, uint32_t zero_below) {
+  static_assert(!(LIST && DIRECT), "DIRECT is a form of the array pass");
+  __shared__ uint32_t lh[(!LIST && !DIRECT) ? kHistBins : 4];
   __shared__ uint64_t wave_tot[8];
   __shared__ uint64_t tile_excl;
   __shared__ int64_t tile_sh;
 
-  const SegView sv = seg_view(p, blockIdx.y);
-  SelState* __restrict__ stp = sv.st;
   int64_t n = p.n, e_lo = sv.d.e_lo, e_hi = sv.d.e_hi;
   const uint32_t cap = sv.d.cap;
   uint32_t* __restrict__ hist_next = sv.hist2;
@@ -1717,17 +1723,9 @@ k_compact(SelParams p, int level, int launch_id) {
   const uint32_t lane = lane_id();
 
   // With zeroing on the way: the level-1 pass zeroed the keys above its range if it wrote the
-  // list (stored compact_level 1); the final pass zeroes the kept rest, or all of them otherwise.
-  float* __restrict__ zero_vec = LIST ? p.zero_vec : nullptr;
-  const uint32_t zero_below = (stp->compact_level == 1u && stp->use_mask == 0u) ? stp->hi : kKeyMask;
-  // the level-1 survivors fitted the list: the deeper array passes have nothing to do
-  if (!LIST && (stp->compact_level == 1u || *err)) return;
-  if (LIST && *err) return;
-  // tiles are handed out by a counter, so blocks beyond the number of list tiles are not needed
-  if (LIST && stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
-  __shared__ SelState st;
-  __shared__ uint32_t pick_part[kCompactThreads];
-  derive_state<kCompactThreads>(sv, st, LIST ? 3 : level, pick_part, err);
+  // list (zero_below = the top of that range); the pass that writes idx_out zeroes the kept rest,
+  // or all of them otherwise (zero_below = every key).
+  float* __restrict__ zero_vec = (LIST || DIRECT) ? p.zero_vec : nullptr;
   bool write_out;
   bool do_hist;
   uint32_t quota;
@@ -1737,7 +1735,7 @@ k_compact(SelParams p, int level, int launch_id) {
     if (level == 3 && st.compact_level != 3u) return;
     quota = (level == 3) ? st.need : kQuotaInf;
     write_out = st.compact_level == (uint32_t)level;
-    do_hist = level < 3;
+    do_hist = level < 3 && !DIRECT;
     first_tile = e_lo / kCompactTile;
     ntiles = (e_hi + kCompactTile - 1) / kCompactTile - first_tile;
   } else {
@@ -1882,7 +1880,13 @@ k_compact(SelParams p, int level, int launch_id) {
               if (a || (b && befB < quota)) {
                 const uint32_t pos = befA + (befB < quota ? befB : quota);
                 const int64_t j = tbase + (int64_t)r * 256 + (int64_t)lane * 4 + e;
-                if (!LIST) {
+                if (!LIST && DIRECT) {
+                  if (pos < k_out) {
+                    idx_out[pos] = (int32_t)j;
+                    if (vals_row) vals_row[pos] = __uint_as_float(key[r][e]);
+                    if (zero_vec && ((key[r][e] & kKeyMask) <= zero_below) && j < p.n) zero_vec[j] = 0.0f;
+                  }
+                } else if (!LIST) {
                   if (pos < cap) list[pos] = make_uint2((uint32_t)j, key[r][e]);
                 } else {
                   if (pos < k_out) {
@@ -1917,6 +1921,51 @@ k_compact(SelParams p, int level, int launch_id) {
   }
 }
 
+// Keys the level-1 pass has already put to +0.0 in zero_vec lie above this one (every key if it
+// has not zeroed any).
+__device__ __forceinline__ uint32_t zeroed_above(const SelState* stp) {
+  return (stp->compact_level == 1u && stp->use_mask == 0u) ? stp->hi : kKeyMask;
+}
+
+template <bool LIST>
+__global__ void __launch_bounds__(kCompactThreads)
+k_compact(SelParams p, int level, int launch_id) {
+  __shared__ SelState st;
+  __shared__ uint32_t pick_part[kCompactThreads];
+  const SegView sv = seg_view(p, blockIdx.y);
+  const SelState* __restrict__ stp = sv.st;
+  const uint32_t zero_below = zeroed_above(stp);
+  // the level-1 survivors fitted the list: the deeper array passes have nothing to do
+  if (!LIST && (stp->compact_level == 1u || *p.err)) return;
+  if (LIST && *p.err) return;
+  // tiles are handed out by a counter, so blocks beyond the number of list tiles are not needed
+  if (LIST && stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
+  derive_state<kCompactThreads>(sv, st, LIST ? 3 : level, pick_part, p.err);
+  compact_body<LIST, false>(p, sv, st, level, launch_id, zero_below);
+}
+
+// ---------------------------------------------------------------------------
+// k_final : the last selection kernel where the deeper array passes exist.  If a list
+// was written (at level 1, from the mask, or by the level-2 pass) it is the final
+// pass over the list; if not even the level-2 survivors fitted one (e.g. an all-equal
+// vector) it is the level-3 pass over the array, which then writes the outputs itself.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kCompactThreads)
+k_final(SelParams p) {
+  __shared__ SelState st;
+  __shared__ uint32_t pick_part[kCompactThreads];
+  const SegView sv = seg_view(p, blockIdx.y);
+  const SelState* __restrict__ stp = sv.st;
+  const uint32_t zero_below = zeroed_above(stp);
+  if (*p.err) return;
+  if (stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
+  derive_state<kCompactThreads>(sv, st, 3, pick_part, p.err);
+  if (st.compact_level == 3u)
+    compact_body<false, true>(p, sv, st, 3, 1, zero_below);
+  else
+    compact_body<true, false>(p, sv, st, 3, 2, zero_below);
+}
+
 // ---------------------------------------------------------------------------
 // k_list_hist : histogram of digit `digit` (1 or 2) over the candidates in the
 // survivor list; runs only when the list was written at level 1 or from the
@@ -1924,11 +1973,12 @@ k_compact(SelParams p, int level, int launch_id) {
 // counts it on the way); for digit 2 the digit-1 pick is replayed from hist1 in
 // the prologue.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_list_hist(SelParams p, int digit) {
+template <int T>
+__device__ __forceinline__ void list_hist_body(const SelParams& p, int digit) {
+  constexpr int PER = 8192 / T;  // entries per thread and round
   __shared__ uint32_t lh[kHistBins];
   __shared__ SelState st;
-  __shared__ uint32_t pick_part[256];
+  __shared__ uint32_t pick_part[T];
   const SegView sv = seg_view(p, blockIdx.y);
   if (sv.st->compact_level != 1u || *p.err) return;
   if (digit == 1 && sv.st->use_mask == 0u) return;
@@ -1939,35 +1989,81 @@ k_list_hist(SelParams p, int digit) {
   if (nb > gridDim.x) nb = gridDim.x;
   if (blockIdx.x >= nb) return;
   if (digit == 2) {
-    derive_state<256>(sv, st, 2, pick_part, p.err);
+    derive_state<T>(sv, st, 2, pick_part, p.err);
   } else {
     if (tid == 0) st = *sv.st;
     __syncthreads();
   }
   const int nbins = (int)digit_mask(digit) + 1;
-  for (int b = tid; b < nbins; b += 256) lh[b] = 0u;
+  for (int b = tid; b < nbins; b += T) lh[b] = 0u;
   __syncthreads();
   const uint32_t klo = st.lo, khi = st.hi;
   const int sh = digit_shift(digit);
   const uint32_t dm = digit_mask(digit);
   for (uint64_t base = (uint64_t)blockIdx.x * 8192u; base < cnt; base += (uint64_t)nb * 8192u) {
-    uint32_t key[32];
+    uint32_t key[PER];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const uint64_t q = base + (uint64_t)i * 256u + tid;
+    for (int i = 0; i < PER; ++i) {
+      const uint64_t q = base + (uint64_t)i * T + tid;
       key[i] = q < cnt ? (sv.list[q].y & kKeyMask) : 0xffffffffu;  // the filler is above every range
     }
 #pragma unroll
-    for (int i = 0; i < 32; ++i)
+    for (int i = 0; i < PER; ++i)
       if (key[i] >= klo && key[i] <= khi) atomicAdd(&lh[(key[i] >> sh) & dm], 1u);
   }
   __syncthreads();
   uint32_t* __restrict__ dst = digit == 1 ? sv.hist1 : sv.hist2;
-  for (int b = tid; b < nbins; b += 256) {
+  for (int b = tid; b < nbins; b += T) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&dst[b], v);
   }
 }
+
+__global__ void __launch_bounds__(256)
+k_list_hist(SelParams p, int digit) {
+  list_hist_body<256>(p, digit);
+}
+
+template <int WAVES, int R>
+__global__ void __launch_bounds__(64 * WAVES)
+k_compact1(SelParams p) {
+  compact1_body<WAVES, R>(p);
+}
+
+// ---------------------------------------------------------------------------
+// k_level1 : the kernel behind the first pick on the guess route.  If the list was
+// written from the mask it counts the second digit over the list's candidates; if the
+// guess did not hold it is the level-1 compaction of the histogram route.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_level1(SelParams p) {
+  if (seg_view(p, blockIdx.y).st->use_mask != 0u)
+    list_hist_body<256>(p, 1);
+  else
+    compact1_body<4, 4>(p);
+}
+
+// ---------------------------------------------------------------------------
+// k_level2 : the kernel between the level-1 pass and k_final where the deeper array
+// passes exist.  If a list was written at level 1 (or from the mask) it counts the
+// last digit over the list's candidates; if the level-1 survivors did not fit one it
+// is the level-2 pass over the array (which writes the list if its survivors fit, and
+// counts the last digit on the way).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kCompactThreads)
+k_level2(SelParams p) {
+  const SegView sv = seg_view(p, blockIdx.y);
+  if (*p.err) return;
+  if (sv.st->compact_level == 1u) {
+    list_hist_body<kCompactThreads>(p, 2);
+  } else {
+    __shared__ SelState st;
+    __shared__ uint32_t pick_part[kCompactThreads];
+    derive_state<kCompactThreads>(sv, st, 2, pick_part, p.err);
+    compact_body<false, false>(p, sv, st, 2, 0, kKeyMask);
+  }
+}
+
 
 // ---------------------------------------------------------------------------
 // k_tile_starts : tile_start[t] = number of kept indices below t * kPassTile, for

@@ -572,16 +572,26 @@ def test_leader_by_variance_of_the_raw_gradient(layout, monkeypatch):
     assert disagreements >= 1
 
 
-@pytest.mark.parametrize("case", ["all_equal", "two_valued_many_ties"])
-def test_deeper_array_passes_on_a_long_degenerate_vector(case):
+@pytest.mark.parametrize("case", ["all_equal", "two_valued_many_ties", "one_top_digit", "one_top_digit_guess"])
+def test_deeper_array_passes_on_a_long_degenerate_vector(case, monkeypatch):
     """Vectors short enough to fit the survivor list whole never take the deeper array passes, so
-    they are exercised here on a vector of 5 M elements whose level-1 survivors overflow the list."""
+    they are exercised here on a vector of 5 M elements whose level-1 survivors overflow the list.
+    all_equal / two_valued: not even the level-2 survivors fit, the level-3 array pass writes the
+    outputs itself; one_top_digit: every magnitude shares the top 12 key bits and differs below,
+    so the level-2 array pass writes the list and the final pass reads it (also behind a guess
+    that cannot work, since the whole vector reaches any bound in that digit)."""
     n, w, k = 5_000_003, 2, 60_000
     rng = np.random.default_rng(77)
+    if case == "one_top_digit_guess":
+        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
 
     def gen():
         if case == "all_equal":
             return np.full(n, 0.75, dtype=np.float32)
+        if case.startswith("one_top_digit"):   # [1, 1.0625): exponent and the first four mantissa bits equal
+            x = (1.0 + 0.0625 * rng.random(n)).astype(np.float32)
+            x = np.minimum(x, np.float32(1.0624999))
+            return x * np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
         x = np.where(rng.random(n) < 0.004, 3.0, 1.0).astype(np.float32)  # ~20 k large, 40 k of 4.98 M ties kept
         return x * np.where(rng.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
 
