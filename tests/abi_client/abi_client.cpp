@@ -6,7 +6,8 @@
 //   build:  hipcc -O2 --offload-arch=gfx950 -I include tests/abi_client/abi_client.cpp \
 //                 -L paper_2312_02493_amd -lartopk -Wl,-rpath,$PWD/paper_2312_02493_amd \
 //                 -o tests/abi_client/abi_client        (python -m paper_2312_02493_amd.build does this)
-//   run:    tests/abi_client/abi_client [N] [W] [k]          (exit code 0 = all outputs identical)
+//   run:    tests/abi_client/abi_client [N] [W] [k] [segments]   (exit code 0 = all outputs identical;
+//           with segments > 1 the selection is per segment, k split in proportion to the sizes)
 
 #include <hip/hip_runtime.h>
 
@@ -58,10 +59,25 @@ static float draw(uint64_t& s) {
 int main(int argc, char** argv) {
   const int64_t n = argc > 1 ? std::atoll(argv[1]) : 200003;
   const int32_t w = argc > 2 ? std::atoi(argv[2]) : 3;
-  const int64_t k = argc > 3 ? std::atoll(argv[3]) : (n + 99) / 100;
-  if (n < 1 || w < 1 || w > ARTOPK_MAX_WORKERS || k < 1 || k > n) {
-    std::fprintf(stderr, "usage: abi_client [N] [W] [k]\n");
+  int64_t k = argc > 3 ? std::atoll(argv[3]) : (n + 99) / 100;
+  const int32_t nseg = argc > 4 ? std::atoi(argv[4]) : 1;
+  if (n < 1 || w < 1 || w > ARTOPK_MAX_WORKERS || k < 1 || k > n || nseg < 1 || nseg > n) {
+    std::fprintf(stderr, "usage: abi_client [N] [W] [k] [segments]\n");
     return 2;
+  }
+  // segment table (host memory): equal parts, every part keeping its share of k (at least one)
+  std::vector<int64_t> seg_off(nseg + 1), seg_k(nseg);
+  for (int s = 0; s <= nseg; ++s) seg_off[s] = n * s / nseg;
+  if (nseg > 1) {
+    const int64_t k_asked = k;
+    k = 0;
+    for (int s = 0; s < nseg; ++s) {
+      const int64_t size = seg_off[s + 1] - seg_off[s];
+      seg_k[s] = std::max<int64_t>(1, std::min<int64_t>(size, k_asked * size / n));
+      k += seg_k[s];
+    }
+  } else {
+    seg_k[0] = k;
   }
 
   std::vector<std::vector<float>> g(w, std::vector<float>(n)), res(w, std::vector<float>(n, 0.0f));
@@ -83,7 +99,7 @@ int main(int argc, char** argv) {
   hipStream_t stream;
   HIP_OK(hipStreamCreate(&stream));
   artopk_ctx* ctx = nullptr;
-  if (artopk_create(&ctx, w, n, k, 1, stream) != ARTOPK_OK) {
+  if (artopk_create(&ctx, w, n, k, nseg, stream) != ARTOPK_OK) {
     std::fprintf(stderr, "artopk_create failed\n");
     return 2;
   }
@@ -95,8 +111,9 @@ int main(int argc, char** argv) {
       for (int64_t i = 0; i < n; ++i) g[r][i] = draw(seed);
       HIP_OK(hipMemcpyAsync(g_dev[r], g[r].data(), n * sizeof(float), hipMemcpyHostToDevice, stream));
     }
-    ART_OK(ctx, artopk_step(ctx, g_dev.data(), res_dev.data(), w, n, 1, nullptr, nullptr, k, ARTOPK_STAR, step, 0,
-                            leader_dev, nullptr, idx_dev, vals_dev, sum_dev, update_dev));
+    ART_OK(ctx, artopk_step(ctx, g_dev.data(), res_dev.data(), w, n, nseg, nseg > 1 ? seg_off.data() : nullptr,
+                            nseg > 1 ? seg_k.data() : nullptr, k, ARTOPK_STAR, step, 0, leader_dev, nullptr, idx_dev,
+                            vals_dev, sum_dev, update_dev));
     ART_OK(ctx, artopk_status(ctx));  // synchronises the stream
 
     // ---- the same step on the host, straight from the definitions -------------------------
@@ -107,11 +124,14 @@ int main(int argc, char** argv) {
     std::vector<int32_t> order(n);
     for (int64_t i = 0; i < n; ++i) order[i] = (int32_t)i;
     const std::vector<float>& lead = acc[leader];
-    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {  // larger magnitude first, then lower index
-      const uint32_t ka = bits_of(lead[a]) & 0x7fffffffu, kb = bits_of(lead[b]) & 0x7fffffffu;
-      return ka != kb ? ka > kb : a < b;
-    });
-    std::vector<int32_t> idx(order.begin(), order.begin() + k);
+    std::vector<int32_t> idx;
+    for (int s = 0; s < nseg; ++s) {  // per segment: larger magnitude first, then lower index; keep seg_k[s]
+      std::sort(order.begin() + seg_off[s], order.begin() + seg_off[s + 1], [&](int32_t a, int32_t b) {
+        const uint32_t ka = bits_of(lead[a]) & 0x7fffffffu, kb = bits_of(lead[b]) & 0x7fffffffu;
+        return ka != kb ? ka > kb : a < b;
+      });
+      idx.insert(idx.end(), order.begin() + seg_off[s], order.begin() + seg_off[s] + seg_k[s]);
+    }
     std::sort(idx.begin(), idx.end());
     std::vector<float> sum(k), update(n, 0.0f);
     for (int64_t m = 0; m < k; ++m) {

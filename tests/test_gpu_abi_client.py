@@ -18,6 +18,7 @@ BIN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_client", "ab
     (["1", "1", "1"], {}),                                        # the smallest problem there is
     (["300000", "4", "30000"], {}),                               # one in ten kept
     (["262147", "2", "300"], {"ARTOPK_GUESS_MIN_N": "4096", "ARTOPK_UPDATE_TILES_MIN_N": "1"}),   # guess route
+    (["400001", "3", "4000", "7"], {}),                           # seven segments, selection per segment
 ])
 def test_abi_client(args, env):
     if not os.path.exists(BIN):
