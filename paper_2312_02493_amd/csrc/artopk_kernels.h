@@ -210,7 +210,7 @@ constexpr int kTile = 8192;       // chunk granularity (a quarter of a tile of t
 constexpr int kMaxChunks = 1024;  // chunks per vector range
 static_assert(kSlotWords == kSlotMcount + kMaxChunks, "a slot ends with one count per chunk");
 constexpr int kPassTile = 32768;      // elements per block iteration of the streaming passes (1024 threads x 8 float4)
-constexpr int kMaxPassBlocks = 2048;  // blocks per worker of a streaming pass that strides over tiles
+constexpr int kMaxPassBlocks = 4096;  // blocks per worker of a streaming pass that strides over tiles
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
