@@ -1076,9 +1076,20 @@ __device__ int block_take_leader(const LeaderArgs& la) {
   const int wave = t >> 6, lane = t & 63;
   for (int w = wave; w < la.w_count; w += 16) {
     double s = 0.0, ss = 0.0;
-    for (int b = lane; b < la.nblk; b += 64) {
-      s += la.partials[((size_t)w * la.nblk + b) * 2 + 0];
-      ss += la.partials[((size_t)w * la.nblk + b) * 2 + 1];
+    // (sum, sum of squares) pairs of the worker's blocks; four loads in flight, added in block order
+    const double2* __restrict__ pp = reinterpret_cast<const double2*>(la.partials) + (size_t)w * la.nblk;
+    int b = lane;
+    for (; b + 192 < la.nblk; b += 256) {
+      const double2 a0 = pp[b], a1 = pp[b + 64], a2 = pp[b + 128], a3 = pp[b + 192];
+      s += a0.x; ss += a0.y;
+      s += a1.x; ss += a1.y;
+      s += a2.x; ss += a2.y;
+      s += a3.x; ss += a3.y;
+    }
+    for (; b < la.nblk; b += 64) {
+      const double2 a0 = pp[b];
+      s += a0.x;
+      ss += a0.y;
     }
     s = wave_sum(s);
     ss = wave_sum(ss);
