@@ -1483,8 +1483,10 @@ __device__ __forceinline__ void compact1_body(const SelParams& p) {
 template <int UB>
 __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
   constexpr int T = 1024, WAVES = 16;
+  constexpr uint32_t STAGE = 4096;  // a slab with at most this many marks keeps their indices on chip
   __shared__ uint32_t wtot[WAVES];
   __shared__ uint32_t lh[kHistBins];
+  __shared__ uint32_t sidx[STAGE];
 
   const SegView sv = seg_view(p, blockIdx.y);
   const int c = blockIdx.x;
@@ -1514,16 +1516,25 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
   const int64_t row_hi = (v_end + 255) >> 8;                  // exclusive
 
   uint32_t run = sv.chunk_off[c];  // list position of the next entry of this chunk
+  // a row's four mask words; rows behind the chunk re-read its last row (unused), so that the
+  // loads sit in no branch and the next slab's can be in flight while this slab is worked on
+  auto load_row = [&](int64_t row, uint4& lo2, uint4& hi2) {
+    const int64_t rr = row < row_hi ? row : row_hi - 1;
+    lo2 = reinterpret_cast<const uint4*>(mk + mask_word(rr))[0];
+    hi2 = reinterpret_cast<const uint4*>(mk + mask_word(rr))[1];
+  };
+  uint4 cur_lo = make_uint4(0u, 0u, 0u, 0u), cur_hi = cur_lo;
+  if (row_lo < row_hi) load_row(row_lo + tid, cur_lo, cur_hi);
   for (int64_t slab = row_lo; slab < row_hi; slab += T) {
     const int64_t row = slab + tid;
+    uint4 nxt_lo = cur_lo, nxt_hi = cur_hi;
+    if (slab + T < row_hi) load_row(row + T, nxt_lo, nxt_hi);  // block-uniform condition
     uint64_t m[4] = {0ull, 0ull, 0ull, 0ull};
     if (row < row_hi) {
-      const uint4 lo2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[0];
-      const uint4 hi2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[1];
-      m[0] = ((uint64_t)lo2.y << 32) | lo2.x;
-      m[1] = ((uint64_t)lo2.w << 32) | lo2.z;
-      m[2] = ((uint64_t)hi2.y << 32) | hi2.x;
-      m[3] = ((uint64_t)hi2.w << 32) | hi2.z;
+      m[0] = ((uint64_t)cur_lo.y << 32) | cur_lo.x;
+      m[1] = ((uint64_t)cur_lo.w << 32) | cur_lo.z;
+      m[2] = ((uint64_t)cur_hi.y << 32) | cur_hi.x;
+      m[3] = ((uint64_t)cur_hi.w << 32) | cur_hi.z;
     }
     const uint32_t cnt = (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
     // exclusive prefix of cnt (<= 256) over the lanes and the wave total, from the bit planes of cnt
@@ -1543,7 +1554,9 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
       if (i < wave) pos += wt;
       total += wt;
     }
-    // the row's marked elements in ascending order: by group, then by position in the group
+    // the row's marked elements in ascending order: by group, then by position in the group;
+    // their indices go to the on-chip stage if the slab's marks fit there, else into the list
+    const bool staged = total <= STAGE;  // the same in every thread
     uint64_t any = m[0] | m[1] | m[2] | m[3];
     while (any) {
       const int g = __builtin_ctzll(any);
@@ -1552,7 +1565,11 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         if (m[e] & bit) {
-          if (pos < cap) list[pos].x = (uint32_t)(row * 256 + 4 * g + e);
+          const uint32_t j = (uint32_t)(row * 256 + 4 * g + e);
+          if (staged)
+            sidx[pos - run] = j;
+          else if (pos < cap)
+            list[pos].x = j;
           ++pos;
         }
       }
@@ -1566,19 +1583,24 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
       for (int u = 0; u < UB; ++u) {
         const uint32_t e = e0 + (uint32_t)u * T;
         ok[u] = e < total && run + e < cap;
-        j[u] = ok[u] ? list[run + e].x : 0u;
+        j[u] = !ok[u] ? 0u : staged ? sidx[e] : list[run + e].x;
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) raw[u] = __float_as_uint(xp[j[u]]);
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         if (ok[u]) {
-          list[run + e0 + (uint32_t)u * T].y = raw[u];
+          if (staged)
+            list[run + e0 + (uint32_t)u * T] = make_uint2(j[u], raw[u]);  // the whole entry at once
+          else
+            list[run + e0 + (uint32_t)u * T].y = raw[u];
           atomicAdd(&lh[(raw[u] & kKeyMask) >> 19], 1u);
         }
       }
     }
     run += total;
+    cur_lo = nxt_lo;  // (only here: the copy waits for the loads)
+    cur_hi = nxt_hi;
   }
   // the elements behind the last whole group of four are not in the mask
   if (c_end == n && n_vec < n && tid == 0) {
