@@ -20,7 +20,9 @@
  *   - W is the paper's cluster size N, N here is the number of gradient
  *     elements (the paper's G), k = ceil(c * N) is computed by the caller.
  *   - All data buffers are caller-owned DEVICE memory, float32 / int32 /
- *     float64 as typed, 16-byte aligned, non-overlapping.  Arrays of pointers
+ *     float64 as typed, 16-byte aligned.  A buffer that a call writes must not
+ *     overlap any other buffer of that call (checked on the host: ARTOPK_EINVAL);
+ *     buffers that are only read may overlap each other.  Arrays of pointers
  *     (g, residual, acc, x) and the segment tables are HOST memory and are
  *     read before the call returns.
  *   - Work is enqueued on the stream given to artopk_create(); calls return
@@ -89,36 +91,57 @@ enum {
  * max_w workers, max_n elements, max_k kept entries and max_segments segments.
  * *out is set only on success.  A context serialises nothing by itself: calls
  * on one context must not overlap (its scratch is shared between them), and
- * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.3 MiB per worker plus
- * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes, and,
- * for max_n >= 2^25, max_n / 8 bytes per worker of survivor bit masks.
- *
- * Four environment variables, read here, switch between routes that give
- * identical results (for tests and measurements; unset = the defaults):
- *   ARTOPK_GUESS_MIN_N   shortest vector that gets the sampled threshold guess
- *                        before its fused pass (default 33554432)
- *   ARTOPK_UPDATE_TILES_MIN_N  shortest vector whose dense update is streamed
- *                        tile by tile with the values stored behind the zeros
- *                        (default 4194304); shorter ones are built chunk by
- *                        chunk in on-chip memory
- *   ARTOPK_LEADER_FIRST  0: also with a leader known up front, run the fused
- *                        pass over all workers first and gather entry by entry
- *   ARTOPK_PASS_A_NT     0: ordinary instead of non-temporal loads and stores
- *                        in the streaming passes
+ * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.4 MiB per worker plus
+ * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes plus
+ * max_n / 8 bytes per worker of survivor bit masks.  The library reads no environment
+ * variable and keeps no state outside its contexts.
  */
 int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
                   int32_t max_segments, void* hip_stream);
 
+/*
+ * Switches between routes that give identical results (for tests and tuning; the
+ * defaults are what the measurements chose).  Takes effect from the next call on
+ * the context.  ARTOPK_EINVAL for an unknown key or a value outside its range.
+ *   ARTOPK_OPT_GUESS_MIN_N        shortest flat vector that gets the sampled
+ *                                 threshold guess before its fused pass;
+ *                                 1 .. 2^31 (2^31 = never), default 33554432
+ *   ARTOPK_OPT_UPDATE_TILES_MIN_N shortest vector whose dense update is
+ *                                 streamed tile by tile with the values stored
+ *                                 behind the zeros, shorter ones are built
+ *                                 chunk by chunk in on-chip memory; 1 .. 2^31,
+ *                                 default 4194304
+ *   ARTOPK_OPT_LEADER_FIRST       1 (default): with a leader known up front run
+ *                                 its pass and the selection first, then one
+ *                                 fused pass over the other workers; 0: the
+ *                                 fused pass over all workers first and an
+ *                                 entry-by-entry gather, as under the variance rule
+ *   ARTOPK_OPT_NONTEMPORAL        1 (default): non-temporal loads and stores in
+ *                                 the streaming passes; 0: ordinary ones
+ */
+enum {
+  ARTOPK_OPT_GUESS_MIN_N = 0,
+  ARTOPK_OPT_UPDATE_TILES_MIN_N = 1,
+  ARTOPK_OPT_LEADER_FIRST = 2,
+  ARTOPK_OPT_NONTEMPORAL = 3
+};
+int artopk_set_option(artopk_ctx* ctx, int32_t key, int64_t value);
+int artopk_get_option(const artopk_ctx* ctx, int32_t key, int64_t* value_out);
+
 /* Free the scratch.  The caller must have synchronised the stream. */
 int artopk_destroy(artopk_ctx* ctx);
 
-/* Text of the last error on this context (never NULL). */
+/* Text of the last error on this context (never NULL); with ctx = NULL the text of the
+ * calling thread's last failed call that takes no context. */
 const char* artopk_last_error(const artopk_ctx* ctx);
 
 /*
  * Synchronise the context's stream and report whether any kernel since the
  * last call flagged an internal error (ARTOPK_ESTATE) -- e.g. a bounded wait
- * that expired.  Returns ARTOPK_OK otherwise.
+ * that expired.  Returns ARTOPK_OK otherwise.  The error word is sticky: while it
+ * is set the selection kernels of later calls return at once, so every output
+ * produced between the failing kernel and the artopk_status call that reports
+ * (and clears) it is unspecified.
  */
 int artopk_status(artopk_ctx* ctx);
 

@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK, ARTOPK_VAR_G = 0, 1, 2, 3, 4
 ARTOPK_G_F32, ARTOPK_G_BF16, ARTOPK_G_F16 = 0, 1, 2
+ARTOPK_OPT_GUESS_MIN_N, ARTOPK_OPT_UPDATE_TILES_MIN_N, ARTOPK_OPT_LEADER_FIRST, ARTOPK_OPT_NONTEMPORAL = 0, 1, 2, 3
 PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 
 _SYMBOLS = (
@@ -21,6 +22,7 @@ _SYMBOLS = (
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
     "artopk_apply_update", "artopk_topk_workers", "artopk_select_info", "artopk_step_g16",
+    "artopk_set_option", "artopk_get_option",
 )
 
 
@@ -68,6 +70,9 @@ def load_library():
     lib.artopk_apply_update.argtypes = [vp, vp, i64, vp, vp, i64, C.c_float]
     lib.artopk_set_profile.argtypes = [vp, i32]
     lib.artopk_get_profile.argtypes = [vp, C.POINTER(C.c_float), i32]
+    lib.artopk_select_info.argtypes = [vp, C.POINTER(i32), i32]
+    lib.artopk_set_option.argtypes = [vp, i32, i64]
+    lib.artopk_get_option.argtypes = [vp, i32, C.POINTER(i64)]
     lib.artopk_version.restype = i32
     for name in _SYMBOLS:
         if name not in ("artopk_last_error", "artopk_version"):
@@ -134,6 +139,14 @@ class Context:
     def set_profile(self, level: int):
         """0 off, 1 events around pass A only, 2 events at every stage boundary."""
         self._check(self._lib.artopk_set_profile(self._h, int(level)))
+
+    def set_option(self, key: int, value: int):
+        self._check(self._lib.artopk_set_option(self._h, int(key), int(value)))
+
+    def get_option(self, key: int) -> int:
+        out = C.c_int64()
+        self._check(self._lib.artopk_get_option(self._h, int(key), C.byref(out)))
+        return int(out.value)
 
     def select_info(self) -> dict:
         buf = (C.c_int32 * 5)()

@@ -8,6 +8,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -28,7 +29,7 @@ constexpr int kPassRestThreads = 1024, kPassRestU = 8;
 struct Scratch {
   // zeroed before every select: one kSegWords block per segment, then the look-back flags
   uint32_t* h_all = nullptr;      // [max_w][kSlotWords] whole-vector histograms of the fused pass, guess sample
-  uint64_t* mask = nullptr;       // [max_w][mask_stride] survivor bit masks of the fused pass (if guessing is on)
+  uint64_t* mask = nullptr;       // [max_w][mask_stride] survivor bit masks of the fused pass
   int64_t mask_stride = 0;        // 64-bit words per worker
   uint32_t* zero_base = nullptr;  // [max_seg][kSegWords]
   uint64_t* flags = nullptr;      // [max_tiles][kNumLookback], directly behind the blocks
@@ -36,7 +37,7 @@ struct Scratch {
   // not zeroed
   uint32_t* S = nullptr;          // [max_w * kMaxChunks + max_seg][4096] per-chunk suffix histograms
   uint32_t* chunk_off = nullptr;  // [kMaxChunks + max_seg]
-  double* partials = nullptr;     // [max_w][kMaxPassBlocks][2]
+  double* partials = nullptr;     // [max_w][kMaxPassBlocks][3] per-block moments (or [2] sums)
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
   uint32_t* err_dev = nullptr;
@@ -100,18 +101,18 @@ struct artopk_ctx {
   int cur = 0;          // ring slot of the call being recorded
   char err[512] = {0};
 };
+static_assert(sizeof(artopk_ctx::err) == 512, "fail() writes up to 512 bytes");
 
 namespace {
 
-char g_noctx_err[] = "";
+// error text of calls that have no context (artopk_last_error(NULL) returns it)
+thread_local char g_noctx_err[512] = {0};
 
 int fail(artopk_ctx* c, int code, const char* fmt, ...) {
-  if (c) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(c->err, sizeof(c->err), fmt, ap);
-    va_end(ap);
-  }
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(c ? c->err : g_noctx_err, sizeof(g_noctx_err), fmt, ap);
+  va_end(ap);
   return code;
 }
 
@@ -169,6 +170,54 @@ int check_segments(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_of
   return ARTOPK_OK;
 }
 
+// The buffers of one call as byte ranges.  Ranges that are only read may overlap each other
+// (two workers may share a gradient buffer); a range that is written must not overlap any other.
+class RangeSet {
+ public:
+  void add(const void* p, size_t bytes, bool written, const char* name, int index = -1) {
+    if (!p || bytes == 0 || n_ >= kCap) return;
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    r_[n_++] = Range{lo, lo + bytes, written, name, index};
+  }
+  void add_table(const void* const* tab, int32_t w, size_t bytes, bool written, const char* name) {
+    for (int i = 0; i < w; ++i) add(tab[i], bytes, written, name, i);
+  }
+  // ARTOPK_OK, or ARTOPK_EINVAL with the first offending pair in the context's error text
+  int check(artopk_ctx* c) {
+    std::sort(r_, r_ + n_, [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    int far_any = -1, far_written = -1;  // ranges seen so far that reach furthest: any, written ones
+    for (int i = 0; i < n_; ++i) {
+      const int other = r_[i].written ? far_any : far_written;
+      if (other >= 0 && r_[i].lo < r_[other].hi) {
+        char a[48], b[48];
+        label(r_[other], a, sizeof(a));
+        label(r_[i], b, sizeof(b));
+        return fail(c, ARTOPK_EINVAL, "buffers %s and %s overlap", a, b);
+      }
+      if (far_any < 0 || r_[i].hi > r_[far_any].hi) far_any = i;
+      if (r_[i].written && (far_written < 0 || r_[i].hi > r_[far_written].hi)) far_written = i;
+    }
+    return ARTOPK_OK;
+  }
+
+ private:
+  struct Range {
+    uintptr_t lo, hi;
+    bool written;
+    const char* name;
+    int index;
+  };
+  static void label(const Range& r, char* out, size_t cap) {
+    if (r.index >= 0)
+      snprintf(out, cap, "%s[%d]", r.name, r.index);
+    else
+      snprintf(out, cap, "%s", r.name);
+  }
+  static constexpr int kCap = 2 * kMaxW + 8;
+  Range r_[kCap];
+  int n_ = 0;
+};
+
 PtrTable make_table(const float* const* tab, int32_t w) {
   PtrTable t;
   for (int i = 0; i < kMaxW; ++i) t.p[i] = (i < w) ? const_cast<float*>(tab[i]) : nullptr;
@@ -197,12 +246,12 @@ ChunkGeom make_geom(int64_t e_lo, int64_t e_hi, int64_t max_chunks = kMaxChunks,
 }
 
 // Blocks per worker of the stand-alone variance kernel.
-int stats_blocks(const artopk_ctx* c, int32_t w, int64_t n) {
+int stats_blocks(int num_cu, int32_t w, int64_t n) {
   const int64_t n4 = n >> 2;
   const int64_t tile = 256 * kPassAUnroll;
   int64_t ntile = (n4 + tile - 1) / tile;
   if (ntile < 1) ntile = 1;
-  int64_t want = ((int64_t)c->num_cu * 8 + w - 1) / w;
+  int64_t want = ((int64_t)num_cu * 8 + w - 1) / w;
   if (want < 1) want = 1;
   int64_t nblk = ntile < want ? ntile : want;
   if (nblk > kMaxChunks) nblk = kMaxChunks;
@@ -705,10 +754,6 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return ARTOPK_EHIP;
   }
   c->num_cu = cus > 0 ? cus : 256;
-  if (const char* e_nt = getenv("ARTOPK_PASS_A_NT")) c->pass_a_nt = atoi(e_nt) != 0;
-  if (const char* e_lf = getenv("ARTOPK_LEADER_FIRST")) c->leader_first = atoi(e_lf) != 0;
-  if (const char* e_g = getenv("ARTOPK_GUESS_MIN_N")) c->guess_min_n = atoll(e_g);
-  if (const char* e_u = getenv("ARTOPK_UPDATE_TILES_MIN_N")) c->update_tiles_min_n = atoll(e_u);
 
   Scratch& s = c->s;
   // list capacity: every key above the range (< k of them) plus a generous share of candidates
@@ -732,14 +777,14 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   };
   // zeroed region: one block per segment, then the look-back flags
   const size_t o_hall = take((size_t)max_w * kSlotWords * sizeof(uint32_t));
-  // one bit per element and worker, in rows of 256 elements, if the vectors are long enough to guess on
-  s.mask_stride = max_n >= c->guess_min_n ? (max_n + kPassTile - 1) / kPassTile * (kPassTile / 64) : 0;
+  // one bit per element and worker, in rows of 256 elements (whole tiles of the fused pass)
+  s.mask_stride = (max_n + kPassTile - 1) / kPassTile * (kPassTile / 64);
   const size_t o_mask = take((size_t)max_w * (size_t)s.mask_stride * sizeof(uint64_t));
   const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
                              (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
   const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
   const size_t o_coff = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
-  const size_t o_part = take((size_t)max_w * kMaxPassBlocks * 2 * sizeof(double));
+  const size_t o_part = take((size_t)max_w * kMaxPassBlocks * 3 * sizeof(double));
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
@@ -757,7 +802,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   }
   char* base = static_cast<char*>(c->slab);
   s.h_all = reinterpret_cast<uint32_t*>(base + o_hall);
-  s.mask = s.mask_stride ? reinterpret_cast<uint64_t*>(base + o_mask) : nullptr;
+  s.mask = reinterpret_cast<uint64_t*>(base + o_mask);
   s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
   // kSegWords is even, so the flags stay 8-byte aligned
   s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
@@ -825,6 +870,42 @@ int artopk_set_profile(artopk_ctx* ctx, int32_t enable) {
   return ARTOPK_OK;
 }
 
+int artopk_set_option(artopk_ctx* ctx, int32_t key, int64_t value) {
+  if (!ctx) return ARTOPK_EINVAL;
+  switch (key) {
+    case ARTOPK_OPT_GUESS_MIN_N:
+      if (value < 1 || value > (1ll << 31)) return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_GUESS_MIN_N outside [1, 2^31]");
+      ctx->guess_min_n = value;
+      return ARTOPK_OK;
+    case ARTOPK_OPT_UPDATE_TILES_MIN_N:
+      if (value < 1 || value > (1ll << 31))
+        return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_UPDATE_TILES_MIN_N outside [1, 2^31]");
+      ctx->update_tiles_min_n = value;
+      return ARTOPK_OK;
+    case ARTOPK_OPT_LEADER_FIRST:
+      if (value != 0 && value != 1) return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_LEADER_FIRST takes 0 or 1");
+      ctx->leader_first = value != 0;
+      return ARTOPK_OK;
+    case ARTOPK_OPT_NONTEMPORAL:
+      if (value != 0 && value != 1) return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_NONTEMPORAL takes 0 or 1");
+      ctx->pass_a_nt = value != 0;
+      return ARTOPK_OK;
+    default:
+      return fail(ctx, ARTOPK_EINVAL, "unknown option %d", key);
+  }
+}
+
+int artopk_get_option(const artopk_ctx* ctx, int32_t key, int64_t* value_out) {
+  if (!ctx || !value_out) return ARTOPK_EINVAL;
+  switch (key) {
+    case ARTOPK_OPT_GUESS_MIN_N: *value_out = ctx->guess_min_n; return ARTOPK_OK;
+    case ARTOPK_OPT_UPDATE_TILES_MIN_N: *value_out = ctx->update_tiles_min_n; return ARTOPK_OK;
+    case ARTOPK_OPT_LEADER_FIRST: *value_out = ctx->leader_first ? 1 : 0; return ARTOPK_OK;
+    case ARTOPK_OPT_NONTEMPORAL: *value_out = ctx->pass_a_nt ? 1 : 0; return ARTOPK_OK;
+    default: return ARTOPK_EINVAL;
+  }
+}
+
 // Reads back the selection state of segment 0 as the last step left it.
 int artopk_select_info(artopk_ctx* ctx, int32_t* info_out, int32_t count) {
   if (!ctx || !info_out || count < 0) return ARTOPK_EINVAL;
@@ -878,8 +959,15 @@ int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n
   if (rc) return rc;
   if ((rc = check_ptr_table(ctx, x, w, "x"))) return rc;
   if (!var_out) return fail(ctx, ARTOPK_EINVAL, "var_out is NULL");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(x), w, (size_t)n * 4, false, "x");
+    rs.add(var_out, (size_t)w * 8, true, "var_out");
+    rs.add(argmax_out, 4, true, "argmax_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const PtrTable tab = make_table(x, w);
-  const int nblk = stats_blocks(ctx, w, n);
+  const int nblk = stats_blocks(ctx->num_cu, w, n);
   Scratch& s = ctx->s;
   hipLaunchKernelGGL((k_stats<true, true>), dim3(nblk, w), dim3(256), 0, ctx->stream, tab, n, s.partials);
   hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, ctx->stream, s.partials, (int)w, nblk, n, s.var_scratch,
@@ -895,6 +983,12 @@ int artopk_select_topk(artopk_ctx* ctx, const float* acc, int64_t n, int32_t nse
   if (!acc || !aligned16(acc)) return fail(ctx, ARTOPK_EINVAL, "acc is NULL or not 16-byte aligned");
   if (!idx_out) return fail(ctx, ARTOPK_EINVAL, "idx_out is NULL");
   if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
+  {
+    RangeSet rs;
+    rs.add(acc, (size_t)n * 4, false, "acc");
+    rs.add(idx_out, (size_t)k * 4, true, "idx_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const float* one[1] = {acc};
   const PtrTable tab = make_table(one, 1);
   prof_begin(ctx);
@@ -918,6 +1012,14 @@ int artopk_gather_sum(artopk_ctx* ctx, const float* const* acc, int32_t w, int64
   if (rc) return rc;
   if ((rc = check_ptr_table(ctx, acc, w, "acc"))) return rc;
   if (!idx || !sum_out) return fail(ctx, ARTOPK_EINVAL, "idx or sum_out is NULL");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(acc), w, (size_t)n * 4, false, "acc");
+    rs.add(idx, (size_t)k * 4, false, "idx");
+    rs.add(vals_out, (size_t)w * (size_t)k * 4, true, "vals_out");
+    rs.add(sum_out, (size_t)k * 4, true, "sum_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const PtrTable tab = make_table(acc, w);
   return enqueue_gather(ctx, tab, w, n, idx, k, vals_out, sum_out, false);
 }
@@ -929,9 +1031,18 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
   if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
   if (!idx || !sum || !update) return fail(ctx, ARTOPK_EINVAL, "idx, sum or update is NULL");
   if (!aligned16(update)) return fail(ctx, ARTOPK_EINVAL, "update is not 16-byte aligned");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(residual), w, (size_t)n * 4, true, "residual");
+    rs.add(idx, (size_t)k * 4, false, "idx");
+    rs.add(sum, (size_t)k * 4, false, "sum");
+    rs.add(update, (size_t)n * 4, true, "update");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const PtrTable tab = make_table(residual, w);
   const int blocks = (int)((k + 255) / 256);
   hipLaunchKernelGGL(k_zero_at, dim3(blocks), dim3(256), 0, ctx->stream, tab, (int)w, n, idx, k, ctx->s.err_dev);
+  HIP_TRY(ctx, hipGetLastError());
   return enqueue_update_fill(ctx, update, n, idx, sum, k);
 }
 
@@ -941,6 +1052,15 @@ int artopk_topk_workers(artopk_ctx* ctx, const float* const* acc, int32_t w, int
   if (rc) return rc;
   if ((rc = check_ptr_table(ctx, acc, w, "acc"))) return rc;
   if (!idx_out) return fail(ctx, ARTOPK_EINVAL, "idx_out is NULL");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(acc), w, (size_t)n * 4, false, "acc");
+    rs.add(idx_out, (size_t)w * (size_t)k * 4, true, "idx_out");
+    rs.add(vals_out, (size_t)w * (size_t)k * 4, true, "vals_out");
+    rs.add(sqnorm_out, (size_t)w * 8, true, "sqnorm_out");
+    rs.add(argmax_out, 4, true, "argmax_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const PtrTable tab = make_table(acc, w);
   return enqueue_topk_workers(ctx, tab, w, n, k, idx_out, vals_out ? vals_out : ctx->s.vals, sqnorm_out,
                               argmax_out, false);
@@ -952,11 +1072,18 @@ int artopk_compression_gain(artopk_ctx* ctx, const float* const* residual, int32
   if (rc) return rc;
   if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
   if (!vals || !gain_out) return fail(ctx, ARTOPK_EINVAL, "vals or gain_out is NULL");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(residual), w, (size_t)n * 4, false, "residual");
+    rs.add(vals, (size_t)w * (size_t)k * 4, false, "vals");
+    rs.add(gain_out, (size_t)w * 8, true, "gain_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   Scratch& s = ctx->s;
   const PtrTable rtab = make_table(residual, w);
   PtrTable vtab;
   for (int i = 0; i < kMaxW; ++i) vtab.p[i] = (i < w) ? const_cast<float*>(vals) + (size_t)i * (size_t)k : nullptr;
-  const int nblk_res = stats_blocks(ctx, w, n);
+  const int nblk_res = stats_blocks(ctx->num_cu, w, n);
   int nblk_vals = (int)((k + 256 * 16 - 1) / (256 * 16));
   if (nblk_vals < 1) nblk_vals = 1;
   if (nblk_vals > kMaxChunks / 2) nblk_vals = kMaxChunks / 2;
@@ -977,6 +1104,13 @@ int artopk_apply_update(artopk_ctx* ctx, float* weights, int64_t n, const int32_
   int rc = check_common(ctx, 1, n, k);
   if (rc) return rc;
   if (!weights || !idx || !sum) return fail(ctx, ARTOPK_EINVAL, "weights, idx or sum is NULL");
+  {
+    RangeSet rs;
+    rs.add(weights, (size_t)n * 4, true, "weights");
+    rs.add(idx, (size_t)k * 4, false, "idx");
+    rs.add(sum, (size_t)k * 4, false, "sum");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   const int blocks = (int)((k + 255) / 256);
   hipLaunchKernelGGL(k_apply_update, dim3(blocks), dim3(256), 0, ctx->stream, weights, n, idx, sum, k, eta,
                      ctx->s.err_dev);
@@ -1002,6 +1136,18 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   if (!idx_out || !sum_out || !update_out) return fail(ctx, ARTOPK_EINVAL, "idx_out, sum_out or update_out is NULL");
   if (!aligned16(update_out)) return fail(ctx, ARTOPK_EINVAL, "update_out is not 16-byte aligned");
   if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(g), w, (size_t)n * (g_type == ARTOPK_G_F32 ? 4 : 2), false, "g");
+    rs.add_table(reinterpret_cast<const void* const*>(residual), w, (size_t)n * 4, true, "residual");
+    rs.add(leader_out, 4, true, "leader_out");
+    rs.add(var_out, (size_t)w * 8, true, "var_out");
+    rs.add(idx_out, (size_t)k * 4, true, "idx_out");
+    rs.add(vals_out, (size_t)w * (size_t)k * 4, true, "vals_out");
+    rs.add(sum_out, (size_t)k * 4, true, "sum_out");
+    rs.add(update_out, (size_t)n * 4, true, "update_out");
+    if ((rc = rs.check(ctx))) return rc;
+  }
   int leader_host = -1;
   if (mode == ARTOPK_STAR) {
     leader_host = (int)(step % (uint64_t)w);

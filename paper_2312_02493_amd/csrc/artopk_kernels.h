@@ -214,6 +214,124 @@ constexpr int kMaxPassBlocks = 4096;  // blocks per worker of a streaming pass t
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+// ---------------------------------------------------------------------------
+// Variance in one pass that no single element can spoil.  Every thread keeps
+// the count and the float64 sums of (x - c) and (x - c)^2 of the values it sees,
+// with c the mean of the first four of them (its own shift: for any data, a
+// thread that sees m values has (mean - c)^2 <= (m / 4) variance, so the usual
+// cancellation of the one-pass formula is bounded by the few hundred values a
+// thread handles and does not grow with an outlier).  Threads, waves, blocks
+// and finally the blocks' partials (count, mean, M2 = sum of squared deviations
+// from the mean) are then combined pairwise with the update formula for merged
+// samples, M2 = M2a + M2b + (mean_b - mean_a)^2 na nb / (na + nb), which adds
+// only non-negative terms.  The order of every merge is fixed by the launch
+// shape, so the result is reproducible.
+// ---------------------------------------------------------------------------
+struct Moments {
+  double n, mean, m2;
+};
+
+__device__ __forceinline__ void moments_merge(Moments& a, const Moments& b) {
+  if (b.n > 0.0) {
+    if (a.n > 0.0) {
+      const double nt = a.n + b.n;
+      const double d = b.mean - a.mean;
+      const double f = b.n / nt;
+      a.mean += d * f;
+      a.m2 += b.m2 + d * d * a.n * f;
+      a.n = nt;
+    } else {
+      a = b;
+    }
+  }
+}
+
+struct VarAcc {
+  double c = 0.0, s = 0.0, ss = 0.0;
+  uint32_t cnt = 0u;
+  __device__ __forceinline__ void add4(const v4f t) {
+    if (cnt == 0u) c = (((double)t.x + (double)t.y) + ((double)t.z + (double)t.w)) * 0.25;
+    const double d0 = (double)t.x - c, d1 = (double)t.y - c, d2 = (double)t.z - c, d3 = (double)t.w - c;
+    s += (d0 + d1) + (d2 + d3);
+    ss = fma(d0, d0, ss);
+    ss = fma(d1, d1, ss);
+    ss = fma(d2, d2, ss);
+    ss = fma(d3, d3, ss);
+    cnt += 4u;
+  }
+  __device__ __forceinline__ void add1(float x) {
+    if (cnt == 0u) c = (double)x;
+    const double d = (double)x - c;
+    s += d;
+    ss = fma(d, d, ss);
+    cnt += 1u;
+  }
+  __device__ __forceinline__ Moments moments() const {
+    Moments m{0.0, 0.0, 0.0};
+    if (cnt != 0u) {
+      const double dn = (double)cnt;
+      m.n = dn;
+      m.mean = c + s / dn;
+      m.m2 = ss - s * s / dn;
+      if (m.m2 < 0.0) m.m2 = 0.0;  // rounding only (NaN stays NaN)
+    }
+    return m;
+  }
+};
+
+// Merges the threads' moments of a block of T threads (all of them call it); thread 0 returns
+// the block's.  `red` is 3 * (T / 64) doubles of shared memory.
+template <int T>
+__device__ __forceinline__ Moments block_moments(const VarAcc& acc, double* red) {
+  Moments m = acc.moments();
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {  // lane l takes lane l + off: pairs, then pairs of pairs, ...
+    Moments o;
+    o.n = __shfl_down(m.n, off, 64);
+    o.mean = __shfl_down(m.mean, off, 64);
+    o.m2 = __shfl_down(m.m2, off, 64);
+    if ((threadIdx.x & 63) + off < 64) moments_merge(m, o);
+  }
+  const int tid = threadIdx.x;
+  if ((tid & 63) == 0) {
+    red[3 * (tid >> 6) + 0] = m.n;
+    red[3 * (tid >> 6) + 1] = m.mean;
+    red[3 * (tid >> 6) + 2] = m.m2;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int i = 1; i < T / 64; ++i) {
+      const Moments o{red[3 * i + 0], red[3 * i + 1], red[3 * i + 2]};
+      moments_merge(m, o);
+    }
+  }
+  return m;
+}
+
+// Variance of worker w from its blocks' moments partials[w][0 .. nblk)[3]; the 64 lanes of one
+// wave call it, lane 0 returns the variance (population: M2 / n).
+__device__ __forceinline__ double wave_variance(const double* __restrict__ partials, int w, int nblk) {
+  const int lane = threadIdx.x & 63;
+  const double* __restrict__ pp = partials + (size_t)w * nblk * 3;
+  Moments m{0.0, 0.0, 0.0};
+  for (int b = lane; b < nblk; b += 64) {
+    const Moments o{pp[3 * b + 0], pp[3 * b + 1], pp[3 * b + 2]};
+    moments_merge(m, o);
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    Moments o;
+    o.n = __shfl_down(m.n, off, 64);
+    o.mean = __shfl_down(m.mean, off, 64);
+    o.m2 = __shfl_down(m.m2, off, 64);
+    if (lane + off < 64) moments_merge(m, o);
+  }
+  double v = m.n > 0.0 ? m.m2 / m.n : 0.0;
+  if (!(v > 0.0)) v = (v != v) ? v : 0.0;
+  return v;
+}
+
+
 template <bool NT>
 __device__ __forceinline__ v4f load4(const float* p) {
   return NT ? __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p)) : *reinterpret_cast<const v4f*>(p);
@@ -353,9 +471,9 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 //   HIST: 0 nothing for the selection, 1 only for worker `hist_worker` (slot 0),
 //         2 for every worker (worker w in slot w): per-chunk top-digit suffix
 //         histograms S[slot][c] and the whole-vector histogram of the slot.
-//   STATS: 0 none, 1 variance partials of acc, 2 of the raw gradient g.  They
-//   use the shift c_w = g_w[0]: per block the sums of (x - c_w) and (x - c_w)^2
-//   in float64, written to partials[w][c][0..1].
+//   STATS: 0 none, 1 variance partials of acc, 2 of the raw gradient g: the
+//   block's (count, mean, sum of squared deviations) in float64, written to
+//   partials[w][c][0..2] (see Moments).
 //   NT: non-temporal loads of g and stores of acc.
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
@@ -367,7 +485,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   constexpr bool LH = HIST != 0;  // an LDS histogram is built
   __shared__ __attribute__((aligned(16))) uint32_t lh[LH ? kHistBins : 4];
   __shared__ uint32_t red_u[LH ? T : 1];
-  __shared__ double red[2][T / 64];
+  __shared__ double red[3 * (T / 64)];
 
   // with a known leader its blocks (the only ones that work for the selection) are dispatched first
   const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
@@ -386,8 +504,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     __syncthreads();
   }
 
-  double cshift = 0.0, s = 0.0, ss = 0.0;
-  if (STATS) cshift = (double)load1g<GT>(gp, 0);  // g is never written, so every block sees the same shift
+  VarAcc va;
 
   const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
   int64_t c_hi = c_lo + geom.chunk_elems;
@@ -419,16 +536,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
         store4<NT>(rp + 4 * q, v);
-        if (STATS) {
-          const v4f t = STATS == 2 ? a[u] : v;  // the raw gradient, or the error-fed value
-          double d0 = (double)t.x - cshift, d1 = (double)t.y - cshift, d2 = (double)t.z - cshift,
-                 d3 = (double)t.w - cshift;
-          s += (d0 + d1) + (d2 + d3);
-          ss = fma(d0, d0, ss);
-          ss = fma(d1, d1, ss);
-          ss = fma(d2, d2, ss);
-          ss = fma(d3, d3, ss);
-        }
+        if (STATS) va.add4(STATS == 2 ? a[u] : v);  // the raw gradient, or the error-fed value
         if (LH) {
           if (do_hist) {
             atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
@@ -453,11 +561,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       const float gj = load1g<GT>(gp, j);
       const float v = gj + rp[j];
       rp[j] = v;
-      if (STATS) {
-        const double d = (double)(STATS == 2 ? gj : v) - cshift;
-        s += d;
-        ss = fma(d, d, ss);
-      }
+      if (STATS) va.add1(STATS == 2 ? gj : v);
       if (LH) {
         if (do_hist) atomicAdd(&lh[(__float_as_uint(v) & kKeyMask) >> 19], 1u);
       }
@@ -465,23 +569,13 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   }
 
   if (STATS) {
-    s = wave_sum(s);
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) {
-      red[0][tid >> 6] = s;
-      red[1][tid >> 6] = ss;
+    const Moments m = block_moments<T>(va, red);
+    if (tid == 0) {
+      double* __restrict__ out = partials + ((size_t)w * nblk + c) * 3;
+      out[0] = m.n;
+      out[1] = m.mean;
+      out[2] = m.m2;
     }
-  }
-  __syncthreads();
-  if (STATS && tid == 0) {
-    double S1 = 0.0, S2 = 0.0;
-#pragma unroll
-    for (int i = 0; i < T / 64; ++i) {
-      S1 += red[0][i];
-      S2 += red[1][i];
-    }
-    partials[((size_t)w * nblk + c) * 2 + 0] = S1;
-    partials[((size_t)w * nblk + c) * 2 + 1] = S2;
   }
   if (LH) {
     if (do_hist) {
@@ -510,7 +604,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   chunk) but have no mask bit.
 //   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
 //   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
-//   Variance partials go to partials[y][b][0..1].
+//   Variance partials go to partials[y][b][0..2].
 // ---------------------------------------------------------------------------
 // First of the four mask words of row `row` (256 elements) of a vector: tiles of 128 rows, inside a
 // tile row r belongs to wave r mod 16 as its (r / 16)-th row.
@@ -522,7 +616,7 @@ template <int STATS, bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
             uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials) {
-  __shared__ double red[2][T / 64];
+  __shared__ double red[3 * (T / 64)];
   const int w = blockIdx.y;
   const int bx = blockIdx.x;
   const int nblk = gridDim.x;
@@ -538,8 +632,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
   const uint32_t gkey = slot[kSlotCtrl + 1];
   const float gf = gkey != kNoGuess ? __uint_as_float(gkey) : __builtin_inff();
 
-  double cshift = 0.0, s = 0.0, ss = 0.0;
-  if (STATS) cshift = (double)load1g<GT>(gp, 0);  // g is never written, so every block sees the same shift
+  VarAcc va;
 
   const int64_t q_hi = n >> 2;  // whole float4 groups of the vector
   constexpr int64_t TQ = (int64_t)T * U;  // groups per tile
@@ -574,16 +667,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
         store4<NT>(rp + 4 * q, v);
-        if (STATS) {
-          const v4f t = STATS == 2 ? a[u] : v;  // the raw gradient, or the error-fed value
-          double d0 = (double)t.x - cshift, d1 = (double)t.y - cshift, d2 = (double)t.z - cshift,
-                 d3 = (double)t.w - cshift;
-          s += (d0 + d1) + (d2 + d3);
-          ss = fma(d0, d0, ss);
-          ss = fma(d1, d1, ss);
-          ss = fma(d2, d2, ss);
-          ss = fma(d3, d3, ss);
-        }
+        if (STATS) va.add4(STATS == 2 ? a[u] : v);  // the raw gradient, or the error-fed value
       }
       const uint64_t m0 = __ballot(valid && !(__builtin_fabsf(v.x) < gf));
       const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
@@ -612,57 +696,45 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       const float gj = load1g<GT>(gp, j);
       const float v = gj + rp[j];
       rp[j] = v;
-      if (STATS) {
-        const double d = (double)(STATS == 2 ? gj : v) - cshift;
-        s += d;
-        ss = fma(d, d, ss);
-      }
+      if (STATS) va.add1(STATS == 2 ? gj : v);
       if (!(__builtin_fabsf(v) < gf)) atomicAdd(&mcount[(n - 1) / chunk_elems], 1u);
     }
   }
 
   if (STATS) {
-    s = wave_sum(s);
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) {
-      red[0][tid >> 6] = s;
-      red[1][tid >> 6] = ss;
-    }
-    __syncthreads();
+    const Moments m = block_moments<T>(va, red);
     if (tid == 0) {
-      double S1 = 0.0, S2 = 0.0;
-#pragma unroll
-      for (int i = 0; i < T / 64; ++i) {
-        S1 += red[0][i];
-        S2 += red[1][i];
-      }
-      partials[((size_t)w * nblk + bx) * 2 + 0] = S1;
-      partials[((size_t)w * nblk + bx) * 2 + 1] = S2;
+      double* __restrict__ out = partials + ((size_t)w * nblk + bx) * 3;
+      out[0] = m.n;
+      out[1] = m.mean;
+      out[2] = m.m2;
     }
   }
 }
 
 // ---------------------------------------------------------------------------
-// k_stats : per-block sums of (x - c) and (x - c)^2 of read-only vectors in
-// float64, c = x[0] with SHIFT (variance) or 0 (sum of squares).  grid = (nblk, W).
+// k_stats : statistics of read-only vectors in float64.  grid = (nblk, W).
+//   SHIFT (variance): the block's moments (count, mean, sum of squared
+//   deviations) to partials[w][b][0..2], see Moments.
+//   !SHIFT (sum of squares): the block's sum of x and of x^2 to partials[w][b][0..1].
 // VEC reads float4 groups (rows must be 16-byte aligned).
 // ---------------------------------------------------------------------------
 template <bool SHIFT, bool VEC>
 __global__ void __launch_bounds__(256)
 k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
-  __shared__ double red[2][4];
+  __shared__ double red[3 * 4];
   const int w = blockIdx.y, bx = blockIdx.x, nblk = gridDim.x, tid = threadIdx.x;
   const float* __restrict__ xp = x.p[w];
-  const double c = SHIFT ? (double)xp[0] : 0.0;
-  double s = 0.0, ss = 0.0;
+  VarAcc va;               // SHIFT
+  double s = 0.0, ss = 0.0;  // !SHIFT
   const int64_t n4 = VEC ? (n >> 2) : 0;
   if (VEC) {
-    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(xp);
+    const v4f* __restrict__ x4 = reinterpret_cast<const v4f*>(xp);
     const int64_t tile = 256 * kPassAUnroll;
     const int64_t ntile = (n4 + tile - 1) / tile;
     for (int64_t t = bx; t < ntile; t += nblk) {
       const int64_t q0 = t * tile + tid;
-      float4 a[kPassAUnroll];
+      v4f a[kPassAUnroll];
 #pragma unroll
       for (int u = 0; u < kPassAUnroll; ++u) {
         const int64_t q = q0 + u * 256;
@@ -672,32 +744,50 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
       for (int u = 0; u < kPassAUnroll; ++u) {
         const int64_t q = q0 + u * 256;
         if (q < n4) {
-          double d0 = (double)a[u].x - c, d1 = (double)a[u].y - c, d2 = (double)a[u].z - c, d3 = (double)a[u].w - c;
-          s += (d0 + d1) + (d2 + d3);
-          ss = fma(d0, d0, ss);
-          ss = fma(d1, d1, ss);
-          ss = fma(d2, d2, ss);
-          ss = fma(d3, d3, ss);
+          if (SHIFT) {
+            va.add4(a[u]);
+          } else {
+            const double d0 = (double)a[u].x, d1 = (double)a[u].y, d2 = (double)a[u].z, d3 = (double)a[u].w;
+            s += (d0 + d1) + (d2 + d3);
+            ss = fma(d0, d0, ss);
+            ss = fma(d1, d1, ss);
+            ss = fma(d2, d2, ss);
+            ss = fma(d3, d3, ss);
+          }
         }
       }
     }
   }
   // elements not covered by whole float4 groups (all of them when the row is not 16-byte aligned)
   for (int64_t j = n4 * 4 + (int64_t)bx * 256 + tid; j < n; j += (int64_t)nblk * 256) {
-    const double d = (double)xp[j] - c;
-    s += d;
-    ss = fma(d, d, ss);
+    if (SHIFT) {
+      va.add1(xp[j]);
+    } else {
+      const double d = (double)xp[j];
+      s += d;
+      ss = fma(d, d, ss);
+    }
   }
-  s = wave_sum(s);
-  ss = wave_sum(ss);
-  if ((tid & 63) == 0) {
-    red[0][tid >> 6] = s;
-    red[1][tid >> 6] = ss;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    partials[((size_t)w * nblk + bx) * 2 + 0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-    partials[((size_t)w * nblk + bx) * 2 + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  if (SHIFT) {
+    const Moments m = block_moments<256>(va, red);
+    if (tid == 0) {
+      double* __restrict__ out = partials + ((size_t)w * nblk + bx) * 3;
+      out[0] = m.n;
+      out[1] = m.mean;
+      out[2] = m.m2;
+    }
+  } else {
+    s = wave_sum(s);
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) {
+      red[tid >> 6] = s;
+      red[4 + (tid >> 6)] = ss;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      partials[((size_t)w * nblk + bx) * 2 + 0] = (red[0] + red[1]) + (red[2] + red[3]);
+      partials[((size_t)w * nblk + bx) * 2 + 1] = (red[4] + red[5]) + (red[6] + red[7]);
+    }
   }
 }
 
@@ -774,8 +864,8 @@ k_apply_update(float* __restrict__ weights, int64_t n, const int32_t* __restrict
 }
 
 // ---------------------------------------------------------------------------
-// k_leader : one block of 1024 threads.  Sums the per-block partials of every
-// worker in a fixed order, var_w = (SS - S*S/n)/n, leader = first argmax.
+// k_leader : one block of 1024 threads.  Merges the per-block moments of every
+// worker in a fixed order, var_w = M2 / n, leader = first argmax.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
 k_leader(const double* __restrict__ partials, int w_count, int nblk, int64_t n,
@@ -783,17 +873,8 @@ k_leader(const double* __restrict__ partials, int w_count, int nblk, int64_t n,
          int32_t* __restrict__ leader_dev, int32_t* __restrict__ leader_out) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   for (int w = wave; w < w_count; w += 16) {
-    double s = 0.0, ss = 0.0;
-    for (int b = lane; b < nblk; b += 64) {
-      s += partials[((size_t)w * nblk + b) * 2 + 0];
-      ss += partials[((size_t)w * nblk + b) * 2 + 1];
-    }
-    s = wave_sum(s);
-    ss = wave_sum(ss);
+    const double v = wave_variance(partials, w, nblk);
     if (lane == 0) {
-      const double dn = (double)n;
-      double v = (ss - s * s / dn) / dn;
-      if (!(v > 0.0)) v = (v != v) ? v : 0.0;
       var_scratch[w] = v;
       if (var_out) var_out[w] = v;
     }
@@ -1075,28 +1156,8 @@ __device__ int block_take_leader(const LeaderArgs& la) {
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
   for (int w = wave; w < la.w_count; w += 16) {
-    double s = 0.0, ss = 0.0;
-    // (sum, sum of squares) pairs of the worker's blocks; four loads in flight, added in block order
-    const double2* __restrict__ pp = reinterpret_cast<const double2*>(la.partials) + (size_t)w * la.nblk;
-    int b = lane;
-    for (; b + 192 < la.nblk; b += 256) {
-      const double2 a0 = pp[b], a1 = pp[b + 64], a2 = pp[b + 128], a3 = pp[b + 192];
-      s += a0.x; ss += a0.y;
-      s += a1.x; ss += a1.y;
-      s += a2.x; ss += a2.y;
-      s += a3.x; ss += a3.y;
-    }
-    for (; b < la.nblk; b += 64) {
-      const double2 a0 = pp[b];
-      s += a0.x;
-      ss += a0.y;
-    }
-    s = wave_sum(s);
-    ss = wave_sum(ss);
+    const double v = wave_variance(la.partials, w, la.nblk);
     if (lane == 0) {
-      const double dn = (double)la.n;
-      double v = (ss - s * s / dn) / dn;
-      if (!(v > 0.0)) v = (v != v) ? v : 0.0;
       la.var_scratch[w] = v;
       if (la.var_out) la.var_out[w] = v;
     }

@@ -61,8 +61,9 @@ int main(int argc, char** argv) {
   const int32_t w = argc > 2 ? std::atoi(argv[2]) : 3;
   int64_t k = argc > 3 ? std::atoll(argv[3]) : (n + 99) / 100;
   const int32_t nseg = argc > 4 ? std::atoi(argv[4]) : 1;
+  const bool short_routes = argc > 5 && std::atoi(argv[5]) != 0;  // take the long-vector routes on this short one
   if (n < 1 || w < 1 || w > ARTOPK_MAX_WORKERS || k < 1 || k > n || nseg < 1 || nseg > n) {
-    std::fprintf(stderr, "usage: abi_client [N] [W] [k] [segments]\n");
+    std::fprintf(stderr, "usage: abi_client [N] [W] [k] [segments] [long-vector routes: 0|1]\n");
     return 2;
   }
   // segment table (host memory): equal parts, every part keeping its share of k (at least one)
@@ -102,6 +103,10 @@ int main(int argc, char** argv) {
   if (artopk_create(&ctx, w, n, k, nseg, stream) != ARTOPK_OK) {
     std::fprintf(stderr, "artopk_create failed\n");
     return 2;
+  }
+  if (short_routes) {
+    ART_OK(ctx, artopk_set_option(ctx, ARTOPK_OPT_GUESS_MIN_N, 4096));
+    ART_OK(ctx, artopk_set_option(ctx, ARTOPK_OPT_UPDATE_TILES_MIN_N, 1));
   }
 
   uint64_t seed = 0x9e3779b97f4a7c15ull;

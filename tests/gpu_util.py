@@ -6,6 +6,23 @@ import numpy as np
 from oracle import artopk_oracle as orc
 
 
+# Route switches applied to every context these helpers create (name -> value; a test changes
+# them with monkeypatch.setitem, so that they revert when it ends).  The routes give identical
+# results, so every parity test may run on any of them.
+OPTIONS = {}
+_OPTION_KEYS = {"guess_min_n": 0, "update_tiles_min_n": 1, "leader_first": 2, "nontemporal": 3}
+
+
+def make_context(*args, **kwargs):
+    """lib.Context(...) with the current OPTIONS applied through artopk_set_option."""
+    import paper_2312_02493_amd as lib
+
+    ctx = lib.Context(*args, **kwargs)
+    for name, value in OPTIONS.items():
+        ctx.set_option(_OPTION_KEYS[name], value)
+    return ctx
+
+
 def bits(x):
     return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
 
@@ -21,7 +38,7 @@ class GpuRunner:
         self.w, self.n = w, n
         dev = torch.device("cuda:0")
         self.dev = dev
-        self.ctx = lib.Context(w, n, max_k, max_segments)
+        self.ctx = make_context(w, n, max_k, max_segments)
         self.g = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(w)]
         self.res = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(w)]
         self.update = torch.empty(n, dtype=torch.float32, device=dev)

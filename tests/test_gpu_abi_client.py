@@ -13,16 +13,16 @@ pytestmark = pytest.mark.gpu
 BIN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_client", "abi_client")
 
 
-@pytest.mark.parametrize("args,env", [
-    (["200003", "3"], {}),                                        # histogram route, ragged length
-    (["1", "1", "1"], {}),                                        # the smallest problem there is
-    (["300000", "4", "30000"], {}),                               # one in ten kept
-    (["262147", "2", "300"], {"ARTOPK_GUESS_MIN_N": "4096", "ARTOPK_UPDATE_TILES_MIN_N": "1"}),   # guess route
-    (["400001", "3", "4000", "7"], {}),                           # seven segments, selection per segment
+@pytest.mark.parametrize("args", [
+    ["200003", "3"],                                        # histogram route, ragged length
+    ["1", "1", "1"],                                        # the smallest problem there is
+    ["300000", "4", "30000"],                               # one in ten kept
+    ["262147", "2", "300", "1", "1"],                       # guess route (switched on through artopk_set_option)
+    ["400001", "3", "4000", "7"],                           # seven segments, selection per segment
 ])
-def test_abi_client(args, env):
+def test_abi_client(args):
     if not os.path.exists(BIN):
         pytest.skip("tests/abi_client/abi_client is not built (python -m paper_2312_02493_amd.build builds it)")
-    run = subprocess.run([BIN, *args], capture_output=True, text=True, timeout=120, env={**os.environ, **env})
+    run = subprocess.run([BIN, *args], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0, run.stdout + run.stderr
     assert "abi_client: ok" in run.stdout

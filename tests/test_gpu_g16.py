@@ -11,7 +11,8 @@ import pytest
 
 import artopk_inputs as inp
 from oracle import artopk_oracle as orc
-from gpu_util import GpuRunner, assert_step_matches, top_two_gap
+from tests import gpu_util
+from tests.gpu_util import GpuRunner, assert_step_matches, top_two_gap
 
 pytestmark = pytest.mark.gpu
 
@@ -122,7 +123,7 @@ def test_g16_f16_subnormals_infinities_and_signed_zero():
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
 def test_g16_guess_route(kind, monkeypatch):
-    monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     n, w = (1 << 20) + 2, 3
     wl = inp.workload(1, n=n, w=w)
     runner = _run(kind, wl, n, w, wl.k(0.001), orc.MODE_STAR, 2)

@@ -7,7 +7,7 @@ lower bound on the key of the k-th largest magnitude, lets the fused pass mark
 the elements that reach it, and builds the survivor list from the marks.  The
 guess can be wrong in both directions; then the library must notice and take
 the full route.  The route is switched on here for short vectors through the
-environment switch the library reads when a context is created.
+library's option ARTOPK_OPT_GUESS_MIN_N (artopk_set_option).
 """
 
 import math
@@ -17,14 +17,15 @@ import pytest
 
 import artopk_inputs as inp
 from oracle import artopk_oracle as orc
-from gpu_util import GpuRunner, assert_step_matches, top_two_gap
+from tests import gpu_util
+from tests.gpu_util import GpuRunner, assert_step_matches, top_two_gap
 
 pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture
 def guess_on(monkeypatch):
-    monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
 
 
 def _sample_positions(n):

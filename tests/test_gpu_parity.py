@@ -7,6 +7,7 @@ import pytest
 
 import artopk_inputs as inp
 from oracle import artopk_oracle as orc
+from tests import gpu_util
 from tests.gpu_util import GpuRunner, assert_step_matches, bits, top_two_gap
 
 pytestmark = pytest.mark.gpu
@@ -83,6 +84,7 @@ def _one_step(g, res, k, mode=orc.MODE_FIXED, leader=0, step_no=0):
     want = orc.step(g, res, k, mode, step_no=step_no, fixed_leader=leader)
     got = run.step(k, mode, step_no, fixed_leader=leader)
     assert_step_matches(got, want, mode)
+    got["info"] = run.ctx.select_info()
     return got, want
 
 
@@ -389,13 +391,13 @@ def test_generic_path_with_host_known_leader(monkeypatch):
     """STAR / FIXED normally take the leader-first pipeline; the library's switch back to the
     generic pipeline (histogram for the leader only inside the all-worker pass, scattered gather)
     must give the same bits."""
-    monkeypatch.setenv("ARTOPK_LEADER_FIRST", "0")
+    monkeypatch.setitem(gpu_util.OPTIONS, "leader_first", 0)
     rng = np.random.default_rng(42)
     w, n, k = 4, 450_003, 4500
     g = [rng.standard_normal(n).astype(np.float32) for _ in range(w)]
     res = [(rng.standard_normal(n) * 0.4).astype(np.float32) for _ in range(w)]
-    run = GpuRunner(w, n, k)            # the context reads the switch when it is created
-    monkeypatch.delenv("ARTOPK_LEADER_FIRST")
+    run = GpuRunner(w, n, k)
+    assert run.ctx.get_option(2) == 0   # ARTOPK_OPT_LEADER_FIRST
     for step_no in (5, 6):
         run.load_g(g)
         run.load_res(res)
@@ -452,8 +454,8 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
     import paper_2312_02493_amd as lib
 
     if route == "guess":
-        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
-        monkeypatch.setenv("ARTOPK_UPDATE_TILES_MIN_N", "1")
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+        monkeypatch.setitem(gpu_util.OPTIONS, "update_tiles_min_n", 1)
     mode_lib = lib.ARTOPK_VAR if rule == "var" else lib.ARTOPK_STAR
     mode_orc = orc.MODE_VAR if rule == "var" else orc.MODE_STAR
     n, w = 200_003, 4
@@ -463,7 +465,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
     side = torch.cuda.Stream()
     g_np = [wl.gen(1, r) for r in range(w)]
     with torch.cuda.stream(side):
-        ctx = lib.Context(w, n, k, 1, stream=side.cuda_stream)
+        ctx = gpu_util.make_context(w, n, k, 1, stream=side.cuda_stream)
         g = [torch.from_numpy(a).to(dev) for a in g_np]
         res = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(w)]
         idx = torch.empty(k, dtype=torch.int32, device=dev)
@@ -543,7 +545,7 @@ def test_leader_by_variance_of_the_raw_gradient(layout, monkeypatch):
     Sec. III-B's "largest gradient variance").  Gradient scales rotate over the steps while the
     residuals go stale, so the raw-gradient rule and the error-fed rule disagree on the way."""
     if layout == "flat_guess":
-        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     n, w = 120_001, 4
     wl = inp.workload(1, n=n, w=w)
     seg_off = seg_k = None
@@ -583,7 +585,7 @@ def test_deeper_array_passes_on_a_long_degenerate_vector(case, monkeypatch):
     n, w, k = 5_000_003, 2, 60_000
     rng = np.random.default_rng(77)
     if case == "one_top_digit_guess":
-        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
 
     def gen():
         if case == "all_equal":
@@ -654,7 +656,7 @@ def test_dense_update_streamed_tile_by_tile(n, monkeypatch):
     under a rule that gathers entry by entry (VAR) and one that streams the other workers (STAR);
     also the stand-alone scatter entry point."""
     import torch
-    monkeypatch.setenv("ARTOPK_UPDATE_TILES_MIN_N", "1")
+    monkeypatch.setitem(gpu_util.OPTIONS, "update_tiles_min_n", 1)
     w = 3
     rng = np.random.default_rng(31)
     kk = min(n, max(n // 200, 12)) if n > 12 else 2   # few enough kept entries for the streamed form when n is not tiny
@@ -692,9 +694,9 @@ def test_dense_update_streamed_tile_by_tile(n, monkeypatch):
 def test_ordinary_loads_and_stores_give_the_same_bits(guess, monkeypatch):
     """The streaming passes use non-temporal loads and stores by default; the library's switch to
     ordinary ones must not change a bit, on either selection route and under either kind of leader."""
-    monkeypatch.setenv("ARTOPK_PASS_A_NT", "0")
+    monkeypatch.setitem(gpu_util.OPTIONS, "nontemporal", 0)
     if guess:
-        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     w, n = 3, 6 * 32768 + 77
     wl = inp.workload(2, n=n, w=w)
     k = wl.k(0.01)
@@ -711,3 +713,108 @@ def test_ordinary_loads_and_stores_give_the_same_bits(guess, monkeypatch):
             assert run.ctx.select_info()["guessed"] == (1 if guess else 0)
             assert_step_matches(got, want, mode)
             res = want.residual
+
+
+# ------------------------------------------------------------------ variance against awkward data
+@pytest.mark.parametrize("case", ["outlier_first", "outlier_first_four", "common_offset", "outlier_last"])
+@pytest.mark.parametrize("route", ["stand_alone", "step_histogram", "step_guess"])
+def test_variance_is_not_spoilt_by_one_element_or_an_offset(case, route, monkeypatch):
+    """The per-worker variance (Sec. III-B leader rule) must stay within 1e-5 of the two-pass
+    float64 definition whatever sits at the start of a vector: an element a million standard
+    deviations out at index 0 (or the first four, or the last one), or a common offset a
+    thousand standard deviations large.  Checked through artopk_variance and through a variance-
+    rule step on both selection routes (the step's fused passes accumulate their own sums)."""
+    import torch
+
+    rng = np.random.default_rng(77)
+    w, n, k = 3, 1_200_003, 1200
+    sigma = [1.0e-3, 1.2e-3, 1.5e-3]
+    g = [(rng.standard_normal(n) * s).astype(np.float32) for s in sigma]
+    if case == "outlier_first":
+        for r in range(w):
+            g[r][0] = np.float32(1.0e6 * sigma[r])
+    elif case == "outlier_first_four":
+        for r in range(w):
+            g[r][:4] = np.float32(-1.0e6 * sigma[r])
+    elif case == "outlier_last":
+        for r in range(w):
+            g[r][-1] = np.float32(1.0e6 * sigma[r])
+    else:
+        g = [(x.astype(np.float64) + 1.0).astype(np.float32) for x in g]
+    ref = np.array([orc.variance(x) for x in g])
+    assert top_two_gap(ref) > VAR_GAP
+    if route == "stand_alone":
+        dev = torch.device("cuda:0")
+        ctx = gpu_util.make_context(w, n, k)
+        x = [torch.from_numpy(a).to(dev) for a in g]
+        var = torch.zeros(w, dtype=torch.float64, device=dev)
+        am = torch.full((1,), -1, dtype=torch.int32, device=dev)
+        ctx.artopk_variance(x, var, am)
+        ctx.status()
+        np.testing.assert_allclose(var.cpu().numpy(), ref, rtol=1e-5, atol=0.0)
+        assert int(am.item()) == orc.leader_var(list(ref))
+        return
+    if route == "step_guess":
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+    res = [np.zeros(n, np.float32) for _ in range(w)]
+    got, want = _one_step(g, res, k, mode=orc.MODE_VAR)
+    assert got["info"]["guessed"] == (1 if route == "step_guess" else 0)
+    np.testing.assert_allclose(got["var"], ref, rtol=1e-5, atol=0.0)
+
+
+# ------------------------------------------------------------------ boundary rules
+def test_overlapping_buffers_are_rejected():
+    """A buffer a call writes must not overlap any other buffer of the call: the in-place EF add
+    and the scatter would otherwise corrupt silently.  Read-only buffers may be shared."""
+    import torch
+    import paper_2312_02493_amd as lib
+
+    dev = torch.device("cuda:0")
+    n, k, w = 4096, 64, 2
+    ctx = lib.Context(w, n, k)
+    g = [torch.randn(n, device=dev) for _ in range(w)]
+    res = [torch.zeros(n, device=dev) for _ in range(w)]
+    big = torch.zeros(2 * n, device=dev)
+    idx = torch.zeros(k, dtype=torch.int32, device=dev)
+    s = torch.zeros(k, device=dev)
+    u = torch.zeros(n, device=dev)
+    vals = torch.zeros(w * k, device=dev)
+
+    def rejected(fn):
+        with pytest.raises(lib.ArTopkError) as e:
+            fn()
+        assert e.value.code == -1 and "overlap" in str(e.value), str(e.value)
+
+    rejected(lambda: ctx.artopk_step(g, g, k, lib.ARTOPK_STAR, 1, idx, s, u))                     # g[w] is residual[w]
+    rejected(lambda: ctx.artopk_step(g, [res[0], res[0]], k, lib.ARTOPK_STAR, 1, idx, s, u))      # one residual twice
+    rejected(lambda: ctx.artopk_step(g, [big[:n], big[n - 4:2 * n - 4]], k, lib.ARTOPK_STAR, 1, idx, s, u))  # partial overlap
+    rejected(lambda: ctx.artopk_step(g, res, k, lib.ARTOPK_STAR, 1, idx, s, res[1]))              # update inside a residual
+    rejected(lambda: ctx.artopk_step(g, res, k, lib.ARTOPK_STAR, 1, idx, s, u, vals_out=s))       # vals_out over sum_out
+    rejected(lambda: ctx.artopk_step(g, res, k, lib.ARTOPK_STAR, 1, idx, idx.view(torch.float32), u))  # sum_out is idx_out
+    rejected(lambda: ctx.artopk_gather_sum(res, idx, k, vals, vals[:k]))
+    rejected(lambda: ctx.artopk_scatter_residual(res, idx, k, s, res[0]))
+    rejected(lambda: ctx.artopk_select_topk(res[0], k, res[0][:k].view(torch.int32)))
+    # two workers reading one gradient buffer is allowed, and nothing above was enqueued or spoilt the context
+    ctx.artopk_step([g[0], g[0]], res, k, lib.ARTOPK_STAR, 1, idx, s, u, vals_out=vals)
+    ctx.status()
+    want = orc.step([g[0].cpu().numpy()] * 2, [np.zeros(n, np.float32)] * 2, k, orc.MODE_STAR, step_no=1)
+    assert np.array_equal(idx.cpu().numpy(), want.idx)
+    assert np.array_equal(bits(u.cpu().numpy()), bits(want.update))
+
+
+def test_options_are_validated_and_reported():
+    import paper_2312_02493_amd as lib
+
+    ctx = lib.Context(2, 4096, 16)
+    assert ctx.get_option(lib.ARTOPK_OPT_GUESS_MIN_N) == 1 << 25
+    assert ctx.get_option(lib.ARTOPK_OPT_UPDATE_TILES_MIN_N) == 1 << 22
+    assert ctx.get_option(lib.ARTOPK_OPT_LEADER_FIRST) == 1
+    assert ctx.get_option(lib.ARTOPK_OPT_NONTEMPORAL) == 1
+    for key, bad in ((lib.ARTOPK_OPT_GUESS_MIN_N, 0), (lib.ARTOPK_OPT_GUESS_MIN_N, (1 << 31) + 1),
+                     (lib.ARTOPK_OPT_UPDATE_TILES_MIN_N, -5), (lib.ARTOPK_OPT_LEADER_FIRST, 2),
+                     (lib.ARTOPK_OPT_NONTEMPORAL, -1), (99, 1)):
+        with pytest.raises(lib.ArTopkError) as e:
+            ctx.set_option(key, bad)
+        assert e.value.code == -1
+    ctx.set_option(lib.ARTOPK_OPT_GUESS_MIN_N, 4096)
+    assert ctx.get_option(lib.ARTOPK_OPT_GUESS_MIN_N) == 4096

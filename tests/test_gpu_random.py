@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 from oracle import artopk_oracle as orc
-from gpu_util import GpuRunner, assert_step_matches, top_two_gap
+from tests import gpu_util
+from tests.gpu_util import GpuRunner, assert_step_matches, top_two_gap
 
 pytestmark = pytest.mark.gpu
 
@@ -51,7 +52,7 @@ def _problem(seed):
 @pytest.mark.parametrize("seed", range(48))
 def test_random_problem(seed, monkeypatch):
     if seed % 2 == 1:
-        monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     rng, n, w, mode, kind, k, seg_off, seg_k = _problem(seed)
     run = GpuRunner(w, n, k, 1 if seg_k is None else len(seg_k))
     res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
@@ -77,10 +78,10 @@ def test_one_context_reused_for_problems_of_many_shapes(monkeypatch):
     import torch
     import paper_2312_02493_amd as lib
 
-    monkeypatch.setenv("ARTOPK_GUESS_MIN_N", "4096")
+    monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     max_w, max_n, max_seg = 6, 300_007, 8
     dev = torch.device("cuda:0")
-    ctx = lib.Context(max_w, max_n, max_n, max_seg)
+    ctx = gpu_util.make_context(max_w, max_n, max_n, max_seg)
     gbuf = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(max_w)]
     rbuf = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(max_w)]
     idx = torch.empty(max_n, dtype=torch.int32, device=dev)
