@@ -1,10 +1,13 @@
-"""GPU parity at the full workload sizes, in the launch configuration the
-benchmark times.  Workloads 2 and 3 are compared with the complete oracle step.
-Workloads 4 and 5 (138 M x 4 and 1 G x 8 elements) are compared element by
-element too, but the leader's Top-k set is checked with the oracle's O(N)
-uniqueness certificate instead of a full sort (the certificate accepts exactly
-the full-sort answer; it is pinned against brute force in the CPU tests), and
-every other output is rebuilt from its definition with plain NumPy."""
+"""GPU parity at the full workload sizes, for the number of steps each workload
+defines (residual carried), in the launch configuration the benchmark times.
+Workloads 2 and 3 are compared with the complete oracle step at every step, and
+so is the first step of workload 4 at each keep fraction (a full sort of 138 M
+keys).  The later steps of workload 4 and all of workload 5 (1 G x 8 elements)
+are compared element by element too, but the leader's Top-k set is checked with
+the oracle's O(N) uniqueness certificate instead of a full sort (the certificate
+accepts exactly the full-sort answer; it is pinned against brute force in the
+CPU tests), and every other output is rebuilt from its definition with plain
+NumPy."""
 
 import os
 import time
@@ -25,7 +28,7 @@ def _say(msg):
     print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
-@pytest.mark.parametrize("rho,steps", [(0.01, 3), (0.001, 2)])
+@pytest.mark.parametrize("rho,steps", [(0.01, 10), (0.001, 10)])
 def test_c2_full(rho, steps):
     wl = inp.workload(2)
     k = wl.k(rho)
@@ -50,7 +53,7 @@ def test_c3_full_segmented():
     seg_k = [int(v) for v in wl.seg_k(rho)]
     run = GpuRunner(wl.w, wl.n, k, max_segments=len(seg_k))
     res = [np.zeros(wl.n, np.float32) for _ in range(wl.w)]
-    for s in range(1, 3):
+    for s in range(1, 6):
         g = [wl.gen(s, r, threads=THREADS) for r in range(wl.w)]
         want = orc.step(g, res, k, orc.MODE_VAR, step_no=s, seg_off=seg_off, seg_k=seg_k)
         assert top_two_gap(want.variances) > 1e-4, "reseed workload 3"
@@ -114,11 +117,19 @@ def test_c4_full_star(rho):
     k = wl.k(rho)
     run = GpuRunner(wl.w, wl.n, k)
     res = [np.zeros(wl.n, np.float32) for _ in range(wl.w)]
-    for s in (1, 2):
+    for s in range(1, 6):
         g = [wl.gen(s, r, threads=THREADS) for r in range(wl.w)]
         run.load_g(g)
         _say(f"c4 rho={rho} step={s}: inputs ready")
-        res = _check_step_by_definition(f"c4 rho={rho} step={s}", run, g, res, k, orc.MODE_STAR, s)
+        if s == 1:   # the complete oracle step, full sort included
+            want = orc.step(g, res, k, orc.MODE_STAR, step_no=s)
+            _say(f"c4 rho={rho} step={s}: oracle step done")
+            got = run.step(k, orc.MODE_STAR, s)
+            assert_step_matches(got, want, orc.MODE_STAR)
+            res = want.residual
+            del got, want
+        else:
+            res = _check_step_by_definition(f"c4 rho={rho} step={s}", run, g, res, k, orc.MODE_STAR, s)
         # vectors this long take the sampled-guess route whenever 32 k <= N, and on this data the guess holds
         info = run.ctx.select_info()
         assert info["guessed"] == (1 if 32 * k <= wl.n else 0), info
@@ -166,6 +177,27 @@ def test_c5_full_var():
         res = _check_step_by_definition(f"c5 step={s}", run, g, res, k, orc.MODE_VAR, s, variances=variances)
         info = run.ctx.select_info()
         assert info["guessed"] == 1 and info["from_mask"] == 1, info
+
+
+def test_c5_full_var_leader_is_not_the_last_worker():
+    """One step of the 1e9 x 8 workload with the workers' gradient streams rotated by three places
+    (worker r gets the stream the generator makes for worker (r + 3) mod 8), so that the worker of
+    largest variance is worker 4 and the device-side leader choice points the selection, the
+    gather and the zeroing at a worker other than the last one at this size."""
+    wl = inp.workload(5)
+    k = wl.k(0.001)
+    run = GpuRunner(wl.w, wl.n, k)
+    res = [np.zeros(wl.n, np.float32) for _ in range(wl.w)]
+    g, variances = [], []
+    for r in range(wl.w):
+        x = wl.gen(1, (r + 3) % wl.w, threads=THREADS)
+        run.g[r].copy_(run.torch.from_numpy(x))
+        variances.append(orc.variance(x))
+        g.append(x)
+        _say(f"c5 rotated: worker {r} generated, var={variances[-1]:.6e}")
+    assert orc.leader_var(variances) == 4
+    _check_step_by_definition("c5 rotated", run, g, res, k, orc.MODE_VAR, 1, variances=variances)
+    assert int(run.leader.item()) == 4
 
 
 def test_longest_vector_the_library_takes():
