@@ -94,7 +94,8 @@ enum {
  * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.4 MiB per worker plus
  * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes plus
  * max_n / 8 bytes per worker of survivor bit masks.  The library reads no environment
- * variable and keeps no state outside its contexts.
+ * variable and keeps no state outside its contexts (artopk_variance_static's fixed
+ * scratch excepted, see there).
  */
 int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
                   int32_t max_segments, void* hip_stream);
@@ -155,6 +156,24 @@ int artopk_status(artopk_ctx* ctx);
  */
 int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n,
                     double* var_out, int32_t* argmax_out);
+
+/*
+ * artopk_variance for callers that cannot allocate device memory: code that is being
+ * recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  It
+ * takes no context (creating one allocates): its kernels' scratch -- the per-block
+ * partial results, 1.5 MiB -- is a fixed array inside the library's device code, which
+ * every GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing, on the device or through any library.  Limits: 1 <= W <=
+ * ARTOPK_MAX_WORKERS (what the fixed array holds) and 1 <= N < 2^31; anything beyond is
+ * ARTOPK_EINVAL with nothing enqueued (text: artopk_last_error(NULL)).
+ *   x, var_out, argmax_out   as for artopk_variance; results are the same bits
+ *   hip_stream               the hipStream_t to enqueue on (NULL = the default stream)
+ * All calls on one GPU share that GPU's array, whatever their stream: calls whose
+ * kernels may overlap on one GPU race and must be ordered by the caller.  Nothing in
+ * the array needs clearing between calls (every word read is written first).
+ */
+int artopk_variance_static(const float* const* x, int32_t w, int64_t n, double* var_out,
+                           int32_t* argmax_out, void* hip_stream);
 
 /*
  * Exact Top-k by magnitude (Sec. II-C "largest k%", Sec. III-A, Alg. 1 Topk).

@@ -22,7 +22,7 @@ _SYMBOLS = (
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
     "artopk_apply_update", "artopk_topk_workers", "artopk_select_info", "artopk_step_g16",
-    "artopk_set_option", "artopk_get_option",
+    "artopk_set_option", "artopk_get_option", "artopk_variance_static",
 )
 
 
@@ -73,6 +73,7 @@ def load_library():
     lib.artopk_select_info.argtypes = [vp, C.POINTER(i32), i32]
     lib.artopk_set_option.argtypes = [vp, i32, i64]
     lib.artopk_get_option.argtypes = [vp, i32, C.POINTER(i64)]
+    lib.artopk_variance_static.argtypes = [vp, i32, i64, vp, vp, vp]
     lib.artopk_version.restype = i32
     for name in _SYMBOLS:
         if name not in ("artopk_last_error", "artopk_version"):
@@ -99,6 +100,19 @@ def _i64_array(values):
     for i, v in enumerate(values):
         arr[i] = int(v)
     return arr
+
+
+def artopk_variance_static(x: Sequence, var_out, argmax_out=None, stream: Optional[int] = None):
+    """The context-free variance call that allocates nothing (enqueued on `stream`, default: torch's current)."""
+    import torch
+
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = lib.artopk_variance_static(_ptr_table(x), len(x), x[0].numel(), _ptr(var_out), _ptr(argmax_out),
+                                    C.c_void_p(stream))
+    if rc != 0:
+        raise ArTopkError(rc, lib.artopk_last_error(None).decode())
 
 
 class Context:

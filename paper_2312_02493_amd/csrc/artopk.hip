@@ -14,12 +14,21 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "artopk_kernels.h"
 
 using namespace artopk;
+
+// Fixed scratch of artopk_variance_static (the entry point that allocates nothing): the per-block
+// moments of up to kMaxW workers x kMaxChunks blocks, then kMaxW variances, then the argmax word.
+// Every GPU the library runs on holds its own copy until the process ends.  In host code this name
+// is only a handle for hipGetSymbolAddress; the kernels get the address that call returns.
+constexpr size_t kStaticPartials = (size_t)kMaxW * kMaxChunks * 3;
+constexpr size_t kStaticDoubles = kStaticPartials + kMaxW + 1;
+static __device__ __align__(256) double scratch[kStaticDoubles];
 
 namespace {
 
@@ -973,6 +982,78 @@ int artopk_variance(artopk_ctx* ctx, const float* const* x, int32_t w, int64_t n
   hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, ctx->stream, s.partials, (int)w, nblk, n, s.var_scratch,
                      var_out, s.leader_dev, argmax_out);
   HIP_TRY(ctx, hipGetLastError());
+  return ARTOPK_OK;
+}
+
+namespace {
+
+// Per-device address of the fixed scratch and the device's compute-unit count, looked up the
+// first time artopk_variance_static runs with that device current.
+struct StaticDevice {
+  bool ready = false;
+  double* ptr = nullptr;
+  int num_cu = 0;
+};
+constexpr int kMaxDevices = 64;
+StaticDevice g_static_dev[kMaxDevices];
+std::mutex g_static_mu;
+
+int static_device(const StaticDevice** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(nullptr, ARTOPK_EHIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, ARTOPK_EINVAL, "device %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  StaticDevice& sd = g_static_dev[dev];
+  if (!sd.ready) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr)
+      return fail(nullptr, ARTOPK_EHIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev,
+                  hipGetErrorString(e));
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail(nullptr, ARTOPK_EHIP, "hipDeviceGetAttribute failed: %s", hipGetErrorString(e));
+    sd.ptr = static_cast<double*>(p);
+    sd.num_cu = cus > 0 ? cus : 256;
+    sd.ready = true;
+  }
+  *out = &sd;
+  return ARTOPK_OK;
+}
+
+}  // namespace
+
+int artopk_variance_static(const float* const* x, int32_t w, int64_t n, double* var_out, int32_t* argmax_out,
+                           void* hip_stream) {
+  if (w < 1 || w > ARTOPK_MAX_WORKERS)
+    return fail(nullptr, ARTOPK_EINVAL, "W=%d outside [1, %d] (the fixed scratch holds %d workers)", w,
+                ARTOPK_MAX_WORKERS, ARTOPK_MAX_WORKERS);
+  if (n < 1 || n >= (1ll << 31)) return fail(nullptr, ARTOPK_EINVAL, "N=%lld outside [1, 2^31)", (long long)n);
+  int rc = check_ptr_table(nullptr, x, w, "x");
+  if (rc) return rc;
+  if (!var_out) return fail(nullptr, ARTOPK_EINVAL, "var_out is NULL");
+  {
+    RangeSet rs;
+    rs.add_table(reinterpret_cast<const void* const*>(x), w, (size_t)n * 4, false, "x");
+    rs.add(var_out, (size_t)w * 8, true, "var_out");
+    rs.add(argmax_out, 4, true, "argmax_out");
+    if ((rc = rs.check(nullptr))) return rc;
+  }
+  const StaticDevice* sd = nullptr;
+  if ((rc = static_device(&sd))) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const PtrTable tab = make_table(x, w);
+  const int nblk = stats_blocks(sd->num_cu, w, n);  // <= kMaxChunks, so w * nblk * 3 <= kStaticPartials
+  double* partials = sd->ptr;
+  double* var_scratch = sd->ptr + kStaticPartials;
+  int32_t* leader_word = reinterpret_cast<int32_t*>(sd->ptr + kStaticPartials + kMaxW);
+  // every word of the scratch that is read is written first by these two launches: nothing to clear
+  hipLaunchKernelGGL((k_stats<true, true>), dim3(nblk, w), dim3(256), 0, st, tab, n, partials);
+  hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, partials, (int)w, nblk, n, var_scratch, var_out,
+                     leader_word, argmax_out);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, ARTOPK_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
   return ARTOPK_OK;
 }
 
