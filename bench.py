@@ -7,15 +7,24 @@ A "step" is one artopk_step() call: EF add + leader choice + exact Top-k on the
 leader + gather + ordered sum + residual rewrite + dense update, for all W
 simulated workers, with every input already resident in HBM.  Prints ONE JSON
 line.  `value` is W*N / t_step in G elements/s.  `roofline` describes the
-dominant kernel (the fused EF-add / variance / histogram pass, 12*W*N
-algorithmic bytes per launch), timed with HIP events on the library's stream.
-`cpu_baseline` is the NumPy oracle timed on a bounded sample of the same
-workload on the host (single thread).
+dominant kernel (the fused pass over all workers, 12*W*N algorithmic bytes per
+launch; or, with a leader known up front, the fused pass over the other W-1
+workers), timed with HIP events on the library's stream.  `cpu_baseline` is the
+NumPy oracle timed on a bounded sample of the same workload on the host (single
+thread).  With the default workload (c5, the 1e9 x 8 configuration) the line
+also carries the three keep fractions of the 138 M x 4 configuration under
+`other` (--no-c4 leaves them out).
+
+Inputs: two gradient sets (steps 1 and 2 of the workload's seeded recipe) are
+generated and uploaded before the timed region and alternate from step to step,
+with the residual carried, so leader, threshold and guess outcome change between
+steps as they do with a fresh gradient per step.
 """
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -25,54 +34,89 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, measured with two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a plain 1 GiB
-# device copy (profiles/artopk_step_<workload>_rho<rho>.md); None where it was not measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("c5", 0.001): 97127.0e6,   # k_pass_mark, all 8 workers: 64.0 GB fetched + 33.1 GB written (1 GB of it bit masks)
-    ("c4", 0.01): 5006.4e6,     # k_pass_rest, 3 workers: 3.33 GB fetched + 1.68 GB written
-}
-
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, n, k, with_vals, g_bytes=4):
-    """Bytes one step must move (fp32, 4-byte granularity for the k-sized terms)."""
+def profile_traffic(tag, rho, kernel):
+    """HBM bytes per launch of `kernel` as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the counter reads for a plain copy): read from the committed summary of the same
+    workload, profiles/artopk_step_<tag>_rho<rho>.md.  (None, None) if there is no such summary or
+    it does not list the kernel: the figure is never carried in this file."""
+    rel = os.path.join("profiles", f"artopk_step_{tag}_rho{rho}.md")
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None, None
+    in_table = False
+    for line in open(path):
+        if line.startswith("## HBM traffic per launch"):
+            in_table = True
+            continue
+        if in_table and line.startswith("|"):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and re.match(rf"{re.escape(kernel)}(<|$)", cells[0]):
+                try:
+                    return float(cells[4]) * 1e6, rel
+                except ValueError:
+                    return None, None
+    return None, None
+
+
+def algorithmic_bytes(w, n, k, with_vals, g_bytes=4, reread=True):
+    """Bytes one step must move (fp32, 4-byte granularity for the k-sized terms).  reread: the
+    selection reads the leader's vector once more after the fused pass (it does not when the
+    survivor list is written from the fused pass' bit mask)."""
     pass_a = (8 + g_bytes) * w * n      # read g, read residual, write acc
-    select = 4 * n                      # one re-read of the leader after the threshold digit is known
+    select = 4 * n if reread else 0
     update = 4 * n                      # dense update written once
     ksized = k * (8 * w + (4 * w if with_vals else 0) + 20)
     return pass_a, pass_a + select + update + ksized
 
 
-def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
-    wl = inp.workload(cfg)
+class Inputs:
+    """Two gradient sets of one workload resident on the GPU (generated once, shared by all its keep
+    fractions) and the residuals."""
+
+    def __init__(self, args, cfg, torch, inp):
+        import numpy as np
+
+        self.wl = wl = inp.workload(cfg)
+        dev = torch.device("cuda:0")
+        t0 = time.perf_counter()
+        host = np.empty(wl.n, dtype=np.float32)
+        self.g_sets = []
+        for step in (1, 2):
+            g = []
+            for r in range(wl.w):
+                wl.gen_into(host, step, r, threads=args.gen_threads)
+                t = torch.from_numpy(host).to(dev)
+                if args.g16:  # 16-bit gradient storage: rounded once here, outside the timed region
+                    t = t.to(torch.bfloat16 if args.g16 == "bf16" else torch.float16)
+                g.append(t)
+            self.g_sets.append(g)
+            log(f"[bench]   {wl.name}: gradient set {step} generated and uploaded ({time.perf_counter() - t0:.1f} s)")
+        self.res = [torch.zeros(wl.n, dtype=torch.float32, device=dev) for _ in range(wl.w)]
+        self.update = torch.empty(wl.n, dtype=torch.float32, device=dev)
+
+    def reset(self):
+        for r in self.res:
+            r.zero_()
+
+
+def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
+    wl = data.wl
     k = wl.k(rho)
     seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
     seg_k = None if wl.seg_off is None else [int(v) for v in wl.seg_k(rho)]
     dev = torch.device("cuda:0")
     mode = pkg.ARTOPK_STAR if wl.mode == inp.MODE_STAR else pkg.ARTOPK_VAR
     log(f"[bench] workload {wl.name}: N={wl.n} W={wl.w} rho={rho} k={k} mode={'STAR' if mode == 0 else 'VAR'}")
-
-    t0 = time.perf_counter()
-    g, res = [], []
-    import numpy as np
-    host = np.empty(wl.n, dtype=np.float32)
-    for r in range(wl.w):
-        wl.gen_into(host, 1, r, threads=args.gen_threads)
-        t = torch.from_numpy(host).to(dev)
-        if args.g16:  # 16-bit gradient storage: rounded once here, outside the timed region
-            t = t.to(torch.bfloat16 if args.g16 == "bf16" else torch.float16)
-        g.append(t)
-        res.append(torch.zeros(wl.n, dtype=torch.float32, device=dev))
-        log(f"[bench]   worker {r} generated and uploaded ({time.perf_counter() - t0:.1f} s)")
-    del host
+    data.reset()
+    res, update = data.res, data.update
     ctx = pkg.Context(wl.w, wl.n, k, 1 if seg_k is None else len(seg_k))
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     summed = torch.empty(k, dtype=torch.float32, device=dev)
-    update = torch.empty(wl.n, dtype=torch.float32, device=dev)
     leader = torch.zeros(1, dtype=torch.int32, device=dev)
     var = torch.zeros(wl.w, dtype=torch.float64, device=dev)
 
@@ -80,6 +124,7 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     g_type = {None: pkg.ARTOPK_G_F32, "bf16": pkg.ARTOPK_G_BF16, "f16": pkg.ARTOPK_G_F16}[args.g16]
 
     def one(step_no):
+        g = data.g_sets[(step_no - 1) % 2]
         if args.g16:
             ctx.artopk_step_g16(g, g_type, res, k, mode, step_no, idx, summed, update, leader_out=leader,
                                 var_out=var, seg_off=seg_off, seg_k=seg_k)
@@ -94,7 +139,7 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     torch.cuda.synchronize()
     ctx.status()
 
-    # timed region: K steps, pass A bracketed by HIP events on the library's stream
+    # timed region: K steps, the dominant kernel bracketed by HIP events on the library's stream
     ctx.set_profile(1)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -105,46 +150,59 @@ def run_workload(args, cfg, rho, steps, warmup, torch, pkg, inp):
     t_total = time.perf_counter() - t_start
     # level-1 events bracket the dominant kernel: the fused pass over all workers (VAR) or,
     # when the leader is known up front, the fused pass over the W-1 other workers
-    # (the library says which of the two it ran: an environment switch can turn the second off)
+    # (the library says which of the two it ran: an option can turn the second off)
     info = ctx.select_info()
     star = info["dominant_workers"] == wl.w - 1 and wl.w > 1
     fused = "k_pass_mark" if info["guessed"] else "k_pass_a"   # the fused pass of the guess / histogram route
     dom_name, dom_stage, dom_workers = ("k_pass_rest", "gather", wl.w - 1) if star else (fused, "pass_a", wl.w)
-    pass_a_ms = [ctx.get_profile()[dom_stage]]  # averaged over the timed steps
+    dom_ms = ctx.get_profile()[dom_stage]  # averaged over the timed steps
     # stage breakdown from a few extra, untimed steps (an event at every stage boundary)
     ctx.set_profile(2)
-    for _ in range(min(3, steps)):
+    for _ in range(min(4, steps)):
         one(step_no)
         step_no += 1
-    stage_ms = [ctx.get_profile()]
+    stage_ms = ctx.get_profile()
     ctx.set_profile(0)
     ctx.status()
     ms_per_step = 1e3 * t_total / steps
-    pa = sum(pass_a_ms) / len(pass_a_ms)
-    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes)
-    b_pass_a = (8 + g_bytes) * dom_workers * wl.n
+    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes, reread=not info["from_mask"])
+    b_dom = (8 + g_bytes) * dom_workers * wl.n
     out = {
         "wl": wl, "k": k, "rho": rho, "ms_per_step": ms_per_step,
         "gelem_per_s": wl.w * wl.n / (ms_per_step * 1e-3) / 1e9,
-        "pass_a_ms": pa, "pass_a_gbps": b_pass_a / (pa * 1e-3) / 1e9,
+        "dom_ms": dom_ms, "dom_gbps": b_dom / (dom_ms * 1e-3) / 1e9,
         "step_alg_gbps": b_step / (ms_per_step * 1e-3) / 1e9,
-        "stages": {name: sum(s[name] for s in stage_ms) / len(stage_ms) for name in stage_ms[0]},
-        "b_pass_a": b_pass_a, "b_step": b_step, "leader": int(leader.item()), "dom_name": dom_name,
+        "stages": stage_ms, "b_dom": b_dom, "b_step": b_step, "leader": int(leader.item()), "dom_name": dom_name,
+        "from_mask": bool(info["from_mask"]),
     }
-    log(f"[bench]   {ms_per_step:.3f} ms/step, {out['gelem_per_s']:.1f} G elem/s, {dom_name} {pa:.3f} ms = "
-        f"{out['pass_a_gbps']:.0f} GB/s, whole step {out['step_alg_gbps']:.0f} GB/s algorithmic; stages {out['stages']}")
-    del g, res, update, ctx
-    torch.cuda.empty_cache()
+    log(f"[bench]   {ms_per_step:.3f} ms/step, {out['gelem_per_s']:.1f} G elem/s, {dom_name} {dom_ms:.3f} ms = "
+        f"{out['dom_gbps']:.0f} GB/s, whole step {out['step_alg_gbps']:.0f} GB/s algorithmic; stages {out['stages']}")
+    del ctx
     return out
 
 
-def cpu_baseline(cfg, rho, inp, budget_s=15.0):
+def roofline_of(r, tag, g16):
+    traffic, source = (None, None) if g16 else profile_traffic(tag, r["rho"], r["dom_name"])
+    return {"bound": "hbm", "kernel": r["dom_name"], "achieved": round(r["dom_gbps"], 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r["dom_gbps"] / HBM_PEAK_GBPS, 4),
+            "traffic": traffic, "traffic_source": source, "algorithmic_bytes_per_launch": r["b_dom"],
+            "avg_launch_ms": round(r["dom_ms"], 4)}
+
+
+def step_of(r):
+    return {"bytes": r["b_step"], "GBps": round(r["step_alg_gbps"], 1),
+            "frac_of_hbm_peak": round(r["step_alg_gbps"] / HBM_PEAK_GBPS, 4),
+            "leader_reread_counted": not r["from_mask"],
+            "stage_ms": {k_: round(v, 4) for k_, v in r["stages"].items()}}
+
+
+def cpu_baseline(cfg, rho, inp, n_cap=1 << 24, budget_s=15.0, max_steps=12):
     """The oracle, as it stands, on a bounded sample of the workload (one thread)."""
     import numpy as np
     from oracle import artopk_oracle as orc
 
     full = inp.workload(cfg)
-    n = min(full.n, 1 << 24)
+    n = min(full.n, n_cap)
     wl = inp.workload(cfg, n=n)
     k = wl.k(rho)
     seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
@@ -152,16 +210,17 @@ def cpu_baseline(cfg, rho, inp, budget_s=15.0):
     mode = orc.MODE_STAR if wl.mode == inp.MODE_STAR else orc.MODE_VAR
     res = [np.zeros(n, np.float32) for _ in range(wl.w)]
     steps, spent = 0, 0.0
-    while spent < budget_s and steps < 12:
-        g = [wl.gen(steps + 1, r) for r in range(wl.w)]
+    while spent < budget_s and steps < max_steps:
+        g = [wl.gen(steps + 1, r, threads=8) for r in range(wl.w)]
         t0 = time.perf_counter()
         out = orc.step(g, res, k, mode, step_no=steps + 1, seg_off=seg_off, seg_k=seg_k)
         spent += time.perf_counter() - t0
         res = out.residual
         steps += 1
+    size = "at its full size" if n == full.n else f"shrunk to N={n}"
     return {
         "value": wl.w * n * steps / spent / 1e9, "unit": "G elements/s", "cores": 1, "kind": "oracle",
-        "sample": f"{steps} steps of workload {wl.name} shrunk to N={n} (W={wl.w}, rho={rho}), "
+        "sample": f"{steps} step(s) of workload {wl.name} {size} (W={wl.w}, rho={rho}), "
                   f"{spent:.1f} s of single-thread NumPy",
     }
 
@@ -177,7 +236,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--g16", choices=["bf16", "f16"], default=None,
                     help="store the gradients in 16 bits (artopk_step_g16); not the headline configuration")
-    ap.add_argument("--also-c4", action="store_true", help="append the 138M workload's numbers under 'other'")
+    ap.add_argument("--no-c4", action="store_true",
+                    help="with the default workload: leave out the 138 M x 4 configuration's rows under 'other'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -208,20 +268,29 @@ def main():
     cfg = int(args.workload[1])
     wl0 = inp.workload(cfg)
     rho = args.rho if args.rho is not None else {1: 0.01, 2: 0.01, 3: 0.01, 4: 0.01, 5: 0.001}[cfg]
-    r = run_workload(args, cfg, rho, args.steps, args.warmup, torch, pkg, inp)
+    data = Inputs(args, cfg, torch, inp)
+    r = run_workload(args, data, rho, args.steps, args.warmup, torch, pkg, inp)
+    del data
+    torch.cuda.empty_cache()
 
+    # the second target configuration (138 M x 4, round-robin leader) at its three keep fractions
     other = {}
-    if args.also_c4 and cfg != 4:
+    if cfg == 5 and args.rho is None and not args.no_c4:
+        data4 = Inputs(args, 4, torch, inp)
         for rh in (0.1, 0.01, 0.001):
-            o = run_workload(args, 4, rh, args.steps, args.warmup, torch, pkg, inp)
-            other[f"c4_rho{rh}"] = {"ms_per_step": round(o["ms_per_step"], 4),
-                                    "G_elements_per_s": round(o["gelem_per_s"], 2),
-                                    "step_alg_GBps": round(o["step_alg_gbps"], 1),
-                                    "pass_a_GBps": round(o["pass_a_gbps"], 1)}
+            o = run_workload(args, data4, rh, max(args.steps, 20), max(args.warmup, 3), torch, pkg, inp)
+            other[f"c4_rho{rh}"] = {
+                "config": {"workload": data4.wl.name, "N": data4.wl.n, "W": data4.wl.w, "rho": rh, "k": o["k"],
+                           "leader_rule": "STAR"},
+                "ms_per_step": round(o["ms_per_step"], 4), "value": round(o["gelem_per_s"], 2),
+                "unit": "G elements/s", "roofline": roofline_of(o, "c4", args.g16), "step_algorithmic": step_of(o)}
+        del data4
+        torch.cuda.empty_cache()
+        if not args.no_cpu_baseline:   # the oracle at this configuration's own size: one step, a full sort of 138 M keys
+            other["c4_rho0.01"]["cpu_baseline"] = cpu_baseline(4, 0.01, inp, n_cap=1 << 31, budget_s=1.0, max_steps=1)
 
     base = None if args.no_cpu_baseline else cpu_baseline(cfg, rho, inp)
 
-    traffic = None if args.g16 else MEASURED_TRAFFIC_BYTES.get((args.workload, rho))
     line = {
         "metric": "compressed gradient elements/s per AR-Topk step (1 GPU)",
         "value": round(r["gelem_per_s"], 3),
@@ -234,17 +303,13 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32" if not args.g16 else f"f32 (gradients stored as {args.g16})",
-        "data": "synthetic (seeded recipe of the workload; step-1 gradients reused every step, residual carried)",
+        "data": "synthetic (seeded recipe of the workload; two pre-generated gradient sets, steps 1 and 2 of "
+                "the recipe, alternate from step to step; residual carried)",
         "config": {"workload": wl0.name, "N": wl0.n, "W": wl0.w, "rho": rho, "k": r["k"],
                    "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR",
                    **({"gradient_storage": args.g16} if args.g16 else {})},
-        "roofline": {"bound": "hbm", "kernel": r["dom_name"], "achieved": round(r["pass_a_gbps"], 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r["pass_a_gbps"] / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic, "algorithmic_bytes_per_launch": r["b_pass_a"],
-                     "avg_launch_ms": round(r["pass_a_ms"], 4)},
-        "step_algorithmic": {"bytes": r["b_step"], "GBps": round(r["step_alg_gbps"], 1),
-                             "frac_of_hbm_peak": round(r["step_alg_gbps"] / HBM_PEAK_GBPS, 4),
-                             "stage_ms": {k_: round(v, 4) for k_, v in r["stages"].items()}},
+        "roofline": roofline_of(r, args.workload, args.g16),
+        "step_algorithmic": step_of(r),
         "cpu_baseline": base,
     }
     if other:

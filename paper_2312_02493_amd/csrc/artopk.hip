@@ -635,9 +635,9 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   // the second digit over a list that was written from the mask
   if (guessed && hist_ready) {
     const int64_t b1 = lblocks > pl.max_chunks ? lblocks : pl.max_chunks;
-    hipLaunchKernelGGL(k_level1, dim3((unsigned)b1, nseg), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(k_level1, dim3((unsigned)b1, nseg), dim3(64 * kC1Waves), 0, st, p);
   } else {
-    hipLaunchKernelGGL((k_compact1<4, 4>), dim3(pl.max_chunks, nseg), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((k_compact1<kC1Waves, kC1R>), dim3(pl.max_chunks, nseg), dim3(64 * kC1Waves), 0, st, p);
   }
   // A list of many millions of entries (one element in 32 kept, or more) is counted faster by the
   // lean kernel of its own (99 vs 66 us on 15 M entries: the merged one carries the array pass'

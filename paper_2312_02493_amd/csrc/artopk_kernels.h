@@ -215,42 +215,34 @@ constexpr int kMaxPassBlocks = 4096;  // blocks per worker of a streaming pass t
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
-// Variance in one pass that no single element can spoil.  Every thread keeps
-// the count and the float64 sums of (x - c) and (x - c)^2 of the values it sees,
-// with c the mean of the first four of them (its own shift: for any data, a
-// thread that sees m values has (mean - c)^2 <= (m / 4) variance, so the usual
-// cancellation of the one-pass formula is bounded by the few hundred values a
-// thread handles and does not grow with an outlier).  Threads, waves, blocks
-// and finally the blocks' partials (count, mean, M2 = sum of squared deviations
-// from the mean) are then combined pairwise with the update formula for merged
-// samples, M2 = M2a + M2b + (mean_b - mean_a)^2 na nb / (na + nb), which adds
-// only non-negative terms.  The order of every merge is fixed by the launch
-// shape, so the result is reproducible.
+// Variance in one pass that no single element can spoil.  Every thread keeps, in
+// float64, the count and the sums of (x - c) and (x - c)^2 of the values it sees,
+// with a shift c of its own: the mean of the first four of them.  At the end of a
+// block the threads re-base their sums (exactly: S' = S + n d, SS' = SS + d (2 S + n d),
+// d = c - r) to the shift r of the block's first thread and add them up.  For any
+// data, a block that sees m values has (mean - r)^2 <= (m / 4) variance of its
+// values (Cauchy-Schwarz: r is the mean of four of them), so the cancellation of
+// the shifted one-pass formula is bounded by the block's length and does not grow
+// with an outlier or an offset.  The block's sums become (count n, mean, M2 = sum
+// of squared deviations from its mean); the blocks' triples of one worker are
+// combined the same way, with the mean of the worker's first block as the shift:
+//     N = sum n_b, A = sum n_b (mean_b - r), B = sum (M2_b + n_b (mean_b - r)^2),
+//     mean = r + A / N, M2 = B - A^2 / N.
+// The order of every sum is fixed by the launch shape, so the result is reproducible.
+// Partials layout: partials[w][0][b] = n_b, [w][1][b] = mean_b, [w][2][b] = M2_b.
 // ---------------------------------------------------------------------------
-struct Moments {
-  double n, mean, m2;
-};
-
-__device__ __forceinline__ void moments_merge(Moments& a, const Moments& b) {
-  if (b.n > 0.0) {
-    if (a.n > 0.0) {
-      const double nt = a.n + b.n;
-      const double d = b.mean - a.mean;
-      const double f = b.n / nt;
-      a.mean += d * f;
-      a.m2 += b.m2 + d * d * a.n * f;
-      a.n = nt;
-    } else {
-      a = b;
-    }
-  }
-}
-
 struct VarAcc {
   double c = 0.0, s = 0.0, ss = 0.0;
   uint32_t cnt = 0u;
-  __device__ __forceinline__ void add4(const v4f t) {
+  // the shift is taken from the first group (or element) a thread sees: call seed before the
+  // first add of every batch (it acts once)
+  __device__ __forceinline__ void seed4(const v4f t) {
     if (cnt == 0u) c = (((double)t.x + (double)t.y) + ((double)t.z + (double)t.w)) * 0.25;
+  }
+  __device__ __forceinline__ void seed1(float x) {
+    if (cnt == 0u) c = (double)x;
+  }
+  __device__ __forceinline__ void add4(const v4f t) {
     const double d0 = (double)t.x - c, d1 = (double)t.y - c, d2 = (double)t.z - c, d3 = (double)t.w - c;
     s += (d0 + d1) + (d2 + d3);
     ss = fma(d0, d0, ss);
@@ -260,77 +252,102 @@ struct VarAcc {
     cnt += 4u;
   }
   __device__ __forceinline__ void add1(float x) {
-    if (cnt == 0u) c = (double)x;
     const double d = (double)x - c;
     s += d;
     ss = fma(d, d, ss);
     cnt += 1u;
   }
-  __device__ __forceinline__ Moments moments() const {
-    Moments m{0.0, 0.0, 0.0};
-    if (cnt != 0u) {
-      const double dn = (double)cnt;
-      m.n = dn;
-      m.mean = c + s / dn;
-      m.m2 = ss - s * s / dn;
-      if (m.m2 < 0.0) m.m2 = 0.0;  // rounding only (NaN stays NaN)
-    }
-    return m;
-  }
 };
 
-// Merges the threads' moments of a block of T threads (all of them call it); thread 0 returns
-// the block's.  `red` is 3 * (T / 64) doubles of shared memory.
-template <int T>
-__device__ __forceinline__ Moments block_moments(const VarAcc& acc, double* red) {
-  Moments m = acc.moments();
+__device__ __forceinline__ double wave_allsum(double v) {
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {  // lane l takes lane l + off: pairs, then pairs of pairs, ...
-    Moments o;
-    o.n = __shfl_down(m.n, off, 64);
-    o.mean = __shfl_down(m.mean, off, 64);
-    o.m2 = __shfl_down(m.m2, off, 64);
-    if ((threadIdx.x & 63) + off < 64) moments_merge(m, o);
-  }
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;  // the total, in every lane (the same bits: every lane adds the same pairs)
+}
+
+// Adds up the threads' sums of a block of T threads (all of them call it) and thread 0 writes
+// the block's (n, mean, M2) to partials[w][.][b] (nblk blocks per worker).  Thread 0 must be a
+// thread that saw a value whenever any thread of the block did (it owns the block's first group).
+template <int T>
+__device__ __forceinline__ void block_moments(const VarAcc& acc, double* __restrict__ partials, int w, int nblk,
+                                              int b) {
+  constexpr int NW = T / 64;
+  __shared__ double red[3 * NW + 1];
   const int tid = threadIdx.x;
+  if (tid == 0) red[3 * NW] = acc.c;
+  __syncthreads();
+  const double r = red[3 * NW];
+  const double n_t = (double)acc.cnt;
+  const double d = acc.cnt != 0u ? acc.c - r : 0.0;
+  const double s = wave_sum(acc.s + n_t * d), ss = wave_sum(acc.ss + d * (2.0 * acc.s + n_t * d)), n = wave_sum(n_t);
   if ((tid & 63) == 0) {
-    red[3 * (tid >> 6) + 0] = m.n;
-    red[3 * (tid >> 6) + 1] = m.mean;
-    red[3 * (tid >> 6) + 2] = m.m2;
+    red[tid >> 6] = s;
+    red[NW + (tid >> 6)] = ss;
+    red[2 * NW + (tid >> 6)] = n;
   }
   __syncthreads();
   if (tid == 0) {
-    for (int i = 1; i < T / 64; ++i) {
-      const Moments o{red[3 * i + 0], red[3 * i + 1], red[3 * i + 2]};
-      moments_merge(m, o);
+    double S1 = 0.0, S2 = 0.0, N = 0.0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      S1 += red[i];
+      S2 += red[NW + i];
+      N += red[2 * NW + i];
     }
+    double mean = 0.0, m2 = 0.0;
+    if (N > 0.0) {
+      const double sm = S1 / N;
+      mean = r + sm;
+      m2 = S2 - S1 * sm;
+      if (m2 < 0.0) m2 = 0.0;  // rounding only (NaN stays NaN)
+    }
+    double* __restrict__ out = partials + (size_t)w * 3 * nblk + b;
+    out[0] = N;
+    out[nblk] = mean;
+    out[2 * (size_t)nblk] = m2;
   }
-  return m;
 }
 
-// Variance of worker w from its blocks' moments partials[w][0 .. nblk)[3]; the 64 lanes of one
-// wave call it, lane 0 returns the variance (population: M2 / n).
+// Variance of worker w from its blocks' partials; the 64 lanes of one wave call it, every lane
+// returns the variance (population: M2 / N).
 __device__ __forceinline__ double wave_variance(const double* __restrict__ partials, int w, int nblk) {
   const int lane = threadIdx.x & 63;
-  const double* __restrict__ pp = partials + (size_t)w * nblk * 3;
-  Moments m{0.0, 0.0, 0.0};
-  for (int b = lane; b < nblk; b += 64) {
-    const Moments o{pp[3 * b + 0], pp[3 * b + 1], pp[3 * b + 2]};
-    moments_merge(m, o);
-  }
+  const double* __restrict__ pn = partials + (size_t)w * 3 * nblk;
+  const double* __restrict__ pm = pn + nblk;
+  const double* __restrict__ pq = pm + nblk;
+  const double r = pm[0];
+  double n = 0.0, a = 0.0, bq = 0.0;
+  int b = lane;
+  for (; b + 448 < nblk; b += 512) {  // eight blocks' triples in flight per lane
+    double nb[8], mb[8], qb[8];
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    Moments o;
-    o.n = __shfl_down(m.n, off, 64);
-    o.mean = __shfl_down(m.mean, off, 64);
-    o.m2 = __shfl_down(m.m2, off, 64);
-    if (lane + off < 64) moments_merge(m, o);
+    for (int j = 0; j < 8; ++j) {
+      nb[j] = pn[b + 64 * j];
+      mb[j] = pm[b + 64 * j];
+      qb[j] = pq[b + 64 * j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const double d = mb[j] - r;
+      n += nb[j];
+      a += nb[j] * d;
+      bq += qb[j] + nb[j] * d * d;
+    }
   }
-  double v = m.n > 0.0 ? m.m2 / m.n : 0.0;
+  for (; b < nblk; b += 64) {
+    const double nb = pn[b], d = pm[b] - r;
+    n += nb;
+    a += nb * d;
+    bq += pq[b] + nb * d * d;
+  }
+  n = wave_allsum(n);
+  a = wave_allsum(a);
+  bq = wave_allsum(bq);
+  double v = 0.0;
+  if (n > 0.0) v = (bq - a * (a / n)) / n;
   if (!(v > 0.0)) v = (v != v) ? v : 0.0;
   return v;
 }
-
 
 template <bool NT>
 __device__ __forceinline__ v4f load4(const float* p) {
@@ -472,8 +489,7 @@ k_fill_zero(uint32_t* __restrict__ p1, size_t words1, uint32_t* __restrict__ p2,
 //         2 for every worker (worker w in slot w): per-chunk top-digit suffix
 //         histograms S[slot][c] and the whole-vector histogram of the slot.
 //   STATS: 0 none, 1 variance partials of acc, 2 of the raw gradient g: the
-//   block's (count, mean, sum of squared deviations) in float64, written to
-//   partials[w][c][0..2] (see Moments).
+//   block's (count, mean, sum of squared deviations) in float64 (see VarAcc).
 //   NT: non-temporal loads of g and stores of acc.
 // ---------------------------------------------------------------------------
 constexpr int kPassAUnroll = 4;
@@ -485,7 +501,6 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
   constexpr bool LH = HIST != 0;  // an LDS histogram is built
   __shared__ __attribute__((aligned(16))) uint32_t lh[LH ? kHistBins : 4];
   __shared__ uint32_t red_u[LH ? T : 1];
-  __shared__ double red[3 * (T / 64)];
 
   // with a known leader its blocks (the only ones that work for the selection) are dispatched first
   const int w = (HIST == 1) ? (int)((blockIdx.y + (unsigned)hist_worker) % gridDim.y) : (int)blockIdx.y;
@@ -504,12 +519,12 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
     __syncthreads();
   }
 
-  VarAcc va;
-
   const int64_t c_lo = geom.chunk0 + (int64_t)c * geom.chunk_elems;
   int64_t c_hi = c_lo + geom.chunk_elems;
   if (c_hi > n) c_hi = n;
   const int64_t q_hi = c_hi >> 2;  // whole float4 groups of this chunk
+
+  VarAcc va;
 
   // One tile: U rows of T float4 groups; the wave's rows start at group qw (a multiple of 64).
   // FULL: every group of the wave's rows lies inside the chunk, so nothing is predicated.
@@ -536,7 +551,10 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
         store4<NT>(rp + 4 * q, v);
-        if (STATS) va.add4(STATS == 2 ? a[u] : v);  // the raw gradient, or the error-fed value
+        if (STATS) {  // of the raw gradient, or of the error-fed value
+          if (u == 0) va.seed4(STATS == 2 ? a[u] : v);
+          va.add4(STATS == 2 ? a[u] : v);
+        }
         if (LH) {
           if (do_hist) {
             atomicAdd(&lh[(__float_as_uint(v.x) & kKeyMask) >> 19], 1u);
@@ -561,22 +579,17 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       const float gj = load1g<GT>(gp, j);
       const float v = gj + rp[j];
       rp[j] = v;
-      if (STATS) va.add1(STATS == 2 ? gj : v);
+      if (STATS) {
+        va.seed1(STATS == 2 ? gj : v);
+        va.add1(STATS == 2 ? gj : v);
+      }
       if (LH) {
         if (do_hist) atomicAdd(&lh[(__float_as_uint(v) & kKeyMask) >> 19], 1u);
       }
     }
   }
 
-  if (STATS) {
-    const Moments m = block_moments<T>(va, red);
-    if (tid == 0) {
-      double* __restrict__ out = partials + ((size_t)w * nblk + c) * 3;
-      out[0] = m.n;
-      out[1] = m.mean;
-      out[2] = m.m2;
-    }
-  }
+  if (STATS) block_moments<T>(va, partials, w, nblk, c);
   if (LH) {
     if (do_hist) {
       // many blocks add to the same few hundred bins: spread them over kHistReps partial copies
@@ -604,7 +617,7 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   chunk) but have no mask bit.
 //   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
 //   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
-//   Variance partials go to partials[y][b][0..2].
+//   Variance partials: block b of worker y (see VarAcc).
 // ---------------------------------------------------------------------------
 // First of the four mask words of row `row` (256 elements) of a vector: tiles of 128 rows, inside a
 // tile row r belongs to wave r mod 16 as its (r / 16)-th row.
@@ -616,7 +629,6 @@ template <int STATS, bool NT, int GT, int T, int U>
 __global__ void __launch_bounds__(T)
 k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
             uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials) {
-  __shared__ double red[3 * (T / 64)];
   const int w = blockIdx.y;
   const int bx = blockIdx.x;
   const int nblk = gridDim.x;
@@ -632,11 +644,11 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
   const uint32_t gkey = slot[kSlotCtrl + 1];
   const float gf = gkey != kNoGuess ? __uint_as_float(gkey) : __builtin_inff();
 
-  VarAcc va;
-
   const int64_t q_hi = n >> 2;  // whole float4 groups of the vector
   constexpr int64_t TQ = (int64_t)T * U;  // groups per tile
   const int64_t ntiles = (q_hi + TQ - 1) / TQ;
+
+  VarAcc va;
   const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
   static_assert(T == 1024 && U == 8, "mask_word() is laid out for 16 waves x 8 rows");
 
@@ -667,7 +679,10 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
         store4<NT>(rp + 4 * q, v);
-        if (STATS) va.add4(STATS == 2 ? a[u] : v);  // the raw gradient, or the error-fed value
+        if (STATS) {  // of the raw gradient, or of the error-fed value
+          if (u == 0) va.seed4(STATS == 2 ? a[u] : v);
+          va.add4(STATS == 2 ? a[u] : v);
+        }
       }
       const uint64_t m0 = __ballot(valid && !(__builtin_fabsf(v.x) < gf));
       const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
@@ -696,26 +711,20 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       const float gj = load1g<GT>(gp, j);
       const float v = gj + rp[j];
       rp[j] = v;
-      if (STATS) va.add1(STATS == 2 ? gj : v);
+      if (STATS) {
+        va.seed1(STATS == 2 ? gj : v);
+        va.add1(STATS == 2 ? gj : v);
+      }
       if (!(__builtin_fabsf(v) < gf)) atomicAdd(&mcount[(n - 1) / chunk_elems], 1u);
     }
   }
 
-  if (STATS) {
-    const Moments m = block_moments<T>(va, red);
-    if (tid == 0) {
-      double* __restrict__ out = partials + ((size_t)w * nblk + bx) * 3;
-      out[0] = m.n;
-      out[1] = m.mean;
-      out[2] = m.m2;
-    }
-  }
+  if (STATS) block_moments<T>(va, partials, w, nblk, bx);
 }
 
 // ---------------------------------------------------------------------------
 // k_stats : statistics of read-only vectors in float64.  grid = (nblk, W).
-//   SHIFT (variance): the block's moments (count, mean, sum of squared
-//   deviations) to partials[w][b][0..2], see Moments.
+//   SHIFT (variance): the block's (count, mean, sum of squared deviations), see VarAcc.
 //   !SHIFT (sum of squares): the block's sum of x and of x^2 to partials[w][b][0..1].
 // VEC reads float4 groups (rows must be 16-byte aligned).
 // ---------------------------------------------------------------------------
@@ -725,9 +734,9 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
   __shared__ double red[3 * 4];
   const int w = blockIdx.y, bx = blockIdx.x, nblk = gridDim.x, tid = threadIdx.x;
   const float* __restrict__ xp = x.p[w];
-  VarAcc va;               // SHIFT
-  double s = 0.0, ss = 0.0;  // !SHIFT
   const int64_t n4 = VEC ? (n >> 2) : 0;
+  VarAcc va;                 // SHIFT
+  double s = 0.0, ss = 0.0;  // !SHIFT
   if (VEC) {
     const v4f* __restrict__ x4 = reinterpret_cast<const v4f*>(xp);
     const int64_t tile = 256 * kPassAUnroll;
@@ -745,6 +754,7 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
         const int64_t q = q0 + u * 256;
         if (q < n4) {
           if (SHIFT) {
+            if (u == 0) va.seed4(a[u]);
             va.add4(a[u]);
           } else {
             const double d0 = (double)a[u].x, d1 = (double)a[u].y, d2 = (double)a[u].z, d3 = (double)a[u].w;
@@ -761,6 +771,7 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
   // elements not covered by whole float4 groups (all of them when the row is not 16-byte aligned)
   for (int64_t j = n4 * 4 + (int64_t)bx * 256 + tid; j < n; j += (int64_t)nblk * 256) {
     if (SHIFT) {
+      va.seed1(xp[j]);
       va.add1(xp[j]);
     } else {
       const double d = (double)xp[j];
@@ -769,13 +780,7 @@ k_stats(PtrTable x, int64_t n, double* __restrict__ partials) {
     }
   }
   if (SHIFT) {
-    const Moments m = block_moments<256>(va, red);
-    if (tid == 0) {
-      double* __restrict__ out = partials + ((size_t)w * nblk + bx) * 3;
-      out[0] = m.n;
-      out[1] = m.mean;
-      out[2] = m.m2;
-    }
+    block_moments<256>(va, partials, w, nblk, bx);
   } else {
     s = wave_sum(s);
     ss = wave_sum(ss);
@@ -1358,6 +1363,14 @@ k_pick_mask(SelParams p, LeaderArgs la) {
 // plus its position among the lane's own survivors: five or six ballots per
 // tile instead of one per element.
 // ---------------------------------------------------------------------------
+#ifndef ARTOPK_C1_WAVES
+#define ARTOPK_C1_WAVES 4
+#endif
+#ifndef ARTOPK_C1_R
+#define ARTOPK_C1_R 4
+#endif
+constexpr int kC1Waves = ARTOPK_C1_WAVES, kC1R = ARTOPK_C1_R;
+
 template <int WAVES, int R>
 __device__ __forceinline__ void compact1_body(const SelParams& p) {
   constexpr int T = 64 * WAVES;
@@ -2129,12 +2142,12 @@ k_compact1(SelParams p) {
 // written from the mask it counts the second digit over the list's candidates; if the
 // guess did not hold it is the level-1 compaction of the histogram route.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * kC1Waves)
 k_level1(SelParams p) {
   if (seg_view(p, blockIdx.y).st->use_mask != 0u)
-    list_hist_body<256>(p, 1);
+    list_hist_body<64 * kC1Waves>(p, 1);
   else
-    compact1_body<4, 4>(p);
+    compact1_body<kC1Waves, kC1R>(p);
 }
 
 // ---------------------------------------------------------------------------
