@@ -97,7 +97,6 @@ class Inputs:
             self.g_sets.append(g)
             log(f"[bench]   {wl.name}: gradient set {step} generated and uploaded ({time.perf_counter() - t0:.1f} s)")
         self.res = [torch.zeros(wl.n, dtype=torch.float32, device=dev) for _ in range(wl.w)]
-        self.update = torch.empty(wl.n, dtype=torch.float32, device=dev)
 
     def reset(self):
         for r in self.res:
@@ -113,8 +112,9 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     mode = pkg.ARTOPK_STAR if wl.mode == inp.MODE_STAR else pkg.ARTOPK_VAR
     log(f"[bench] workload {wl.name}: N={wl.n} W={wl.w} rho={rho} k={k} mode={'STAR' if mode == 0 else 'VAR'}")
     data.reset()
-    res, update = data.res, data.update
+    res = data.res
     ctx = pkg.Context(wl.w, wl.n, k, 1 if seg_k is None else len(seg_k))
+    update = torch.empty(wl.n, dtype=torch.float32, device=dev)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     summed = torch.empty(k, dtype=torch.float32, device=dev)
     leader = torch.zeros(1, dtype=torch.int32, device=dev)

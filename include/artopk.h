@@ -119,12 +119,23 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
  *                                 entry-by-entry gather, as under the variance rule
  *   ARTOPK_OPT_NONTEMPORAL        1 (default): non-temporal loads and stores in
  *                                 the streaming passes; 0: ordinary ones
+ *   ARTOPK_OPT_STAGE_TILES        on the guess route with a leader known up
+ *                                 front, the leader's fused pass can hand the
+ *                                 elements that reach the guessed bound on as
+ *                                 list entries, tile by tile, instead of leaving
+ *                                 only the bit mask (from which the list is
+ *                                 built by fetching the marked values one by
+ *                                 one).  1 (default): for selections denser than
+ *                                 one element in 32, which otherwise take the
+ *                                 histogram route; 2: for every selection;
+ *                                 0: never
  */
 enum {
   ARTOPK_OPT_GUESS_MIN_N = 0,
   ARTOPK_OPT_UPDATE_TILES_MIN_N = 1,
   ARTOPK_OPT_LEADER_FIRST = 2,
-  ARTOPK_OPT_NONTEMPORAL = 3
+  ARTOPK_OPT_NONTEMPORAL = 3,
+  ARTOPK_OPT_STAGE_TILES = 4
 };
 int artopk_set_option(artopk_ctx* ctx, int32_t key, int64_t value);
 int artopk_get_option(const artopk_ctx* ctx, int32_t key, int64_t* value_out);

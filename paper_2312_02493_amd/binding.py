@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK, ARTOPK_VAR_G = 0, 1, 2, 3, 4
 ARTOPK_G_F32, ARTOPK_G_BF16, ARTOPK_G_F16 = 0, 1, 2
 ARTOPK_OPT_GUESS_MIN_N, ARTOPK_OPT_UPDATE_TILES_MIN_N, ARTOPK_OPT_LEADER_FIRST, ARTOPK_OPT_NONTEMPORAL = 0, 1, 2, 3
+ARTOPK_OPT_STAGE_TILES = 4
 PROF_NAMES = ("pass_a", "select", "gather", "update", "total")
 
 _SYMBOLS = (

@@ -55,6 +55,9 @@ struct Scratch {
   float* vals = nullptr;          // [max_w][max_k] gathered rows when the caller passes no vals_out
   int32_t* idx_rows = nullptr;    // [max_w][max_k] every worker's own Top-k (literal Alg. 1 leader rule)
   int32_t* tile_start = nullptr;  // [max_n / kPassTile + 2] kept indices below every tile of the streaming pass
+  uint2* tilebuf = nullptr;       // list entries the fused pass stages per tile (guess route, one marking worker)
+  int64_t tilebuf_entries = 0;
+  uint32_t* tile_cnt = nullptr;   // [max_n / kPassTile + 1] entries staged per tile
   SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
   uint32_t cap = 0;               // list capacity of a flat (one-segment) select
 };
@@ -87,6 +90,8 @@ struct artopk_ctx {
   int64_t guess_min_n = (int64_t)1 << 25;
   // vectors of at least this many elements get their dense update from k_update_tiles
   int64_t update_tiles_min_n = (int64_t)1 << 22;
+  int stage_tiles = 1;  // guess route, one marking worker: the fused pass hands the marked elements on per tile
+                        // (0 never, 1 for selections denser than one in 32, 2 whenever a piece can hold a tile's share)
   void* slab = nullptr;
   Scratch s;
   // how the last step ran (artopk_select_info)
@@ -389,6 +394,7 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.h_all = hist_from_pass ? s.h_all : nullptr;
   p.mask = nullptr;
   p.mask_stride = s.mask_stride;
+  p.tiles = TileBuf{nullptr, nullptr, 0, 0, 0};
   p.use_mcount = 0;
   p.from_list = 0;
   p.after_mask = 0;
@@ -480,34 +486,45 @@ int rest_blocks(int64_t n) {
   return (int)(ntiles < 512 ? ntiles : 512);
 }
 
-// The fused pass of the guess route over the first nw workers of the tables (worker y in slot y).
-template <int STATS, int GT>
-void launch_pass_mark_g(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems) {
-  Scratch& s = c->s;
-  const dim3 grid(pass_blocks(n), nw);
-  if (c->pass_a_nt)
-    hipLaunchKernelGGL((k_pass_mark<STATS, true, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, c->stream,
-                       g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials);
-  else
-    hipLaunchKernelGGL((k_pass_mark<STATS, false, GT, kPassAThreads, kPassAU>), grid, dim3(kPassAThreads), 0, c->stream,
-                       g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials);
+// What the fused pass stages per tile for one marking worker (slot 0), or nothing.
+TileBuf tile_buf(const artopk_ctx* c, int32_t tile_cap) {
+  if (tile_cap <= 0) return TileBuf{nullptr, nullptr, 0, 0, 0};
+  return TileBuf{c->s.tilebuf, c->s.tile_cnt, 0, 0, tile_cap};
 }
 
-template <int STATS>
-void launch_pass_mark_t(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems) {
-  if (c->g_type == ARTOPK_G_BF16)
-    launch_pass_mark_g<STATS, kGBF16>(c, nw, g, r, n, chunk_elems);
-  else if (c->g_type == ARTOPK_G_F16)
-    launch_pass_mark_g<STATS, kGF16>(c, nw, g, r, n, chunk_elems);
+// The fused pass of the guess route over the first nw workers of the tables (worker y in slot y).
+// tile_cap > 0 (one worker, no statistics): the pass also stages the marked elements per tile.
+template <int STATS, int GT, bool STAGE>
+void launch_pass_mark_g(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems,
+                        int32_t tile_cap) {
+  Scratch& s = c->s;
+  const dim3 grid(pass_blocks(n), nw);
+  const TileBuf tb = tile_buf(c, STAGE ? tile_cap : 0);
+  if (c->pass_a_nt)
+    hipLaunchKernelGGL((k_pass_mark<STATS, true, GT, kPassAThreads, kPassAU, STAGE>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials, tb);
   else
-    launch_pass_mark_g<STATS, kGF32>(c, nw, g, r, n, chunk_elems);
+    hipLaunchKernelGGL((k_pass_mark<STATS, false, GT, kPassAThreads, kPassAU, STAGE>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, chunk_elems, s.h_all, s.mask, s.mask_stride, s.partials, tb);
+}
+
+template <int STATS, bool STAGE>
+void launch_pass_mark_t(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n, int64_t chunk_elems,
+                        int32_t tile_cap) {
+  if (c->g_type == ARTOPK_G_BF16)
+    launch_pass_mark_g<STATS, kGBF16, STAGE>(c, nw, g, r, n, chunk_elems, tile_cap);
+  else if (c->g_type == ARTOPK_G_F16)
+    launch_pass_mark_g<STATS, kGF16, STAGE>(c, nw, g, r, n, chunk_elems, tile_cap);
+  else
+    launch_pass_mark_g<STATS, kGF32, STAGE>(c, nw, g, r, n, chunk_elems, tile_cap);
 }
 
 void launch_pass_mark(artopk_ctx* c, int stats, int nw, const PtrTable& g, const PtrTable& r, int64_t n,
-                      int64_t chunk_elems) {
-  if (stats == 0) return launch_pass_mark_t<0>(c, nw, g, r, n, chunk_elems);
-  if (stats == 1) return launch_pass_mark_t<1>(c, nw, g, r, n, chunk_elems);
-  return launch_pass_mark_t<2>(c, nw, g, r, n, chunk_elems);
+                      int64_t chunk_elems, int32_t tile_cap = 0) {
+  if (stats == 0 && tile_cap > 0 && nw == 1) return launch_pass_mark_t<0, true>(c, nw, g, r, n, chunk_elems, tile_cap);
+  if (stats == 0) return launch_pass_mark_t<0, false>(c, nw, g, r, n, chunk_elems, 0);
+  if (stats == 1) return launch_pass_mark_t<1, false>(c, nw, g, r, n, chunk_elems, 0);
+  return launch_pass_mark_t<2, false>(c, nw, g, r, n, chunk_elems, 0);
 }
 
 template <int GT>
@@ -548,11 +565,29 @@ struct GuessPlan {
   int runs = 0;
   int64_t stride = 0;
   uint32_t m_hi = 0;
+  int32_t tile_cap = 0;  // > 0: one marking worker, whose fused pass stages up to this many list entries per tile
 };
 
-GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k) {
+// marking = number of workers whose fused pass will mark (1: a leader known up front).
+GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k, int marking) {
   GuessPlan gp;
-  if (c->s.mask == nullptr || n < c->guess_min_n || k * 32 > n) return gp;
+  if (c->s.mask == nullptr || n < c->guess_min_n) return gp;
+  // A selection of more than one element in 32 is not worth fetching entry by entry from the mask.
+  // With one marking worker its fused pass hands the marked elements on per tile instead (measured on
+  // 138 M elements, one in ten kept: 1.84 ms a step against 1.92 on the histogram route; for sparser
+  // selections the pieces cost the pass more than they save behind it, so those keep the mask alone
+  // unless the option asks for pieces everywhere).  Entries a tile is expected to hand on: the keys
+  // reaching the guessed bound are at most about 1.2 k (the bound is the lower edge of a top-digit
+  // bin), spread over the tiles; room for 1.3 k's share plus six standard deviations of a tile's
+  // count.  Selections too dense for a piece take the histogram route.
+  const bool dense = k * 32 > n;
+  const double per_tile = 1.3 * (double)k * (double)kPassTile / (double)n;
+  const int64_t want = ((int64_t)std::ceil(per_tile + 6.0 * std::sqrt(per_tile) + 32.0) + 63) / 64 * 64;
+  const int64_t ntiles = (n + kPassTile - 1) / kPassTile;
+  if ((c->stage_tiles == 2 || (c->stage_tiles == 1 && dense)) && marking == 1 && want <= kStageMax &&
+      ntiles * want <= c->s.tilebuf_entries)
+    gp.tile_cap = (int32_t)want;
+  if (gp.tile_cap == 0 && dense) return gp;
   int64_t runs = n / (4 * kGuessRun);  // at most a quarter of the vector
   if (runs > 16384) runs = 16384;
   if (runs < 256) return gp;
@@ -590,7 +625,8 @@ void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const 
 // the leader's values at the selected indices.
 int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n, int32_t* idx_out,
                    bool hist_ready, int slot_by_leader, float* vals_row = nullptr,
-                   const LeaderArgs* leader_args = nullptr, bool guessed = false, float* zero_vec = nullptr) {
+                   const LeaderArgs* leader_args = nullptr, bool guessed = false, float* zero_vec = nullptr,
+                   int32_t tile_cap = 0) {
   hipStream_t st = c->stream;
   const unsigned nseg = (unsigned)pl.nseg;
   SelParams p = make_params(c, pl, tab, n, idx_out, vals_row, hist_ready ? slot_by_leader : 0, hist_ready);
@@ -604,6 +640,7 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
     // state says need_full, and the same two launches build the histogram of every key and pick
     // from that, after which the selection goes on as without a guess.
     p.mask = c->s.mask;
+    p.tiles = tile_buf(c, tile_cap);
     p.use_mcount = 1;
     hipLaunchKernelGGL(k_pick_mask, dim3(1, nseg), dim3(1024), 0, st, p, la);
     SelParams pf = p;
@@ -633,7 +670,13 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   // level 1: ordered compaction of the array (4 waves, 16 consecutive elements per lane: best of the
   // shapes measured on the 138 M and 1 G workloads); on the guess route the same launch counts
   // the second digit over a list that was written from the mask
-  if (guessed && hist_ready) {
+  const bool long_list = nseg == 1 && (int64_t)pl.desc[0].k * 32 > n;
+  if (guessed && hist_ready && long_list) {
+    // a list of many millions of entries written from the staged pieces: the lean list kernel
+    // counts its second digit; the array pass stands by for a guess that did not hold
+    hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 1);
+    hipLaunchKernelGGL((k_compact1<kC1Waves, kC1R>), dim3(pl.max_chunks, nseg), dim3(64 * kC1Waves), 0, st, p);
+  } else if (guessed && hist_ready) {
     const int64_t b1 = lblocks > pl.max_chunks ? lblocks : pl.max_chunks;
     hipLaunchKernelGGL(k_level1, dim3((unsigned)b1, nseg), dim3(64 * kC1Waves), 0, st, p);
   } else {
@@ -642,7 +685,6 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   // A list of many millions of entries (one element in 32 kept, or more) is counted faster by the
   // lean kernel of its own (99 vs 66 us on 15 M entries: the merged one carries the array pass'
   // registers), which is worth the launch of an array pass that has nothing to do.
-  const bool long_list = nseg == 1 && (int64_t)pl.desc[0].k * 32 > n;
   if (always_fits) {
     hipLaunchKernelGGL(k_list_hist, dim3((unsigned)lblocks, nseg), dim3(256), 0, st, p, 2);
   } else if (long_list) {
@@ -651,6 +693,12 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   } else {  // the same launch is the level-2 array pass where the level-1 survivors did not fit the list
     const int64_t b2 = lblocks > cblocks ? lblocks : cblocks;
     hipLaunchKernelGGL(k_level2, dim3((unsigned)b2, nseg), dim3(kCompactThreads), 0, st, p);
+  }
+  if (guessed && hist_ready && tile_cap > 0) {
+    // the fused pass stored +0.0 for every element it handed on: give back the ones below the threshold key
+    int64_t rblocks = ((int64_t)pl.desc[0].k * 2 + 2047) / 2048;
+    if (rblocks > per_seg * 4) rblocks = per_seg * 4;
+    hipLaunchKernelGGL(k_restore_pieces, dim3((unsigned)rblocks, nseg), dim3(256), 0, st, p);
   }
   int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < per_seg ? ltiles : per_seg);
@@ -683,7 +731,10 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
                         int64_t k, bool tiles_ready = false) {
   // long vectors with few kept entries: zeros streamed tile by tile, values stored behind them
   // (measured on 138 M elements: faster at k = N / 1000, even at N / 100, 40 % slower at N / 10)
-  if (n >= c->update_tiles_min_n && k * 128 <= n) {
+#ifndef ARTOPK_TILES_DENSITY
+#define ARTOPK_TILES_DENSITY 128
+#endif
+  if (n >= c->update_tiles_min_n && k * ARTOPK_TILES_DENSITY <= n) {
     if (!tiles_ready) enqueue_tile_starts(c, idx, n, k);
     hipLaunchKernelGGL((k_update_tiles<kPassRestThreads, kPassRestU>), dim3(pass_blocks(n)), dim3(kPassRestThreads), 0,
                        c->stream, update, n, idx, sum, k, c->s.tile_start, c->s.err_dev);
@@ -802,6 +853,12 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
   const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
   const size_t o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
+  // pieces of the survivor list staged per tile by the fused pass: room for kStageMax entries in
+  // every tile of the longest vector, but not more than the list itself takes
+  const int64_t max_tiles_pass = (max_n + kPassTile - 1) / kPassTile;
+  s.tilebuf_entries = max_tiles_pass * (int64_t)kStageMax;
+  const size_t o_tbuf = take((size_t)s.tilebuf_entries * sizeof(uint2));
+  const size_t o_tcnt = take((size_t)(max_tiles_pass + 1) * sizeof(uint32_t));
   const size_t total = off;
 
   e = hipMalloc(&c->slab, total);
@@ -826,6 +883,8 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
   s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
   s.tile_start = reinterpret_cast<int32_t*>(base + o_tstart);
+  s.tilebuf = reinterpret_cast<uint2*>(base + o_tbuf);
+  s.tile_cnt = reinterpret_cast<uint32_t*>(base + o_tcnt);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
@@ -899,6 +958,10 @@ int artopk_set_option(artopk_ctx* ctx, int32_t key, int64_t value) {
       if (value != 0 && value != 1) return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_NONTEMPORAL takes 0 or 1");
       ctx->pass_a_nt = value != 0;
       return ARTOPK_OK;
+    case ARTOPK_OPT_STAGE_TILES:
+      if (value < 0 || value > 2) return fail(ctx, ARTOPK_EINVAL, "ARTOPK_OPT_STAGE_TILES takes 0, 1 or 2");
+      ctx->stage_tiles = (int)value;
+      return ARTOPK_OK;
     default:
       return fail(ctx, ARTOPK_EINVAL, "unknown option %d", key);
   }
@@ -911,6 +974,7 @@ int artopk_get_option(const artopk_ctx* ctx, int32_t key, int64_t* value_out) {
     case ARTOPK_OPT_UPDATE_TILES_MIN_N: *value_out = ctx->update_tiles_min_n; return ARTOPK_OK;
     case ARTOPK_OPT_LEADER_FIRST: *value_out = ctx->leader_first ? 1 : 0; return ARTOPK_OK;
     case ARTOPK_OPT_NONTEMPORAL: *value_out = ctx->pass_a_nt ? 1 : 0; return ARTOPK_OK;
+    case ARTOPK_OPT_STAGE_TILES: *value_out = ctx->stage_tiles; return ARTOPK_OK;
     default: return ARTOPK_EINVAL;
   }
 }
@@ -1249,7 +1313,8 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   const bool segmented = seg_off != nullptr && nseg > 1;
   // a flat selection on a long vector samples a threshold guess first; its chunks are then whole
   // tiles of the fused pass, which strides over the tiles and counts per chunk
-  const GuessPlan gp = segmented ? GuessPlan{} : plan_guess(ctx, n, k);
+  const bool leader_first = (mode == ARTOPK_STAR || mode == ARTOPK_FIXED) && !segmented && ctx->leader_first;
+  const GuessPlan gp = segmented ? GuessPlan{} : plan_guess(ctx, n, k, leader_first ? 1 : (int)w);
   Plan flat;
   const Plan* pl = &flat;
   if (segmented) {
@@ -1294,7 +1359,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     return ARTOPK_OK;
   }
 
-  if (mode != ARTOPK_VAR && mode != ARTOPK_VAR_G && !segmented && ctx->leader_first) {
+  if (leader_first) {
     // The leader is known up front: run its pass and the selection first, then
     // stream over the other workers once, gathering and zeroing on the way.
     const int L = leader_host;
@@ -1311,7 +1376,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     ctx->last_dom_workers = w > 1 ? w - 1 : 1;
     if (gp.on) {
       enqueue_guess(ctx, gp, g1t, r1t, 1);
-      launch_pass_mark(ctx, 0, 1, g1t, r1t, n, geom.chunk_elems);
+      launch_pass_mark(ctx, 0, 1, g1t, r1t, n, geom.chunk_elems, gp.tile_cap);
     } else {
       launch_pass_a(ctx, 0, 1, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
     }
@@ -1319,7 +1384,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     // The leader's residual is zeroed inside the selection: its kernels have the kept values in
     // registers (level-1 compaction) or write the kept indices anyway (final list pass).
     if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on,
-                             residual[L])))
+                             residual[L], gp.tile_cap)))
       return rc;
     prof_mark(ctx, 2);
     const int rest = (int)w - 1;

@@ -66,7 +66,7 @@ constexpr int kHistReps = 16;            // partial copies of a whole-vector his
 // One slot of whole-vector scratch (32-bit words): the partial histogram copies, then the
 // histogram of the threshold-guess sample, then its control words.
 constexpr int kSlotGuessHist = kHistReps * kHistBins;
-constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound
+constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound, [2] a tile kept its marks to the mask
 constexpr int kSlotMcount = kSlotCtrl + 16;            // marked elements per chunk (kMaxChunks words)
 constexpr int kSlotWords = kSlotMcount + 1024;
 constexpr uint32_t kNoGuess = 0xffffffffu;             // no key reaches this bound
@@ -77,6 +77,17 @@ constexpr uint32_t kQuotaInf = 0x7fffffffu;
 // digit l (0,1,2) of a key: shift and mask
 __host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 19 : (level == 1 ? 7 : 0); }
 __host__ __device__ constexpr uint32_t digit_mask(int level) { return level == 2 ? 0x7fu : 0xfffu; }
+
+constexpr uint32_t kTileOverflow = 0xffffffffu;
+constexpr int kStageMax = 6144;  // list entries a tile can hand on (48 KiB of on-chip memory)
+
+struct TileBuf {
+  uint2* buf;       // [slot][tile][cap] staged list entries, or nullptr
+  uint32_t* cnt;    // [slot][tile] entries staged per tile, or kTileOverflow
+  int64_t buf_stride;  // entries per slot
+  int64_t cnt_stride;  // tiles per slot
+  int32_t cap;         // entries per tile (<= kStageMax)
+};
 
 struct PtrTable {
   float* p[kMaxW];
@@ -140,6 +151,7 @@ struct SelParams {
   const uint32_t* h_all;   // [workers][kSlotWords] whole-vector histograms from the fused pass, or nullptr
   const uint64_t* mask;    // [workers][mask_stride] survivor bit masks from the fused pass, or nullptr
   int64_t mask_stride;     // 64-bit words per worker
+  TileBuf tiles;           // list entries the fused pass staged per tile (buf == nullptr: none)
   int32_t use_mcount;      // the slots' per-chunk counts of marked elements are valid
   int32_t from_list;       // k_pick0: the top-digit histogram covers the survivor list written from the mask
   int32_t after_mask;      // k_pick0 behind k_mask_or_hist: from_list if the mask was used, else the full pick
@@ -171,6 +183,9 @@ struct SegView {
   uint32_t* hseg;       // the segment's own top-digit histogram (single copy), what k_hist0 fills without h_all
   const uint32_t* ctrl;  // control words of the vector's slot (guessed bound), or nullptr
   const uint64_t* mask;  // survivor bit mask of the vector, or nullptr
+  const uint2* tbuf;     // list entries the fused pass staged per tile of the vector, or nullptr
+  const uint32_t* tcnt;  // their number per tile (kTileOverflow: none, use the mask)
+  int32_t tcap;          // entries per tile in tbuf
   const uint32_t* mcount;  // marked elements per chunk of the vector, or nullptr
   uint64_t* flags;
   uint32_t* S;
@@ -455,6 +470,9 @@ __device__ __forceinline__ SegView seg_view(const SelParams& p, int seg, int lea
   v.hseg = zb + kSegHtop;
   v.ctrl = p.h_all ? p.h_all + slot * kSlotWords + kSlotCtrl : nullptr;
   v.mask = p.mask ? p.mask + slot * (size_t)p.mask_stride : nullptr;
+  v.tbuf = (p.mask && p.tiles.buf) ? p.tiles.buf + slot * (size_t)p.tiles.buf_stride : nullptr;
+  v.tcnt = (p.mask && p.tiles.buf) ? p.tiles.cnt + slot * (size_t)p.tiles.cnt_stride : nullptr;
+  v.tcap = p.tiles.cap;
   v.mcount = (p.h_all && p.use_mcount) ? p.h_all + slot * kSlotWords + kSlotMcount : nullptr;
   v.S = p.S + (slot * kMaxChunks + (size_t)v.d.chunk_begin) * kHistBins;
   v.chunk_off = p.chunk_off + v.d.chunk_begin;
@@ -618,17 +636,41 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
 //   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
 //   Variance partials: block b of worker y (see VarAcc).
+//   STAGE: the marked elements of a tile are also handed on as list entries
+//   (index, raw bits), in ascending element order: ranked inside the block (the
+//   128 row counts of the tile are scanned by every wave), collected in on-chip
+//   memory and stored as one contiguous piece to tiles.buf[tile][0 .. count), with
+//   tiles.cnt[tile] = count.  A tile with more marks than tiles.cap entries stores
+//   none and reports kTileOverflow; its marks are still in the mask.  Whoever
+//   builds the survivor list then copies the pieces instead of fetching the marked
+//   values one by one.  In a tile that hands its marks on, the marked elements are
+//   stored to the residual as +0.0 straight away: nearly all of them will be kept,
+//   and k_restore_pieces puts the others back once the threshold is known
+//   (restore_pieces() does it for all of them if the guess does not hold).
 // ---------------------------------------------------------------------------
+// Inclusive prefix sums over the 64 lanes of a wave.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t x = __shfl_up(v, off, 64);
+    if (lane >= off) v += x;
+  }
+  return v;
+}
+
 // First of the four mask words of row `row` (256 elements) of a vector: tiles of 128 rows, inside a
 // tile row r belongs to wave r mod 16 as its (r / 16)-th row.
 __device__ __forceinline__ int64_t mask_word(int64_t row) {
   return (row >> 7) * 512 + (row & 15) * 32 + ((row >> 4) & 7) * 4;
 }
 
-template <int STATS, bool NT, int GT, int T, int U>
+template <int STATS, bool NT, int GT, int T, int U, bool STAGE>
 __global__ void __launch_bounds__(T)
 k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
-            uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials) {
+            uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials, TileBuf tiles) {
+  __shared__ uint32_t wcnt[STAGE ? (T / 64) * U : 1];  // the tile's 128 row counts, row-major
+  __shared__ uint2 stage[STAGE ? kStageMax : 1];
   const int w = blockIdx.y;
   const int bx = blockIdx.x;
   const int nblk = gridDim.x;
@@ -651,6 +693,13 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
   VarAcc va;
   const int wave_first = __builtin_amdgcn_readfirstlane(tid - lane);
   static_assert(T == 1024 && U == 8, "mask_word() is laid out for 16 waves x 8 rows");
+  const int wave = wave_first >> 6;
+  uint2* __restrict__ tbuf = STAGE ? tiles.buf + (size_t)w * (size_t)tiles.buf_stride : nullptr;
+  uint32_t* __restrict__ tcnt = STAGE ? tiles.cnt + (size_t)w * (size_t)tiles.cnt_stride : nullptr;
+  // STAGE: what a lane keeps of a tile until its marks are ranked
+  uint32_t own = 0u;      // bit 4 u + e: element e of this lane's group in row u is marked
+  uint32_t rows_cnt = 0u; // lane u < U: marks of the wave's row u
+  uint32_t bits[STAGE ? U : 1][4];
 
   // One tile: U rows of T float4 groups; the wave's rows start at group qw (a multiple of 64).
   // FULL: every group of the tile lies inside the vector, so nothing is predicated.
@@ -678,7 +727,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
         v.y = a[u].y + b[u].y;
         v.z = a[u].z + b[u].z;
         v.w = a[u].w + b[u].w;
-        store4<NT>(rp + 4 * q, v);
+        if (!STAGE) store4<NT>(rp + 4 * q, v);  // (STAGE stores below, the marked elements as +0.0)
         if (STATS) {  // of the raw gradient, or of the error-fed value
           if (u == 0) va.seed4(STATS == 2 ? a[u] : v);
           va.add4(STATS == 2 ? a[u] : v);
@@ -688,7 +737,30 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       const uint64_t m1 = __ballot(valid && !(__builtin_fabsf(v.y) < gf));
       const uint64_t m2 = __ballot(valid && !(__builtin_fabsf(v.z) < gf));
       const uint64_t m3 = __ballot(valid && !(__builtin_fabsf(v.w) < gf));
-      marked += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+      const uint32_t row_marked = (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+      marked += row_marked;
+      if (STAGE) {
+        const uint32_t o = (uint32_t)((m0 >> lane) & 1ull) | (uint32_t)((m1 >> lane) & 1ull) << 1 |
+                           (uint32_t)((m2 >> lane) & 1ull) << 2 | (uint32_t)((m3 >> lane) & 1ull) << 3;
+        own |= o << (4 * u);
+        rows_cnt = lane == u ? row_marked : rows_cnt;
+        bits[STAGE ? u : 0][0] = __float_as_uint(v.x);
+        bits[STAGE ? u : 0][1] = __float_as_uint(v.y);
+        bits[STAGE ? u : 0][2] = __float_as_uint(v.z);
+        bits[STAGE ? u : 0][3] = __float_as_uint(v.w);
+        if (valid) {
+          // The marked elements go out as +0.0: they are survivors, nearly all of which the
+          // selection keeps; the list carries their values on, and its final pass puts back the
+          // few that are not kept.  (A tile that turns out not to hand its marks on stores them
+          // again, below.)
+          v4f z;
+          z.x = (o & 1u) ? 0.0f : v.x;
+          z.y = (o & 2u) ? 0.0f : v.y;
+          z.z = (o & 4u) ? 0.0f : v.z;
+          z.w = (o & 8u) ? 0.0f : v.w;
+          store4<NT>(rp + 4 * q, z);
+        }
+      }
       mine = lane == 4 * u + 0 ? m0 : mine;
       mine = lane == 4 * u + 1 ? m1 : mine;
       mine = lane == 4 * u + 2 ? m2 : mine;
@@ -701,8 +773,62 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
 
   for (int64_t ti = bx; ti < ntiles; ti += nblk) {
     const int64_t qw = ti * TQ + wave_first;  // wave-uniform, so all 64 lanes stay together (the masks need that)
+    if (STAGE) own = 0u;
     const uint32_t marked = (ti + 1) * TQ <= q_hi ? tile(qw, std::true_type{}) : tile(qw, std::false_type{});
     if (lane == 0 && marked != 0u) atomicAdd(&mcount[(ti * TQ * 4) / chunk_elems], marked);
+    if (STAGE) {
+      // rank the tile's marks: element order is row-major, row = 16 u + wave, then lane, then e
+      if (lane < U) wcnt[lane * (T / 64) + wave] = rows_cnt;
+      __syncthreads();
+      const uint32_t c0 = wcnt[lane], c1 = wcnt[64 + lane];  // (every wave scans the 128 counts itself)
+      const uint32_t s0 = wave_incl_scan(c0), s1 = wave_incl_scan(c1);
+      const uint32_t half = __shfl(s0, 63, 64);
+      const uint32_t total = half + __shfl(s1, 63, 64);
+      const bool fits = total <= (uint32_t)tiles.cap;
+      if (!fits) {  // rare: the marks stay in the mask only, so their values go back into the vector
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (((own >> (4 * u)) & 0xfu) != 0u) {
+            const int64_t q = qw + lane + u * T;
+            v4f v;
+            v.x = __uint_as_float(bits[STAGE ? u : 0][0]);
+            v.y = __uint_as_float(bits[STAGE ? u : 0][1]);
+            v.z = __uint_as_float(bits[STAGE ? u : 0][2]);
+            v.w = __uint_as_float(bits[STAGE ? u : 0][3]);
+            store4<NT>(rp + 4 * q, v);
+          }
+        }
+        if (tid == 0) atomicOr(&slot[kSlotCtrl + 2], 1u);
+      }
+      if (fits && total != 0u) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int r = u * (T / 64) + wave;  // this wave's row u among the tile's 128
+          // marks in the rows before it
+          const uint32_t before = r < 64 ? __shfl(s0 - c0, r, 64) : half + __shfl(s1 - c1, r - 64, 64);
+          const uint64_t b0 = __ballot((own >> (4 * u + 0)) & 1u), b1 = __ballot((own >> (4 * u + 1)) & 1u);
+          const uint64_t b2 = __ballot((own >> (4 * u + 2)) & 1u), b3 = __ballot((own >> (4 * u + 3)) & 1u);
+          if (((own >> (4 * u)) & 0xfu) != 0u) {
+            uint32_t pos = before + popc_lt(b0) + popc_lt(b1) + popc_lt(b2) + popc_lt(b3);
+            const uint32_t j0 = (uint32_t)(4 * (qw + lane + u * T));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if ((own >> (4 * u + e)) & 1u) {
+                stage[pos] = make_uint2(j0 + (uint32_t)e, bits[STAGE ? u : 0][e]);
+                ++pos;
+              }
+            }
+          }
+        }
+      }
+      __syncthreads();
+      if (fits) {
+        uint2* __restrict__ dst = tbuf + (size_t)ti * (size_t)tiles.cap;
+        for (uint32_t i = (uint32_t)tid; i < total; i += T) dst[i] = stage[i];
+      }
+      if (tid == 0) tcnt[ti] = fits ? total : kTileOverflow;
+      // (the next tile writes wcnt before its first barrier and stage behind it: both are free by then)
+    }
   }
   // scalar tail (n not a multiple of 4): the first block
   if (bx == 0) {
@@ -991,6 +1117,27 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
 // Whole aligned float4 groups are read where they lie inside the array, single
 // elements at its ragged end; elements outside the chunk are masked out.
 // ---------------------------------------------------------------------------
+// The guess did not hold after a fused pass that handed marked elements on per tile and stored
+// +0.0 in their place: the block that owns chunk c puts the values of its tiles' pieces back into
+// the vector before anything reads it (chunks are whole tiles on this route, so this is local to
+// the block; the caller's barrier and this fence order it before the block's own reads).
+template <int T>
+__device__ __forceinline__ void restore_pieces(const SelParams& p, const SegView& sv, int c) {
+  const int64_t c_begin = sv.d.geom.chunk0 + (int64_t)c * sv.d.geom.chunk_elems;
+  int64_t c_end = c_begin + sv.d.geom.chunk_elems;
+  if (c_end > (p.n & ~(int64_t)3)) c_end = p.n & ~(int64_t)3;
+  for (int64_t t = c_begin / kPassTile; t * kPassTile < c_end; ++t) {
+    const uint32_t cnt = sv.tcnt[t];
+    if (cnt == kTileOverflow) continue;
+    const uint2* __restrict__ piece = sv.tbuf + (size_t)t * (size_t)sv.tcap;
+    for (uint32_t e = threadIdx.x; e < cnt; e += T) {
+      const uint2 ent = piece[e];
+      if ((int64_t)ent.x < p.n) p.zero_vec[ent.x] = __uint_as_float(ent.y);
+    }
+  }
+  __threadfence();
+}
+
 template <int T>
 __device__ __forceinline__ void hist0_body(const SelParams& p) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
@@ -1002,6 +1149,7 @@ __device__ __forceinline__ void hist0_body(const SelParams& p) {
   const int tid = threadIdx.x;
   const float* __restrict__ xp = sv.x;
   for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
+  if (sv.tbuf != nullptr && p.zero_vec != nullptr) restore_pieces<T>(p, sv, c);
   __syncthreads();
   int64_t cs = sv.d.geom.chunk0 + (int64_t)c * sv.d.geom.chunk_elems;
   int64_t ce = cs + sv.d.geom.chunk_elems;
@@ -1697,6 +1845,149 @@ __device__ __forceinline__ void compact_mask_body(const SelParams& p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// compact_tiles_body : the survivor list from what the fused pass staged per tile
+// (k_pass_mark with STAGE): one block of 1024 threads per chunk copies the tiles'
+// pieces, in tile order, to the list from chunk_off[c] on and counts the entries'
+// top digits, as compact_mask_body does.  The chunk is walked in slabs of eight
+// tiles; a slab with a tile that staged nothing (kTileOverflow: more marks than a
+// piece holds) is built from the mask instead: one thread per mask row writes the
+// row's marked indices, then the block fetches the values entry by entry.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void compact_tiles_body(const SelParams& p) {
+  constexpr int T = 1024, WAVES = 16, SLAB = 8;  // tiles per slab (1024 mask rows)
+  __shared__ uint32_t wtot[WAVES];
+  __shared__ uint32_t lh[kHistBins];
+  __shared__ uint32_t tc[SLAB];
+
+  const SegView sv = seg_view(p, blockIdx.y);
+  const int c = blockIdx.x;
+  if (c >= sv.d.geom.nchunks) return;
+  const SelState st = *sv.st;
+  if (st.use_mask == 0u || sv.mask == nullptr || *p.err) return;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const uint32_t lane = lane_id();
+  const int64_t n = p.n;
+  const ChunkGeom geom = sv.d.geom;
+  const uint32_t cap = sv.d.cap;
+  const uint32_t list_lo = st.list_lo;
+  const float* __restrict__ xp = sv.x;
+  const uint64_t* __restrict__ mk = sv.mask;
+  uint2* list = sv.list;
+
+  for (int b = tid; b < kHistBins; b += T) lh[b] = 0u;
+
+  const int64_t c_begin = geom.chunk0 + (int64_t)c * geom.chunk_elems;  // a whole number of tiles
+  int64_t c_end = c_begin + geom.chunk_elems;
+  if (c_end > n) c_end = n;
+  const int64_t n_vec = n & ~(int64_t)3;                      // marked elements end here
+  const int64_t v_end = c_end < n_vec ? c_end : n_vec;
+  const int64_t tile_lo = c_begin / kPassTile;
+  const int64_t tile_hi = (v_end + kPassTile - 1) / kPassTile;  // exclusive
+  const int64_t row_end = (v_end + 255) >> 8;                   // exclusive
+
+  uint32_t run = sv.chunk_off[c];  // list position of the next entry of this chunk
+  for (int64_t t0 = tile_lo; t0 < tile_hi; t0 += SLAB) {
+    const int ntl = (int)(tile_hi - t0 < SLAB ? tile_hi - t0 : SLAB);
+    __syncthreads();  // tc, wtot and the histogram's clearing
+    if (tid < SLAB) tc[tid] = tid < ntl ? sv.tcnt[t0 + tid] : 0u;
+    __syncthreads();
+    uint32_t pre[SLAB + 1];
+    bool staged = true;
+    pre[0] = 0u;
+#pragma unroll
+    for (int i = 0; i < SLAB; ++i) {
+      const uint32_t v = tc[i];
+      staged = staged && v != kTileOverflow;
+      pre[i + 1] = pre[i] + (v != kTileOverflow ? v : 0u);
+    }
+    if (staged) {  // the same in every thread
+      const uint32_t total = pre[SLAB];
+      for (uint32_t f = (uint32_t)tid; f < total; f += T) {
+        int i = 0;
+#pragma unroll
+        for (int q = 1; q < SLAB; ++q) i += f >= pre[q] ? 1 : 0;  // the tile this entry belongs to
+        const uint2 ent = sv.tbuf[(size_t)(t0 + i) * (size_t)sv.tcap + (f - pre[i])];
+        if (run + f < cap) list[run + f] = ent;
+        atomicAdd(&lh[(ent.y & kKeyMask) >> 19], 1u);
+      }
+      run += total;
+      continue;
+    }
+    // from the mask: thread t owns row 128 t0 + t
+    const int64_t row = t0 * (kPassTile / 256) + tid;
+    uint64_t m[4] = {0ull, 0ull, 0ull, 0ull};
+    if (row < row_end) {
+      const uint4 lo2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[0];
+      const uint4 hi2 = reinterpret_cast<const uint4*>(mk + mask_word(row))[1];
+      m[0] = ((uint64_t)lo2.y << 32) | lo2.x;
+      m[1] = ((uint64_t)lo2.w << 32) | lo2.z;
+      m[2] = ((uint64_t)hi2.y << 32) | hi2.x;
+      m[3] = ((uint64_t)hi2.w << 32) | hi2.z;
+    }
+    const uint32_t cnt = (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+    uint32_t before = 0u, wsum = 0u;
+#pragma unroll
+    for (int b = 0; b <= 8; ++b) {
+      const uint64_t plane = __ballot((cnt >> b) & 1u);
+      before += popc_lt(plane) << b;
+      wsum += (uint32_t)__popcll(plane) << b;
+    }
+    if (lane == 0) wtot[wave] = wsum;
+    __syncthreads();
+    uint32_t pos = run + before, total = 0u;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      const uint32_t wt = wtot[i];
+      if (i < wave) pos += wt;
+      total += wt;
+    }
+    uint64_t any = m[0] | m[1] | m[2] | m[3];
+    while (any) {
+      const int g = __builtin_ctzll(any);
+      const uint64_t bit = 1ull << g;
+      any &= ~bit;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (m[e] & bit) {
+          if (pos < cap) list[pos].x = (uint32_t)(row * 256 + 4 * g + e);
+          ++pos;
+        }
+      }
+    }
+    __threadfence_block();  // the indices are written before any thread of the block reads them
+    __syncthreads();
+    for (uint32_t e0 = (uint32_t)tid; e0 < total; e0 += T) {
+      if (run + e0 < cap) {
+        const uint32_t raw = __float_as_uint(xp[list[run + e0].x]);
+        list[run + e0].y = raw;
+        atomicAdd(&lh[(raw & kKeyMask) >> 19], 1u);
+      }
+    }
+    run += total;
+  }
+  // the elements behind the last whole group of four are not in the mask
+  if (c_end == n && n_vec < n && tid == 0) {
+    for (int64_t j = n_vec; j < n; ++j) {
+      const uint32_t raw = __float_as_uint(xp[j]);
+      const uint32_t kk = raw & kKeyMask;
+      if (kk >= list_lo) {
+        atomicAdd(&lh[kk >> 19], 1u);
+        if (run < cap) list[run] = make_uint2((uint32_t)j, raw);
+        ++run;
+      }
+    }
+  }
+
+  __syncthreads();
+  uint32_t* __restrict__ htop = sv.htop + (size_t)(c % sv.htop_reps) * kHistBins;
+  for (int b = tid; b < kHistBins; b += T) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&htop[b], v);
+  }
+}
+
 // k_mask_or_hist : the kernel behind k_pick_mask.  Per segment it does whichever of the two
 // jobs the state asks for: the list from the mask (use_mask), or, after a guess that did not
 // hold, the per-chunk histograms of every key (need_full; p_full are the parameters of that
@@ -1707,7 +1998,10 @@ __global__ void __launch_bounds__(1024)
 k_mask_or_hist(SelParams p, SelParams p_full) {
   const SelState* st = seg_view(p, blockIdx.y).st;
   if (st->use_mask != 0u) {
-    compact_mask_body<UB>(p);
+    if (p.tiles.buf != nullptr)
+      compact_tiles_body(p);
+    else
+      compact_mask_body<UB>(p);
   } else if (st->need_full != 0u) {
     hist0_body<1024>(p_full);
   }
@@ -1999,7 +2293,7 @@ __device__ __forceinline__ void compact_body(const SelParams& p, const SegView& 
                   if (pos < k_out) {
                     idx_out[pos] = pay[LIST ? r : 0][e];
                     if (vals_row) vals_row[pos] = __uint_as_float(key[r][e]);
-                    // kept entries that the level-1 pass has not already put to +0.0
+                    // kept entries that nothing has put to +0.0 yet
                     if (zero_vec && ((key[r][e] & kKeyMask) <= zero_below)) {
                       const int32_t zi = pay[LIST ? r : 0][e];
                       if (zi >= 0 && (int64_t)zi < p.n) zero_vec[zi] = 0.0f;
@@ -2028,6 +2322,57 @@ __device__ __forceinline__ void compact_body(const SelParams& p, const SegView& 
   }
 }
 
+// The survivor list was copied from pieces staged by a fused pass that stored +0.0 in place of
+// every element it handed on (k_pass_mark with STAGE).  k_restore_pieces, which runs before the final
+// pass over the list, then leaves exactly the keys above the threshold key at +0.0; the final pass
+// has the kept ties (key = threshold) left to zero.
+__device__ __forceinline__ bool from_pieces(const SelParams& p, const SegView& sv) {
+  return p.zero_vec != nullptr && sv.tbuf != nullptr && sv.st->use_mask != 0u;
+}
+
+// ---------------------------------------------------------------------------
+// k_restore_pieces : runs between the last digit histogram and the final pass over a list that
+// was copied from staged pieces.  The threshold key T is known by now (replayed from the digit
+// histograms).  Elements handed on in a piece are +0.0 in the vector: those with key <= T get their
+// values back from the list (the kept ones among the ties are zeroed again by the final pass).
+// Elements of the list that no piece handed on (a tile whose marks stayed in the mask, the n mod 4
+// last elements) still hold their values: those with key > T become +0.0 here.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_restore_pieces(SelParams p) {
+  __shared__ SelState st;
+  __shared__ uint32_t pick_part[256];
+  const SegView sv = seg_view(p, blockIdx.y);
+  if (!from_pieces(p, sv) || *p.err) return;
+  const uint32_t cnt = sv.st->list_count;
+  if ((uint64_t)blockIdx.x * 2048u >= (uint64_t)cnt) return;
+  derive_state<256>(sv, st, 3, pick_part, p.err);
+  if (st.level != 3u) return;
+  const uint32_t t_key = st.hi;
+  const bool all_pieces = sv.ctrl != nullptr && sv.ctrl[2] == 0u;  // no tile kept its marks to the mask
+  const int64_t n_vec = p.n & ~(int64_t)3;
+  for (uint64_t base = (uint64_t)blockIdx.x * 2048u; base < cnt; base += (uint64_t)gridDim.x * 2048u) {
+    uint2 ent[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint64_t q = base + (uint64_t)i * 256u + threadIdx.x;
+      ent[i] = q < cnt ? sv.list[q] : make_uint2(0xffffffffu, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t j = (int64_t)ent[i].x;
+      if (j >= p.n) continue;  // (the filler, or not an index)
+      const uint32_t key = ent[i].y & kKeyMask;
+      const bool handed_on = j < n_vec && (all_pieces || sv.tcnt[j / kPassTile] != kTileOverflow);
+      if (handed_on) {
+        if (key <= t_key) p.zero_vec[j] = __uint_as_float(ent[i].y);
+      } else if (key > t_key) {
+        p.zero_vec[j] = 0.0f;
+      }
+    }
+  }
+}
+
 // Keys the level-1 pass has already put to +0.0 in zero_vec lie above this one (every key if it
 // has not zeroed any).
 __device__ __forceinline__ uint32_t zeroed_above(const SelState* stp) {
@@ -2048,7 +2393,7 @@ k_compact(SelParams p, int level, int launch_id) {
   // tiles are handed out by a counter, so blocks beyond the number of list tiles are not needed
   if (LIST && stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
   derive_state<kCompactThreads>(sv, st, LIST ? 3 : level, pick_part, p.err);
-  compact_body<LIST, false>(p, sv, st, level, launch_id, zero_below);
+  compact_body<LIST, false>(p, sv, st, level, launch_id, (LIST && from_pieces(p, sv)) ? st.hi : zero_below);
 }
 
 // ---------------------------------------------------------------------------
@@ -2070,7 +2415,7 @@ k_final(SelParams p) {
   if (st.compact_level == 3u)
     compact_body<false, true>(p, sv, st, 3, 1, zero_below);
   else
-    compact_body<true, false>(p, sv, st, 3, 2, zero_below);
+    compact_body<true, false>(p, sv, st, 3, 2, from_pieces(p, sv) ? st.hi : zero_below);
 }
 
 // ---------------------------------------------------------------------------

@@ -23,9 +23,12 @@ from tests.gpu_util import GpuRunner, assert_step_matches, top_two_gap
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture
-def guess_on(monkeypatch):
+@pytest.fixture(params=["pieces", "mask_only"])
+def guess_on(monkeypatch, request):
+    """The guess route on short vectors, in both of its forms for a leader known up front: the
+    fused pass hands the marked elements on tile by tile (the default), or leaves only the mask."""
     monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+    monkeypatch.setitem(gpu_util.OPTIONS, "stage_tiles", 2 if request.param == "pieces" else 0)
 
 
 def _sample_positions(n):
@@ -224,3 +227,62 @@ def test_guess_kept_elements_clustered_in_two_tiles(guess_on, mode):
 
     runner = GpuRunner(w, n, k)
     _run_steps(runner, gen, w, n, k, orc.MODE_STAR if mode == "star" else orc.MODE_VAR, 2, expect_mask=None)
+
+
+@pytest.mark.parametrize("n", [16_384, 32_768, 32_769, 3 * 32_768 + 2, 9 * 32_768 - 1, 17 * 32_768 + 131])
+def test_guess_pieces_ragged_lengths(guess_on, n):
+    """Vector lengths around the tile and slab borders of the staged pieces (a slab is eight tiles)."""
+    w = 2
+    wl = inp.workload(1, n=n, w=w)
+    k = max(1, n // 200)
+    runner = GpuRunner(w, n, k)
+    _run_steps(runner, lambda s, r: wl.gen(s, r), w, n, k, orc.MODE_STAR, 2, expect_mask=None)
+
+
+@pytest.mark.parametrize("rho", [0.1, 0.05])
+def test_guess_pieces_dense_keep(guess_on, rho):
+    """One element in ten kept: with the pieces the guess route also serves selections this dense
+    (without them it stands back for the histogram route)."""
+    n, w = 1_200_003, 3
+    wl = inp.workload(4, n=n, w=w)
+    k = wl.k(rho)
+    runner = GpuRunner(w, n, k)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (1, 2, 3):
+        g = [wl.gen(step_no, r) for r in range(w)]
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
+        runner.load_g(g)
+        got = runner.step(k, orc.MODE_STAR, step_no)
+        info = runner.ctx.select_info()
+        staged = gpu_util.OPTIONS["stage_tiles"] != 0
+        assert info["guessed"] == (1 if staged else 0), info
+        if staged:
+            assert info["from_mask"] == 1, info
+        assert_step_matches(got, want, orc.MODE_STAR)
+        res = want.residual
+
+
+@pytest.mark.parametrize("where", ["one_tile_overflows", "every_eighth_tile_overflows", "all_in_last_tile"])
+def test_guess_pieces_tiles_with_more_marks_than_a_piece_holds(guess_on, where):
+    """Tiles whose marks exceed the piece size report an overflow and their slab is built from the
+    mask, next to slabs built from pieces."""
+    n, w, k = 37 * 32768 + 77, 2, 6_000
+    rng = np.random.default_rng(31)
+
+    def gen(step_no, r):
+        x = (1e-3 * rng.standard_normal(n)).astype(np.float32)
+        big = lambda m: ((1.0 + rng.random(m)) * np.where(rng.random(m) < 0.5, -1.0, 1.0)).astype(np.float32)
+        if where == "one_tile_overflows":
+            lo = 9 * 32768 + 100
+            x[lo:lo + 4000] = big(4000)
+            x[::997] = big(len(x[::997]))
+        elif where == "every_eighth_tile_overflows":
+            for t in range(3, 37, 8):
+                x[t * 32768 + 5: t * 32768 + 1505] = big(1500)
+        else:
+            x[36 * 32768 + 10: 36 * 32768 + 5010] = big(5000)
+            x[n - 2] = np.float32(9.0)
+        return x
+
+    runner = GpuRunner(w, n, k)
+    _run_steps(runner, gen, w, n, k, orc.MODE_STAR, 2, expect_mask=None)

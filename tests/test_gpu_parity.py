@@ -810,9 +810,10 @@ def test_options_are_validated_and_reported():
     assert ctx.get_option(lib.ARTOPK_OPT_UPDATE_TILES_MIN_N) == 1 << 22
     assert ctx.get_option(lib.ARTOPK_OPT_LEADER_FIRST) == 1
     assert ctx.get_option(lib.ARTOPK_OPT_NONTEMPORAL) == 1
+    assert ctx.get_option(lib.ARTOPK_OPT_STAGE_TILES) == 1
     for key, bad in ((lib.ARTOPK_OPT_GUESS_MIN_N, 0), (lib.ARTOPK_OPT_GUESS_MIN_N, (1 << 31) + 1),
                      (lib.ARTOPK_OPT_UPDATE_TILES_MIN_N, -5), (lib.ARTOPK_OPT_LEADER_FIRST, 2),
-                     (lib.ARTOPK_OPT_NONTEMPORAL, -1), (99, 1)):
+                     (lib.ARTOPK_OPT_NONTEMPORAL, -1), (lib.ARTOPK_OPT_STAGE_TILES, 3), (99, 1)):
         with pytest.raises(lib.ArTopkError) as e:
             ctx.set_option(key, bad)
         assert e.value.code == -1
