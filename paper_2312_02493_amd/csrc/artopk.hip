@@ -58,6 +58,7 @@ struct Scratch {
   uint2* tilebuf = nullptr;       // list entries the fused pass stages per tile (guess route, one marking worker)
   int64_t tilebuf_entries = 0;
   uint32_t* tile_cnt = nullptr;   // [max_n / kPassTile + 1] entries staged per tile
+  uint32_t* sample_keys = nullptr;  // [16384 kGuessRun] keys of one vector's guess sample
   SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
   uint32_t cap = 0;               // list capacity of a flat (one-segment) select
 };
@@ -542,8 +543,14 @@ void launch_pass_rest_g(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTa
 // The number of kept indices below every tile of the streaming passes.
 void enqueue_tile_starts(artopk_ctx* c, const int32_t* idx, int64_t n, int64_t k) {
   const int32_t ntiles = (int32_t)((n + kPassTile - 1) / kPassTile);
-  hipLaunchKernelGGL(k_tile_starts, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, c->stream, idx, k, ntiles,
-                     c->s.tile_start);
+  // many kept indices per tile: a search per tile boundary beats a thread per index
+  // (138 M elements, one in ten kept: 20 us with a thread per index)
+  if (k > (int64_t)256 * ntiles)
+    hipLaunchKernelGGL(k_tile_starts_search, dim3((unsigned)(ntiles / 256 + 1)), dim3(256), 0, c->stream, idx, k,
+                       ntiles, c->s.tile_start);
+  else
+    hipLaunchKernelGGL(k_tile_starts, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, c->stream, idx, k, ntiles,
+                       c->s.tile_start);
 }
 
 // The other workers' streaming pass (leader known, idx final), striding over the tiles;
@@ -602,6 +609,9 @@ GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k, int marking) {
 
 // Samples the first nvec vectors of (g + residual) into slots 0 .. nvec-1 (cleared beforehand).
 void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const PtrTable& res, int nvec) {
+  // one vector whose marked elements are handed on per tile: a finer bound keeps the list (and the
+  // number of values to give back afterwards) close to k
+  uint32_t* sample = (nvec == 1 && gp.tile_cap > 0) ? c->s.sample_keys : nullptr;
   // about 128 blocks over all vectors (measured: 8 vectors take 70 us with 64 blocks each, 32 us
   // with 16; one vector 15 us with 64 blocks, 19 us with 16)
   int gblocks = 128 / nvec;
@@ -609,13 +619,16 @@ void enqueue_guess(artopk_ctx* c, const GuessPlan& gp, const PtrTable& g, const 
   if (gblocks < 8) gblocks = 8;
   if (c->g_type == ARTOPK_G_BF16)
     hipLaunchKernelGGL(k_guess<kGBF16>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
-                       gp.stride, gp.m_hi);
+                       gp.stride, gp.m_hi, sample);
   else if (c->g_type == ARTOPK_G_F16)
     hipLaunchKernelGGL(k_guess<kGF16>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
-                       gp.stride, gp.m_hi);
+                       gp.stride, gp.m_hi, sample);
   else
     hipLaunchKernelGGL(k_guess<kGF32>, dim3(gblocks, nvec), dim3(256), 0, c->stream, g, res, c->s.h_all, gp.runs,
-                       gp.stride, gp.m_hi);
+                       gp.stride, gp.m_hi, sample);
+  if (sample != nullptr)
+    hipLaunchKernelGGL(k_guess_refine, dim3(64), dim3(256), 0, c->stream, c->s.h_all, sample, gp.runs * kGuessRun,
+                       gp.m_hi);
 }
 
 // Top-k of every segment of the plan on the vector tab.p[*leader_dev]; the
@@ -693,12 +706,6 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   } else {  // the same launch is the level-2 array pass where the level-1 survivors did not fit the list
     const int64_t b2 = lblocks > cblocks ? lblocks : cblocks;
     hipLaunchKernelGGL(k_level2, dim3((unsigned)b2, nseg), dim3(kCompactThreads), 0, st, p);
-  }
-  if (guessed && hist_ready && tile_cap > 0) {
-    // the fused pass stored +0.0 for every element it handed on: give back the ones below the threshold key
-    int64_t rblocks = ((int64_t)pl.desc[0].k * 2 + 2047) / 2048;
-    if (rblocks > per_seg * 4) rblocks = per_seg * 4;
-    hipLaunchKernelGGL(k_restore_pieces, dim3((unsigned)rblocks, nseg), dim3(256), 0, st, p);
   }
   int64_t ltiles = (pl.max_cap + kCompactTile - 1) / kCompactTile;
   int fblocks = (int)(ltiles < per_seg ? ltiles : per_seg);
@@ -859,6 +866,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.tilebuf_entries = max_tiles_pass * (int64_t)kStageMax;
   const size_t o_tbuf = take((size_t)s.tilebuf_entries * sizeof(uint2));
   const size_t o_tcnt = take((size_t)(max_tiles_pass + 1) * sizeof(uint32_t));
+  const size_t o_sample = take((size_t)16384 * kGuessRun * sizeof(uint32_t));
   const size_t total = off;
 
   e = hipMalloc(&c->slab, total);
@@ -885,6 +893,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.tile_start = reinterpret_cast<int32_t*>(base + o_tstart);
   s.tilebuf = reinterpret_cast<uint2*>(base + o_tbuf);
   s.tile_cnt = reinterpret_cast<uint32_t*>(base + o_tcnt);
+  s.sample_keys = reinterpret_cast<uint32_t*>(base + o_sample);
 
   // leader and error words start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,

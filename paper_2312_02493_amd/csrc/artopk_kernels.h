@@ -66,9 +66,11 @@ constexpr int kHistReps = 16;            // partial copies of a whole-vector his
 // One slot of whole-vector scratch (32-bit words): the partial histogram copies, then the
 // histogram of the threshold-guess sample, then its control words.
 constexpr int kSlotGuessHist = kHistReps * kHistBins;
-constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound, [2] a tile kept its marks to the mask
+constexpr int kSlotCtrl = kSlotGuessHist + kHistBins;  // [0] blocks done, [1] guessed key bound, [2] a tile kept its marks to the mask,
+                                                       // [3] top digit of the bound, [4] sample keys above that digit, [5] refine blocks done
 constexpr int kSlotMcount = kSlotCtrl + 16;            // marked elements per chunk (kMaxChunks words)
-constexpr int kSlotWords = kSlotMcount + 1024;
+constexpr int kSlotRefine = kSlotMcount + 1024;        // second-digit histogram of the guess sample (k_guess_refine)
+constexpr int kSlotWords = kSlotRefine + kHistBins;
 constexpr uint32_t kNoGuess = 0xffffffffu;             // no key reaches this bound
 constexpr int kGuessRun = 16;                          // consecutive elements per sample run
 constexpr uint32_t kKeyMask = 0x7fffffffu;
@@ -223,7 +225,7 @@ __device__ __forceinline__ uint64_t wave_allsum_u64(uint64_t v) {
 
 constexpr int kTile = 8192;       // chunk granularity (a quarter of a tile of the fused pass)
 constexpr int kMaxChunks = 1024;  // chunks per vector range
-static_assert(kSlotWords == kSlotMcount + kMaxChunks, "a slot ends with one count per chunk");
+static_assert(kSlotRefine == kSlotMcount + kMaxChunks, "one count per chunk");
 constexpr int kPassTile = 32768;      // elements per block iteration of the streaming passes (1024 threads x 8 float4)
 constexpr int kMaxPassBlocks = 4096;  // blocks per worker of a streaming pass that strides over tiles
 
@@ -645,8 +647,9 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   builds the survivor list then copies the pieces instead of fetching the marked
 //   values one by one.  In a tile that hands its marks on, the marked elements are
 //   stored to the residual as +0.0 straight away: nearly all of them will be kept,
-//   and k_restore_pieces puts the others back once the threshold is known
-//   (restore_pieces() does it for all of them if the guess does not hold).
+//   and the others get their values back from the list once the threshold is known
+//   (see from_pieces(); restore_pieces() does it for all of them if the guess does
+//   not hold).
 // ---------------------------------------------------------------------------
 // Inclusive prefix sums over the 64 lanes of a wave.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
@@ -1036,13 +1039,17 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
 // m_hi-th largest key and publishes d << 19 (kNoGuess if the sample is smaller
 // than m_hi).  The bound is only a guess: whoever uses it checks that at least
 // k keys of the whole vector reach it.
+//   With sample_keys (vector 0 only: room for runs kGuessRun keys) every block
+//   also stores its sample's keys there, for k_guess_refine.
 // ---------------------------------------------------------------------------
 template <int GT>
 __global__ void __launch_bounds__(256)
-k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_t stride, uint32_t m_hi) {
+k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_t stride, uint32_t m_hi,
+        uint32_t* __restrict__ sample_keys) {
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint32_t wsum[4];
   __shared__ int last_sh, hit_sh;
+  __shared__ uint32_t hit_above_sh;
   const int tid = threadIdx.x;
   const int v = blockIdx.y;
   const float* __restrict__ gp = g.p[v];
@@ -1061,10 +1068,16 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
     }
 #pragma unroll
     for (int i = 0; i < kGuessRun / 4; ++i) {
-      atomicAdd(&lh[(__float_as_uint(a[i].x + b[i].x) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(a[i].y + b[i].y) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(a[i].z + b[i].z) & kKeyMask) >> 19], 1u);
-      atomicAdd(&lh[(__float_as_uint(a[i].w + b[i].w) & kKeyMask) >> 19], 1u);
+      uint4 kq;
+      kq.x = __float_as_uint(a[i].x + b[i].x) & kKeyMask;
+      kq.y = __float_as_uint(a[i].y + b[i].y) & kKeyMask;
+      kq.z = __float_as_uint(a[i].z + b[i].z) & kKeyMask;
+      kq.w = __float_as_uint(a[i].w + b[i].w) & kKeyMask;
+      atomicAdd(&lh[kq.x >> 19], 1u);
+      atomicAdd(&lh[kq.y >> 19], 1u);
+      atomicAdd(&lh[kq.z >> 19], 1u);
+      atomicAdd(&lh[kq.w >> 19], 1u);
+      if (sample_keys != nullptr && v == 0) reinterpret_cast<uint4*>(sample_keys + (size_t)r * kGuessRun)[i] = kq;
     }
   }
   __syncthreads();
@@ -1102,12 +1115,89 @@ k_guess(PtrTable g, PtrTable res, uint32_t* __restrict__ slots, int runs, int64_
   for (int i = (tid >> 6) + 1; i < 4; ++i) above += wsum[i];
 #pragma unroll
   for (int j = 15; j >= 0; --j) {
+    if (above < m_hi && above + h[j] >= m_hi) {  // one thread, one bin
+      hit_sh = 16 * tid + j;
+      hit_above_sh = above;
+    }
+    above += h[j];
+  }
+  __syncthreads();
+  const int hit = hit_sh;
+  // bounds above infinity's digit would not survive the floating-point comparison of the fused pass
+  const uint32_t bound = hit >= 0 ? (uint32_t)(hit < 0xff0 ? hit : 0xff0) << 19 : kNoGuess;
+  if (tid == 0) {
+    ctrl[3] = (hit >= 0 && hit < 0xff0) ? (uint32_t)hit : kNoGuess;  // (what k_guess_refine may refine)
+    ctrl[4] = hit_above_sh;
+  }
+  if (tid == 0) ctrl[1] = bound;
+}
+
+// ---------------------------------------------------------------------------
+// k_guess_refine : refines the bound k_guess published for vector 0 by the next 12
+// key bits: among the stored sample keys of the bound's top digit d it takes the
+// second digit of the key that is m_hi-th largest in the whole sample.  A bound
+// this fine admits about 1 % more keys than needed (plus the margin in m_hi)
+// instead of up to 15 %.  grid = blocks of 256 threads striding over the nkeys
+// sample keys; the last block to finish picks.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_guess_refine(uint32_t* __restrict__ slots, const uint32_t* __restrict__ sample_keys, int nkeys, uint32_t m_hi) {
+  __shared__ uint32_t lh[kHistBins];
+  __shared__ uint32_t wsum[4];
+  __shared__ int last_sh, hit_sh;
+  const int tid = threadIdx.x;
+  uint32_t* __restrict__ ctrl = slots + kSlotCtrl;
+  uint32_t* __restrict__ hist = slots + kSlotRefine;
+  const uint32_t d0 = ctrl[3];
+  if (d0 == kNoGuess) return;  // (the same in every block)
+  for (int b = tid; b < kHistBins; b += 256) lh[b] = 0u;
+  __syncthreads();
+  const uint4* __restrict__ sk = reinterpret_cast<const uint4*>(sample_keys);
+  for (int q = blockIdx.x * 256 + tid; q < nkeys / 4; q += gridDim.x * 256) {
+    const uint4 kq = sk[q];
+    if ((kq.x >> 19) == d0) atomicAdd(&lh[(kq.x >> 7) & 0xfffu], 1u);
+    if ((kq.y >> 19) == d0) atomicAdd(&lh[(kq.y >> 7) & 0xfffu], 1u);
+    if ((kq.z >> 19) == d0) atomicAdd(&lh[(kq.z >> 7) & 0xfffu], 1u);
+    if ((kq.w >> 19) == d0) atomicAdd(&lh[(kq.w >> 7) & 0xfffu], 1u);
+  }
+  __syncthreads();
+  for (int b = tid; b < kHistBins; b += 256) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&hist[b], c);
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    last_sh = atomicAdd(&ctrl[5], 1u) == gridDim.x - 1 ? 1 : 0;
+    hit_sh = -1;
+  }
+  __syncthreads();
+  if (!last_sh) return;
+  __threadfence();
+  uint32_t h[16];
+  uint32_t tot = 0u;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    h[j] = __hip_atomic_load(&hist[16 * tid + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    tot += h[j];
+  }
+  uint32_t suf = tot;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t x = __shfl_down(suf, off, 64);
+    if ((tid & 63) + off < 64) suf += x;
+  }
+  if ((tid & 63) == 0) wsum[tid >> 6] = suf;
+  __syncthreads();
+  uint32_t above = ctrl[4] + suf - tot;  // sample keys of higher top digit, or of higher second digit
+  for (int i = (tid >> 6) + 1; i < 4; ++i) above += wsum[i];
+#pragma unroll
+  for (int j = 15; j >= 0; --j) {
     if (above < m_hi && above + h[j] >= m_hi) hit_sh = 16 * tid + j;  // one thread, one bin
     above += h[j];
   }
   __syncthreads();
-  // bounds above infinity's digit would not survive the floating-point comparison of the fused pass
-  if (tid == 0) ctrl[1] = hit_sh >= 0 ? (uint32_t)(hit_sh < 0xff0 ? hit_sh : 0xff0) << 19 : kNoGuess;
+  if (tid == 0 && hit_sh >= 0) ctrl[1] = (d0 << 19) | ((uint32_t)hit_sh << 7);
 }
 
 // ---------------------------------------------------------------------------
@@ -1904,13 +1994,24 @@ __device__ __forceinline__ void compact_tiles_body(const SelParams& p) {
     }
     if (staged) {  // the same in every thread
       const uint32_t total = pre[SLAB];
-      for (uint32_t f = (uint32_t)tid; f < total; f += T) {
-        int i = 0;
+      for (uint32_t f0 = (uint32_t)tid; f0 < total; f0 += 4 * T) {  // four entries in flight per thread
+        uint2 ent[4];
 #pragma unroll
-        for (int q = 1; q < SLAB; ++q) i += f >= pre[q] ? 1 : 0;  // the tile this entry belongs to
-        const uint2 ent = sv.tbuf[(size_t)(t0 + i) * (size_t)sv.tcap + (f - pre[i])];
-        if (run + f < cap) list[run + f] = ent;
-        atomicAdd(&lh[(ent.y & kKeyMask) >> 19], 1u);
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t f = f0 + (uint32_t)u * T < total ? f0 + (uint32_t)u * T : total - 1u;
+          int i = 0;
+#pragma unroll
+          for (int q = 1; q < SLAB; ++q) i += f >= pre[q] ? 1 : 0;  // the tile this entry belongs to
+          ent[u] = sv.tbuf[(size_t)(t0 + i) * (size_t)sv.tcap + (f - pre[i])];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t f = f0 + (uint32_t)u * T;
+          if (f < total) {
+            if (run + f < cap) list[run + f] = ent[u];
+            atomicAdd(&lh[(ent[u].y & kKeyMask) >> 19], 1u);
+          }
+        }
       }
       run += total;
       continue;
@@ -2323,54 +2424,13 @@ __device__ __forceinline__ void compact_body(const SelParams& p, const SegView& 
 }
 
 // The survivor list was copied from pieces staged by a fused pass that stored +0.0 in place of
-// every element it handed on (k_pass_mark with STAGE).  k_restore_pieces, which runs before the final
-// pass over the list, then leaves exactly the keys above the threshold key at +0.0; the final pass
-// has the kept ties (key = threshold) left to zero.
+// every element it handed on (k_pass_mark with STAGE).  The pass that counts the last digit over the
+// list (list_hist_body, digit 2) knows the threshold key up to its last seven bits, [lo, hi]: it gives
+// the handed-on elements with key <= hi their values back and puts +0.0 over the keys > hi that no
+// piece handed on (a tile whose marks stayed in the mask, the n mod 4 last elements).  The final pass
+// over the list then has the kept entries with key <= hi left to zero.
 __device__ __forceinline__ bool from_pieces(const SelParams& p, const SegView& sv) {
   return p.zero_vec != nullptr && sv.tbuf != nullptr && sv.st->use_mask != 0u;
-}
-
-// ---------------------------------------------------------------------------
-// k_restore_pieces : runs between the last digit histogram and the final pass over a list that
-// was copied from staged pieces.  The threshold key T is known by now (replayed from the digit
-// histograms).  Elements handed on in a piece are +0.0 in the vector: those with key <= T get their
-// values back from the list (the kept ones among the ties are zeroed again by the final pass).
-// Elements of the list that no piece handed on (a tile whose marks stayed in the mask, the n mod 4
-// last elements) still hold their values: those with key > T become +0.0 here.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_restore_pieces(SelParams p) {
-  __shared__ SelState st;
-  __shared__ uint32_t pick_part[256];
-  const SegView sv = seg_view(p, blockIdx.y);
-  if (!from_pieces(p, sv) || *p.err) return;
-  const uint32_t cnt = sv.st->list_count;
-  if ((uint64_t)blockIdx.x * 2048u >= (uint64_t)cnt) return;
-  derive_state<256>(sv, st, 3, pick_part, p.err);
-  if (st.level != 3u) return;
-  const uint32_t t_key = st.hi;
-  const bool all_pieces = sv.ctrl != nullptr && sv.ctrl[2] == 0u;  // no tile kept its marks to the mask
-  const int64_t n_vec = p.n & ~(int64_t)3;
-  for (uint64_t base = (uint64_t)blockIdx.x * 2048u; base < cnt; base += (uint64_t)gridDim.x * 2048u) {
-    uint2 ent[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint64_t q = base + (uint64_t)i * 256u + threadIdx.x;
-      ent[i] = q < cnt ? sv.list[q] : make_uint2(0xffffffffu, 0u);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int64_t j = (int64_t)ent[i].x;
-      if (j >= p.n) continue;  // (the filler, or not an index)
-      const uint32_t key = ent[i].y & kKeyMask;
-      const bool handed_on = j < n_vec && (all_pieces || sv.tcnt[j / kPassTile] != kTileOverflow);
-      if (handed_on) {
-        if (key <= t_key) p.zero_vec[j] = __uint_as_float(ent[i].y);
-      } else if (key > t_key) {
-        p.zero_vec[j] = 0.0f;
-      }
-    }
-  }
 }
 
 // Keys the level-1 pass has already put to +0.0 in zero_vec lie above this one (every key if it
@@ -2393,7 +2453,7 @@ k_compact(SelParams p, int level, int launch_id) {
   // tiles are handed out by a counter, so blocks beyond the number of list tiles are not needed
   if (LIST && stp->compact_level == 1u && (uint64_t)blockIdx.x * kCompactTile >= (uint64_t)stp->list_count) return;
   derive_state<kCompactThreads>(sv, st, LIST ? 3 : level, pick_part, p.err);
-  compact_body<LIST, false>(p, sv, st, level, launch_id, (LIST && from_pieces(p, sv)) ? st.hi : zero_below);
+  compact_body<LIST, false>(p, sv, st, level, launch_id, (LIST && from_pieces(p, sv)) ? (st.hi | 0x7fu) : zero_below);
 }
 
 // ---------------------------------------------------------------------------
@@ -2415,7 +2475,7 @@ k_final(SelParams p) {
   if (st.compact_level == 3u)
     compact_body<false, true>(p, sv, st, 3, 1, zero_below);
   else
-    compact_body<true, false>(p, sv, st, 3, 2, from_pieces(p, sv) ? st.hi : zero_below);
+    compact_body<true, false>(p, sv, st, 3, 2, from_pieces(p, sv) ? (st.hi | 0x7fu) : zero_below);
 }
 
 // ---------------------------------------------------------------------------
@@ -2452,16 +2512,44 @@ __device__ __forceinline__ void list_hist_body(const SelParams& p, int digit) {
   const uint32_t klo = st.lo, khi = st.hi;
   const int sh = digit_shift(digit);
   const uint32_t dm = digit_mask(digit);
-  for (uint64_t base = (uint64_t)blockIdx.x * 8192u; base < cnt; base += (uint64_t)nb * 8192u) {
-    uint32_t key[PER];
+  if (digit == 2 && from_pieces(p, sv)) {
+    // the same count, and on the way the residual is put right around the threshold (see from_pieces)
+    const bool all_pieces = sv.ctrl != nullptr && sv.ctrl[2] == 0u;  // no tile kept its marks to the mask
+    const int64_t n_vec = p.n & ~(int64_t)3;
+    for (uint64_t base = (uint64_t)blockIdx.x * 8192u; base < cnt; base += (uint64_t)nb * 8192u) {
+      uint2 ent[PER];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const uint64_t q = base + (uint64_t)i * T + tid;
-      key[i] = q < cnt ? (sv.list[q].y & kKeyMask) : 0xffffffffu;  // the filler is above every range
+      for (int i = 0; i < PER; ++i) {  // (no branch around the loads: behind the list they re-read its last entry)
+        const uint64_t q = base + (uint64_t)i * T + tid;
+        ent[i] = sv.list[q < cnt ? q : cnt - 1u];
+      }
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int64_t j = (int64_t)ent[i].x;
+        if (base + (uint64_t)i * T + tid >= cnt || j >= p.n) continue;
+        const uint32_t kk = ent[i].y & kKeyMask;
+        if (kk >= klo && kk <= khi) atomicAdd(&lh[(kk >> sh) & dm], 1u);
+        const bool handed_on = j < n_vec && (all_pieces || sv.tcnt[j / kPassTile] != kTileOverflow);
+        if (handed_on) {
+          if (kk <= khi) p.zero_vec[j] = __uint_as_float(ent[i].y);
+        } else if (kk > khi) {
+          p.zero_vec[j] = 0.0f;
+        }
+      }
     }
+  } else {
+    for (uint64_t base = (uint64_t)blockIdx.x * 8192u; base < cnt; base += (uint64_t)nb * 8192u) {
+      uint32_t key[PER];
 #pragma unroll
-    for (int i = 0; i < PER; ++i)
-      if (key[i] >= klo && key[i] <= khi) atomicAdd(&lh[(key[i] >> sh) & dm], 1u);
+      for (int i = 0; i < PER; ++i) {  // (no branch around the loads: behind the list they re-read its last entry)
+        const uint64_t q = base + (uint64_t)i * T + tid;
+        key[i] = sv.list[q < cnt ? q : cnt - 1u].y & kKeyMask;
+      }
+#pragma unroll
+      for (int i = 0; i < PER; ++i)
+        if (base + (uint64_t)i * T + tid < cnt && key[i] >= klo && key[i] <= khi)
+          atomicAdd(&lh[(key[i] >> sh) & dm], 1u);
+    }
   }
   __syncthreads();
   uint32_t* __restrict__ dst = digit == 1 ? sv.hist1 : sv.hist2;
@@ -2553,6 +2641,26 @@ k_tile_starts(const int32_t* __restrict__ idx, int64_t k, int32_t ntiles, int32_
     const int32_t a = __shfl(t_last, src, 64) + 1;
     for (int32_t t = a + lane; t <= ntiles; t += 64) tile_start[t] = (int32_t)k;
   }
+}
+
+// ---------------------------------------------------------------------------
+// k_tile_starts_search : the same table when there are many more kept indices than
+// tiles: one thread per entry t looks up the first position whose index is not
+// below t * kPassTile (binary search in the ascending list; the upper levels of the
+// search are shared by all threads and stay in the cache).  A list that does not
+// ascend gives bounds that k_pass_rest / k_update_tiles reject or clip.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_tile_starts_search(const int32_t* __restrict__ idx, int64_t k, int32_t ntiles, int32_t* __restrict__ tile_start) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t > ntiles) return;
+  const int64_t target = t * kPassTile;
+  int64_t lo = 0, hi = k;  // the answer lies in [lo, hi]
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)idx[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  tile_start[t] = (int32_t)lo;
 }
 
 // ---------------------------------------------------------------------------
