@@ -545,7 +545,7 @@ void enqueue_tile_starts(artopk_ctx* c, const int32_t* idx, int64_t n, int64_t k
   const int32_t ntiles = (int32_t)((n + kPassTile - 1) / kPassTile);
   // many kept indices per tile: a search per tile boundary beats a thread per index
   // (138 M elements, one in ten kept: 20 us with a thread per index)
-  if (k > (int64_t)256 * ntiles)
+  if (k > (int64_t)1024 * ntiles)
     hipLaunchKernelGGL(k_tile_starts_search, dim3((unsigned)(ntiles / 256 + 1)), dim3(256), 0, c->stream, idx, k,
                        ntiles, c->s.tile_start);
   else
