@@ -114,6 +114,8 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     data.reset()
     res = data.res
     ctx = pkg.Context(wl.w, wl.n, k, 1 if seg_k is None else len(seg_k))
+    for name, value in args.options.items():   # route switches (results are the same on every route)
+        ctx.set_option(getattr(pkg, "ARTOPK_OPT_" + name.upper()), value)
     update = torch.empty(wl.n, dtype=torch.float32, device=dev)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     summed = torch.empty(k, dtype=torch.float32, device=dev)
@@ -238,10 +240,14 @@ def main():
                     help="store the gradients in 16 bits (artopk_step_g16); not the headline configuration")
     ap.add_argument("--no-c4", action="store_true",
                     help="with the default workload: leave out the 138 M x 4 configuration's rows under 'other'")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a library route switch before measuring, e.g. guess_min_n=4096 or stage_tiles=2 "
+                         "(artopk_set_option; recorded under config.options)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
+    args.options = {o.split("=", 1)[0]: int(o.split("=", 1)[1]) for o in args.option}
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
@@ -307,7 +313,8 @@ def main():
                 "the recipe, alternate from step to step; residual carried)",
         "config": {"workload": wl0.name, "N": wl0.n, "W": wl0.w, "rho": rho, "k": r["k"],
                    "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR",
-                   **({"gradient_storage": args.g16} if args.g16 else {})},
+                   **({"gradient_storage": args.g16} if args.g16 else {}),
+                   **({"options": args.options} if args.options else {})},
         "roofline": roofline_of(r, args.workload, args.g16),
         "step_algorithmic": step_of(r),
         "cpu_baseline": base,

@@ -442,7 +442,8 @@ def test_bucketed_layout_16mi_elements():
     assert_step_matches(got, want, orc.MODE_STAR)
 
 
-@pytest.mark.parametrize("rule,route", [("var", "histogram"), ("var", "guess"), ("star", "histogram"), ("star", "guess")])
+@pytest.mark.parametrize("rule,route", [("var", "histogram"), ("var", "guess"), ("star", "histogram"), ("star", "guess"),
+                                        ("star", "pieces")])
 def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monkeypatch):
     """One step recorded into a HIP graph (through torch's capture) and replayed three times,
     with host work and synchronisation between the replays: every replay must be the next step
@@ -453,9 +454,11 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
     import torch
     import paper_2312_02493_amd as lib
 
-    if route == "guess":
+    if route in ("guess", "pieces"):
         monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
         monkeypatch.setitem(gpu_util.OPTIONS, "update_tiles_min_n", 1)
+        # the leader's fused pass hands the marked elements on tile by tile, or leaves only the mask
+        monkeypatch.setitem(gpu_util.OPTIONS, "stage_tiles", 2 if route == "pieces" else 0)
     mode_lib = lib.ARTOPK_VAR if rule == "var" else lib.ARTOPK_STAR
     mode_orc = orc.MODE_VAR if rule == "var" else orc.MODE_STAR
     n, w = 200_003, 4
@@ -506,7 +509,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
                 "residual": [r.cpu().numpy() for r in res], "vals": vals.cpu().numpy().reshape(w, k),
             }
             assert_step_matches(got, want, mode_orc)
-            assert ctx.select_info()["guessed"] == (1 if route == "guess" else 0)
+            assert ctx.select_info()["guessed"] == (0 if route == "histogram" else 1)
             want_res = want.residual
             _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
 

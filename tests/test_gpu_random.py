@@ -53,6 +53,8 @@ def _problem(seed):
 def test_random_problem(seed, monkeypatch):
     if seed % 2 == 1:
         monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+        if seed % 4 == 3:   # pieces handed on by the fused pass whenever a leader is known up front
+            monkeypatch.setitem(gpu_util.OPTIONS, "stage_tiles", 2)
     rng, n, w, mode, kind, k, seg_off, seg_k = _problem(seed)
     run = GpuRunner(w, n, k, 1 if seg_k is None else len(seg_k))
     res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
