@@ -125,10 +125,10 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
  *                                 list entries, tile by tile, instead of leaving
  *                                 only the bit mask (from which the list is
  *                                 built by fetching the marked values one by
- *                                 one).  1 (default): for selections denser than
- *                                 one element in 32, which otherwise take the
- *                                 histogram route; 2: for every selection;
- *                                 0: never
+ *                                 one).  1 (default): for selections of one
+ *                                 element in 256 or denser (beyond one in 32
+ *                                 the alternative is the histogram route);
+ *                                 2: for every selection; 0: never
  */
 enum {
   ARTOPK_OPT_GUESS_MIN_N = 0,

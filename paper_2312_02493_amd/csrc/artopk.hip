@@ -92,7 +92,7 @@ struct artopk_ctx {
   // vectors of at least this many elements get their dense update from k_update_tiles
   int64_t update_tiles_min_n = (int64_t)1 << 22;
   int stage_tiles = 1;  // guess route, one marking worker: the fused pass hands the marked elements on per tile
-                        // (0 never, 1 for selections denser than one in 32, 2 whenever a piece can hold a tile's share)
+                        // (0 never, 1 for selections of one element in 256 or denser, 2 whenever a piece can hold a tile's share)
   void* slab = nullptr;
   Scratch s;
   // how the last step ran (artopk_select_info)
@@ -581,17 +581,20 @@ GuessPlan plan_guess(const artopk_ctx* c, int64_t n, int64_t k, int marking) {
   if (c->s.mask == nullptr || n < c->guess_min_n) return gp;
   // A selection of more than one element in 32 is not worth fetching entry by entry from the mask.
   // With one marking worker its fused pass hands the marked elements on per tile instead (measured on
-  // 138 M elements, one in ten kept: 1.84 ms a step against 1.92 on the histogram route; for sparser
-  // selections the pieces cost the pass more than they save behind it, so those keep the mask alone
-  // unless the option asks for pieces everywhere).  Entries a tile is expected to hand on: the keys
-  // reaching the guessed bound are at most about 1.2 k (the bound is the lower edge of a top-digit
-  // bin), spread over the tiles; room for 1.3 k's share plus six standard deviations of a tile's
-  // count.  Selections too dense for a piece take the histogram route.
+  // 138 M elements: one in ten kept 1.73 ms a step against 1.92 on the histogram route, one in a
+  // hundred 1.40 against 1.43 with the mask alone, one in a thousand 1.365 against 1.347: a tile has
+  // to hand on a hundred elements or so for the pieces to pay for what they cost the pass, so
+  // sparser selections keep the mask alone unless the option asks for pieces everywhere).  Entries a
+  // tile is expected to hand on: the keys reaching the guessed bound are at most about 1.2 k (the
+  // bound is the lower edge of a top-digit bin, or with pieces of a second-digit bin), spread over
+  // the tiles; room for 1.3 k's share plus six standard deviations of a tile's count.  Selections
+  // too dense for a piece take the histogram route.
   const bool dense = k * 32 > n;
+  const bool worth_pieces = k * 256 >= n;  // 128 kept elements per tile or more
   const double per_tile = 1.3 * (double)k * (double)kPassTile / (double)n;
   const int64_t want = ((int64_t)std::ceil(per_tile + 6.0 * std::sqrt(per_tile) + 32.0) + 63) / 64 * 64;
   const int64_t ntiles = (n + kPassTile - 1) / kPassTile;
-  if ((c->stage_tiles == 2 || (c->stage_tiles == 1 && dense)) && marking == 1 && want <= kStageMax &&
+  if ((c->stage_tiles == 2 || (c->stage_tiles == 1 && worth_pieces)) && marking == 1 && want <= kStageMax &&
       ntiles * want <= c->s.tilebuf_entries)
     gp.tile_cap = (int32_t)want;
   if (gp.tile_cap == 0 && dense) return gp;
@@ -743,8 +746,12 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
 #endif
   if (n >= c->update_tiles_min_n && k * ARTOPK_TILES_DENSITY <= n) {
     if (!tiles_ready) enqueue_tile_starts(c, idx, n, k);
-    hipLaunchKernelGGL((k_update_tiles<kPassRestThreads, kPassRestU>), dim3(pass_blocks(n)), dim3(kPassRestThreads), 0,
-                       c->stream, update, n, idx, sum, k, c->s.tile_start, c->s.err_dev);
+    if (n < ((int64_t)1 << 28))  // (which kind of store the zeros take: measured, see the kernel)
+      hipLaunchKernelGGL((k_update_tiles<kPassRestThreads, kPassRestU, true>), dim3(pass_blocks(n)),
+                         dim3(kPassRestThreads), 0, c->stream, update, n, idx, sum, k, c->s.tile_start, c->s.err_dev);
+    else
+      hipLaunchKernelGGL((k_update_tiles<kPassRestThreads, kPassRestU, false>), dim3(pass_blocks(n)),
+                         dim3(kPassRestThreads), 0, c->stream, update, n, idx, sum, k, c->s.tile_start, c->s.err_dev);
     HIP_TRY(c, hipGetLastError());
     return ARTOPK_OK;
   }

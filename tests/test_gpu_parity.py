@@ -577,18 +577,21 @@ def test_leader_by_variance_of_the_raw_gradient(layout, monkeypatch):
     assert disagreements >= 1
 
 
-@pytest.mark.parametrize("case", ["all_equal", "two_valued_many_ties", "one_top_digit", "one_top_digit_guess"])
+@pytest.mark.parametrize("case", ["all_equal", "two_valued_many_ties", "one_top_digit", "one_top_digit_guess",
+                                  "one_top_digit_pieces"])
 def test_deeper_array_passes_on_a_long_degenerate_vector(case, monkeypatch):
     """Vectors short enough to fit the survivor list whole never take the deeper array passes, so
     they are exercised here on a vector of 5 M elements whose level-1 survivors overflow the list.
     all_equal / two_valued: not even the level-2 survivors fit, the level-3 array pass writes the
     outputs itself; one_top_digit: every magnitude shares the top 12 key bits and differs below,
     so the level-2 array pass writes the list and the final pass reads it (also behind a guess
-    that cannot work, since the whole vector reaches any bound in that digit)."""
+    that cannot work, since the whole vector reaches any bound in that digit; with pieces the
+    bound is refined by a second digit, the guess holds and no array pass is needed)."""
     n, w, k = 5_000_003, 2, 60_000
     rng = np.random.default_rng(77)
-    if case == "one_top_digit_guess":
+    if case in ("one_top_digit_guess", "one_top_digit_pieces"):
         monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+        monkeypatch.setitem(gpu_util.OPTIONS, "stage_tiles", 0 if case == "one_top_digit_guess" else 1)
 
     def gen():
         if case == "all_equal":
@@ -607,8 +610,11 @@ def test_deeper_array_passes_on_a_long_degenerate_vector(case, monkeypatch):
         want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no)
         run.load_g(g)
         got = run.step(k, orc.MODE_STAR, step_no)
-        if step_no == 1:  # (at step 2 the residual has split the tie class and the list fits again)
-            assert run.ctx.select_info()["list_level"] == 0   # the deeper array passes wrote the list
+        info = run.ctx.select_info()
+        if case == "one_top_digit_pieces":
+            assert info["guessed"] == 1 and info["from_mask"] == 1, info
+        elif step_no == 1:  # (at step 2 the residual has split the tie class and the list fits again)
+            assert info["list_level"] == 0   # the deeper array passes wrote the list
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
 
