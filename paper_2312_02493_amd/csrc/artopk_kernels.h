@@ -33,6 +33,8 @@
 //   k_tile_starts    number of kept indices below every tile of a streaming pass
 //   k_pass_rest      (leader known up front) EF add + gather + residual zeroing
 //                    of all other workers in one streaming pass over the tiles
+//   k_sum_update     (leader known up front) ordered sum over the workers' gathered
+//                    rows and the dense update in one pass over the tiles
 //   k_sum_rows       ordered sum over the workers' gathered rows
 //   k_gather         vals / ordered sum / residual zeroing at the k indices
 //   k_zero_at        residual zeroing alone
@@ -3038,6 +3040,111 @@ k_update_tiles(float* __restrict__ update, int64_t n, const int32_t* __restrict_
     }
     m0 = n0;
     m1 = n1;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_sum_update : the end of a step whose leader was known up front, behind the
+// other workers' pass: sum[m] = ((vals[0][m] + vals[1][m]) + ...) + vals[W-1][m] in
+// float32, in that order, and the dense update, zeros with sum[m] at idx[m], every
+// element written once.  Blocks stride over the tiles as in k_pass_rest and mark a
+// tile's kept positions, idx[tile_start[t] .. tile_start[t+1]), in the same 16-bit
+// slot table; the thread that owns a kept position adds up the rows' entries and
+// stores the sum on its way through the tile's float4 groups.
+// ---------------------------------------------------------------------------
+template <int T, int U>
+__global__ void __launch_bounds__(T)
+k_sum_update(const float* __restrict__ vals, int w_count, int64_t n, const int32_t* __restrict__ idx, int64_t k,
+             const int32_t* __restrict__ tile_start, float* __restrict__ sum_out, float* __restrict__ update,
+             uint32_t* __restrict__ err) {
+  constexpr int TILE = T * 4 * U;
+  static_assert(TILE == kPassTile, "tile_start is laid out for this tile");
+  static_assert(TILE <= 32768, "slot entries are 16-bit offsets from the tile's first index");
+  __shared__ __attribute__((aligned(16))) int16_t slot[TILE];
+  const int tid = threadIdx.x;
+  uint2* s2 = reinterpret_cast<uint2*>(slot);  // four 16-bit slots: one float4 group
+  const int64_t q_end = n >> 2;  // whole float4 groups end here
+  const int64_t ntiles = q_end > 0 ? (n + TILE - 1) / TILE : 0;
+
+  // sum of the rows' entries at position m, in worker order
+  auto ordered_sum = [&](int64_t m) {
+    float sacc = vals[m];
+    for (int w = 1; w < w_count; ++w) sacc = sacc + vals[(size_t)w * (size_t)k + (size_t)m];
+    return sacc;
+  };
+
+  int64_t ti = blockIdx.x;
+  int32_t m0 = 0, m1 = 0;
+  if (ti < ntiles) {
+    m0 = tile_start[ti];
+    m1 = tile_start[ti + 1];
+  }
+  for (; ti < ntiles; ti += gridDim.x) {
+    const int64_t ti_next = ti + gridDim.x;
+    int32_t n0 = 0, n1 = 0;
+    if (ti_next < ntiles) {  // the next tile's bounds, one tile ahead
+      n0 = tile_start[ti_next];
+      n1 = tile_start[ti_next + 1];
+    }
+    int64_t m_base = (int64_t)m0, m_end = (int64_t)m1;
+    if (m_base < 0 || m_end > k || m_end < m_base || m_end - m_base > TILE) {  // idx was not ascending
+      if (tid == 0) atomicOr(err, kErrIndex);
+      m_end = m_base = 0;
+    }
+    const int64_t lo = ti * TILE;
+    const int64_t p0 = m_base + tid;
+    const int32_t i0 = idx[p0 < m_end ? p0 : k - 1];
+    const int64_t q0 = (lo >> 2) + tid;
+    const bool full = lo + TILE <= 4 * q_end;
+#pragma unroll
+    for (int u = 0; u < U; ++u) s2[tid + u * T] = make_uint2(0xffffffffu, 0xffffffffu);
+    __syncthreads();
+    {
+      const int64_t i = (int64_t)i0 - lo;
+      if (p0 < m_end && i >= 0 && i < TILE) slot[i] = (int16_t)tid;
+    }
+    for (int64_t p = p0 + T; p < m_end; p += T) {  // dense tiles only (more than T kept of 32 T elements)
+      const int64_t i = (int64_t)idx[p] - lo;
+      if (i >= 0 && i < TILE) slot[i] = (int16_t)(p - m_base);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * T;
+      if (full || q < q_end) {
+        const uint2 sl = s2[tid + u * T];
+        v4f z = {0.f, 0.f, 0.f, 0.f};
+        if ((sl.x & sl.y) != 0xffffffffu) {  // some element of this group is kept
+          const int s0 = (int16_t)(sl.x & 0xffffu), s1 = (int16_t)(sl.x >> 16);
+          const int s2v = (int16_t)(sl.y & 0xffffu), s3 = (int16_t)(sl.y >> 16);
+          if (s0 >= 0) { z.x = ordered_sum(m_base + s0); sum_out[m_base + s0] = z.x; }
+          if (s1 >= 0) { z.y = ordered_sum(m_base + s1); sum_out[m_base + s1] = z.y; }
+          if (s2v >= 0) { z.z = ordered_sum(m_base + s2v); sum_out[m_base + s2v] = z.z; }
+          if (s3 >= 0) { z.w = ordered_sum(m_base + s3); sum_out[m_base + s3] = z.w; }
+        }
+        store4<true>(update + 4 * q, z);
+      }
+    }
+    __syncthreads();  // the slot table is rebuilt for the next tile
+    m0 = n0;
+    m1 = n1;
+  }
+  // the n mod 4 last elements: the first block
+  if (blockIdx.x == 0) {
+    const int64_t j = (n >> 2) * 4 + tid;
+    if (j < n) {
+      int64_t lo = 0, hi = k;  // binary search for j among the indices
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)idx[mid] < j) lo = mid + 1; else hi = mid;
+      }
+      float upd = 0.0f;
+      if (lo < k && (int64_t)idx[lo] == j) {
+        upd = ordered_sum(lo);
+        sum_out[lo] = upd;
+      }
+      update[j] = upd;
+    }
   }
 }
 
