@@ -411,6 +411,56 @@ __device__ __forceinline__ float load1g(const float* base, int64_t e) {
   return widen16<GT>(reinterpret_cast<const unsigned short*>(base)[e]);
 }
 
+// Block-wide inclusive scans of one word per thread: a shuffle scan inside each
+// wave, then the wave totals through `wtot` (T/64 words of shared memory that no
+// thread still reads on entry).  Two barriers; `wtot` is free again on return.
+// The exclusive value is the result minus the thread's own word.
+template <int T>
+__device__ __forceinline__ uint32_t block_suffix_incl(uint32_t v, uint32_t* wtot, uint32_t* total = nullptr) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t s = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t x = __shfl_down(s, off, 64);
+    if (lane + off < 64) s += x;
+  }
+  if (lane == 0) wtot[wave] = s;
+  __syncthreads();
+  uint32_t add = 0u, tot = 0u;
+#pragma unroll
+  for (int i = 0; i < T / 64; ++i) {
+    const uint32_t x = wtot[i];
+    tot += x;
+    if (i > wave) add += x;
+  }
+  __syncthreads();
+  if (total) *total = tot;
+  return s + add;
+}
+
+template <int T>
+__device__ __forceinline__ uint32_t block_prefix_incl(uint32_t v, uint32_t* wtot, uint32_t* total = nullptr) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t s = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t x = __shfl_up(s, off, 64);
+    if (lane >= off) s += x;
+  }
+  if (lane == 63) wtot[wave] = s;
+  __syncthreads();
+  uint32_t add = 0u, tot = 0u;
+#pragma unroll
+  for (int i = 0; i < T / 64; ++i) {
+    const uint32_t x = wtot[i];
+    tot += x;
+    if (i < wave) add += x;
+  }
+  __syncthreads();
+  if (total) *total = tot;
+  return s + add;
+}
+
 // Adds the 4096-bin LDS histogram `lh` of a T-thread block to total[0..4096)
 // and writes its suffix sums to dst[0..4096).  `red` is T words of LDS.  All
 // threads of the block must call it after their last histogram update.
@@ -436,15 +486,7 @@ __device__ __forceinline__ void flush_suffix_hist(uint32_t* lh, uint32_t* red, u
     if (v[j]) atomicAdd(&total[BPT * t + j], v[j]);
 #pragma unroll
   for (int j = BPT - 2; j >= 0; --j) v[j] += v[j + 1];
-  red[t] = v[0];
-  __syncthreads();
-  for (int off = 1; off < T; off <<= 1) {
-    const uint32_t x = (t + off < T) ? red[t + off] : 0u;
-    __syncthreads();
-    red[t] += x;
-    __syncthreads();
-  }
-  const uint32_t carry = (t + 1 < T) ? red[t + 1] : 0u;
+  const uint32_t carry = block_suffix_incl<T>(v[0], red) - v[0];
 #pragma unroll
   for (int j = 0; j < BPT / 4; ++j) {
     uint4 q;
@@ -1317,16 +1359,8 @@ __device__ void block_pick(SelState& st, const uint32_t* __restrict__ hist, int 
     tot += h[j];
   }
   __syncthreads();  // st is stable and `part` is free
-  part[t] = tot;
-  __syncthreads();
-  for (int off = 1; off < T; off <<= 1) {  // inclusive suffix sums
-    const uint32_t v = (t + off < T) ? part[t + off] : 0u;
-    __syncthreads();
-    part[t] += v;
-    __syncthreads();
-  }
-  uint32_t above = (t + 1 < T) ? part[t + 1] : 0u;
-  const uint32_t total = part[0];
+  uint32_t total;
+  uint32_t above = block_suffix_incl<T>(tot, part, &total) - tot;
   const uint32_t need = st.need;
   int hit = -1;
   uint32_t hit_above = 0u, hit_cnt = 0u;
@@ -1478,16 +1512,9 @@ k_pick0(SelParams p, LeaderArgs la) {
     h[2] = q.z;
     h[3] = q.w;
   }
-  part[t] = h[0] + h[1] + h[2] + h[3];
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const uint32_t v = (t + off < 1024) ? part[t + off] : 0u;
-    __syncthreads();
-    part[t] += v;
-    __syncthreads();
-  }
+  const uint32_t hsum = h[0] + h[1] + h[2] + h[3];
   uint32_t sx[5];
-  sx[4] = (t + 1 < 1024) ? part[t + 1] : 0u;
+  sx[4] = block_suffix_incl<1024>(hsum, part) - hsum;
 #pragma unroll
   for (int j = 3; j >= 0; --j) sx[j] = sx[j + 1] + h[j];
 #pragma unroll
@@ -1522,15 +1549,8 @@ k_pick0(SelParams p, LeaderArgs la) {
   if (from_list) return;
   // exclusive scan of the per-chunk survivor counts
   const uint32_t mine = (t < nchunks) ? sv.S[(size_t)t * kHistBins + b0] : 0u;
-  part[t] = mine;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {  // inclusive prefix sums
-    const uint32_t v = (t >= off) ? part[t - off] : 0u;
-    __syncthreads();
-    part[t] += v;
-    __syncthreads();
-  }
-  if (t < nchunks) sv.chunk_off[t] = part[t] - mine;
+  const uint32_t upto = block_prefix_incl<1024>(mine, part);
+  if (t < nchunks) sv.chunk_off[t] = upto - mine;
 }
 
 // ---------------------------------------------------------------------------
@@ -1558,22 +1578,15 @@ k_pick_mask(SelParams p, LeaderArgs la) {
   const int nchunks = sv.d.geom.nchunks;
   const uint32_t gkey = sv.ctrl[1];
   const uint32_t mine = (t < nchunks) ? sv.mcount[t] : 0u;
-  part[t] = mine;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {  // inclusive prefix sums
-    const uint32_t v = (t >= off) ? part[t - off] : 0u;
-    __syncthreads();
-    part[t] += v;
-    __syncthreads();
-  }
-  const uint32_t total = part[1023];
+  uint32_t total;
+  const uint32_t upto = block_prefix_incl<1024>(mine, part, &total);
   // accepted if the bound holds at least k keys and not more than the list takes; a list far
   // longer than k (beyond k + n/8) is not worth fetching entry by entry either
   const uint64_t span = (uint64_t)(sv.d.e_hi - sv.d.e_lo);
   uint64_t limit = (uint64_t)k + (span >> 3);
   if (limit > sv.d.cap) limit = sv.d.cap;
   const bool ok = gkey != kNoGuess && total >= k && total <= limit;
-  if (ok && t < nchunks) sv.chunk_off[t] = part[t] - mine;
+  if (ok && t < nchunks) sv.chunk_off[t] = upto - mine;
   if (t == 0) {
     SelState st{};
     if (ok) {
