@@ -61,8 +61,16 @@ enum {
  * whose k values have the largest squared norm leads (first maximum); its
  * cost is W selections instead of one.  VAR_G reads "largest gradient
  * variance" as the variance of the raw gradient g_w, before the residual is
- * added; everything else is as in VAR (same kernels, same cost). */
-enum { ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3, ARTOPK_VAR_G = 4 };
+ * added; everything else is as in VAR (same kernels, same cost).
+ * STAR_COUNTER is the round-robin rule of STAR with the iteration counter kept
+ * in the context's device memory: leader = counter mod W, and every step (every
+ * replay of a recorded one) advances the counter by one.  The leader is then
+ * not known to the host, so the step takes the route of the variance rules
+ * (every worker's pass prepares the selection) without their statistics. */
+enum {
+  ARTOPK_STAR = 0, ARTOPK_VAR = 1, ARTOPK_FIXED = 2, ARTOPK_VAR_TOPK = 3, ARTOPK_VAR_G = 4,
+  ARTOPK_STAR_COUNTER = 5
+};
 
 /* Element type of the gradients handed to artopk_step_g16. */
 enum { ARTOPK_G_F32 = 0, ARTOPK_G_BF16 = 1, ARTOPK_G_F16 = 2 };
@@ -234,8 +242,9 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  *   nseg/seg_off/seg_k/k  as in artopk_select_topk (one leader per step even
  *                when the selection is per segment)
  *   mode         ARTOPK_STAR (leader = step mod W), ARTOPK_VAR, ARTOPK_FIXED,
- *                ARTOPK_VAR_TOPK or ARTOPK_VAR_G (see the enum)
- *   step         the paper's iteration counter i
+ *                ARTOPK_VAR_TOPK, ARTOPK_VAR_G or ARTOPK_STAR_COUNTER (see the enum)
+ *   step         the paper's iteration counter i (ignored by ARTOPK_STAR_COUNTER,
+ *                which counts on the device: artopk_set_step_counter)
  *   fixed_leader used by ARTOPK_FIXED only
  *   leader_out   device int32 (may be NULL)
  *   var_out      device W float64 (may be NULL): the per-worker variances in VAR
@@ -250,13 +259,22 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  * the device the first time it is seen, so make one call with it before
  * recording).  With stage timing off it can therefore be recorded into a HIP
  * graph and replayed; in VAR mode the leader is taken on the device at every
- * replay, in STAR / FIXED mode the recorded leader is replayed.
+ * replay, in STAR / FIXED mode the recorded leader is replayed, and in
+ * STAR_COUNTER mode every replay takes the next leader of the round.
  */
 int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w,
                 int64_t n, int32_t nseg, const int64_t* seg_off, const int64_t* seg_k,
                 int64_t k, int32_t mode, uint64_t step, int32_t fixed_leader,
                 int32_t* leader_out, double* var_out, int32_t* idx_out, float* vals_out,
                 float* sum_out, float* update_out);
+
+/*
+ * Sets the iteration counter that ARTOPK_STAR_COUNTER steps read and advance
+ * (Alg. 1, STAR branch: leader = i mod W).  A new context starts at 0.  The
+ * value is written by a kernel on the context's stream, in order with the
+ * steps around it; nothing is allocated or synchronised.
+ */
+int artopk_set_step_counter(artopk_ctx* ctx, uint64_t value);
 
 /*
  * artopk_step for gradients stored in 16 bits (the residual, and everything

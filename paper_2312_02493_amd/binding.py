@@ -13,6 +13,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 ARTOPK_STAR, ARTOPK_VAR, ARTOPK_FIXED, ARTOPK_VAR_TOPK, ARTOPK_VAR_G = 0, 1, 2, 3, 4
+ARTOPK_STAR_COUNTER = 5
 ARTOPK_G_F32, ARTOPK_G_BF16, ARTOPK_G_F16 = 0, 1, 2
 ARTOPK_OPT_GUESS_MIN_N, ARTOPK_OPT_UPDATE_TILES_MIN_N, ARTOPK_OPT_LEADER_FIRST, ARTOPK_OPT_NONTEMPORAL = 0, 1, 2, 3
 ARTOPK_OPT_STAGE_TILES = 4
@@ -23,7 +24,7 @@ _SYMBOLS = (
     "artopk_select_topk", "artopk_gather_sum", "artopk_scatter_residual", "artopk_step",
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
     "artopk_apply_update", "artopk_topk_workers", "artopk_select_info", "artopk_step_g16",
-    "artopk_set_option", "artopk_get_option", "artopk_variance_static",
+    "artopk_set_option", "artopk_get_option", "artopk_variance_static", "artopk_set_step_counter",
 )
 
 
@@ -75,6 +76,7 @@ def load_library():
     lib.artopk_set_option.argtypes = [vp, i32, i64]
     lib.artopk_get_option.argtypes = [vp, i32, C.POINTER(i64)]
     lib.artopk_variance_static.argtypes = [vp, i32, i64, vp, vp, vp]
+    lib.artopk_set_step_counter.argtypes = [vp, C.c_uint64]
     lib.artopk_version.restype = i32
     for name in _SYMBOLS:
         if name not in ("artopk_last_error", "artopk_version"):
@@ -157,6 +159,9 @@ class Context:
 
     def set_option(self, key: int, value: int):
         self._check(self._lib.artopk_set_option(self._h, int(key), int(value)))
+
+    def set_step_counter(self, value: int):
+        self._check(self._lib.artopk_set_step_counter(self._h, int(value)))
 
     def get_option(self, key: int) -> int:
         out = C.c_int64()

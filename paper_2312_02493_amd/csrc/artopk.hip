@@ -49,6 +49,7 @@ struct Scratch {
   double* partials = nullptr;     // [max_w][kMaxPassBlocks][3] per-block moments (or [2] sums)
   double* var_scratch = nullptr;  // [max_w]
   int32_t* leader_dev = nullptr;
+  uint64_t* counter_dev = nullptr;  // iteration counter of ARTOPK_STAR_COUNTER steps
   uint32_t* err_dev = nullptr;
   uint2* list = nullptr;          // survivor lists: (index, raw float bits)
   int64_t list_entries = 0;       // allocated entries
@@ -866,6 +867,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_var = take((size_t)max_w * sizeof(double));
   const size_t o_leader = take(sizeof(int32_t));
   const size_t o_err = take(sizeof(uint32_t));
+  const size_t o_counter = take(sizeof(uint64_t));
   const size_t o_list = take((size_t)s.list_entries * sizeof(uint2));
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
   const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
@@ -897,6 +899,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.var_scratch = reinterpret_cast<double*>(base + o_var);
   s.leader_dev = reinterpret_cast<int32_t*>(base + o_leader);
   s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
+  s.counter_dev = reinterpret_cast<uint64_t*>(base + o_counter);
   s.list = reinterpret_cast<uint2*>(base + o_list);
   s.vals = reinterpret_cast<float*>(base + o_vals);
   s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
@@ -906,10 +909,11 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.tile_cnt = reinterpret_cast<uint32_t*>(base + o_tcnt);
   s.sample_keys = reinterpret_cast<uint32_t*>(base + o_sample);
 
-  // leader and error words start at zero (stream-ordered before any later call)
+  // leader, error word and step counter start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
                      reinterpret_cast<uint32_t*>(s.leader_dev), (size_t)1, s.err_dev, (size_t)1,
-                     (uint32_t*)nullptr, (size_t)0, 0, (int32_t*)nullptr, (int32_t*)nullptr);
+                     reinterpret_cast<uint32_t*>(s.counter_dev), (size_t)2, 0, (int32_t*)nullptr,
+                     (int32_t*)nullptr);
   if (hipGetLastError() != hipSuccess) {
     (void)hipFree(c->slab);
     delete c;
@@ -1322,9 +1326,11 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   } else if (mode == ARTOPK_VAR_TOPK) {
     if (seg_off != nullptr && nseg > 1)
       return fail(ctx, ARTOPK_EINVAL, "ARTOPK_VAR_TOPK is defined for the unsegmented selection only");
-  } else if (mode != ARTOPK_VAR && mode != ARTOPK_VAR_G) {
+  } else if (mode != ARTOPK_VAR && mode != ARTOPK_VAR_G && mode != ARTOPK_STAR_COUNTER) {
     return fail(ctx, ARTOPK_EINVAL, "unknown mode %d", mode);
   }
+  // the leader is found on the device, from statistics of the pass or from the counter
+  const bool device_leader = mode == ARTOPK_VAR || mode == ARTOPK_VAR_G || mode == ARTOPK_STAR_COUNTER;
 
   Scratch& s = ctx->s;
   hipStream_t st = ctx->stream;
@@ -1436,12 +1442,30 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   prof_begin(ctx);
   prof_mark(ctx, 0);
   // the flat select reuses the histograms pass A builds; segments build their own afterwards
-  if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : ((mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) ? (int)w : 1))))
-    return rc;
+  if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : (device_leader ? (int)w : 1)))) return rc;
   int slot_by_leader = 0;
   LeaderArgs leader_args{};
-  const bool marking = gp.on && (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G);
-  if (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) {
+  const bool marking = gp.on && device_leader;
+  if (mode == ARTOPK_STAR_COUNTER) {
+    // every worker's pass prepares the selection, as under the variance rules, and the selection
+    // kernels read the leader word that the counter kernel leaves
+    hipLaunchKernelGGL(k_counter_leader, dim3(1), dim3(64), 0, st, s.counter_dev, (int32_t)w, s.leader_dev, leader_out);
+    HIP_TRY(ctx, hipGetLastError());
+    ctx->last_guessed = marking ? 1 : 0;
+    if (marking) enqueue_guess(ctx, gp, gt, rt, (int)w);
+    prof_dom(ctx, false);
+    if (segmented) {
+      launch_pass_a(ctx, 0, 0, grid, gt, rt, n, geom, -1);
+    } else if (marking) {
+      launch_pass_mark(ctx, 0, (int)w, gt, rt, n, geom.chunk_elems);
+      slot_by_leader = 1;
+    } else {
+      launch_pass_a(ctx, 0, 2, grid, gt, rt, n, geom, -1);
+      slot_by_leader = 1;
+    }
+    prof_dom(ctx, true);
+    prof_mark(ctx, 1);
+  } else if (mode == ARTOPK_VAR || mode == ARTOPK_VAR_G) {
     const int stats = mode == ARTOPK_VAR_G ? 2 : 1;  // variance of the raw gradient, or of g + residual
     if (segmented) {
       prof_dom(ctx, false);
@@ -1493,6 +1517,13 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
 }
 
 }  // namespace
+
+int artopk_set_step_counter(artopk_ctx* ctx, uint64_t value) {
+  if (!ctx) return fail(nullptr, ARTOPK_EINVAL, "artopk_set_step_counter: ctx is NULL");
+  hipLaunchKernelGGL(k_set_counter, dim3(1), dim3(64), 0, ctx->stream, ctx->s.counter_dev, value);
+  HIP_TRY(ctx, hipGetLastError());
+  return ARTOPK_OK;
+}
 
 int artopk_step(artopk_ctx* ctx, const float* const* g, float* const* residual, int32_t w, int64_t n,
                 int32_t nseg, const int64_t* seg_off, const int64_t* seg_k, int64_t k, int32_t mode,

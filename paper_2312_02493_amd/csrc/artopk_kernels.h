@@ -1074,6 +1074,23 @@ __global__ void k_set_leader(int32_t leader, int32_t* __restrict__ leader_dev, i
   }
 }
 
+// The round-robin leader from the iteration counter kept on the device (Alg. 1,
+// STAR branch): leader = counter mod w, then the counter moves on by one.
+__global__ void k_counter_leader(uint64_t* __restrict__ counter, int32_t w, int32_t* __restrict__ leader_dev,
+                                 int32_t* __restrict__ leader_out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    const uint64_t c = *counter;
+    const int32_t leader = (int32_t)(c % (uint64_t)w);
+    *leader_dev = leader;
+    if (leader_out) *leader_out = leader;
+    *counter = c + 1u;
+  }
+}
+
+__global__ void k_set_counter(uint64_t* __restrict__ counter, uint64_t value) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *counter = value;
+}
+
 // ---------------------------------------------------------------------------
 // k_guess : a lower bound on the key of the k-th largest |g + residual| of each
 // vector, from a sample, before the fused pass runs.  grid = (blocks, vectors),

@@ -443,14 +443,16 @@ def test_bucketed_layout_16mi_elements():
 
 
 @pytest.mark.parametrize("rule,route", [("var", "histogram"), ("var", "guess"), ("star", "histogram"), ("star", "guess"),
-                                        ("star", "pieces")])
+                                        ("star", "pieces"), ("counter", "histogram"), ("counter", "guess")])
 def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monkeypatch):
     """One step recorded into a HIP graph (through torch's capture) and replayed three times,
     with host work and synchronisation between the replays: every replay must be the next step
     of the oracle, residual carried.  The step allocates nothing, clears its scratch with a fill
     kernel (no memset nodes) and takes every data-dependent decision on the device.  Under the
-    round-robin rule the recorded leader (step 1 -> worker 1) is the one every replay uses; the
-    dense update is written in its tile-by-tile form on the guess route."""
+    round-robin rule the recorded leader (step 1 -> worker 1) is the one every replay uses, unless
+    the iteration counter lives on the device (rule "counter"): then replay r is step 1 + r with the
+    next worker of the round leading.  The dense update is written in its tile-by-tile form on the
+    guess route."""
     import torch
     import paper_2312_02493_amd as lib
 
@@ -459,7 +461,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
         monkeypatch.setitem(gpu_util.OPTIONS, "update_tiles_min_n", 1)
         # the leader's fused pass hands the marked elements on tile by tile, or leaves only the mask
         monkeypatch.setitem(gpu_util.OPTIONS, "stage_tiles", 2 if route == "pieces" else 0)
-    mode_lib = lib.ARTOPK_VAR if rule == "var" else lib.ARTOPK_STAR
+    mode_lib = {"var": lib.ARTOPK_VAR, "star": lib.ARTOPK_STAR, "counter": lib.ARTOPK_STAR_COUNTER}[rule]
     mode_orc = orc.MODE_VAR if rule == "var" else orc.MODE_STAR
     n, w = 200_003, 4
     wl = inp.workload(2, n=n, w=w)
@@ -487,6 +489,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
         ctx.status()
         for r in res:
             r.zero_()
+        ctx.set_step_counter(1)  # the warm-up step has advanced it
         side.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
@@ -497,7 +500,9 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
 
         want_res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
         for replay in range(3):
-            want = orc.step(g_np, want_res, k, mode_orc, step_no=1)
+            want = orc.step(g_np, want_res, k, mode_orc, step_no=1 + replay if rule == "counter" else 1)
+            if rule == "counter":
+                assert want.leader == (1 + replay) % w
             if rule == "var":
                 assert top_two_gap(want.variances) > 1e-4
             graph.replay()
@@ -512,6 +517,42 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
             assert ctx.select_info()["guessed"] == (0 if route == "histogram" else 1)
             want_res = want.residual
             _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
+
+
+@pytest.mark.parametrize("route", ["histogram", "guess", "segments"])
+def test_round_robin_leader_from_the_counter_on_the_device(route, monkeypatch):
+    """ARTOPK_STAR_COUNTER: the iteration counter of the round-robin rule (Alg. 1, STAR branch) is
+    kept by the context on the device, the `step` argument is ignored, and every call moves the
+    counter on.  Four steps from counter 5 with three workers (leaders 2, 0, 1, 2), fresh gradients
+    and the residual carried, against the oracle's STAR steps 5..8; then the counter is set back."""
+    import paper_2312_02493_amd as lib
+
+    if route == "guess":
+        monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
+    n, w = 150_011, 3
+    wl = inp.workload(2, n=n, w=w)
+    seg_off = seg_k = None
+    if route == "segments":
+        seg_off = [0, 40_000, 40_003, 99_999, n]
+        seg_k = [400, 1, 600, 500]
+        k = sum(seg_k)
+    else:
+        k = wl.k(0.01)
+    run = GpuRunner(w, n, k, max_segments=4)
+    run.ctx.set_step_counter(5)
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in (5, 6, 7, 8, 1):
+        if step_no == 1:
+            run.ctx.set_step_counter(1)
+        g = [wl.gen(step_no, r) for r in range(w)]
+        want = orc.step(g, res, k, orc.MODE_STAR, step_no=step_no, seg_off=seg_off, seg_k=seg_k)
+        assert want.leader == step_no % w
+        run.load_g(g)
+        got = run.step(k, lib.ARTOPK_STAR_COUNTER, 123_456, seg_off=seg_off, seg_k=seg_k)  # step argument unused
+        assert_step_matches(got, want, orc.MODE_STAR)
+        if route != "segments":
+            assert run.ctx.select_info()["guessed"] == (1 if route == "guess" else 0)
+        res = want.residual
 
 
 @pytest.mark.parametrize("case", ["all_equal", "two_valued", "normal"])
