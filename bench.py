@@ -63,13 +63,14 @@ def profile_traffic(tag, rho, kernel):
     return None, None
 
 
-def algorithmic_bytes(w, n, k, with_vals, g_bytes=4, reread=True):
+def algorithmic_bytes(w, n, k, with_vals, g_bytes=4, reread=True, dense_update=True):
     """Bytes one step must move (fp32, 4-byte granularity for the k-sized terms).  reread: the
     selection reads the leader's vector once more after the fused pass (it does not when the
-    survivor list is written from the fused pass' bit mask)."""
+    survivor list is written from the fused pass' bit mask).  dense_update False: the model update
+    in its sparse form (idx and sum read, k weights read and written) instead of N floats written."""
     pass_a = (8 + g_bytes) * w * n      # read g, read residual, write acc
     select = 4 * n if reread else 0
-    update = 4 * n                      # dense update written once
+    update = 4 * n if dense_update else 16 * k
     ksized = k * (8 * w + (4 * w if with_vals else 0) + 20)
     return pass_a, pass_a + select + update + ksized
 
@@ -116,7 +117,8 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     ctx = pkg.Context(wl.w, wl.n, k, 1 if seg_k is None else len(seg_k))
     for name, value in args.options.items():   # route switches (results are the same on every route)
         ctx.set_option(getattr(pkg, "ARTOPK_OPT_" + name.upper()), value)
-    update = torch.empty(wl.n, dtype=torch.float32, device=dev)
+    update = None if args.sparse_update else torch.empty(wl.n, dtype=torch.float32, device=dev)
+    weights = torch.zeros(wl.n, dtype=torch.float32, device=dev) if args.sparse_update else None
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     summed = torch.empty(k, dtype=torch.float32, device=dev)
     leader = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -133,6 +135,8 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
         else:
             ctx.artopk_step(g, res, k, mode, step_no, idx, summed, update, leader_out=leader, var_out=var,
                             seg_off=seg_off, seg_k=seg_k)
+        if args.sparse_update:   # `update` is the model here: w[idx] -= eta * sum instead of N floats written
+            ctx.artopk_apply_update(weights, idx, summed, k, 1e-3)
 
     step_no = 1
     for _ in range(warmup):
@@ -167,8 +171,9 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     ctx.set_profile(0)
     ctx.status()
     ms_per_step = 1e3 * t_total / steps
-    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes, reread=not info["from_mask"])
-    _, b_scope = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes, reread=True)
+    _, b_step = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes, reread=not info["from_mask"],
+                                  dense_update=not args.sparse_update)
+    _, b_scope = algorithmic_bytes(wl.w, wl.n, k, False, g_bytes, reread=True, dense_update=not args.sparse_update)
     b_dom = (8 + g_bytes) * dom_workers * wl.n
     out = {
         "wl": wl, "k": k, "rho": rho, "ms_per_step": ms_per_step,
@@ -244,6 +249,9 @@ def main():
                     help="store the gradients in 16 bits (artopk_step_g16); not the headline configuration")
     ap.add_argument("--no-c4", action="store_true",
                     help="with the default workload: leave out the 138 M x 4 configuration's rows under 'other'")
+    ap.add_argument("--sparse-update", action="store_true",
+                    help="leave out the dense update (update_out = NULL) and apply w[idx] -= eta * sum instead "
+                         "(artopk_apply_update); not the headline configuration")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="set a library route switch before measuring, e.g. guess_min_n=4096 or stage_tiles=2 "
                          "(artopk_set_option; recorded under config.options)")
@@ -318,6 +326,7 @@ def main():
         "config": {"workload": wl0.name, "N": wl0.n, "W": wl0.w, "rho": rho, "k": r["k"],
                    "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR",
                    **({"gradient_storage": args.g16} if args.g16 else {}),
+                   **({"update": "sparse (artopk_apply_update)"} if args.sparse_update else {}),
                    **({"options": args.options} if args.options else {})},
         "roofline": roofline_of(r, args.workload, args.g16),
         "step_algorithmic": step_of(r),

@@ -253,7 +253,9 @@ int artopk_scatter_residual(artopk_ctx* ctx, float* const* residual, int32_t w, 
  *   idx_out      device k int32
  *   vals_out     device W*k float32 (may be NULL)
  *   sum_out      device k float32
- *   update_out   device N float32
+ *   update_out   device N float32 (may be NULL: the dense update is then not
+ *                written, for callers that take (idx_out, sum_out) to
+ *                artopk_apply_update instead)
  * The call only enqueues kernels on the context's stream: it allocates nothing,
  * issues no memset and does not synchronise (a segmented layout is copied to
  * the device the first time it is seen, so make one call with it before

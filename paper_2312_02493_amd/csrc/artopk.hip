@@ -1302,8 +1302,8 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   ctx->g_type = g_type;
   if ((rc = check_ptr_table(ctx, g, w, "g", g_type == ARTOPK_G_F32 ? 16 : 8))) return rc;
   if ((rc = check_ptr_table(ctx, residual, w, "residual"))) return rc;
-  if (!idx_out || !sum_out || !update_out) return fail(ctx, ARTOPK_EINVAL, "idx_out, sum_out or update_out is NULL");
-  if (!aligned16(update_out)) return fail(ctx, ARTOPK_EINVAL, "update_out is not 16-byte aligned");
+  if (!idx_out || !sum_out) return fail(ctx, ARTOPK_EINVAL, "idx_out or sum_out is NULL");
+  if (update_out && !aligned16(update_out)) return fail(ctx, ARTOPK_EINVAL, "update_out is not 16-byte aligned");
   if ((rc = check_segments(ctx, n, nseg, seg_off, seg_k, k))) return rc;
   {
     RangeSet rs;
@@ -1380,7 +1380,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_mark(ctx, 2);
     if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;
     prof_mark(ctx, 3);
-    if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+    if (update_out && (rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
     prof_mark(ctx, 4);
     return ARTOPK_OK;
   }
@@ -1421,7 +1421,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     }
     prof_dom(ctx, true);
     prof_mark(ctx, 3);
-    if (k * 128 <= n) {
+    if (update_out && k * 128 <= n) {
       // few kept entries: the ordered sums and the dense update in one pass over the tiles, whose bounds
       // in idx are there already (138 M elements, one in a thousand kept: 96 us against 104 + 4; one in a
       // hundred: 133 against 116 + 5, the owner threads' loads of the rows' entries take over)
@@ -1431,7 +1431,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     } else {
       hipLaunchKernelGGL(k_sum_rows, dim3((int)((k + 1023) / 1024)), dim3(256), 0, st, vals, (int)w, k, sum_out);
       HIP_TRY(ctx, hipGetLastError());
-      if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k, true))) return rc;
+      if (update_out && (rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k, true))) return rc;
     }
     prof_mark(ctx, 4);
     return ARTOPK_OK;
@@ -1511,7 +1511,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   prof_mark(ctx, 2);
   if ((rc = enqueue_gather(ctx, rt, w, n, idx_out, k, vals_out, sum_out, true))) return rc;
   prof_mark(ctx, 3);
-  if ((rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
+  if (update_out && (rc = enqueue_update_fill(ctx, update_out, n, idx_out, sum_out, k))) return rc;
   prof_mark(ctx, 4);
   return ARTOPK_OK;
 }
