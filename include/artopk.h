@@ -101,7 +101,8 @@ enum {
  * on one context must not overlap (its scratch is shared between them), and
  * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.4 MiB per worker plus
  * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes plus
- * max_n / 8 bytes per worker of survivor bit masks.  The library reads no environment
+ * max_n / 8 bytes per worker of survivor bit masks plus 1.5 max_n bytes in which a
+ * leader's fused pass stages list entries tile by tile.  The library reads no environment
  * variable and keeps no state outside its contexts (artopk_variance_static's fixed
  * scratch excepted, see there).
  */

@@ -874,7 +874,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
   const size_t o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
   // pieces of the survivor list staged per tile by the fused pass: room for kStageMax entries in
-  // every tile of the longest vector, but not more than the list itself takes
+  // every tile of the longest vector (1.5 bytes per element)
   const int64_t max_tiles_pass = (max_n + kPassTile - 1) / kPassTile;
   s.tilebuf_entries = max_tiles_pass * (int64_t)kStageMax;
   const size_t o_tbuf = take((size_t)s.tilebuf_entries * sizeof(uint2));
