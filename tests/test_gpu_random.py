@@ -1,7 +1,9 @@
 """Randomised differential parity: many small random problems (sizes, worker counts, keep
 ratios, leader rules, segment layouts, value distributions with ties / zeros / denormals), each
 run for two steps with the residual carried, GPU against the oracle bit for bit.  Seeds are
-fixed, so every run sees the same problems; the guess route is switched on for half of them."""
+fixed, so every run sees the same problems; the guess route is switched on for half of them.
+A second set draws the route switches, the leader rule, the gradient storage and the optional
+outputs at random as well."""
 
 import numpy as np
 import pytest
@@ -70,6 +72,98 @@ def test_random_problem(seed, monkeypatch):
                        seg_off=None if seg_off is None else [int(v) for v in seg_off],
                        seg_k=None if seg_k is None else [int(v) for v in seg_k])
         assert_step_matches(got, want, mode)
+        res = want.residual
+
+
+def _to_bits16(x32, kind):
+    """16-bit storage of float32 test data (how it rounds is irrelevant: the oracle gets the widened values)."""
+    if kind == "f16":
+        with np.errstate(over="ignore"):
+            return x32.astype(np.float16).view(np.uint16)
+    u = x32.view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("seed", range(100, 228))
+def test_random_problem_on_random_routes(seed, monkeypatch):
+    """The random problems again, each with a random draw of everything that chooses a route or a
+    form of the call: the five route switches, every leader rule (the round-robin counter kept on the
+    device, the raw-gradient variance and the literal rule of Alg. 1 included), gradients stored as
+    float32, bfloat16 or float16, with or without vals_out and the dense update.  Three steps with
+    the residual carried, bit for bit against the oracle."""
+    import torch
+    import paper_2312_02493_amd as lib
+
+    rng, n, w, _, kind, k, seg_off, seg_k = _problem(seed)
+    opt = np.random.default_rng(7000 + seed)
+    for name, choices in (("guess_min_n", [1 << 25, 4096, 4096]), ("stage_tiles", [0, 1, 2]), ("leader_first", [0, 1, 1]),
+                          ("update_tiles_min_n", [1 << 22, 1]), ("nontemporal", [0, 1])):
+        monkeypatch.setitem(gpu_util.OPTIONS, name, int(opt.choice(choices)))
+    rules = [("star", lib.ARTOPK_STAR, orc.MODE_STAR), ("fixed", lib.ARTOPK_FIXED, orc.MODE_FIXED),
+             ("var", lib.ARTOPK_VAR, orc.MODE_VAR), ("var_g", lib.ARTOPK_VAR_G, orc.MODE_VAR_G),
+             ("counter", lib.ARTOPK_STAR_COUNTER, orc.MODE_STAR)]
+    if seg_off is None:
+        rules.append(("var_topk", lib.ARTOPK_VAR_TOPK, orc.MODE_VAR_TOPK))
+    rule, mode_lib, mode_orc = rules[int(opt.integers(0, len(rules)))]
+    storage = str(opt.choice(["f32", "f32", "bf16", "f16"]))
+    with_vals = bool(opt.random() < 0.7)
+    with_update = bool(opt.random() < 0.7)
+    first_step = int(opt.integers(0, 1000))
+    fixed = int(opt.integers(0, w))
+
+    dev = torch.device("cuda:0")
+    ctx = gpu_util.make_context(w, n, k, 1 if seg_k is None else len(seg_k))
+    tdtype = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[storage]
+    g_dev = [torch.empty(n, dtype=tdtype, device=dev) for _ in range(w)]
+    res_dev = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(w)]
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    summed = torch.empty(k, dtype=torch.float32, device=dev)
+    update = torch.empty(n, dtype=torch.float32, device=dev) if with_update else None
+    vals = torch.empty(w * k, dtype=torch.float32, device=dev) if with_vals else None
+    leader = torch.zeros(1, dtype=torch.int32, device=dev)
+    var = torch.zeros(w, dtype=torch.float64, device=dev)
+    if rule == "counter":
+        ctx.set_step_counter(first_step)
+    so = None if seg_off is None else [int(v) for v in seg_off]
+    sk = None if seg_k is None else [int(v) for v in seg_k]
+    res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
+    for step_no in range(first_step, first_step + 3):
+        scales = 1.0 + 0.2 * rng.permutation(w)
+        g = [(_values(rng, n, kind) * np.float32(scales[r])) for r in range(w)]
+        if storage != "f32":
+            if storage == "f16":   # keep the values inside float16's range
+                g = [np.clip(x, -6.0e4, 6.0e4) for x in g]
+            bits16 = [_to_bits16(x, storage) for x in g]
+            g = [orc.widen_gradient(b, storage) for b in bits16]
+            for dst, b in zip(g_dev, bits16):
+                dst.copy_(torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).view(tdtype))
+        else:
+            for dst, x in zip(g_dev, g):
+                dst.copy_(torch.from_numpy(x))
+        want = orc.step(g, res, k, mode_orc, step_no=step_no, fixed_leader=fixed, seg_off=seg_off, seg_k=seg_k)
+        if mode_orc in (orc.MODE_VAR, orc.MODE_VAR_G, orc.MODE_VAR_TOPK) and w > 1 and top_two_gap(want.variances) <= 1e-4:
+            pytest.skip("leader statistics too close for the leader comparison")
+        idx.fill_(-1)
+        summed.fill_(float("nan"))
+        if with_update:
+            update.fill_(float("nan"))
+        kw = dict(vals_out=vals, leader_out=leader, var_out=var, fixed_leader=fixed, seg_off=so, seg_k=sk)
+        if storage == "f32":
+            ctx.artopk_step(g_dev, res_dev, k, mode_lib, step_no, idx, summed, update, **kw)
+        else:
+            g_type = lib.ARTOPK_G_BF16 if storage == "bf16" else lib.ARTOPK_G_F16
+            ctx.artopk_step_g16(g_dev, g_type, res_dev, k, mode_lib, step_no, idx, summed, update, **kw)
+        ctx.status()
+        got = {"leader": int(leader.item()), "var": var.cpu().numpy().copy(), "idx": idx.cpu().numpy(),
+               "sum": summed.cpu().numpy(), "residual": [r.cpu().numpy() for r in res_dev],
+               "update": update.cpu().numpy() if with_update else want.update}
+        if with_vals:
+            got["vals"] = vals.cpu().numpy().reshape(w, k)
+        desc = f"{rule} {storage} vals={with_vals} update={with_update} options={dict(gpu_util.OPTIONS)}"
+        try:
+            assert_step_matches(got, want, mode_orc)
+        except AssertionError as e:
+            raise AssertionError(f"{desc}: {e}") from None
         res = want.residual
 
 
