@@ -95,6 +95,31 @@ def test_random_problem_on_random_routes(seed, monkeypatch):
     import paper_2312_02493_amd as lib
 
     rng, n, w, _, kind, k, seg_off, seg_k = _problem(seed)
+    _run_on_random_routes(seed, monkeypatch, rng, n, w, kind, k, seg_off, seg_k, steps=3)
+
+
+@pytest.mark.parametrize("seed", range(300, 312))
+def test_random_medium_problem_on_random_routes(seed, monkeypatch):
+    """The same draw on vectors of 3 to 40 million elements (hundreds to thousands of tiles; from
+    2^25 elements on the guess route is the library's own choice), one in 20 to one in 2000 kept."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(3_000_000, 40_000_000)) | 1
+    w = int(rng.integers(2, 4))
+    kind = int(rng.choice([0, 0, 3, 2]))
+    k = max(1, int(n / float(rng.choice([20, 100, 500, 2000]))))
+    seg_off = seg_k = None
+    if seed % 3 == 2:
+        cuts = np.sort(rng.choice(np.arange(1, n), size=3, replace=False))
+        seg_off = np.concatenate([[0], cuts, [n]]).astype(np.int64)
+        seg_k = np.maximum(1, (np.diff(seg_off) * (k / n)).astype(np.int64))
+        k = int(seg_k.sum())
+    _run_on_random_routes(seed, monkeypatch, rng, n, w, kind, k, seg_off, seg_k, steps=2)
+
+
+def _run_on_random_routes(seed, monkeypatch, rng, n, w, kind, k, seg_off, seg_k, steps):
+    import torch
+    import paper_2312_02493_amd as lib
+
     opt = np.random.default_rng(7000 + seed)
     for name, choices in (("guess_min_n", [1 << 25, 4096, 4096]), ("stage_tiles", [0, 1, 2]), ("leader_first", [0, 1, 1]),
                           ("update_tiles_min_n", [1 << 22, 1]), ("nontemporal", [0, 1])):
@@ -127,7 +152,7 @@ def test_random_problem_on_random_routes(seed, monkeypatch):
     so = None if seg_off is None else [int(v) for v in seg_off]
     sk = None if seg_k is None else [int(v) for v in seg_k]
     res = [np.zeros(n, dtype=np.float32) for _ in range(w)]
-    for step_no in range(first_step, first_step + 3):
+    for step_no in range(first_step, first_step + steps):
         scales = 1.0 + 0.2 * rng.permutation(w)
         g = [(_values(rng, n, kind) * np.float32(scales[r])) for r in range(w)]
         if storage != "f32":
