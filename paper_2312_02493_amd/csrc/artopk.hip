@@ -746,10 +746,7 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
                         int64_t k, bool tiles_ready = false) {
   // long vectors with few kept entries: zeros streamed tile by tile, values stored behind them
   // (measured on 138 M elements: faster at k = N / 1000, even at N / 100, 40 % slower at N / 10)
-#ifndef ARTOPK_TILES_DENSITY
-#define ARTOPK_TILES_DENSITY 128
-#endif
-  if (n >= c->update_tiles_min_n && k * ARTOPK_TILES_DENSITY <= n) {
+  if (n >= c->update_tiles_min_n && k * 128 <= n) {
     if (!tiles_ready) enqueue_tile_starts(c, idx, n, k);
     if (n < ((int64_t)1 << 28))  // (which kind of store the zeros take: measured, see the kernel)
       hipLaunchKernelGGL((k_update_tiles<kPassRestThreads, kPassRestU, true>), dim3(pass_blocks(n)),

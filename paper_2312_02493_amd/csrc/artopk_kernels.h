@@ -1633,13 +1633,7 @@ k_pick_mask(SelParams p, LeaderArgs la) {
 // plus its position among the lane's own survivors: five or six ballots per
 // tile instead of one per element.
 // ---------------------------------------------------------------------------
-#ifndef ARTOPK_C1_WAVES
-#define ARTOPK_C1_WAVES 4
-#endif
-#ifndef ARTOPK_C1_R
-#define ARTOPK_C1_R 4
-#endif
-constexpr int kC1Waves = ARTOPK_C1_WAVES, kC1R = ARTOPK_C1_R;
+constexpr int kC1Waves = 4, kC1R = 4;  // (flat vectors on the histogram route take 8 waves)
 
 template <int WAVES, int R>
 __device__ __forceinline__ void compact1_body(const SelParams& p) {

