@@ -61,6 +61,7 @@ struct Scratch {
   uint32_t* tile_cnt = nullptr;   // [max_n / kPassTile + 1] entries staged per tile
   uint32_t* sample_keys = nullptr;  // [16384 kGuessRun] keys of one vector's guess sample
   SegDesc* table_dev = nullptr;   // [max_seg] segment descriptors
+  uint32_t* chunk_map = nullptr;  // [kMaxChunks + max_seg] (segment << 16) | chunk, one entry per chunk of the layout
   uint32_t cap = 0;               // list capacity of a flat (one-segment) select
 };
 
@@ -74,6 +75,7 @@ struct Plan {
   int64_t max_tiles = 1;    // largest look-back tile count of a segment
   int64_t total_tiles = 1;
   int64_t max_cap = 1;      // largest list capacity of a segment
+  int32_t total_chunks = 0; // chunks of all segments together (entries of the device chunk map), 0: no map
 };
 
 }  // namespace
@@ -377,6 +379,15 @@ int segmented_plan(artopk_ctx* c, int64_t n, int32_t nseg, const int64_t* seg_of
       return fail(c, ARTOPK_EINVAL, "segment layout exceeds the scratch sized at artopk_create");
     HIP_TRY(c, hipMemcpyAsync(c->s.table_dev, pl.desc.data(), sizeof(SegDesc) * nseg, hipMemcpyHostToDevice,
                               c->stream));
+    // one block per chunk of the layout for the per-chunk kernels (a (chunks, segments) grid of a layout
+    // with one long and many short segments is mostly blocks that find nothing to do)
+    std::vector<uint32_t> cmap;
+    cmap.reserve((size_t)chunk_begin);
+    for (int sgi = 0; sgi < nseg; ++sgi)
+      for (int32_t ch = 0; ch < pl.desc[sgi].geom.nchunks; ++ch) cmap.push_back(((uint32_t)sgi << 16) | (uint32_t)ch);
+    HIP_TRY(c, hipMemcpyAsync(c->s.chunk_map, cmap.data(), sizeof(uint32_t) * cmap.size(), hipMemcpyHostToDevice,
+                              c->stream));
+    pl.total_chunks = chunk_begin;
     c->cached_plan = pl;
     c->cached_n = n;
     c->cached_off.assign(seg_off, seg_off + nseg + 1);
@@ -411,6 +422,7 @@ SelParams make_params(const artopk_ctx* c, const Plan& pl, const PtrTable& tab, 
   p.zero_vec = nullptr;
   p.err = s.err_dev;
   p.table = pl.use_table ? s.table_dev : nullptr;
+  p.chunk_map = (pl.use_table && pl.total_chunks > 0) ? s.chunk_map : nullptr;
   p.slot_by_leader = slot_by_leader;
   p.one = pl.desc[0];
   return p;
@@ -650,6 +662,8 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   p.zero_vec = zero_vec;
   LeaderArgs la{};
   if (leader_args) la = *leader_args;
+  // the per-chunk kernels: one block per chunk of a segmented layout, else a (chunks, segments) grid
+  const dim3 chunk_grid = p.chunk_map ? dim3((unsigned)pl.total_chunks, 1) : dim3(pl.max_chunks, nseg);
 
   if (guessed && hist_ready) {
     // The fused pass marked and counted the keys reaching a guessed bound.  If the bound works out
@@ -668,7 +682,7 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
     pa.after_mask = 1;
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, pa, LeaderArgs{});
   } else {
-    if (!hist_ready) hipLaunchKernelGGL(k_hist0<1024>, dim3(pl.max_chunks, nseg), dim3(1024), 0, st, p);
+    if (!hist_ready) hipLaunchKernelGGL(k_hist0<1024>, chunk_grid, dim3(1024), 0, st, p);
     hipLaunchKernelGGL(k_pick0, dim3(1, nseg), dim3(1024), 0, st, p, la);
   }
 
@@ -696,12 +710,9 @@ int enqueue_select(artopk_ctx* c, const Plan& pl, const PtrTable& tab, int64_t n
   } else if (guessed && hist_ready) {
     const int64_t b1 = lblocks > pl.max_chunks ? lblocks : pl.max_chunks;
     hipLaunchKernelGGL(k_level1, dim3((unsigned)b1, nseg), dim3(64 * kC1Waves), 0, st, p);
-  } else if (nseg == 1) {
-    // (8 waves a block on a flat vector: 21.6 against 27.6 us on 11.7 M elements; with segments, whose
-    // chunks are short, 4 waves: 52 against 59 us on 25.6 M in 54 segments)
-    hipLaunchKernelGGL((k_compact1<8, kC1R>), dim3(pl.max_chunks, nseg), dim3(512), 0, st, p);
   } else {
-    hipLaunchKernelGGL((k_compact1<kC1Waves, kC1R>), dim3(pl.max_chunks, nseg), dim3(64 * kC1Waves), 0, st, p);
+    // (8 waves a block: 21.6 against 27.6 us with 4 on 11.7 M elements, 35 against 38 us on 25.6 M in 54 segments)
+    hipLaunchKernelGGL((k_compact1<8, kC1R>), chunk_grid, dim3(512), 0, st, p);
   }
   // A list of many millions of entries (one element in 32 kept, or more) is counted faster by the
   // lean kernel of its own (99 vs 66 us on 15 M entries: the merged one carries the array pass'
@@ -869,6 +880,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
   const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
   const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
+  const size_t o_cmap = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
   const size_t o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
   // pieces of the survivor list staged per tile by the fused pass: room for kStageMax entries in
   // every tile of the longest vector (1.5 bytes per element)
@@ -901,6 +913,7 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   s.vals = reinterpret_cast<float*>(base + o_vals);
   s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
   s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
+  s.chunk_map = reinterpret_cast<uint32_t*>(base + o_cmap);
   s.tile_start = reinterpret_cast<int32_t*>(base + o_tstart);
   s.tilebuf = reinterpret_cast<uint2*>(base + o_tbuf);
   s.tile_cnt = reinterpret_cast<uint32_t*>(base + o_tcnt);

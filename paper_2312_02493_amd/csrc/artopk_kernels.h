@@ -170,10 +170,25 @@ struct SelParams {
   float* zero_vec;         // the selected vector itself if its kept entries are to become +0.0 on the way, or nullptr
   uint32_t* err;
   const SegDesc* table;
+  // per-chunk kernels of a segmented selection run one block per chunk of the whole layout:
+  // entry b = (segment << 16) | chunk within the segment; nullptr: grid = (chunks, segments)
+  const uint32_t* chunk_map;
   int32_t slot_by_leader;  // S slot = index of the selected vector (histograms of all workers exist) or 0
   int32_t pad;
   SegDesc one;
 };
+
+// The (segment, chunk) a block of a per-chunk kernel works on.
+__device__ __forceinline__ void block_chunk(const SelParams& p, int& seg, int& c) {
+  if (p.chunk_map != nullptr) {
+    const uint32_t m = p.chunk_map[blockIdx.x];
+    seg = (int)(m >> 16);
+    c = (int)(m & 0xffffu);
+  } else {
+    seg = (int)blockIdx.y;
+    c = (int)blockIdx.x;
+  }
+}
 
 struct SegView {
   SegDesc d;
@@ -1293,8 +1308,9 @@ template <int T>
 __device__ __forceinline__ void hist0_body(const SelParams& p) {
   __shared__ __attribute__((aligned(16))) uint32_t lh[kHistBins];
   __shared__ uint32_t red_u[T];
-  const SegView sv = seg_view(p, blockIdx.y);
-  const int c = blockIdx.x;
+  int seg, c;
+  block_chunk(p, seg, c);
+  const SegView sv = seg_view(p, seg);
   if (c >= sv.d.geom.nchunks) return;
   if (p.only_if_need_full && sv.st->need_full == 0u) return;
   const int tid = threadIdx.x;
@@ -1645,8 +1661,9 @@ __device__ __forceinline__ void compact1_body(const SelParams& p) {
   __shared__ uint32_t lh[kHistBins];
   __shared__ uint32_t wtot[2][WAVES];
 
-  const SegView sv = seg_view(p, blockIdx.y);
-  const int c = blockIdx.x;
+  int seg, c;
+  block_chunk(p, seg, c);
+  const SegView sv = seg_view(p, seg);
   if (c >= sv.d.geom.nchunks) return;
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
