@@ -39,12 +39,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def profile_traffic(tag, rho, kernel):
+def profile_traffic(tag, rho, kernel, suffix=""):
     """HBM bytes per launch of `kernel` as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, each
     scaled by what the counter reads for a plain copy): read from the committed summary of the same
-    workload, profiles/artopk_step_<tag>_rho<rho>.md.  (None, None) if there is no such summary or
+    workload, profiles/artopk_step_<tag>_rho<rho><suffix>.md (suffix: _bf16 for gradients stored so).  (None, None) if there is no such summary or
     it does not list the kernel: the figure is never carried in this file."""
-    rel = os.path.join("profiles", f"artopk_step_{tag}_rho{rho}.md")
+    rel = os.path.join("profiles", f"artopk_step_{tag}_rho{rho}{suffix}.md")
     path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
         return None, None
@@ -190,7 +190,7 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
 
 
 def roofline_of(r, tag, g16):
-    traffic, source = (None, None) if g16 else profile_traffic(tag, r["rho"], r["dom_name"])
+    traffic, source = profile_traffic(tag, r["rho"], r["dom_name"], f"_{g16}" if g16 else "")
     return {"bound": "hbm", "kernel": r["dom_name"], "achieved": round(r["dom_gbps"], 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r["dom_gbps"] / HBM_PEAK_GBPS, 4),
             "traffic": traffic, "traffic_source": source, "algorithmic_bytes_per_launch": r["b_dom"],
