@@ -167,7 +167,9 @@ def _run_on_random_routes(seed, monkeypatch, rng, n, w, kind, k, seg_off, seg_k,
                 dst.copy_(torch.from_numpy(x))
         want = orc.step(g, res, k, mode_orc, step_no=step_no, fixed_leader=fixed, seg_off=seg_off, seg_k=seg_k)
         if mode_orc in (orc.MODE_VAR, orc.MODE_VAR_G, orc.MODE_VAR_TOPK) and w > 1 and top_two_gap(want.variances) <= 1e-4:
-            pytest.skip("leader statistics too close for the leader comparison")
+            # leader statistics too close for the leader comparison: this problem goes on round-robin
+            rule, mode_lib, mode_orc = "star", lib.ARTOPK_STAR, orc.MODE_STAR
+            want = orc.step(g, res, k, mode_orc, step_no=step_no, fixed_leader=fixed, seg_off=seg_off, seg_k=seg_k)
         idx.fill_(-1)
         summed.fill_(float("nan"))
         if with_update:
