@@ -100,6 +100,7 @@ enum {
  * *out is set only on success.  A context serialises nothing by itself: calls
  * on one context must not overlap (its scratch is shared between them), and
  * all of them are enqueued on the one stream it was created with.  Scratch size: about 16.4 MiB per worker plus
+ * 64 KiB per segment plus
  * 8 (max_k + max(max_n / 8, 2^22)) bytes of survivor list plus 8 max_w max_k bytes plus
  * max_n / 8 bytes per worker of survivor bit masks plus 1.5 max_n bytes in which a
  * leader's fused pass stages list entries tile by tile.  The library reads no environment
