@@ -23,6 +23,7 @@ steps as they do with a fresh gradient per step.
 
 import argparse
 import json
+import math
 import os
 import re
 import sys
@@ -109,6 +110,10 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     k = wl.k(rho)
     seg_off = None if wl.seg_off is None else [int(v) for v in wl.seg_off]
     seg_k = None if wl.seg_off is None else [int(v) for v in wl.seg_k(rho)]
+    if args.bucket_elems:   # the flat vector cut into buckets, every bucket its own Top-k of the same keep fraction
+        seg_off = list(range(0, wl.n, args.bucket_elems)) + [wl.n]
+        seg_k = [max(1, math.ceil(rho * (seg_off[i + 1] - seg_off[i]))) for i in range(len(seg_off) - 1)]
+        k = sum(seg_k)
     dev = torch.device("cuda:0")
     mode = pkg.ARTOPK_STAR if wl.mode == inp.MODE_STAR else pkg.ARTOPK_VAR
     log(f"[bench] workload {wl.name}: N={wl.n} W={wl.w} rho={rho} k={k} mode={'STAR' if mode == 0 else 'VAR'}")
@@ -159,7 +164,9 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     # (the library says which of the two it ran: an option can turn the second off)
     info = ctx.select_info()
     star = info["dominant_workers"] == wl.w - 1 and wl.w > 1
-    fused = "k_pass_mark" if info["guessed"] else "k_pass_a"   # the fused pass of the guess / histogram route
+    # the fused pass of the guess route (also, without a bound, of a long segmented step) / of the histogram route
+    striding = info["guessed"] or (seg_off is not None and wl.n >= ctx.get_option(pkg.ARTOPK_OPT_GUESS_MIN_N))
+    fused = "k_pass_mark" if striding else "k_pass_a"
     dom_name, dom_stage, dom_workers = ("k_pass_rest", "gather", wl.w - 1) if star else (fused, "pass_a", wl.w)
     dom_ms = ctx.get_profile()[dom_stage]  # averaged over the timed steps
     # stage breakdown from a few extra, untimed steps (an event at every stage boundary)
@@ -252,6 +259,9 @@ def main():
     ap.add_argument("--sparse-update", action="store_true",
                     help="leave out the dense update (update_out = NULL) and apply w[idx] -= eta * sum instead "
                          "(artopk_apply_update); not the headline configuration")
+    ap.add_argument("--bucket-elems", type=int, default=0, metavar="E",
+                    help="run the step bucketed: segments of E elements (16777216 = 64 MB of float32), each with "
+                         "its own Top-k; not the headline configuration")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="set a library route switch before measuring, e.g. guess_min_n=4096 or stage_tiles=2 "
                          "(artopk_set_option; recorded under config.options)")
@@ -327,6 +337,7 @@ def main():
                    "leader_rule": "STAR" if wl0.mode == inp.MODE_STAR else "VAR",
                    **({"gradient_storage": args.g16} if args.g16 else {}),
                    **({"update": "sparse (artopk_apply_update)"} if args.sparse_update else {}),
+                   **({"bucket_elems": args.bucket_elems} if args.bucket_elems else {}),
                    **({"options": args.options} if args.options else {})},
         "roofline": roofline_of(r, args.workload, args.g16),
         "step_algorithmic": step_of(r),

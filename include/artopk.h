@@ -78,7 +78,7 @@ enum { ARTOPK_G_F32 = 0, ARTOPK_G_BF16 = 1, ARTOPK_G_F16 = 2 };
 #define ARTOPK_MAX_WORKERS 64
 
 /* Stages whose duration artopk_get_profile() reports (milliseconds).  With the
- * leader known up front (STAR / FIXED, unsegmented) the step runs the leader's
+ * leader known up front (STAR / FIXED) the step runs the leader's
  * pass and the selection first and then ONE fused pass over the other W-1
  * workers; that pass is reported as ARTOPK_PROF_GATHER. */
 enum {
@@ -115,7 +115,9 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
  * defaults are what the measurements chose).  Takes effect from the next call on
  * the context.  ARTOPK_EINVAL for an unknown key or a value outside its range.
  *   ARTOPK_OPT_GUESS_MIN_N        shortest flat vector that gets the sampled
- *                                 threshold guess before its fused pass;
+ *                                 threshold guess before its fused pass (and
+ *                                 shortest segmented vector whose fused pass
+ *                                 walks the tiles in the same striding order);
  *                                 1 .. 2^31 (2^31 = never), default 33554432
  *   ARTOPK_OPT_UPDATE_TILES_MIN_N shortest vector whose dense update is
  *                                 streamed tile by tile with the values stored

@@ -541,6 +541,37 @@ void launch_pass_mark(artopk_ctx* c, int stats, int nw, const PtrTable& g, const
   return launch_pass_mark_t<2, false>(c, nw, g, r, n, chunk_elems, 0);
 }
 
+// The striding pass without a bound: error-feedback add and statistics of all w workers (per-block
+// moments of pass_blocks(n) blocks per worker in partials).
+template <int STATS, int GT>
+void launch_pass_plain_g(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n) {
+  Scratch& s = c->s;
+  const dim3 grid(pass_blocks(n), nw);
+  const TileBuf tb = tile_buf(c, 0);
+  if (c->pass_a_nt)
+    hipLaunchKernelGGL((k_pass_mark<STATS, true, GT, kPassAThreads, kPassAU, false, true>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, (int64_t)kPassTile, s.h_all, s.mask, s.mask_stride, s.partials, tb);
+  else
+    hipLaunchKernelGGL((k_pass_mark<STATS, false, GT, kPassAThreads, kPassAU, false, true>), grid, dim3(kPassAThreads), 0,
+                       c->stream, g, r, n, (int64_t)kPassTile, s.h_all, s.mask, s.mask_stride, s.partials, tb);
+}
+
+template <int STATS>
+void launch_pass_plain_t(artopk_ctx* c, int nw, const PtrTable& g, const PtrTable& r, int64_t n) {
+  if (c->g_type == ARTOPK_G_BF16)
+    launch_pass_plain_g<STATS, kGBF16>(c, nw, g, r, n);
+  else if (c->g_type == ARTOPK_G_F16)
+    launch_pass_plain_g<STATS, kGF16>(c, nw, g, r, n);
+  else
+    launch_pass_plain_g<STATS, kGF32>(c, nw, g, r, n);
+}
+
+void launch_pass_plain(artopk_ctx* c, int stats, int nw, const PtrTable& g, const PtrTable& r, int64_t n) {
+  if (stats == 0) return launch_pass_plain_t<0>(c, nw, g, r, n);
+  if (stats == 1) return launch_pass_plain_t<1>(c, nw, g, r, n);
+  return launch_pass_plain_t<2>(c, nw, g, r, n);
+}
+
 template <int GT>
 void launch_pass_rest_g(artopk_ctx* c, dim3 grid, const PtrTable& g, const PtrTable& r, int w, int leader, int64_t n,
                         const int32_t* idx, int64_t k, float* vals) {
@@ -1349,7 +1380,7 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   const bool segmented = seg_off != nullptr && nseg > 1;
   // a flat selection on a long vector samples a threshold guess first; its chunks are then whole
   // tiles of the fused pass, which strides over the tiles and counts per chunk
-  const bool leader_first = (mode == ARTOPK_STAR || mode == ARTOPK_FIXED) && !segmented && ctx->leader_first;
+  const bool leader_first = (mode == ARTOPK_STAR || mode == ARTOPK_FIXED) && ctx->leader_first;
   const GuessPlan gp = segmented ? GuessPlan{} : plan_guess(ctx, n, k, leader_first ? 1 : (int)w);
   Plan flat;
   const Plan* pl = &flat;
@@ -1361,6 +1392,10 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
   // pass A always works on whole-vector chunks; for a flat select they are the select's chunks too
   const ChunkGeom geom = make_geom(0, n, kMaxChunks, gp.on);
   const dim3 grid(geom.nchunks, w);
+
+  // a long segmented vector: the fused pass strides over the tiles as on the guess route (the
+  // selection builds the segments' histograms from the leader's vector afterwards either way)
+  const bool seg_stride = segmented && n >= ctx->guess_min_n;
 
   ctx->last_guessed = 0;
   ctx->last_dom_workers = w;
@@ -1407,19 +1442,21 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     const PtrTable g1t = make_table(g1, 1), r1t = make_table(r1, 1);
     prof_begin(ctx);
     prof_mark(ctx, 0);
-    if ((rc = enqueue_clear(ctx, *pl, 1, L, leader_out))) return rc;
+    if ((rc = enqueue_clear(ctx, *pl, segmented ? 0 : 1, L, leader_out))) return rc;
     ctx->last_guessed = gp.on ? 1 : 0;
     ctx->last_dom_workers = w > 1 ? w - 1 : 1;
     if (gp.on) {
       enqueue_guess(ctx, gp, g1t, r1t, 1);
       launch_pass_mark(ctx, 0, 1, g1t, r1t, n, geom.chunk_elems, gp.tile_cap);
-    } else {
-      launch_pass_a(ctx, 0, 1, dim3(geom.nchunks, 1), g1t, r1t, n, geom, 0);
+    } else if (seg_stride) {
+      launch_pass_plain(ctx, 0, 1, g1t, r1t, n);
+    } else {  // (segments build their histograms on the leader's vector afterwards)
+      launch_pass_a(ctx, 0, segmented ? 0 : 1, dim3(geom.nchunks, 1), g1t, r1t, n, geom, segmented ? -1 : 0);
     }
     prof_mark(ctx, 1);
     // The leader's residual is zeroed inside the selection: its kernels have the kept values in
     // registers (level-1 compaction) or write the kept indices anyway (final list pass).
-    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, true, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on,
+    if ((rc = enqueue_select(ctx, *pl, rt, n, idx_out, !segmented, 0, vals + (size_t)L * (size_t)k, nullptr, gp.on,
                              residual[L], gp.tile_cap)))
       return rc;
     prof_mark(ctx, 2);
@@ -1464,7 +1501,9 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     ctx->last_guessed = marking ? 1 : 0;
     if (marking) enqueue_guess(ctx, gp, gt, rt, (int)w);
     prof_dom(ctx, false);
-    if (segmented) {
+    if (seg_stride) {
+      launch_pass_plain(ctx, 0, (int)w, gt, rt, n);
+    } else if (segmented) {
       launch_pass_a(ctx, 0, 0, grid, gt, rt, n, geom, -1);
     } else if (marking) {
       launch_pass_mark(ctx, 0, (int)w, gt, rt, n, geom.chunk_elems);
@@ -1479,7 +1518,10 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     const int stats = mode == ARTOPK_VAR_G ? 2 : 1;  // variance of the raw gradient, or of g + residual
     if (segmented) {
       prof_dom(ctx, false);
-      launch_pass_a(ctx, stats, 0, grid, gt, rt, n, geom, -1);
+      if (seg_stride)
+        launch_pass_plain(ctx, stats, (int)w, gt, rt, n);
+      else
+        launch_pass_a(ctx, stats, 0, grid, gt, rt, n, geom, -1);
     } else {
       ctx->last_guessed = gp.on ? 1 : 0;
       if (gp.on) enqueue_guess(ctx, gp, gt, rt, (int)w);
@@ -1494,8 +1536,9 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     prof_dom(ctx, true);
     prof_mark(ctx, 1);
     if (segmented) {  // the segment histograms are built on the leader's vector, so it is needed now
-      hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w, (int)geom.nchunks, n,
-                         s.var_scratch, var_out, s.leader_dev, leader_out);
+      hipLaunchKernelGGL(k_leader, dim3(1), dim3(1024), 0, st, s.partials, (int)w,
+                         seg_stride ? pass_blocks(n) : (int)geom.nchunks, n, s.var_scratch, var_out, s.leader_dev,
+                         leader_out);
     } else {          // otherwise the selection's first kernel takes the leader itself
       leader_args.partials = s.partials;
       leader_args.w_count = (int)w;
@@ -1508,7 +1551,10 @@ int step_impl(artopk_ctx* ctx, const float* const* g, int32_t g_type, float* con
     }
   } else {
     prof_dom(ctx, false);
-    launch_pass_a(ctx, 0, segmented ? 0 : 1, grid, gt, rt, n, geom, leader_host);
+    if (seg_stride)
+      launch_pass_plain(ctx, 0, (int)w, gt, rt, n);
+    else
+      launch_pass_a(ctx, 0, segmented ? 0 : 1, grid, gt, rt, n, geom, leader_host);
     prof_dom(ctx, true);
     prof_mark(ctx, 1);
     hipLaunchKernelGGL(k_set_leader, dim3(1), dim3(64), 0, st, (int32_t)leader_host, s.leader_dev, leader_out);

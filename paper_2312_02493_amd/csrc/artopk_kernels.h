@@ -697,6 +697,11 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
 //   Counts: every wave adds its tile's count to mcount[chunk of the tile] in the
 //   slot (cleared beforehand); chunk_elems must be a whole number of tiles.
 //   Variance partials: block b of worker y (see VarAcc).
+//   PLAIN: no bound is read and nothing is counted: the error-feedback add and the
+//   statistics in the same striding order, for a step whose selection builds its own
+//   histograms afterwards (long segmented vectors).  The ballots and the mask words
+//   (zero, but for Inf and NaN) stay: without them the same pass streamed slower on
+//   8 x 1e9 elements, 16.6 against 16.1 ms.
 //   STAGE: the marked elements of a tile are also handed on as list entries
 //   (index, raw bits), in ascending element order: ranked inside the block (the
 //   128 row counts of the tile are scanned by every wave), collected in on-chip
@@ -727,10 +732,11 @@ __device__ __forceinline__ int64_t mask_word(int64_t row) {
   return (row >> 7) * 512 + (row & 15) * 32 + ((row >> 4) & 7) * 4;
 }
 
-template <int STATS, bool NT, int GT, int T, int U, bool STAGE>
+template <int STATS, bool NT, int GT, int T, int U, bool STAGE, bool PLAIN = false>
 __global__ void __launch_bounds__(T)
 k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* __restrict__ h_all,
             uint64_t* __restrict__ mask, int64_t mask_stride, double* __restrict__ partials, TileBuf tiles) {
+  static_assert(!(PLAIN && STAGE), "nothing is marked in the plain form");
   __shared__ uint32_t wcnt[STAGE ? (T / 64) * U : 1];  // the tile's 128 row counts, row-major
   __shared__ uint2 stage[STAGE ? kStageMax : 1];
   const int w = blockIdx.y;
@@ -745,7 +751,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
   uint64_t* __restrict__ mrow = mask + (size_t)w * (size_t)mask_stride;
 
   // Marked <=> not (|acc| < bound): the same as key >= bound on the magnitude bits, NaNs included.
-  const uint32_t gkey = slot[kSlotCtrl + 1];
+  const uint32_t gkey = PLAIN ? kNoGuess : slot[kSlotCtrl + 1];
   const float gf = gkey != kNoGuess ? __uint_as_float(gkey) : __builtin_inff();
 
   const int64_t q_hi = n >> 2;  // whole float4 groups of the vector
@@ -837,7 +843,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
     const int64_t qw = ti * TQ + wave_first;  // wave-uniform, so all 64 lanes stay together (the masks need that)
     if (STAGE) own = 0u;
     const uint32_t marked = (ti + 1) * TQ <= q_hi ? tile(qw, std::true_type{}) : tile(qw, std::false_type{});
-    if (lane == 0 && marked != 0u) atomicAdd(&mcount[(ti * TQ * 4) / chunk_elems], marked);
+    if (!PLAIN && lane == 0 && marked != 0u) atomicAdd(&mcount[(ti * TQ * 4) / chunk_elems], marked);
     if (STAGE) {
       // rank the tile's marks: element order is row-major, row = 16 u + wave, then lane, then e
       if (lane < U) wcnt[lane * (T / 64) + wave] = rows_cnt;
@@ -903,7 +909,7 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
         va.seed1(STATS == 2 ? gj : v);
         va.add1(STATS == 2 ? gj : v);
       }
-      if (!(__builtin_fabsf(v) < gf)) atomicAdd(&mcount[(n - 1) / chunk_elems], 1u);
+      if (!PLAIN && !(__builtin_fabsf(v) < gf)) atomicAdd(&mcount[(n - 1) / chunk_elems], 1u);
     }
   }
 
