@@ -470,21 +470,32 @@ def test_two_runs_give_identical_bits():
     assert np.array_equal(a["var"].view(np.uint64), b["var"].view(np.uint64))
 
 
-def test_bucketed_layout_16mi_elements():
+@pytest.mark.parametrize("rule", ["star", "var", "star_all_workers_first"])
+def test_bucketed_layout_16mi_elements(rule, monkeypatch):
     """Fixed-size buckets (64 MB = 16 Mi float32 each, the granularity the paper's
-    communication measurements use) are just a segment table."""
+    communication measurements use) are just a segment table.  40 M elements: the fused pass
+    strides over the tiles; with the round-robin leader its pass and the segments' selection
+    run first and the other worker follows in one pass (or, with that switched off, all
+    workers' pass first).  Two steps, residual carried."""
+    if rule == "star_all_workers_first":
+        monkeypatch.setitem(gpu_util.OPTIONS, "leader_first", 0)
+    mode = orc.MODE_VAR if rule == "var" else orc.MODE_STAR
     wl = inp.workload(4, n=40_000_007, w=2)
     bucket = 16 * 1024 * 1024
     off = list(range(0, wl.n, bucket)) + [wl.n]
     ks = [int(np.ceil(0.001 * (off[i + 1] - off[i]))) for i in range(len(off) - 1)]
     k = sum(ks)
-    g = [wl.gen(1, r, threads=8) for r in range(2)]
     res = [np.zeros(wl.n, np.float32) for _ in range(2)]
     run = GpuRunner(2, wl.n, k, max_segments=len(ks))
-    run.load_g(g)
-    want = orc.step(g, res, k, orc.MODE_STAR, step_no=1, seg_off=off, seg_k=ks)
-    got = run.step(k, orc.MODE_STAR, 1, seg_off=off, seg_k=ks)
-    assert_step_matches(got, want, orc.MODE_STAR)
+    for step_no in (1, 2):
+        g = [wl.gen(step_no, r, threads=8) * np.float32(1.0 + 0.05 * r) for r in range(2)]
+        run.load_g(g)
+        want = orc.step(g, res, k, mode, step_no=step_no, seg_off=off, seg_k=ks)
+        if mode == orc.MODE_VAR:
+            assert top_two_gap(want.variances) > 1e-4
+        got = run.step(k, mode, step_no, seg_off=off, seg_k=ks)
+        assert_step_matches(got, want, mode)
+        res = want.residual
 
 
 @pytest.mark.parametrize("rule,route", [("var", "histogram"), ("var", "guess"), ("star", "histogram"), ("star", "guess"),
