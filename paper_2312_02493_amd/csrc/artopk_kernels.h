@@ -617,6 +617,11 @@ k_pass_a(PtrTable g, PtrTable res, int64_t n, ChunkGeom geom, int hist_worker, u
       const int64_t q = qw + lane + u * T;
       const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
       a[u] = load4g<NT, GT>(gp, 4 * ql);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {  // (one array after the other: see k_pass_mark)
+      const int64_t q = qw + lane + u * T;
+      const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
       b[u] = load4<NT>(rp + 4 * ql);
     }
 #pragma unroll
@@ -781,6 +786,13 @@ k_pass_mark(PtrTable g, PtrTable res, int64_t n, int64_t chunk_elems, uint32_t* 
       const int64_t q = qw + lane + u * T;
       const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
       a[u] = load4g<NT, GT>(gp, 4 * ql);
+    }
+    // The tile's gradient loads first, then its residual loads: issued alternately (g, r, g, r, ...)
+    // the same pass took 16.04 instead of 15.72 ms on 8 x 1e9 elements (residual first: 15.77).
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = qw + lane + u * T;
+      const int64_t ql = (FULL || q < q_hi) ? q : q_hi - 1;
       b[u] = load4<NT>(rp + 4 * ql);
     }
     uint32_t marked = 0u;  // of this wave in this tile
@@ -2775,6 +2787,11 @@ k_pass_rest(PtrTable g, PtrTable res, int w_count, int leader, int64_t n, const 
       const int64_t q = q0 + u * T;
       const int64_t ql = (full || q < q_end) ? q : q_end - 1;
       a[u] = load4g<NT, GT>(gp, 4 * ql);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {  // (one array after the other: see k_pass_mark)
+      const int64_t q = q0 + u * T;
+      const int64_t ql = (full || q < q_end) ? q : q_end - 1;
       b[u] = load4<NT>(rp + 4 * ql);
     }
     // slot[j] = (position in idx) - m_base for a kept element j of this tile, else -1
