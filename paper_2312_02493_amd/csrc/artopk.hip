@@ -847,7 +847,7 @@ int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t 
 
 extern "C" {
 
-int32_t artopk_version(void) { return 100; }
+int32_t artopk_version(void) { return 200; }  // 0.2.0: options, counted round-robin leader, allocation-free variance
 
 const char* artopk_last_error(const artopk_ctx* ctx) { return ctx ? ctx->err : g_noctx_err; }
 
