@@ -111,6 +111,12 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
                   int32_t max_segments, void* hip_stream);
 
 /*
+ * Bytes of device memory that artopk_create would allocate for these limits (host
+ * arithmetic only: no device is touched), or -1 if artopk_create would refuse them.
+ */
+int64_t artopk_scratch_bytes(int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments);
+
+/*
  * Switches between routes that give identical results (for tests and tuning; the
  * defaults are what the measurements chose).  Takes effect from the next call on
  * the context.  ARTOPK_EINVAL for an unknown key or a value outside its range.

@@ -25,6 +25,7 @@ _SYMBOLS = (
     "artopk_set_profile", "artopk_get_profile", "artopk_version", "artopk_compression_gain",
     "artopk_apply_update", "artopk_topk_workers", "artopk_select_info", "artopk_step_g16",
     "artopk_set_option", "artopk_get_option", "artopk_variance_static", "artopk_set_step_counter",
+    "artopk_scratch_bytes",
 )
 
 
@@ -77,9 +78,11 @@ def load_library():
     lib.artopk_get_option.argtypes = [vp, i32, C.POINTER(i64)]
     lib.artopk_variance_static.argtypes = [vp, i32, i64, vp, vp, vp]
     lib.artopk_set_step_counter.argtypes = [vp, C.c_uint64]
+    lib.artopk_scratch_bytes.argtypes = [i32, i64, i64, i32]
     lib.artopk_version.restype = i32
+    lib.artopk_scratch_bytes.restype = i64
     for name in _SYMBOLS:
-        if name not in ("artopk_last_error", "artopk_version"):
+        if name not in ("artopk_last_error", "artopk_version", "artopk_scratch_bytes"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -103,6 +106,11 @@ def _i64_array(values):
     for i, v in enumerate(values):
         arr[i] = int(v)
     return arr
+
+
+def artopk_scratch_bytes(max_w: int, max_n: int, max_k: int, max_segments: int = 1) -> int:
+    """Device bytes a Context of these limits allocates (-1: limits refused); needs no GPU."""
+    return int(load_library().artopk_scratch_bytes(int(max_w), int(max_n), int(max_k), int(max_segments)))
 
 
 def artopk_variance_static(x: Sequence, var_out, argmax_out=None, stream: Optional[int] = None):

@@ -845,6 +845,75 @@ int enqueue_topk_workers(artopk_ctx* c, const PtrTable& tab, int32_t w, int64_t 
 
 }  // namespace
 
+namespace {
+
+// Where everything lies in the one allocation of a context.
+struct Layout {
+  uint32_t cap = 0;
+  int64_t list_entries = 0, max_tiles = 0, mask_stride = 0, tilebuf_entries = 0;
+  size_t o_hall = 0, o_mask = 0, o_zero = 0, o_S = 0, o_coff = 0, o_part = 0, o_var = 0, o_leader = 0, o_err = 0, o_counter = 0, o_list = 0, o_vals = 0, o_rows = 0, o_table = 0, o_cmap = 0, o_tstart = 0, o_tbuf = 0, o_tcnt = 0, o_sample = 0;
+  size_t total = 0;
+};
+
+bool valid_limits(int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments) {
+  return !(max_w < 1 || max_w > ARTOPK_MAX_WORKERS || max_n < 1 || max_n >= (1ll << 31) || max_k < 1 ||
+           max_k > max_n || max_segments < 1 || max_segments > 65535);
+}
+
+Layout scratch_layout(int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments) {
+  Layout L;
+  // list capacity: every key above the range (< k of them) plus a generous share of candidates
+  // (vectors of up to 4 Mi elements fit the list whole: their selection never needs the deeper
+  // array passes, which are then not even launched)
+  int64_t cand_share = max_n / 8;
+  if (cand_share < ((int64_t)1 << 22)) cand_share = (int64_t)1 << 22;
+  int64_t cap = max_k + cand_share;
+  if (cap > max_n) cap = max_n;
+  L.cap = (uint32_t)cap;
+  // segmented layouts add per-segment rounding: n_s/8 may be raised to 4096 and bases are aligned
+  L.list_entries = (int64_t)align_up((size_t)cap + (size_t)max_segments * 4100, kCompactTile) + kCompactTile;
+  // a range [lo, hi) touches at most ceil(len / tile) + 1 look-back tiles
+  L.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 2 * (int64_t)max_segments + 1;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  // zeroed region: one block per segment, then the look-back flags
+  L.o_hall = take((size_t)max_w * kSlotWords * sizeof(uint32_t));
+  // one bit per element and worker, in rows of 256 elements (whole tiles of the fused pass)
+  L.mask_stride = (max_n + kPassTile - 1) / kPassTile * (kPassTile / 64);
+  L.o_mask = take((size_t)max_w * (size_t)L.mask_stride * sizeof(uint64_t));
+  L.o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
+                             (size_t)L.max_tiles * kNumLookback * sizeof(uint64_t));
+  L.o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
+  L.o_coff = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
+  L.o_part = take((size_t)max_w * kMaxPassBlocks * 3 * sizeof(double));
+  L.o_var = take((size_t)max_w * sizeof(double));
+  L.o_leader = take(sizeof(int32_t));
+  L.o_err = take(sizeof(uint32_t));
+  L.o_counter = take(sizeof(uint64_t));
+  L.o_list = take((size_t)L.list_entries * sizeof(uint2));
+  L.o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
+  L.o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
+  L.o_table = take((size_t)max_segments * sizeof(SegDesc));
+  L.o_cmap = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
+  L.o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
+  // pieces of the survivor list staged per tile by the fused pass: room for kStageMax entries in
+  // every tile of the longest vector (1.5 bytes per element)
+  const int64_t max_tiles_pass = (max_n + kPassTile - 1) / kPassTile;
+  L.tilebuf_entries = max_tiles_pass * (int64_t)kStageMax;
+  L.o_tbuf = take((size_t)L.tilebuf_entries * sizeof(uint2));
+  L.o_tcnt = take((size_t)(max_tiles_pass + 1) * sizeof(uint32_t));
+  L.o_sample = take((size_t)16384 * kGuessRun * sizeof(uint32_t));
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
 extern "C" {
 
 int32_t artopk_version(void) { return 200; }  // 0.2.0: options, counted round-robin leader, allocation-free variance
@@ -854,9 +923,7 @@ const char* artopk_last_error(const artopk_ctx* ctx) { return ctx ? ctx->err : g
 int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments,
                   void* hip_stream) {
   if (!out) return ARTOPK_EINVAL;
-  if (max_w < 1 || max_w > ARTOPK_MAX_WORKERS || max_n < 1 || max_n >= (1ll << 31) || max_k < 1 ||
-      max_k > max_n || max_segments < 1 || max_segments > 65535)
-    return ARTOPK_EINVAL;
+  if (!valid_limits(max_w, max_n, max_k, max_segments)) return ARTOPK_EINVAL;
   artopk_ctx* c = new (std::nothrow) artopk_ctx();
   if (!c) return ARTOPK_ENOMEM;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -874,53 +941,13 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   c->num_cu = cus > 0 ? cus : 256;
 
   Scratch& s = c->s;
-  // list capacity: every key above the range (< k of them) plus a generous share of candidates
-  // (vectors of up to 4 Mi elements fit the list whole: their selection never needs the deeper
-  // array passes, which are then not even launched)
-  int64_t cand_share = max_n / 8;
-  if (cand_share < ((int64_t)1 << 22)) cand_share = (int64_t)1 << 22;
-  int64_t cap = max_k + cand_share;
-  if (cap > max_n) cap = max_n;
-  s.cap = (uint32_t)cap;
-  // segmented layouts add per-segment rounding: n_s/8 may be raised to 4096 and bases are aligned
-  s.list_entries = (int64_t)align_up((size_t)cap + (size_t)max_segments * 4100, kCompactTile) + kCompactTile;
-  // a range [lo, hi) touches at most ceil(len / tile) + 1 look-back tiles
-  s.max_tiles = (max_n + kCompactTile - 1) / kCompactTile + 2 * (int64_t)max_segments + 1;
-
-  size_t off = 0;
-  auto take = [&](size_t bytes) {
-    size_t o = off;
-    off = align_up(off + bytes, 256);
-    return o;
-  };
-  // zeroed region: one block per segment, then the look-back flags
-  const size_t o_hall = take((size_t)max_w * kSlotWords * sizeof(uint32_t));
-  // one bit per element and worker, in rows of 256 elements (whole tiles of the fused pass)
-  s.mask_stride = (max_n + kPassTile - 1) / kPassTile * (kPassTile / 64);
-  const size_t o_mask = take((size_t)max_w * (size_t)s.mask_stride * sizeof(uint64_t));
-  const size_t o_zero = take((size_t)max_segments * kSegWords * sizeof(uint32_t) +
-                             (size_t)s.max_tiles * kNumLookback * sizeof(uint64_t));
-  const size_t o_S = take(((size_t)max_w * kMaxChunks + (size_t)max_segments) * kHistBins * sizeof(uint32_t));
-  const size_t o_coff = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
-  const size_t o_part = take((size_t)max_w * kMaxPassBlocks * 3 * sizeof(double));
-  const size_t o_var = take((size_t)max_w * sizeof(double));
-  const size_t o_leader = take(sizeof(int32_t));
-  const size_t o_err = take(sizeof(uint32_t));
-  const size_t o_counter = take(sizeof(uint64_t));
-  const size_t o_list = take((size_t)s.list_entries * sizeof(uint2));
-  const size_t o_vals = take((size_t)max_w * (size_t)max_k * sizeof(float));
-  const size_t o_rows = take((size_t)max_w * (size_t)max_k * sizeof(int32_t));
-  const size_t o_table = take((size_t)max_segments * sizeof(SegDesc));
-  const size_t o_cmap = take(((size_t)kMaxChunks + (size_t)max_segments) * sizeof(uint32_t));
-  const size_t o_tstart = take((size_t)(max_n / kPassTile + 2) * sizeof(int32_t));
-  // pieces of the survivor list staged per tile by the fused pass: room for kStageMax entries in
-  // every tile of the longest vector (1.5 bytes per element)
-  const int64_t max_tiles_pass = (max_n + kPassTile - 1) / kPassTile;
-  s.tilebuf_entries = max_tiles_pass * (int64_t)kStageMax;
-  const size_t o_tbuf = take((size_t)s.tilebuf_entries * sizeof(uint2));
-  const size_t o_tcnt = take((size_t)(max_tiles_pass + 1) * sizeof(uint32_t));
-  const size_t o_sample = take((size_t)16384 * kGuessRun * sizeof(uint32_t));
-  const size_t total = off;
+  const Layout L = scratch_layout(max_w, max_n, max_k, max_segments);
+  s.cap = L.cap;
+  s.list_entries = L.list_entries;
+  s.max_tiles = L.max_tiles;
+  s.mask_stride = L.mask_stride;
+  s.tilebuf_entries = L.tilebuf_entries;
+  const size_t total = L.total;
 
   e = hipMalloc(&c->slab, total);
   if (e != hipSuccess) {
@@ -928,27 +955,27 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
     return ARTOPK_ENOMEM;
   }
   char* base = static_cast<char*>(c->slab);
-  s.h_all = reinterpret_cast<uint32_t*>(base + o_hall);
-  s.mask = reinterpret_cast<uint64_t*>(base + o_mask);
-  s.zero_base = reinterpret_cast<uint32_t*>(base + o_zero);
+  s.h_all = reinterpret_cast<uint32_t*>(base + L.o_hall);
+  s.mask = reinterpret_cast<uint64_t*>(base + L.o_mask);
+  s.zero_base = reinterpret_cast<uint32_t*>(base + L.o_zero);
   // kSegWords is even, so the flags stay 8-byte aligned
   s.flags = reinterpret_cast<uint64_t*>(s.zero_base + (size_t)max_segments * kSegWords);
-  s.S = reinterpret_cast<uint32_t*>(base + o_S);
-  s.chunk_off = reinterpret_cast<uint32_t*>(base + o_coff);
-  s.partials = reinterpret_cast<double*>(base + o_part);
-  s.var_scratch = reinterpret_cast<double*>(base + o_var);
-  s.leader_dev = reinterpret_cast<int32_t*>(base + o_leader);
-  s.err_dev = reinterpret_cast<uint32_t*>(base + o_err);
-  s.counter_dev = reinterpret_cast<uint64_t*>(base + o_counter);
-  s.list = reinterpret_cast<uint2*>(base + o_list);
-  s.vals = reinterpret_cast<float*>(base + o_vals);
-  s.idx_rows = reinterpret_cast<int32_t*>(base + o_rows);
-  s.table_dev = reinterpret_cast<SegDesc*>(base + o_table);
-  s.chunk_map = reinterpret_cast<uint32_t*>(base + o_cmap);
-  s.tile_start = reinterpret_cast<int32_t*>(base + o_tstart);
-  s.tilebuf = reinterpret_cast<uint2*>(base + o_tbuf);
-  s.tile_cnt = reinterpret_cast<uint32_t*>(base + o_tcnt);
-  s.sample_keys = reinterpret_cast<uint32_t*>(base + o_sample);
+  s.S = reinterpret_cast<uint32_t*>(base + L.o_S);
+  s.chunk_off = reinterpret_cast<uint32_t*>(base + L.o_coff);
+  s.partials = reinterpret_cast<double*>(base + L.o_part);
+  s.var_scratch = reinterpret_cast<double*>(base + L.o_var);
+  s.leader_dev = reinterpret_cast<int32_t*>(base + L.o_leader);
+  s.err_dev = reinterpret_cast<uint32_t*>(base + L.o_err);
+  s.counter_dev = reinterpret_cast<uint64_t*>(base + L.o_counter);
+  s.list = reinterpret_cast<uint2*>(base + L.o_list);
+  s.vals = reinterpret_cast<float*>(base + L.o_vals);
+  s.idx_rows = reinterpret_cast<int32_t*>(base + L.o_rows);
+  s.table_dev = reinterpret_cast<SegDesc*>(base + L.o_table);
+  s.chunk_map = reinterpret_cast<uint32_t*>(base + L.o_cmap);
+  s.tile_start = reinterpret_cast<int32_t*>(base + L.o_tstart);
+  s.tilebuf = reinterpret_cast<uint2*>(base + L.o_tbuf);
+  s.tile_cnt = reinterpret_cast<uint32_t*>(base + L.o_tcnt);
+  s.sample_keys = reinterpret_cast<uint32_t*>(base + L.o_sample);
 
   // leader, error word and step counter start at zero (stream-ordered before any later call)
   hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, c->stream,
@@ -962,6 +989,11 @@ int artopk_create(artopk_ctx** out, int32_t max_w, int64_t max_n, int64_t max_k,
   }
   *out = c;
   return ARTOPK_OK;
+}
+
+int64_t artopk_scratch_bytes(int32_t max_w, int64_t max_n, int64_t max_k, int32_t max_segments) {
+  if (!valid_limits(max_w, max_n, max_k, max_segments)) return -1;
+  return (int64_t)scratch_layout(max_w, max_n, max_k, max_segments).total;
 }
 
 int artopk_destroy(artopk_ctx* ctx) {

@@ -28,6 +28,30 @@ def test_header_symbols_are_exported():
     assert lib.artopk_version() >= 100
 
 
+def test_scratch_size_query():
+    """artopk_scratch_bytes is host arithmetic: the size of the one allocation artopk_create makes.
+    Checked against the terms the header's comment on artopk_create lists (dominant ones only, so
+    within a few percent), its monotonicity in every limit, and the limits artopk_create refuses."""
+    import paper_2312_02493_amd as pkg
+
+    q = pkg.artopk_scratch_bytes
+    n, w, k = 1_000_000_000, 8, 1_000_000
+    got = q(w, n, k, 1)
+    model = (w * 16.4 * 2**20            # per-chunk histograms and the rest of a worker's slot
+             + 8 * (k + max(n // 8, 2**22))  # survivor list
+             + 8 * w * k                  # value rows and index rows
+             + w * n / 8                  # bit masks
+             + 1.5 * n)                   # staged list entries
+    assert abs(got - model) / model < 0.03, (got, model)
+    assert 3.5e9 < got < 4.0e9           # the figure the design notes quote for this size
+    assert q(w, n, k, 1) <= q(w + 1, n, k, 1) and q(w, n, k, 1) <= q(w, n, k * 2, 1) and q(w, n, k, 1) <= q(w, n, k, 9)
+    assert q(w, 1 << 20, 1024, 1) < q(w, 1 << 24, 1024, 1)
+    assert q(1, 1, 1, 1) > 0
+    for bad in ((0, 10, 1, 1), (65, 10, 1, 1), (1, 0, 1, 1), (1, 1 << 31, 1, 1), (1, 10, 0, 1), (1, 10, 11, 1),
+                (1, 10, 1, 0), (1, 10, 1, 65536)):
+        assert q(*bad) == -1, bad
+
+
 def test_no_cpu_fallback():
     import torch
     import paper_2312_02493_amd as pkg
