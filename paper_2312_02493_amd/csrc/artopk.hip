@@ -804,6 +804,19 @@ int enqueue_update_fill(artopk_ctx* c, float* update, int64_t n, const int32_t* 
   if (blocks < 1) blocks = 1;
   // kept entries expected per 8192-element chunk decide how many are fetched per round
   const double per_chunk = (double)k / (double)n * kFillChunk;
+  if (tiles_ready && n >= c->update_tiles_min_n) {
+    // the tiles' first indices are there already: blocks stride over the tiles
+    const int64_t ntiles = (n + kPassTile - 1) / kPassTile;
+    const int tb = (int)(ntiles < (int64_t)c->num_cu * 4 ? ntiles : (int64_t)c->num_cu * 4);
+    if (per_chunk <= 160.0)
+      hipLaunchKernelGGL((k_update_fill_tiled<1>), dim3(tb), dim3(256), 0, c->stream, update, n, idx, sum, k, c->s.tile_start);
+    else if (per_chunk <= 400.0)
+      hipLaunchKernelGGL((k_update_fill_tiled<2>), dim3(tb), dim3(256), 0, c->stream, update, n, idx, sum, k, c->s.tile_start);
+    else
+      hipLaunchKernelGGL((k_update_fill_tiled<4>), dim3(tb), dim3(256), 0, c->stream, update, n, idx, sum, k, c->s.tile_start);
+    HIP_TRY(c, hipGetLastError());
+    return ARTOPK_OK;
+  }
   if (per_chunk <= 160.0) {
     hipLaunchKernelGGL((k_update_fill<1>), dim3(blocks), dim3(256), 0, c->stream, update, n, idx, sum, k);
   } else if (per_chunk <= 400.0) {

@@ -2933,6 +2933,85 @@ k_zero_at(PtrTable tab, int w_count, int64_t n, const int32_t* __restrict__ idx,
 // ---------------------------------------------------------------------------
 constexpr int kFillChunk = 8192;
 
+// What a thread holds of the (index, sum) pairs ahead of the chunk being built.
+template <int BATCH>
+struct FillAhead {
+  int64_t ib[BATCH];
+  float sb[BATCH];
+};
+
+constexpr int64_t kFillNone = INT64_MAX;  // no index: beyond every chunk
+
+template <int BATCH>
+__device__ __forceinline__ void fill_fetch(FillAhead<BATCH>& a, const int32_t* __restrict__ idx,
+                                           const float* __restrict__ sum, int64_t k, int64_t from) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < BATCH; ++j) {
+    // (no branch around the loads: behind the list they re-read its last entry, unused)
+    const int64_t p = from + tid + j * 256;
+    const int64_t pc = p < k ? p : k - 1;
+    const int32_t iv = idx[pc];
+    const float sv = sum[pc];
+    a.ib[j] = p < k ? (int64_t)iv : kFillNone;
+    a.sb[j] = sv;
+  }
+}
+
+// Builds and streams out the chunks [c_begin, c_end) of the update; m = number of indices below
+// the first of them, whose first pairs `a` already holds.  The pairs a chunk starts with are
+// fetched one chunk ahead, before the previous chunk is streamed out, so that their latency is
+// not part of the chunk's own chain; behind the last chunk the fetch goes to m_after (the start
+// of the block's next run) if that is not negative.  All 256 threads call it.
+template <int BATCH>
+__device__ __forceinline__ void fill_run(FillAhead<BATCH>& a, float* __restrict__ buf, float* __restrict__ update,
+                                         int64_t n, const int32_t* __restrict__ idx, const float* __restrict__ sum,
+                                         int64_t k, int64_t c_begin, int64_t c_end, int64_t m, int64_t m_after) {
+  constexpr int kGroups = kFillChunk / 4 / 256;  // float4 groups per thread and chunk
+  const int tid = threadIdx.x;
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    const int64_t lo = c * kFillChunk;
+    const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
+    const int64_t len = hi - lo;
+    const int64_t len4 = len >> 2;
+    float4* b4 = reinterpret_cast<float4*>(buf);
+    for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    while (true) {
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const bool in = a.ib[j] < hi;
+        if (in && a.ib[j] >= lo) {  // ib >= lo always holds for ascending idx
+          const int64_t off = a.ib[j] - lo;
+          buf[off] = a.sb[j];
+        }
+        cnt += __syncthreads_count(in);
+      }
+      m += cnt;
+      const bool chunk_done = cnt < BATCH * 256;
+      // the next chunk's first pairs, or the rest of this chunk's
+      fill_fetch<BATCH>(a, idx, sum, k, (chunk_done && c == c_end - 1 && m_after >= 0) ? m_after : m);
+      if (chunk_done) break;
+    }
+    // (the count barrier above also orders the LDS writes before the reads)
+    float* __restrict__ up = update + lo;
+#pragma unroll
+    for (int j = 0; j < kGroups; ++j) {
+      const int64_t i = tid + j * 256;
+      if (i < len4) {
+        // (non-temporal: with ordinary stores the time of this fill depended on what earlier
+        // kernels had left in the caches, 115 to 150 us on 138 M elements; so it is 115 throughout)
+        const float4 t4 = b4[i];
+        const v4f tv = {t4.x, t4.y, t4.z, t4.w};
+        store4<true>(up + 4 * i, tv);
+      }
+    }
+    for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];  // ragged end of the vector
+    __syncthreads();
+  }
+}
+
 template <int BATCH>
 __global__ void __launch_bounds__(256)
 k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
@@ -2974,65 +3053,40 @@ k_update_fill(float* __restrict__ update, int64_t n, const int32_t* __restrict__
     }
     __syncthreads();
   }
-  int64_t m = s_lo;
+  const int64_t m = s_lo;
+  FillAhead<BATCH> a;
+  fill_fetch<BATCH>(a, idx, sum, k, m);
+  fill_run<BATCH>(a, buf, update, n, idx, sum, k, c_begin, c_end, m, -1);
+}
 
-  constexpr int kGroups = kFillChunk / 4 / 256;  // float4 groups per thread and chunk
-  constexpr int64_t kNone = INT64_MAX;           // no index: beyond every chunk
-  // The (index, sum) pairs a chunk starts with are fetched one chunk ahead, before the previous
-  // chunk is streamed out, so that their latency is not part of the chunk's own chain.
-  int64_t ib[BATCH];
-  float sb[BATCH];
-  auto fetch = [&](int64_t from) {
-#pragma unroll
-    for (int j = 0; j < BATCH; ++j) {
-      // (no branch around the loads: behind the list they re-read its last entry, unused)
-      const int64_t p = from + tid + j * 256;
-      const int64_t pc = p < k ? p : k - 1;
-      const int32_t iv = idx[pc];
-      const float sv = sum[pc];
-      ib[j] = p < k ? (int64_t)iv : kNone;
-      sb[j] = sv;
-    }
+// The same with the blocks striding over the tiles of the streaming passes (kPassTile elements, four
+// chunks), whose first indices k_tile_starts has left in tile_start: no search, and at any time the
+// blocks in flight write one contiguous window of the update.
+template <int BATCH>
+__global__ void __launch_bounds__(256)
+k_update_fill_tiled(float* __restrict__ update, int64_t n, const int32_t* __restrict__ idx,
+                    const float* __restrict__ sum, int64_t k, const int32_t* __restrict__ tile_start) {
+  __shared__ __attribute__((aligned(16))) float buf[kFillChunk];
+  constexpr int64_t kPer = kPassTile / kFillChunk;  // chunks per tile
+  const int64_t nchunk = (n + kFillChunk - 1) / kFillChunk;
+  const int64_t ntiles = (n + kPassTile - 1) / kPassTile;
+  // (a start outside [0, k] can only come from an index list that was not ascending)
+  auto start_of = [&](int64_t t) {
+    const int64_t v = (int64_t)tile_start[t];
+    return v < 0 ? (int64_t)0 : (v > k ? k : v);
   };
-  fetch(m);
-  for (int64_t c = c_begin; c < c_end; ++c) {
-    const int64_t lo = c * kFillChunk;
-    const int64_t hi = (lo + kFillChunk < n) ? lo + kFillChunk : n;
-    const int64_t len = hi - lo;
-    const int64_t len4 = len >> 2;
-    float4* b4 = reinterpret_cast<float4*>(buf);
-    for (int i = tid; i < kFillChunk / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
-    while (true) {
-      int cnt = 0;
-#pragma unroll
-      for (int j = 0; j < BATCH; ++j) {
-        const bool in = ib[j] < hi;
-        if (in && ib[j] >= lo) {  // ib >= lo always holds for ascending idx
-          const int64_t off = ib[j] - lo;
-          buf[off] = sb[j];
-        }
-        cnt += __syncthreads_count(in);
-      }
-      m += cnt;
-      fetch(m);  // the next chunk's first pairs, or the rest of this chunk's
-      if (cnt < BATCH * 256) break;
-    }
-    // (the count barrier above also orders the LDS writes before the reads)
-    float* __restrict__ up = update + lo;
-#pragma unroll
-    for (int j = 0; j < kGroups; ++j) {
-      const int64_t i = tid + j * 256;
-      if (i < len4) {
-        // (non-temporal: with ordinary stores the time of this fill depended on what earlier
-        // kernels had left in the caches, 115 to 150 us on 138 M elements; so it is 115 throughout)
-        const float4 t4 = b4[i];
-        const v4f tv = {t4.x, t4.y, t4.z, t4.w};
-        store4<true>(up + 4 * i, tv);
-      }
-    }
-    for (int64_t i = len4 * 4 + tid; i < len; i += 256) up[i] = buf[i];  // ragged end of the vector
-    __syncthreads();
+  int64_t ti = blockIdx.x;
+  if (ti >= ntiles) return;
+  int64_t m = start_of(ti);
+  FillAhead<BATCH> a;
+  fill_fetch<BATCH>(a, idx, sum, k, m);
+  for (; ti < ntiles; ti += gridDim.x) {
+    const int64_t tn = ti + gridDim.x;
+    const int64_t m_next = tn < ntiles ? start_of(tn) : k;
+    const int64_t c_begin = ti * kPer;
+    const int64_t c_end = c_begin + kPer < nchunk ? c_begin + kPer : nchunk;
+    fill_run<BATCH>(a, buf, update, n, idx, sum, k, c_begin, c_end, m, m_next);
+    m = m_next;
   }
 }
 
