@@ -196,6 +196,54 @@ def run_workload(args, data, rho, steps, warmup, torch, pkg, inp):
     return out
 
 
+def run_entry_points(args, data, rho, reps, torch, pkg):
+    """Times the stand-alone calls of the boundary on one workload: every call `reps` times back to
+    back on vectors resident in HBM (gradient set 1 stands for the error-fed vectors, worker 0 is
+    the selected one).  ms per call and the algorithmic bytes it moves."""
+    wl = data.wl
+    n, w = wl.n, wl.w
+    k = wl.k(rho)
+    dev = torch.device("cuda:0")
+    acc = data.g_sets[0]
+    ctx = pkg.Context(w, n, k, 1)
+    for name, value in args.options.items():
+        ctx.set_option(getattr(pkg, "ARTOPK_OPT_" + name.upper()), value)
+    var = torch.zeros(w, dtype=torch.float64, device=dev)
+    arg = torch.zeros(1, dtype=torch.int32, device=dev)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    idx_rows = torch.empty(w * k, dtype=torch.int32, device=dev)
+    vals = torch.empty(w * k, dtype=torch.float32, device=dev)
+    summed = torch.empty(k, dtype=torch.float32, device=dev)
+    sq = torch.zeros(w, dtype=torch.float64, device=dev)
+    gain = torch.zeros(w, dtype=torch.float64, device=dev)
+    update = torch.empty(n, dtype=torch.float32, device=dev)
+    calls = [
+        ("artopk_variance", lambda: ctx.artopk_variance(acc, var, arg), 4 * w * n),
+        ("artopk_select_topk", lambda: ctx.artopk_select_topk(acc[0], k, idx), 8 * n + 4 * k),
+        ("artopk_gather_sum", lambda: ctx.artopk_gather_sum(acc, idx, k, vals, summed), k * (4 + 8 * w + 4)),
+        ("artopk_scatter_residual", lambda: ctx.artopk_scatter_residual(data.res, idx, k, summed, update),
+         4 * n + k * (8 + 4 * w)),
+        ("artopk_topk_workers", lambda: ctx.artopk_topk_workers(acc, k, idx_rows, vals, sq, arg), w * (8 * n + 8 * k)),
+        ("artopk_compression_gain", lambda: ctx.artopk_compression_gain(data.res, vals, k, gain), 4 * w * n + 4 * w * k),
+        ("artopk_apply_update", lambda: ctx.artopk_apply_update(update, idx, summed, k, 1e-3), 16 * k),
+    ]
+    out = {}
+    for name, call, nbytes in calls:
+        call()
+        torch.cuda.synchronize()
+        ctx.status()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            call()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / reps
+        out[name] = {"ms": round(ms, 4), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+        log(f"[bench]   {name}: {ms:.3f} ms, {out[name]['GBps']:.0f} GB/s algorithmic")
+    ctx.status()
+    del ctx
+    return {"workload": wl.name, "N": n, "W": w, "rho": rho, "k": k, "calls": out}
+
+
 def roofline_of(r, tag, g16):
     traffic, source = profile_traffic(tag, r["rho"], r["dom_name"], f"_{g16}" if g16 else "")
     return {"bound": "hbm", "kernel": r["dom_name"], "achieved": round(r["dom_gbps"], 1),
@@ -262,6 +310,9 @@ def main():
     ap.add_argument("--bucket-elems", type=int, default=0, metavar="E",
                     help="run the step bucketed: segments of E elements (16777216 = 64 MB of float32), each with "
                          "its own Top-k; not the headline configuration")
+    ap.add_argument("--entry-points", action="store_true",
+                    help="instead of the step, time the stand-alone calls of the boundary (variance, selection, "
+                         "gather + sum, scatter + residual, and the neighbours of the step) on the workload")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="set a library route switch before measuring, e.g. guess_min_n=4096 or stage_tiles=2 "
                          "(artopk_set_option; recorded under config.options)")
@@ -297,6 +348,12 @@ def main():
     wl0 = inp.workload(cfg)
     rho = args.rho if args.rho is not None else {1: 0.01, 2: 0.01, 3: 0.01, 4: 0.01, 5: 0.001}[cfg]
     data = Inputs(args, cfg, torch, inp)
+    if args.entry_points:
+        if args.g16:
+            print("--entry-points takes float32 vectors", file=sys.stderr)
+            sys.exit(2)
+        print(json.dumps({"entry_points": run_entry_points(args, data, rho, args.steps, torch, pkg)}), flush=True)
+        return
     r = run_workload(args, data, rho, args.steps, args.warmup, torch, pkg, inp)
     del data
     torch.cuda.empty_cache()
